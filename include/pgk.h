@@ -1,0 +1,132 @@
+/*
+ * libpgk -- fused GEMM + epilogue kernels for AMD MI355X (CDNA4, gfx950).
+ *
+ * C ABI: plain pointers and sizes, no C++ or framework types.  Every data
+ * pointer below is a DEVICE pointer (HIP global memory on the current device)
+ * unless it says otherwise; `stream` is a hipStream_t passed as void*
+ * (NULL = the default stream).
+ *
+ * Operator.  PRAGMA (arXiv 2511.06345) optimises operator kernels -- Section 1
+ * names matrix multiplication and reduction operators, Section 4.2 lists the
+ * matmul, activation and pooling/reduction categories -- and gives no formula
+ * for them, so the operation is the textbook one:
+ *
+ *     x[b,i,j]    = bias[j] + sum_k A[b,i,k] * B[b,k,j]      (fp32 accumulate)
+ *     C[b,i,j]    = act(x[b,i,j])
+ *     rowsum[b,i] = sum_j act(x[b,i,j])                      (fp32, taken before
+ *                                                             C is rounded to bf16)
+ *
+ * Layout (all dense, row-major, batch-major):
+ *     A      [batch][M][K]   float32, or bfloat16 when dtype = PGK_DTYPE_BF16
+ *     B      [batch][K][N]   same element type as A
+ *     bias   [N]             float32, shared by every row and batch; NULL = 0
+ *     C      [batch][M][N]   same element type as A (bf16: round-to-nearest-even)
+ *     rowsum [batch][M]      float32; NULL = row reduction not computed
+ *
+ * Ownership.  The caller owns every buffer.  Outputs are fully overwritten
+ * (no accumulate-into-C).  Calls enqueue work on `stream` and return without
+ * synchronising it.  Results are deterministic: no atomics are used, every
+ * reduction has a fixed order, so equal inputs give bit-equal outputs.
+ *
+ * Errors.  Every entry point returns a pgk_status_t as int.  Arguments are
+ * validated on the host before any device work is enqueued, so an error return
+ * means nothing was launched.
+ */
+#ifndef PGK_H
+#define PGK_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    PGK_ACT_NONE = 0,      /* y = x */
+    PGK_ACT_RELU = 1,      /* y = max(x, 0) */
+    PGK_ACT_GELU_TANH = 2, /* y = 0.5 x (1 + tanh(sqrt(2/pi) (x + 0.044715 x^3))) */
+    PGK_ACT_SILU = 3       /* y = x / (1 + exp(-x)) */
+} pgk_act_t;
+
+typedef enum {
+    PGK_DTYPE_F32 = 0, /* A, B, C float32 */
+    PGK_DTYPE_BF16 = 1 /* A, B, C bfloat16; bias, rowsum, accumulation float32 */
+} pgk_dtype_t;
+
+typedef enum {
+    PGK_OK = 0,
+    PGK_ERR_INVALID_ARG = -1, /* NULL A/B/C, non-positive size, unknown act/dtype, bad splits */
+    PGK_ERR_UNSUPPORTED = -2, /* size beyond what the kernels index (see each call) */
+    PGK_ERR_WORKSPACE = -3,   /* workspace missing or smaller than pgk_splitk_workspace_bytes */
+    PGK_ERR_HIP = -4          /* the HIP runtime refused a launch or an allocation */
+} pgk_status_t;
+
+/*
+ * pgk_gemm_fused -- one launch sequence computing C = act(A*B + bias) and,
+ * when rowsum != NULL, rowsum = C*1 (the matmul operator of Sections 1 / 4.2
+ * with the activation and reduction operators fused into its epilogue).
+ *
+ * M, N, K, batch > 0.  Any shape is accepted: shapes that are multiples of the
+ * MFMA tile (and 16-byte aligned pointers) take the matrix-core kernels, all
+ * others a bounds-checked kernel.  M, N, K must each be below 2^31 and
+ * batch*M*N, batch*M*K, batch*K*N below 2^62 (else PGK_ERR_UNSUPPORTED).
+ *
+ * When rowsum is requested and N spans several tile columns the library keeps
+ * a small device scratch buffer per (device, stream) for the per-tile partial
+ * sums; it is allocated on first use (hipMalloc; PGK_ERR_HIP if that fails),
+ * reused afterwards, and released by pgk_release_scratch().
+ */
+int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                   int64_t M, int64_t N, int64_t K, int64_t batch,
+                   int act, int dtype, void* stream);
+
+/*
+ * pgk_gemm_splitk -- the same operator for small M,N and large K, computed in
+ * two passes so that enough workgroups exist to fill the chip:
+ *   pass 1: split s of `splits` multiplies a contiguous K-slice and stores its
+ *           raw fp32 partial product to workspace[b][s][M][N];
+ *   pass 2: per output element, partials are added in the order s = 0, 1, ...,
+ *           then bias, activation, store, and the row sum in a fixed order.
+ * The result is bit-reproducible for given inputs and `splits`.
+ *
+ * splits >= 1, or 0 to let the library choose (pgk_splitk_auto_splits).  The
+ * K range is cut into slices of L = kstep * ceil(ceil(K / kstep) / splits)
+ * elements (kstep = the kernel's K tile: 32 for float32, 64 for bfloat16);
+ * slice s covers [s*L, min(K, (s+1)*L)); trailing empty slices are dropped.
+ * splits > K is PGK_ERR_INVALID_ARG.
+ *
+ * workspace: device buffer of at least pgk_splitk_workspace_bytes(...) bytes,
+ * 16-byte aligned, owned by the caller, contents destroyed.  Too small or NULL
+ * gives PGK_ERR_WORKSPACE.
+ */
+int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                    int64_t M, int64_t N, int64_t K, int64_t batch,
+                    int act, int dtype, int splits,
+                    void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace pgk_gemm_splitk needs for this problem (splits = 0: the
+ * automatic choice).  Pure host arithmetic; returns 0 for invalid arguments. */
+size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch,
+                                  int dtype, int splits);
+
+/* The number of splits pgk_gemm_splitk uses for splits = 0, or the effective
+ * number (after dropping empty slices) for splits >= 1.  0 for invalid
+ * arguments.  Pure host arithmetic. */
+int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch,
+                           int dtype, int splits);
+
+/* Frees the row-sum scratch buffers of the current process (synchronises the
+ * devices that own them).  Optional; safe to call when none exist. */
+int pgk_release_scratch(void);
+
+/* Human-readable name of a status code; never NULL.  Host pointer, static storage. */
+const char* pgk_status_string(int status);
+
+/* Library version as major*10000 + minor*100 + patch. */
+int pgk_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* PGK_H */

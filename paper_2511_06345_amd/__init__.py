@@ -1,0 +1,16 @@
+"""libpgk: fused GEMM + bias/activation/row-sum kernels for AMD MI355X (gfx950).
+
+``inputs`` (seeded synthetic workloads) imports nothing but numpy; the GPU
+binding is loaded lazily on first use of ``gemm_fused`` / ``gemm_splitk``.
+"""
+from . import inputs  # noqa: F401
+
+_LAZY = {"gemm_fused", "gemm_splitk", "splitk_workspace_bytes", "splitk_auto_splits",
+         "status_string", "version", "load_library", "release_scratch", "PgkError"}
+
+
+def __getattr__(name):
+    if name in _LAZY:
+        import importlib
+        return getattr(importlib.import_module(__name__ + ".binding"), name)
+    raise AttributeError(name)

@@ -1,0 +1,164 @@
+"""ctypes binding of libpgk: argument marshalling only.
+
+Every step of the computation runs inside the library's HIP kernels; torch is
+used for device memory and the current stream.  The names mirror the C entry
+points declared in include/pgk.h.  There is no CPU fallback: if the shared
+library is missing the import of a function fails loudly.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Tuple
+
+import torch
+
+from .inputs import ACT_GELU_TANH, ACT_NONE, ACT_RELU, ACT_SILU, BF16, F32  # noqa: F401
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libpgk.so")
+
+EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_splitk_workspace_bytes",
+           "pgk_splitk_auto_splits", "pgk_release_scratch", "pgk_status_string", "pgk_version")
+
+_lib = None
+
+
+class PgkError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} ({status})")
+
+
+def load_library() -> ctypes.CDLL:
+    """dlopen libpgk.so (built in-tree by ``build.build_library``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise FileNotFoundError(
+            f"{LIB_PATH} not found: build it with `python -m paper_2511_06345_amd.build` "
+            "(there is no fallback path)")
+    lib = ctypes.CDLL(LIB_PATH)
+    i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
+    lib.pgk_gemm_fused.restype = ci
+    lib.pgk_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp]
+    lib.pgk_gemm_splitk.restype = ci
+    lib.pgk_gemm_splitk.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp,
+                                    ctypes.c_size_t, vp]
+    lib.pgk_splitk_workspace_bytes.restype = ctypes.c_size_t
+    lib.pgk_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+    lib.pgk_splitk_auto_splits.restype = ci
+    lib.pgk_splitk_auto_splits.argtypes = [i64, i64, i64, i64, ci, ci]
+    lib.pgk_release_scratch.restype = ci
+    lib.pgk_release_scratch.argtypes = []
+    lib.pgk_status_string.restype = ctypes.c_char_p
+    lib.pgk_status_string.argtypes = [ci]
+    lib.pgk_version.restype = ci
+    lib.pgk_version.argtypes = []
+    _lib = lib
+    return lib
+
+
+def status_string(status: int) -> str:
+    return load_library().pgk_status_string(int(status)).decode()
+
+
+def version() -> int:
+    return int(load_library().pgk_version())
+
+
+def splitk_workspace_bytes(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0) -> int:
+    return int(load_library().pgk_splitk_workspace_bytes(M, N, K, batch, dtype, splits))
+
+
+def splitk_auto_splits(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0) -> int:
+    return int(load_library().pgk_splitk_auto_splits(M, N, K, batch, dtype, splits))
+
+
+def release_scratch() -> None:
+    rc = load_library().pgk_release_scratch()
+    if rc != 0:
+        raise PgkError(rc, "pgk_release_scratch")
+
+
+def _shape(A: torch.Tensor, B: torch.Tensor) -> Tuple[int, int, int, int, int]:
+    if A.dim() == 2:
+        A = A.unsqueeze(0)
+    if B.dim() == 2:
+        B = B.unsqueeze(0)
+    if A.dim() != 3 or B.dim() != 3 or A.shape[0] != B.shape[0] or A.shape[2] != B.shape[1]:
+        raise ValueError("expected A [batch, M, K] and B [batch, K, N]")
+    if not (A.is_cuda and B.is_cuda and A.is_contiguous() and B.is_contiguous()):
+        raise ValueError("A and B must be contiguous device tensors")
+    if A.dtype == torch.float32 and B.dtype == torch.float32:
+        dtype = F32
+    elif A.dtype == torch.bfloat16 and B.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("A and B must both be float32 or both bfloat16")
+    batch, M, K = A.shape
+    return int(batch), int(M), int(B.shape[2]), int(K), dtype
+
+
+def _check_bias(bias: Optional[torch.Tensor], N: int) -> int:
+    if bias is None:
+        return 0
+    if not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and bias.numel() == N):
+        raise ValueError("bias must be a contiguous float32 device tensor of N elements")
+    return bias.data_ptr()
+
+
+def _stream_ptr(stream) -> int:
+    s = stream if stream is not None else torch.cuda.current_stream()
+    return int(s.cuda_stream)
+
+
+def gemm_fused(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
+               rowsum: bool = True, out: Optional[torch.Tensor] = None,
+               rowsum_out: Optional[torch.Tensor] = None, stream=None):
+    """C = act(A @ B + bias) and (optionally) rowsum = C.sum(-1) in fp32 via pgk_gemm_fused.
+
+    Returns (C, rowsum) with C [batch, M, N] in the dtype of A and rowsum
+    [batch, M] float32 (None when ``rowsum`` is False).  Asynchronous on the
+    current (or given) torch stream.
+    """
+    lib = load_library()
+    batch, M, N, K, dtype = _shape(A, B)
+    C = out if out is not None else torch.empty((batch, M, N), dtype=A.dtype, device=A.device)
+    rs = None
+    if rowsum:
+        rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
+                                                                   device=A.device)
+    rc = lib.pgk_gemm_fused(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
+                            rs.data_ptr() if rs is not None else None,
+                            M, N, K, batch, int(act), dtype, _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_gemm_fused")
+    return C, rs
+
+
+def gemm_splitk(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
+                splits: int = 0, rowsum: bool = True, out: Optional[torch.Tensor] = None,
+                rowsum_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+                stream=None):
+    """Two-pass split-K variant (pgk_gemm_splitk).  ``workspace`` is a uint8 device
+    tensor of at least ``splitk_workspace_bytes(...)`` bytes; allocated here when None."""
+    lib = load_library()
+    batch, M, N, K, dtype = _shape(A, B)
+    need = splitk_workspace_bytes(M, N, K, batch, dtype, splits)
+    if workspace is None:
+        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=A.device)
+    C = out if out is not None else torch.empty((batch, M, N), dtype=A.dtype, device=A.device)
+    rs = None
+    if rowsum:
+        rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
+                                                                   device=A.device)
+    rc = lib.pgk_gemm_splitk(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
+                             rs.data_ptr() if rs is not None else None,
+                             M, N, K, batch, int(act), dtype, int(splits),
+                             workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+                             _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_gemm_splitk")
+    return C, rs

@@ -1,0 +1,240 @@
+// C-ABI layer of libpgk: argument validation (host only, before any HIP call),
+// choice of kernel path and launch geometry, and the row-sum scratch pool.
+// The contract of every entry point is documented in include/pgk.h.
+#include <hip/hip_runtime.h>
+
+#include <map>
+#include <mutex>
+#include <utility>
+#include <vector>
+
+#include "../../include/pgk.h"
+#include "pgk_kernels.h"
+
+namespace {
+
+using pgk::GemmArgs;
+
+constexpr int64_t kMaxDim = 0x7fffffffLL;
+constexpr int kNumCUs = 256;          // MI355X
+constexpr int kMaxAutoSplits = 32;
+
+bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+int validate_common(const void* A, const void* B, const void* C, int64_t M, int64_t N, int64_t K,
+                    int64_t batch, int act, int dtype)
+{
+    if (!A || !B || !C) return PGK_ERR_INVALID_ARG;
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return PGK_ERR_INVALID_ARG;
+    if (act < PGK_ACT_NONE || act > PGK_ACT_SILU) return PGK_ERR_INVALID_ARG;
+    if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return PGK_ERR_INVALID_ARG;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || batch > kMaxDim) return PGK_ERR_UNSUPPORTED;
+    const long double lim = 4.6e18L;  // 2^62
+    if ((long double)batch * M * N >= lim || (long double)batch * M * K >= lim ||
+        (long double)batch * K * N >= lim)
+        return PGK_ERR_UNSUPPORTED;
+    return PGK_OK;
+}
+
+int kstep_of(int dtype) { return pgk::mfma_tile_shape(dtype).bk; }
+
+// Split geometry shared by the workspace query and the launch: slice length L
+// and the number of non-empty slices.
+struct SplitPlan { int splits; int k_slice; };
+
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
+{
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype);
+    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
+    if (M % t.bm || N % t.bn || K % t.bk) return false;
+    // per-lane 32-bit byte offsets inside one tile
+    if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * N * es >= (1LL << 32)) return false;
+    return true;
+}
+
+SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
+{
+    const int ks = kstep_of(dtype);
+    const int64_t ksteps = (K + ks - 1) / ks;
+    int64_t s = splits;
+    if (s == 0) {
+        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype) : pgk::guarded_tile_shape();
+        const long double tiles = (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
+        s = 1;
+        while (s < kMaxAutoSplits && s < ksteps && tiles * s < 2.0L * kNumCUs) ++s;
+    }
+    if (s > ksteps) s = ksteps;
+    const int64_t per = (ksteps + s - 1) / s;     // K steps per slice
+    const int64_t L = per * ks;
+    const int64_t eff = (K + L - 1) / L;          // drop trailing empty slices
+    return {(int)eff, (int)L};
+}
+
+int group_m_for(int tiles_m, int tiles_n)
+{
+    // 32 workgroups of an XCD run together; keep their tiles near-square.
+    int g = tiles_n >= 8 ? 4 : 8;
+    if (g > tiles_m) g = tiles_m;
+    return g;
+}
+
+// ---- row-sum scratch: one grow-only buffer per (device, stream)
+struct Scratch { void* ptr = nullptr; size_t bytes = 0; };
+std::mutex g_mu;
+std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
+std::vector<void*> g_retired;
+
+hipError_t scratch_get(hipStream_t stream, size_t bytes, float** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Scratch& s = g_scratch[{dev, stream}];
+    if (s.bytes < bytes) {
+        size_t want = bytes < (1u << 20) ? (1u << 20) : bytes;
+        if (want < 2 * s.bytes) want = 2 * s.bytes;
+        void* p = nullptr;
+        e = hipMalloc(&p, want);
+        if (e != hipSuccess) return e;
+        // kernels already queued on the stream may still use the old buffer
+        if (s.ptr) g_retired.push_back(s.ptr);
+        s.ptr = p;
+        s.bytes = want;
+    }
+    *out = static_cast<float*>(s.ptr);
+    return hipSuccess;
+}
+
+struct Path { bool mfma; pgk::TileShape tile; };
+
+Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
+                 int64_t M, int64_t N, int64_t K, int dtype)
+{
+    const bool ok = mfma_shape_ok(M, N, K, dtype) && aligned16(A) && aligned16(B) && aligned16(C) &&
+                    aligned16(bias) && aligned16(ws);
+    return ok ? Path{true, pgk::mfma_tile_shape(dtype)} : Path{false, pgk::guarded_tile_shape()};
+}
+
+}  // namespace
+
+extern "C" {
+
+int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                   int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+{
+    int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
+    if (rc != PGK_OK) return rc;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype);
+    const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
+    const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
+    if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+
+    GemmArgs a{};
+    a.A = A; a.B = B; a.bias = bias; a.C = C; a.ws = nullptr;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
+    a.act = act; a.splits = 1;
+    a.k_slice = (int)(((K + path.tile.bk - 1) / path.tile.bk) * path.tile.bk);
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+
+    float* part = nullptr;
+    if (rowsum) {
+        if (tiles_n == 1) {
+            a.rs_part = rowsum;
+        } else {
+            const size_t bytes = (size_t)batch * (size_t)tiles_n * (size_t)M * sizeof(float);
+            if (scratch_get(st, bytes, &part) != hipSuccess) return PGK_ERR_HIP;
+            a.rs_part = part;
+        }
+    }
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
+    if (e != hipSuccess) return PGK_ERR_HIP;
+    if (part) {
+        e = pgk::launch_rowsum_combine(part, rowsum, (int)M, (int)batch, (int)tiles_n, st);
+        if (e != hipSuccess) return PGK_ERR_HIP;
+    }
+    return PGK_OK;
+}
+
+int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
+    if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return 0;
+    if (M > kMaxDim || N > kMaxDim || K > kMaxDim || batch > kMaxDim) return 0;
+    if (splits < 0 || splits > K) return 0;
+    return plan_splits(M, N, K, batch, dtype, splits).splits;
+}
+
+size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
+{
+    const int s = pgk_splitk_auto_splits(M, N, K, batch, dtype, splits);
+    if (s <= 0) return 0;
+    const long double bytes = (long double)batch * s * M * N * sizeof(float);
+    if (bytes >= 1.8e19L) return 0;
+    return (size_t)batch * (size_t)s * (size_t)M * (size_t)N * sizeof(float);
+}
+
+int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, int splits,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
+    if (rc != PGK_OK) return rc;
+    if (splits < 0 || splits > K) return PGK_ERR_INVALID_ARG;
+    const size_t need = pgk_splitk_workspace_bytes(M, N, K, batch, dtype, splits);
+    if (need == 0) return PGK_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < need) return PGK_ERR_WORKSPACE;
+    if (!aligned16(workspace)) return PGK_ERR_WORKSPACE;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+
+    const SplitPlan plan = plan_splits(M, N, K, batch, dtype, splits);
+    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype);
+    const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
+    const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
+    if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+
+    GemmArgs a{};
+    a.A = A; a.B = B; a.bias = nullptr; a.C = nullptr; a.rs_part = nullptr;
+    a.ws = static_cast<float*>(workspace);
+    a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
+    a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
+    if (e != hipSuccess) return PGK_ERR_HIP;
+    e = pgk::launch_splitk_reduce(a.ws, bias, C, rowsum, (int)M, (int)N, (int)batch, plan.splits, act, dtype, st);
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
+int pgk_release_scratch(void)
+{
+    std::lock_guard<std::mutex> lk(g_mu);
+    int rc = PGK_OK;
+    for (auto& kv : g_scratch)
+        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
+    for (void* p : g_retired)
+        if (hipFree(p) != hipSuccess) rc = PGK_ERR_HIP;
+    g_scratch.clear();
+    g_retired.clear();
+    return rc;
+}
+
+const char* pgk_status_string(int status)
+{
+    switch (status) {
+    case PGK_OK: return "PGK_OK";
+    case PGK_ERR_INVALID_ARG: return "PGK_ERR_INVALID_ARG: null pointer, non-positive size, or unknown act/dtype/splits";
+    case PGK_ERR_UNSUPPORTED: return "PGK_ERR_UNSUPPORTED: size beyond the supported index range";
+    case PGK_ERR_WORKSPACE: return "PGK_ERR_WORKSPACE: workspace missing, misaligned or too small";
+    case PGK_ERR_HIP: return "PGK_ERR_HIP: the HIP runtime reported an error";
+    default: return "PGK: unknown status";
+    }
+}
+
+int pgk_version(void) { return 100; }
+
+}  // extern "C"

@@ -1,0 +1,56 @@
+// Internal launcher interface between the C-ABI layer and the HIP kernels.
+// Not installed; the public contract is include/pgk.h.
+#ifndef PGK_KERNELS_H
+#define PGK_KERNELS_H
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace pgk {
+
+enum { ACT_NONE = 0, ACT_RELU = 1, ACT_GELU_TANH = 2, ACT_SILU = 3 };
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+// One GEMM launch.  Pointers are device pointers.  `out_mode`:
+//   0 = fused epilogue: bias + activation, store C, optional row-sum partials
+//   1 = split-K pass 1: store the raw fp32 accumulators to `ws`
+struct GemmArgs {
+    const void* A;      // [batch][M][K]
+    const void* B;      // [batch][K][N]
+    const float* bias;  // [N] or nullptr
+    void* C;            // [batch][M][N]
+    float* rs_part;     // row-sum partials [batch][tiles_n][M], or final [batch][M]
+                        // when tiles_n == 1; nullptr = no row-sum
+    float* ws;          // split-K partial products [batch][splits][M][N]
+    int M, N, K, batch;
+    int act;
+    int splits;         // >= 1
+    int k_slice;        // K elements per split (multiple of the K tile)
+    int tiles_m, tiles_n;
+    int group_m;        // tile rows per scheduling group
+};
+
+// Tile geometry of the matrix-core kernels (one per element type).
+struct TileShape { int bm, bn, bk; };
+TileShape mfma_tile_shape(int dtype);
+TileShape guarded_tile_shape();
+
+// Matrix-core kernels: require M % bm == 0, N % bn == 0, K % bk == 0,
+// k_slice % bk == 0 and 16-byte aligned A, B, C, ws.
+hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);
+
+// Bounds-checked kernel for every other shape.
+hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);
+
+// rowsum[b][m] = sum over t = 0..tiles_n-1 (in that order) of part[b][t][m]
+hipError_t launch_rowsum_combine(const float* part, float* rowsum, int M, int batch,
+                                 int tiles_n, hipStream_t s);
+
+// Split-K pass 2: C = act(sum_s ws[b][s] + bias), s ascending; optional rowsum.
+hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, float* rowsum,
+                                int M, int N, int batch, int splits, int act, int dtype,
+                                hipStream_t s);
+
+}  // namespace pgk
+#endif

@@ -1,0 +1,108 @@
+"""The C-ABI library without a GPU: it loads, exports every declared symbol, and
+rejects bad arguments on the host before any device work (no compute calls here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2511_06345_amd import binding
+from paper_2511_06345_amd import inputs as gen
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+OK, INVALID, UNSUPPORTED, WORKSPACE, HIP = 0, -1, -2, -3, -4
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2511_06345_amd.build import build_library
+        build_library()
+    return binding.load_library()
+
+
+def test_exports_match_header(lib):
+    text = open(os.path.join(ROOT, "include", "pgk.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(pgk_[a-z_0-9]+)\s*\(", text))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_version_and_status_strings(lib):
+    assert binding.version() == 100
+    seen = set()
+    for code in (OK, INVALID, UNSUPPORTED, WORKSPACE, HIP, 12345):
+        s = binding.status_string(code)
+        assert s and s not in seen
+        seen.add(s)
+    assert binding.status_string(OK) == "PGK_OK"
+
+
+def _fused(lib, A=0x1000, B=0x2000, bias=None, C=0x3000, rs=None, M=4, N=4, K=4, batch=1, act=0, dtype=0):
+    return lib.pgk_gemm_fused(A, B, bias, C, rs, M, N, K, batch, act, dtype, None)
+
+
+def test_fused_rejects_bad_arguments_on_the_host(lib):
+    # the pointers are never dereferenced: validation happens before any HIP call
+    assert _fused(lib, A=None) == INVALID
+    assert _fused(lib, B=None) == INVALID
+    assert _fused(lib, C=None) == INVALID
+    for bad in ({"M": 0}, {"N": -1}, {"K": 0}, {"batch": 0}, {"act": 4}, {"act": -1}, {"dtype": 2}, {"dtype": -1}):
+        assert _fused(lib, **bad) == INVALID, bad
+    assert _fused(lib, M=1 << 31) == UNSUPPORTED
+    assert _fused(lib, M=(1 << 31) - 1, N=(1 << 31) - 1, K=8, batch=2) == UNSUPPORTED
+
+
+def _splitk(lib, ws=0x4000, ws_bytes=1 << 30, splits=0, **kw):
+    a = dict(A=0x1000, B=0x2000, bias=None, C=0x3000, rs=None, M=4, N=4, K=64, batch=1, act=0, dtype=0)
+    a.update(kw)
+    return lib.pgk_gemm_splitk(a["A"], a["B"], a["bias"], a["C"], a["rs"], a["M"], a["N"], a["K"], a["batch"],
+                               a["act"], a["dtype"], splits, ws, ws_bytes, None)
+
+
+def test_splitk_rejects_bad_arguments_on_the_host(lib):
+    assert _splitk(lib, A=None) == INVALID
+    assert _splitk(lib, K=0) == INVALID
+    assert _splitk(lib, splits=-1) == INVALID
+    assert _splitk(lib, splits=65, K=64) == INVALID            # more splits than K
+    assert _splitk(lib, ws=None) == WORKSPACE
+    assert _splitk(lib, ws_bytes=15) == WORKSPACE
+    assert _splitk(lib, ws=0x4004) == WORKSPACE                # misaligned
+    need = binding.splitk_workspace_bytes(4, 4, 64, 1, gen.F32, 2)
+    assert _splitk(lib, splits=2, ws_bytes=need - 1) == WORKSPACE
+
+
+def test_split_plan_arithmetic(lib):
+    F32, BF16 = gen.F32, gen.BF16
+    # the batched tiny-output / huge-K workload: 4 tiles x 16 problems -> 8 splits fill 2 x 256 CUs
+    assert binding.splitk_auto_splits(256, 256, 65536, 16, F32, 0) == 8
+    assert binding.splitk_workspace_bytes(256, 256, 65536, 16, F32, 0) == 16 * 8 * 256 * 256 * 4
+    assert binding.splitk_workspace_bytes(256, 256, 65536, 16, F32, 4) == 16 * 4 * 256 * 256 * 4
+    # K = 100 fp32: 4 K-steps of 32; 3 splits -> 2 steps per slice -> only 2 non-empty slices
+    assert binding.splitk_auto_splits(8, 8, 100, 1, F32, 3) == 2
+    # never more slices than K steps; bf16 K step is 64
+    assert binding.splitk_auto_splits(8, 8, 100, 1, BF16, 2) == 2
+    assert binding.splitk_auto_splits(8, 8, 64, 1, BF16, 5) == 1
+    # a grid that already fills the chip is not split
+    assert binding.splitk_auto_splits(8192, 8192, 8192, 1, BF16, 0) == 1
+    # auto choice is capped
+    assert 1 <= binding.splitk_auto_splits(64, 64, 1 << 20, 1, F32, 0) <= 32
+    # invalid queries
+    assert binding.splitk_auto_splits(0, 8, 8, 1, F32, 0) == 0
+    assert binding.splitk_workspace_bytes(8, 8, 8, 1, 7, 0) == 0
+    assert binding.splitk_workspace_bytes(8, 8, 8, 1, F32, 9) == 0
+
+
+def test_python_binding_validates_before_calling(lib):
+    import torch
+    a = torch.zeros(2, 3)
+    with pytest.raises(ValueError):
+        binding.gemm_fused(a, torch.zeros(3, 2), None, 0)      # host tensors are refused
+    with pytest.raises(ValueError):
+        binding._shape(torch.zeros(2, 3), torch.zeros(4, 2))
+
+
+def test_release_scratch_without_any(lib):
+    binding.release_scratch()

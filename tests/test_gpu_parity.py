@@ -1,0 +1,231 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.
+
+Error bar: max |g - r| / max(|r|, RMS(r)) <= 1e-4 for fp32 and <= 2e-2 for bf16
+inputs with fp32 accumulation; integer-valued inputs with the identity activation
+must match the oracle exactly (every fp32 summation order is exact there).
+"""
+import numpy as np
+import pytest
+
+from paper_2511_06345_amd import inputs as gen
+from util import TOL, c_to_numpy, rel_err, sample_rows, to_device
+
+pytestmark = pytest.mark.gpu
+
+NONE, RELU, GELU, SILU = gen.ACT_NONE, gen.ACT_RELU, gen.ACT_GELU_TANH, gen.ACT_SILU
+F32, BF16 = gen.F32, gen.BF16
+
+
+@pytest.fixture(scope="module")
+def pgk():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2511_06345_amd import binding
+    binding.load_library()          # fails loudly when libpgk.so is missing: there is no fallback
+    return binding
+
+
+def run_fused(pgk, A, B, bias, act, dtype, rowsum=True):
+    import torch
+    dA, dB = to_device(A, dtype), to_device(B, dtype)
+    dbias = torch.from_numpy(bias).cuda() if bias is not None else None
+    C, rs = pgk.gemm_fused(dA, dB, dbias, act, rowsum=rowsum)
+    torch.cuda.synchronize()
+    return c_to_numpy(C, dtype), (rs.cpu().numpy().astype(np.float64) if rs is not None else None)
+
+
+def run_splitk(pgk, A, B, bias, act, dtype, splits=0, rowsum=True):
+    import torch
+    dA, dB = to_device(A, dtype), to_device(B, dtype)
+    dbias = torch.from_numpy(bias).cuda() if bias is not None else None
+    C, rs = pgk.gemm_splitk(dA, dB, dbias, act, splits=splits, rowsum=rowsum)
+    torch.cuda.synchronize()
+    return c_to_numpy(C, dtype), (rs.cpu().numpy().astype(np.float64) if rs is not None else None)
+
+
+def random_case(dtype, M, N, K, batch, seed, bias_std=0.5):
+    rng_seed = 1000 + seed
+    A = gen.uniform(gen.tensor_seed(90, 1, rng_seed), batch * M * K, -1.0, 1.0).reshape(batch, M, K)
+    B = gen.uniform(gen.tensor_seed(90, 2, rng_seed), batch * K * N, -1.0, 1.0).reshape(batch, K, N)
+    bias = gen.normal(gen.tensor_seed(90, 3, rng_seed), N, bias_std)
+    if dtype == BF16:
+        A, B = gen.f32_to_bf16_bits(A), gen.f32_to_bf16_bits(B)
+    return A, B, bias
+
+
+def check(got_c, got_rs, ref_c, ref_rs, dtype, what):
+    e = rel_err(got_c, ref_c)
+    assert e <= TOL[dtype], f"{what}: C error {e:.3e}"
+    if ref_rs is not None and got_rs is not None:
+        e = rel_err(got_rs, ref_rs)
+        assert e <= TOL[dtype], f"{what}: rowsum error {e:.3e}"
+
+
+# shapes: tiny and ragged (bounds-checked kernel), exact tile multiples with several
+# K-tile counts (matrix-core kernels), and mixes with a ragged tail in each dimension
+GUARDED_SHAPES = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (64, 64, 16, 1), (2, 300, 5, 1)]
+F32_TILE_SHAPES = [(128, 128, 32, 1), (128, 128, 64, 1), (256, 128, 96, 1), (128, 384, 160, 2), (384, 256, 224, 1)]
+BF16_TILE_SHAPES = [(256, 256, 64, 1), (256, 256, 128, 1), (256, 512, 192, 1), (512, 256, 320, 2), (256, 256, 448, 1)]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("shape", GUARDED_SHAPES)
+@pytest.mark.parametrize("act", [NONE, RELU, GELU, SILU])
+def test_small_and_ragged_shapes(pgk, oracle, dtype, shape, act):
+    M, N, K, batch = shape
+    A, B, bias = random_case(dtype, M, N, K, batch, seed=M + N + K)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, act)
+    got_c, got_rs = run_fused(pgk, A, B, bias, act, dtype)
+    check(got_c, got_rs, ref_c, ref_rs, dtype, f"guarded {shape} act {act}")
+
+
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES), (BF16, BF16_TILE_SHAPES)])
+@pytest.mark.parametrize("act", [NONE, RELU, GELU, SILU])
+def test_tile_multiple_shapes(pgk, oracle, dtype, shapes, act):
+    for shape in shapes:
+        M, N, K, batch = shape
+        A, B, bias = random_case(dtype, M, N, K, batch, seed=M + 3 * N + 7 * K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, bias, act)
+        got_c, got_rs = run_fused(pgk, A, B, bias, act, dtype)
+        check(got_c, got_rs, ref_c, ref_rs, dtype, f"mfma {shape} act {act}")
+        # no bias, no row sum
+        ref_c, _ = oracle.gemm_fused(A, B, None, act, want_rowsum=False)
+        got_c, got_rs = run_fused(pgk, A, B, None, act, dtype, rowsum=False)
+        assert got_rs is None
+        check(got_c, None, ref_c, None, dtype, f"mfma {shape} act {act} no bias")
+
+
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + GUARDED_SHAPES), (BF16, BF16_TILE_SHAPES + GUARDED_SHAPES)])
+def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
+    """Entries in {-2..2}, identity activation: bit-exact against the oracle, for every
+    K-tile count (catches stage / double-buffer hazards and index slips)."""
+    for shape in shapes:
+        M, N, K, batch = shape
+        A, B = gen.make_int_inputs(dtype, M, N, K, batch, seed=11 * M + K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, None, NONE)
+        got_c, got_rs = run_fused(pgk, A, B, None, NONE, dtype)
+        if dtype == BF16:   # C is stored as bf16: compare against the RNE-rounded exact value
+            ref_c = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref_c.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(got_c, ref_c), f"fused {shape}"
+        assert np.array_equal(got_rs, ref_rs), f"fused rowsum {shape}"
+        for splits in (0, 1, 2, 3):
+            if splits > K:
+                continue
+            got_c, got_rs = run_splitk(pgk, A, B, None, NONE, dtype, splits=splits)
+            assert np.array_equal(got_c, ref_c), f"splitk {shape} splits {splits}"
+            assert np.array_equal(got_rs, ref_rs), f"splitk rowsum {shape} splits {splits}"
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("act", [NONE, SILU])
+def test_splitk_matches_oracle_and_is_deterministic(pgk, oracle, dtype, act):
+    shapes = [(128, 128, 1024, 3), (256, 256, 2048, 2), (100, 36, 1000, 2)]
+    for shape in shapes:
+        M, N, K, batch = shape
+        A, B, bias = random_case(dtype, M, N, K, batch, seed=5 * M + K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, bias, act)
+        for splits in (0, 4, 7):
+            got_c, got_rs = run_splitk(pgk, A, B, bias, act, dtype, splits=splits)
+            check(got_c, got_rs, ref_c, ref_rs, dtype, f"splitk {shape} splits {splits}")
+            again_c, again_rs = run_splitk(pgk, A, B, bias, act, dtype, splits=splits)
+            assert np.array_equal(got_c, again_c) and np.array_equal(got_rs, again_rs)
+        fused_c, fused_rs = run_fused(pgk, A, B, bias, act, dtype)
+        check(fused_c, fused_rs, ref_c, ref_rs, dtype, f"fused {shape}")
+
+
+def test_identity_operand_passes_b_through(pgk, oracle):
+    # A = I: C = act(B + bias) -- exercises operand roles (a transposed B would fail)
+    n = 256
+    B = gen.normal(1234, n * n, 1.0).reshape(1, n, n)
+    bias = gen.normal(1235, n, 1.0)
+    A = np.eye(n, dtype=np.float32).reshape(1, n, n)
+    for dtype in (F32, BF16):
+        a, b = (gen.f32_to_bf16_bits(A), gen.f32_to_bf16_bits(B)) if dtype == BF16 else (A, B)
+        ref_c, ref_rs = oracle.gemm_fused(a, b, bias, RELU)
+        got_c, got_rs = run_fused(pgk, a, b, bias, RELU, dtype)
+        check(got_c, got_rs, ref_c, ref_rs, dtype, "identity operand")
+
+
+def test_fused_is_deterministic(pgk):
+    for dtype, shape in ((F32, (256, 384, 96, 2)), (BF16, (512, 512, 128, 1)), (F32, (70, 130, 33, 2))):
+        M, N, K, batch = shape
+        A, B, bias = random_case(dtype, M, N, K, batch, seed=3)
+        c1, r1 = run_fused(pgk, A, B, bias, GELU, dtype)
+        c2, r2 = run_fused(pgk, A, B, bias, GELU, dtype)
+        assert np.array_equal(c1, c2) and np.array_equal(r1, r2)
+
+
+def test_error_codes_on_device(pgk):
+    import torch
+    a = torch.zeros(1, 8, 8, device="cuda")
+    with pytest.raises(pgk.PgkError) as ei:
+        pgk.gemm_splitk(a, a, None, NONE, splits=9)              # splits > K
+    assert ei.value.status == -1
+    small = torch.empty(16, dtype=torch.uint8, device="cuda")
+    with pytest.raises(pgk.PgkError) as ei:
+        pgk.gemm_splitk(a, a, None, NONE, splits=1, workspace=small)
+    assert ei.value.status == -3
+
+
+# ------------------------------------------------------------------ the five workloads
+def _workload_case(pgk, oracle, name, n_random_rows):
+    import torch
+    w = gen.WORKLOADS[name]
+    A, B, bias = gen.make_inputs(w)
+    tile = 256 if w.dtype == BF16 else 128
+    rows = sample_rows(w.M, tile, n_random_rows, seed=w.index)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, w.act, rows=rows, want_rowsum=w.rowsum)
+    dA, dB = to_device(A, w.dtype), to_device(B, w.dtype)
+    dbias = torch.from_numpy(bias).cuda() if bias is not None else None
+    fn = pgk.gemm_splitk if w.call == "splitk" else pgk.gemm_fused
+    C, rs = fn(dA, dB, dbias, w.act, rowsum=w.rowsum)
+    torch.cuda.synchronize()
+    C2, rs2 = fn(dA, dB, dbias, w.act, rowsum=w.rowsum)
+    torch.cuda.synchronize()
+    assert torch.equal(C.view(torch.int16 if w.dtype == BF16 else torch.int32),
+                       C2.view(torch.int16 if w.dtype == BF16 else torch.int32)), "run-to-run difference"
+    drows = torch.from_numpy(rows).cuda()
+    got_c = c_to_numpy(C[:, drows], w.dtype)
+    got_rs = rs[:, drows].cpu().numpy().astype(np.float64) if rs is not None else None
+    if rs is not None:
+        assert torch.equal(rs, rs2)
+    check(got_c, got_rs, ref_c, ref_rs, w.dtype, f"workload {name}")
+    return rel_err(got_c, ref_c)
+
+
+def test_workload_c1_full(pgk, oracle):
+    w = gen.WORKLOADS["c1"]
+    A, B, bias = gen.make_inputs(w)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, w.act)
+    got_c, got_rs = run_fused(pgk, A, B, bias, w.act, w.dtype)
+    check(got_c, got_rs, ref_c, ref_rs, w.dtype, "workload c1")
+
+
+def test_workload_c2_sampled_rows(pgk, oracle):
+    _workload_case(pgk, oracle, "c2", 64)
+
+
+def test_workload_c3_sampled_rows(pgk, oracle):
+    _workload_case(pgk, oracle, "c3", 64)
+
+
+def test_workload_c4_sampled_rows(pgk, oracle):
+    _workload_case(pgk, oracle, "c4", 128)
+
+
+def test_workload_c5_sampled_rows(pgk, oracle):
+    _workload_case(pgk, oracle, "c5", 24)
+
+
+def test_workload_c3_without_bias_or_activation(pgk, oracle):
+    """The large bf16 workload is bias dominated; check the bare product too."""
+    import torch
+    w = gen.WORKLOADS["c3"]
+    A, B, _ = gen.make_inputs(w, shape=(1024, 1024, 8192, 1))
+    rows = sample_rows(1024, 256, 32, seed=9)
+    ref_c, _ = oracle.gemm_fused(A, B, None, NONE, rows=rows, want_rowsum=False)
+    C, _ = pgk.gemm_fused(to_device(A, BF16), to_device(B, BF16), None, NONE, rowsum=False)
+    torch.cuda.synchronize()
+    got = c_to_numpy(C[:, torch.from_numpy(rows).cuda()], BF16)
+    check(got, None, ref_c, None, BF16, "c3 bare product")
