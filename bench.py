@@ -1,0 +1,212 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused GEMM + epilogue hot path on one MI355X.
+
+One "step" is one pass of the whole hot path over one batch of seeded synthetic
+input: one pgk_gemm_fused (or pgk_gemm_splitk) call, i.e. the matrix-core main
+loop, the bias/activation/row-sum epilogue and any follow-up reduction kernel.
+Inputs are generated on the host by the seeded generator and are resident in HBM
+before the timed region starts.
+
+The headline workload is the large bf16 GEMM (M=N=K=8192, bias + SiLU, bf16 out).
+Timing follows the protocol of the paper's evaluation (PRAGMA Section 4.1): 5
+warm-up runs and 100 timed repetitions by default.
+
+Prints ONE JSON line on stdout.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import numpy as np  # noqa: E402
+
+# MI355X published peaks
+PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
+PEAK_HBM_GBS = 8000.0
+
+DESCR = {
+    "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
+    "c2": "c2: fp32 GEMM 4096x4096x4096, bias + GELU-tanh",
+    "c3": "c3: bf16 GEMM 8192x8192x8192 (fp32 accumulate), bias + SiLU, bf16 out",
+    "c4": "c4: bf16 GEMM 16384x1024x4096, bias + ReLU + fp32 rowsum, bf16 out",
+    "c5": "c5: fp32 split-K GEMM 256x256x65536 x16, identity + rowsum",
+}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def device_inputs(w, gen, torch):
+    A, B, bias = gen.make_inputs(w)
+    if w.dtype == gen.BF16:
+        dA = torch.from_numpy(A.view(np.int16)).cuda().view(torch.bfloat16)
+        dB = torch.from_numpy(B.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        dA, dB = torch.from_numpy(A).cuda(), torch.from_numpy(B).cuda()
+    dbias = torch.from_numpy(bias).cuda() if bias is not None else None
+    return (A, B, bias), (dA, dB, dbias)
+
+
+def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
+    """Times `steps` calls of the hot path on workload `name`; returns a dict."""
+    w = gen.WORKLOADS[name]
+    t0 = time.time()
+    host, (dA, dB, dbias) = device_inputs(w, gen, torch)
+    log(f"[{name}] inputs generated and copied in {time.time() - t0:.1f} s")
+    out_dt = torch.bfloat16 if w.dtype == gen.BF16 else torch.float32
+    C = torch.empty((w.batch, w.M, w.N), dtype=out_dt, device="cuda")
+    rs = torch.empty((w.batch, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None
+    kw = {}
+    if w.call == "splitk":
+        need = pgk.splitk_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, 0)
+        kw["workspace"] = torch.empty(need, dtype=torch.uint8, device="cuda")
+        fn = pgk.gemm_splitk
+    else:
+        fn = pgk.gemm_fused
+
+    def step():
+        fn(dA, dB, dbias, w.act, rowsum=w.rowsum, out=C, rowsum_out=rs, **kw)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    # events are recorded on torch's current stream, the stream the kernels are launched on
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t_start = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])  # ms, per call
+    ms_per_step = wall * 1e3 / steps
+    res = {
+        "workload": DESCR[name],
+        "ms_per_step": ms_per_step,
+        "tflops": w.flops / (ms_per_step * 1e-3) / 1e12,
+        "call_ms_avg": float(per.mean()),
+        "call_ms_median": float(np.median(per)),
+        "call_ms_min": float(per.min()),
+        "algorithmic_gbs": w.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
+    }
+    if keep_host:
+        res["_host"] = host
+    return res
+
+
+def cpu_baseline(w, host, gen, budget_s=15.0):
+    """The CPU oracle, as it stands, on a bounded sample of whole rows of the workload."""
+    import oracle
+    oracle.build()
+    A, B, bias = host
+    rng = np.random.default_rng(12345)
+    probe_rows = np.sort(rng.choice(w.M, size=min(16, w.M), replace=False)).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.gemm_fused(A, B, bias, w.act, rows=probe_rows, want_rowsum=w.rowsum)
+    t_probe = time.perf_counter() - t0
+    n_rows = int(min(w.M, max(16, budget_s / max(t_probe, 1e-6) * probe_rows.size)))
+    n_rows = min(n_rows, 4096)
+    rows = np.sort(rng.choice(w.M, size=n_rows, replace=False)).astype(np.int64)
+    t0 = time.perf_counter()
+    oracle.gemm_fused(A, B, bias, w.act, rows=rows, want_rowsum=w.rowsum)
+    dt = time.perf_counter() - t0
+    flops = 2.0 * n_rows * w.N * w.K * w.batch
+    return {
+        "value": flops / dt / 1e12,
+        "unit": "TFLOP/s",
+        "cores": oracle.num_threads(),
+        "kind": "oracle",
+        "sample": f"{n_rows} seeded random whole rows of the {w.M}-row {w.name} problem "
+                  f"({flops:.3e} flop in {dt:.1f} s, plain C triple loop in double, gcc -O2 -fopenmp)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="c3", choices=sorted(DESCR))
+    ap.add_argument("--others", action="store_true",
+                    help="also time the other four workloads (reported under 'others')")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (nothing here uses a second GPU)")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible")
+    torch.cuda.set_device(0)
+    from paper_2511_06345_amd import binding as pgk
+    from paper_2511_06345_amd import inputs as gen
+    pgk.load_library()   # no fallback: fails here if libpgk.so is not built
+
+    name = args.workload
+    w = gen.WORKLOADS[name]
+    head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True)
+    host = head.pop("_host")
+
+    dtype_key = "bf16" if w.dtype == gen.BF16 else "f32"
+    peak = PEAK_TFLOPS[dtype_key]
+    achieved = w.flops / (head["call_ms_avg"] * 1e-3) / 1e12
+    roofline = {
+        "bound": "mfma",
+        "kernel": "pgk::gemm_mfma_kernel (matrix-core main loop + fused epilogue)",
+        "achieved": achieved,
+        "peak": peak,
+        "unit": "TFLOP/s",
+        "frac": achieved / peak,
+        "launch_ms_avg": head["call_ms_avg"],
+        "traffic": None,
+        "hbm_frac_algorithmic": head["algorithmic_gbs"] / PEAK_HBM_GBS,
+    }
+
+    out = {
+        "metric": "fused GEMM+epilogue TFLOP/s on 1 MI355X",
+        "value": head["tflops"],
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": dtype_key,
+        "data": "synthetic (seeded SplitMix64 generator, resident in HBM before timing)",
+        "config": {"workload": DESCR[name], "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
+                   "call": w.call, "flops_per_step": w.flops, "algorithmic_bytes_per_step": w.algorithmic_bytes},
+        "roofline": roofline,
+    }
+    if not args.no_cpu_baseline:
+        log("[cpu_baseline] timing the oracle on a bounded sample ...")
+        out["cpu_baseline"] = cpu_baseline(w, host, gen)
+    del host
+    if args.others:
+        others = {}
+        for other in sorted(DESCR):
+            if other == name:
+                continue
+            r = run_workload(other, args.steps, args.warmup, pgk, gen, torch)
+            ow = gen.WORKLOADS[other]
+            pk = PEAK_TFLOPS["bf16" if ow.dtype == gen.BF16 else "f32"]
+            r["mfma_frac"] = ow.flops / (r["call_ms_avg"] * 1e-3) / 1e12 / pk
+            r["hbm_frac_algorithmic"] = r["algorithmic_gbs"] / PEAK_HBM_GBS
+            others[other] = r
+            torch.cuda.empty_cache()
+        out["others"] = others
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -31,8 +31,18 @@
 
 namespace pgk {
 
-template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_>
+template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int COPY_PARTS_, int STAGES_ = 2,
+          int WAVES_PER_SIMD_ = 1>
 struct MfmaCfg {
+    // depth of the LDS ring of K tiles (2..4): STAGES - 1 tiles are in flight or landed
+    // ahead of the one being multiplied
+    static constexpr int STAGES = STAGES_;
+    // waves the register allocation must leave room for on one SIMD
+    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
+    // The global -> LDS copy of one K tile is issued in COPY_PARTS_ equal parts, one
+    // part per operand-fetch step, so that the texture-address path (16 cycles per
+    // 1 KiB wave instruction) is never asked for more than it can take in a step.
+    static constexpr int COPY_PARTS = COPY_PARTS_;
     static constexpr bool BF16 = BF16_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
     static constexpr int ES = BF16_ ? 2 : 4;       // element bytes
@@ -48,15 +58,19 @@ struct MfmaCfg {
     static constexpr int B_CPW = B_BYTES / 1024 / NW;
     static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
     static constexpr int A_RPC = 1024 / RA, B_RPC = 1024 / RB;  // rows per 1 KiB
-    static constexpr int LDS_BYTES = 2 * (A_BYTES + B_BYTES);
-    static_assert(RA == 128, "A-tile swizzle assumes 128-byte rows");
+    static constexpr int LDS_BYTES = STAGES * (A_BYTES + B_BYTES);
+    static_assert(STAGES >= 2 && STAGES <= 4 && LDS_BYTES <= 160 * 1024, "LDS ring size");
+    static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
     static_assert(RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile / wave split");
     static_assert(BM <= NT, "row-sum combine uses one thread per tile row");
 };
 
 // Swizzles (in units of 16-byte chunks) applied to the chunk index of a row.
-__device__ __forceinline__ int swz_a(int row) { return (row >> 1) & 7; }
+// A tile: rows of CPR chunks; 16 consecutive rows read the same logical chunk
+// at once, so the 16 chunk slots of a 256-byte bank period must all differ.
+template <int CPR>
+__device__ __forceinline__ int swz_a(int row) { return (row / (16 / CPR)) % CPR; }
 template <bool BF16>
 __device__ __forceinline__ int swz_b(int krow)
 {
@@ -109,7 +123,7 @@ template <int V>
 struct IC { static constexpr int value = V; };
 
 template <typename Cfg>
-__global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, const int out_mode)
+__global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel(const GemmArgs p, const int out_mode)
 {
     constexpr bool BF16 = Cfg::BF16;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ES = Cfg::ES;
@@ -117,13 +131,18 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
     constexpr int NS = BF16 ? BK / 16 : BK / 8;   // operand-fetch steps per K tile
     static_assert(NS % 2 == 0, "fragment double buffer assumes an even step count");
 
-    // Four separate LDS objects (not one array indexed by stage): the compiler can
-    // then tell that a direct-to-LDS copy into one stage does not alias the
-    // operand reads of the other stage, and does not wait for it.
+    // Separate LDS objects per stage and operand (not one array indexed by stage): the
+    // compiler can then tell that a direct-to-LDS copy into one stage does not alias
+    // the operand reads of another stage, and does not wait for it.
+    constexpr int S = Cfg::STAGES;
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a0[Cfg::A_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a1[Cfg::A_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a2[S > 2 ? Cfg::A_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a3[S > 3 ? Cfg::A_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b0[Cfg::B_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b1[Cfg::B_BYTES];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_b2[S > 2 ? Cfg::B_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_b3[S > 3 ? Cfg::B_BYTES : 16];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -155,7 +174,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
     for (int t = 0; t < Cfg::A_CPW; ++t) {
         const int ch = wave * Cfg::A_CPW + t;
         const int r = ch * Cfg::A_RPC + lane / Cfg::A_CPR;
-        const int c = (lane % Cfg::A_CPR) ^ swz_a(r);
+        const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
         voff_a[t] = (unsigned int)r * (unsigned int)p.K * ES + (unsigned int)c * 16u;
     }
 #pragma unroll
@@ -167,24 +186,38 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
     }
 
     auto lds_a = [&](auto st) -> unsigned char* {
-        if constexpr (decltype(st)::value == 0) return lds_a0; else return lds_a1;
+        constexpr int v = decltype(st)::value;
+        if constexpr (v == 0) return lds_a0; else if constexpr (v == 1) return lds_a1;
+        else if constexpr (v == 2) return lds_a2; else return lds_a3;
     };
     auto lds_b = [&](auto st) -> unsigned char* {
-        if constexpr (decltype(st)::value == 0) return lds_b0; else return lds_b1;
+        constexpr int v = decltype(st)::value;
+        if constexpr (v == 0) return lds_b0; else if constexpr (v == 1) return lds_b1;
+        else if constexpr (v == 2) return lds_b2; else return lds_b3;
     };
 
-    // global -> LDS copy of K tile kt into stage st
-    auto load_tile = [&](int kt, auto st) {
+    // global -> LDS copy of K tile kt into stage st: instructions of part `part`
+    // (the A and B instructions of a wave are numbered together, A first)
+    constexpr int N_COPY = Cfg::A_CPW + Cfg::B_CPW;
+    constexpr int PER_PART = (N_COPY + Cfg::COPY_PARTS - 1) / Cfg::COPY_PARTS;
+    auto load_part = [&](int kt, auto st, int part) {
         const unsigned char* ga = Ag + (size_t)kt * a_step;
         const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
 #pragma unroll
-        for (int t = 0; t < Cfg::A_CPW; ++t)
-            __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
+        for (int t = 0; t < N_COPY; ++t) {
+            if (t / PER_PART != part) continue;
+            if (t < Cfg::A_CPW)
+                __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
+            else
+                __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t - Cfg::A_CPW]),
+                                                 PGK_LDS(lb + (t - Cfg::A_CPW) * 1024), 16, 0, 0);
+        }
+    };
+    auto load_tile = [&](int kt, auto st) {
 #pragma unroll
-        for (int t = 0; t < Cfg::B_CPW; ++t)
-            __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t]), PGK_LDS(lb + t * 1024), 16, 0, 0);
+        for (int part = 0; part < Cfg::COPY_PARTS; ++part) load_part(kt, st, part);
     };
 
     // ---- per-lane LDS read offsets
@@ -194,7 +227,7 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
     const int a_row_off = (wm * Cfg::WM + l32) * RA;
     int a_koff[NS];                 // per step: row offset + swizzled chunk offset (bytes)
 #pragma unroll
-    for (int s = 0; s < NS; ++s) a_koff[s] = a_row_off + (((2 * s + half) ^ swz_a(l32)) * 16);
+    for (int s = 0; s < NS; ++s) a_koff[s] = a_row_off + (((2 * s + half) ^ swz_a<Cfg::A_CPR>(l32)) * 16);
     // B columns (MFMA "A" operand)
     int b_off[TN];
     if constexpr (BF16) {
@@ -277,68 +310,107 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
         }
     };
 
-    // Wait for this wave's direct-to-LDS copies, then meet the other waves: after
-    // the barrier the copied tile is visible to everybody, and everybody has
-    // fetched its last operands from the stage that is overwritten next.
-    // (lgkmcnt(0): this wave's own LDS reads have completed as well.  The two
-    // sched_barriers keep the compiler from moving MFMAs or fetches across.)
-    auto wait_copies_and_sync = [&]() {
+    // Wait until at most `allowed` of this wave's direct-to-LDS copy instructions are
+    // still in flight (they complete in order), and for its own LDS reads; then meet
+    // the other waves.  After the barrier the tile that has just landed is visible to
+    // everybody, and everybody has fetched its last operands from the stage that is
+    // overwritten next.  The sched_barriers keep the compiler from moving MFMAs or
+    // fetches across.
+    auto wait_copies_and_sync = [&](auto allowed) {
         __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(decltype(allowed)::value) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
+    // copy instructions per wave per tile; tiles kt+2 .. kt+S-1 may stay in flight
+    // while tile kt+1 is awaited
+    constexpr int STEADY_IN_FLIGHT = (S - 2) * N_COPY;
+    static_assert(STEADY_IN_FLIGHT <= 63, "vmcnt is a 6-bit counter");
 
     Frag frag[2];
 
-    // One K tile out of stage `st`.  Operands of step s+1 are fetched while the
-    // MFMAs of step s run.  Before the MFMAs of the last step, when a next tile
-    // exists: wait for its copy, meet the other waves, fetch its first operands
-    // (other stage), and start the copy of the tile after it into this stage,
-    // which nobody reads any more.
-    auto tile_body = [&](int kt, auto st, auto st_other, bool has_next, bool has_next2) {
+    // One K tile out of stage ST.  Operands of step s+1 are fetched while the MFMAs
+    // of step s run.  Before the MFMAs of the last step, when a next tile exists:
+    // wait for its copy, meet the other waves, fetch its first operands (next
+    // stage), and start the copy of tile kt+S into this stage, which nobody reads
+    // any more.  That copy is issued in parts: part 0 here, parts 1.. during the
+    // first steps of the next tile.  `steady` = every tile up to kt+S exists, so
+    // the in-flight count at the wait is the steady-state one; otherwise the wait
+    // is for all copies.
+    static_assert(Cfg::COPY_PARTS >= 1 && Cfg::COPY_PARTS <= NS, "one copy part per step");
+    auto tile_body = [&](int kt, auto st, auto steady_tag, bool has_next, bool has_copy, bool has_prev_copy) {
+        constexpr int ST = decltype(st)::value;
+        constexpr bool STEADY = decltype(steady_tag)::value != 0;
+        using StNext = IC<(ST + 1) % S>;
+        using StPrev = IC<(ST + S - 1) % S>;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
+            bool copy = false;
             if (s + 1 < NS) {
                 read_frags(st, s + 1, frag[(s + 1) & 1]);
+                if (s + 1 < Cfg::COPY_PARTS && has_prev_copy) {
+                    // rest of the copy of tile kt-1+S, started in the previous tile's last step
+                    load_part(kt - 1 + S, StPrev{}, s + 1);
+                    copy = true;
+                }
             } else if (has_next) {
-                wait_copies_and_sync();
-                read_frags(st_other, 0, frag[0]);
-                if (has_next2) load_tile(kt + 2, st);
+                if constexpr (STEADY) wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
+                else wait_copies_and_sync(IC<0>{});
+                read_frags(StNext{}, 0, frag[0]);
+                if (has_copy) {
+                    load_part(kt + S, st, 0);
+                    copy = true;
+                }
             }
             mfma_step(frag[s & 1]);
-            // Issue order inside this step: one LDS operand fetch (and, in the last
-            // step, one global copy) after each MFMA, so the matrix pipe never
-            // waits for a burst of fetches.
+            // Issue order inside this step: one LDS operand fetch after each MFMA, and
+            // the copy instructions of this step evenly spaced over its MFMAs, so the
+            // matrix pipe never waits for a burst of fetches.
             constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
             constexpr int N_DS = BF16 ? TM + 2 * TN : TM + 4 * TN;
-            constexpr int N_VM = Cfg::A_CPW + Cfg::B_CPW;
             const bool fetch = (s + 1 < NS) || has_next;
-            const bool copy = (s + 1 == NS) && has_next && has_next2;
 #pragma unroll
             for (int m = 0; m < N_MFMA; ++m) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (fetch && m < N_DS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (copy && m < N_VM) __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                if (copy && (m * PER_PART) / N_MFMA != ((m + 1) * PER_PART) / N_MFMA)
+                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
         }
     };
 
+    // prologue: tiles 0 .. S-2 are copied in full; part 0 of tile S-1 follows after
+    // the first barrier (its other parts are issued inside tile 0, like every later copy)
     load_tile(0, IC<0>{});
-    wait_copies_and_sync();
-    if (KT > 1) load_tile(1, IC<1>{});
+    if constexpr (S > 2) { if (KT > 1) load_tile(1, IC<1>{}); }
+    if constexpr (S > 3) { if (KT > 2) load_tile(2, IC<2>{}); }
+    {
+        // tile 0 has landed once at most (tiles issued after it) x N_COPY are in flight
+        const int later = (KT - 1 < S - 2) ? KT - 1 : S - 2;
+        if (later == 2) wait_copies_and_sync(IC<2 * N_COPY>{});
+        else if (later == 1) wait_copies_and_sync(IC<N_COPY>{});
+        else wait_copies_and_sync(IC<0>{});
+    }
+    if (KT > S - 1) load_part(S - 1, IC<S - 1>{}, 0);
     read_frags(IC<0>{}, 0, frag[0]);
+
     int kt = 0;
-    // steady state: both following tiles exist, no conditionals in the loop body
-    for (; kt + 3 < KT; kt += 2) {
-        tile_body(kt, IC<0>{}, IC<1>{}, true, true);
-        tile_body(kt + 1, IC<1>{}, IC<0>{}, true, true);
+    // steady state: S tiles per trip, every tile up to kt+2S-1 exists, no conditionals
+    for (; kt + 2 * S - 1 < KT; kt += S) {
+        tile_body(kt, IC<0>{}, IC<1>{}, true, true, true);
+        tile_body(kt + 1, IC<1>{}, IC<1>{}, true, true, true);
+        if constexpr (S > 2) tile_body(kt + 2, IC<2>{}, IC<1>{}, true, true, true);
+        if constexpr (S > 3) tile_body(kt + 3, IC<3>{}, IC<1>{}, true, true, true);
     }
-    // tail: the last one to three tiles
-    tile_body(kt, IC<0>{}, IC<1>{}, kt + 1 < KT, kt + 2 < KT);
-    if (kt + 1 < KT) {
-        tile_body(kt + 1, IC<1>{}, IC<0>{}, kt + 2 < KT, false);
-        if (kt + 2 < KT) tile_body(kt + 2, IC<0>{}, IC<1>{}, false, false);
-    }
+    // tail: the remaining (at most 2S-1) tiles, with run-time existence checks and
+    // a wait for all copies at each barrier
+    auto tail_tile = [&](int t, auto st) {
+        if (t < KT) tile_body(t, st, IC<0>{}, t + 1 < KT, t + S < KT, t - 1 + S < KT);
+    };
+    tail_tile(kt, IC<0>{});
+    tail_tile(kt + 1, IC<1 % S>{});
+    tail_tile(kt + 2, IC<2 % S>{});
+    if constexpr (S > 2) { tail_tile(kt + 3, IC<3 % S>{}); tail_tile(kt + 4, IC<4 % S>{}); }
+    if constexpr (S > 3) { tail_tile(kt + 5, IC<5 % S>{}); tail_tile(kt + 6, IC<6 % S>{}); }
 
     // ---- epilogue
     const int m_wave = tm * BM + wm * Cfg::WM;
@@ -385,9 +457,12 @@ __global__ __launch_bounds__(Cfg::NT) void gemm_mfma_kernel(const GemmArgs p, co
     }
 }
 
-// Shipping configurations.
-using CfgBF16 = MfmaCfg<true, 256, 256, 64, 2, 2>;
-using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2>;
+// Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, copy parts, stages, waves/SIMD>.
+// bf16: 256x256x64 tile, eight waves of 64x128 (two per SIMD, so one wave's operand
+// fetches and barrier waits overlap the other's MFMAs), 128 KiB of LDS.
+// fp32: 128x128x32 tile, four waves of 64x64, 64 KiB of LDS, two workgroups per CU.
+using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 2, 2, 2>;
+using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 1, 2, 1>;
 
 TileShape mfma_tile_shape(int dtype)
 {
