@@ -30,6 +30,10 @@ import numpy as np  # noqa: E402
 # MI355X published peaks
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 PEAK_HBM_GBS = 8000.0
+# L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
+# (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
+# profiles/.  Valid only for the kernel configuration named here; None otherwise.
+TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,2,2,2>", 1.611e9 + 0.135e9)}
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
@@ -114,7 +118,6 @@ def cpu_baseline(w, host, gen, budget_s=15.0):
     oracle.gemm_fused(A, B, bias, w.act, rows=probe_rows, want_rowsum=w.rowsum)
     t_probe = time.perf_counter() - t0
     n_rows = int(min(w.M, max(16, budget_s / max(t_probe, 1e-6) * probe_rows.size)))
-    n_rows = min(n_rows, 4096)
     rows = np.sort(rng.choice(w.M, size=n_rows, replace=False)).astype(np.int64)
     t0 = time.perf_counter()
     oracle.gemm_fused(A, B, bias, w.act, rows=rows, want_rowsum=w.rowsum)
@@ -139,6 +142,9 @@ def main():
     ap.add_argument("--others", action="store_true",
                     help="also time the other four workloads (reported under 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="launch plain 1 GiB device-to-device copies and exit (run under rocprofv3 --pmc "
+                         "FETCH_SIZE / WRITE_SIZE to get the counters' scale factor)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (nothing here uses a second GPU)")
@@ -147,6 +153,16 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
     torch.cuda.set_device(0)
+    if args.copy_calibration:
+        n = 1 << 28                                   # 2^28 fp32 = 1 GiB read + 1 GiB written per copy
+        src = torch.ones(n, dtype=torch.float32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(4):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_calibration": {"bytes_read_per_copy": 4 * n, "bytes_written_per_copy": 4 * n,
+                                               "copies": 4}}))
+        return
     from paper_2511_06345_amd import binding as pgk
     from paper_2511_06345_amd import inputs as gen
     pgk.load_library()   # no fallback: fails here if libpgk.so is not built
@@ -167,7 +183,8 @@ def main():
         "unit": "TFLOP/s",
         "frac": achieved / peak,
         "launch_ms_avg": head["call_ms_avg"],
-        "traffic": None,
+        "traffic": TRAFFIC_BYTES[name][1] if name in TRAFFIC_BYTES else None,
+        "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
         "hbm_frac_algorithmic": head["algorithmic_gbs"] / PEAK_HBM_GBS,
     }
 
