@@ -34,7 +34,7 @@ namespace pgk {
 template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int COPY_PARTS_, int STAGES_ = 2,
           int WAVES_PER_SIMD_ = 1>
 struct MfmaCfg {
-    // depth of the LDS ring of K tiles (2..4): STAGES - 1 tiles are in flight or landed
+    // depth of the LDS ring of K tiles (2..5): STAGES - 1 tiles are in flight or landed
     // ahead of the one being multiplied
     static constexpr int STAGES = STAGES_;
     // waves the register allocation must leave room for on one SIMD
@@ -59,7 +59,7 @@ struct MfmaCfg {
     static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
     static constexpr int A_RPC = 1024 / RA, B_RPC = 1024 / RB;  // rows per 1 KiB
     static constexpr int LDS_BYTES = STAGES * (A_BYTES + B_BYTES);
-    static_assert(STAGES >= 2 && STAGES <= 4 && LDS_BYTES <= 160 * 1024, "LDS ring size");
+    static_assert(STAGES >= 2 && STAGES <= 5 && LDS_BYTES <= 160 * 1024, "LDS ring size");
     static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
     static_assert(RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile / wave split");
@@ -139,10 +139,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a1[Cfg::A_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a2[S > 2 ? Cfg::A_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a3[S > 3 ? Cfg::A_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a4[S > 4 ? Cfg::A_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b0[Cfg::B_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b1[Cfg::B_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b2[S > 2 ? Cfg::B_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b3[S > 3 ? Cfg::B_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_b4[S > 4 ? Cfg::B_BYTES : 16];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -188,12 +190,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     auto lds_a = [&](auto st) -> unsigned char* {
         constexpr int v = decltype(st)::value;
         if constexpr (v == 0) return lds_a0; else if constexpr (v == 1) return lds_a1;
-        else if constexpr (v == 2) return lds_a2; else return lds_a3;
+        else if constexpr (v == 2) return lds_a2; else if constexpr (v == 3) return lds_a3; else return lds_a4;
     };
     auto lds_b = [&](auto st) -> unsigned char* {
         constexpr int v = decltype(st)::value;
         if constexpr (v == 0) return lds_b0; else if constexpr (v == 1) return lds_b1;
-        else if constexpr (v == 2) return lds_b2; else return lds_b3;
+        else if constexpr (v == 2) return lds_b2; else if constexpr (v == 3) return lds_b3; else return lds_b4;
     };
 
     // global -> LDS copy of K tile kt into stage st: instructions of part `part`
@@ -383,10 +385,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     load_tile(0, IC<0>{});
     if constexpr (S > 2) { if (KT > 1) load_tile(1, IC<1>{}); }
     if constexpr (S > 3) { if (KT > 2) load_tile(2, IC<2>{}); }
+    if constexpr (S > 4) { if (KT > 3) load_tile(3, IC<3>{}); }
     {
         // tile 0 has landed once at most (tiles issued after it) x N_COPY are in flight
         const int later = (KT - 1 < S - 2) ? KT - 1 : S - 2;
-        if (later == 2) wait_copies_and_sync(IC<2 * N_COPY>{});
+        if (later == 3) wait_copies_and_sync(IC<3 * N_COPY>{});
+        else if (later == 2) wait_copies_and_sync(IC<2 * N_COPY>{});
         else if (later == 1) wait_copies_and_sync(IC<N_COPY>{});
         else wait_copies_and_sync(IC<0>{});
     }
@@ -400,6 +404,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         tile_body(kt + 1, IC<1>{}, IC<1>{}, true, true, true);
         if constexpr (S > 2) tile_body(kt + 2, IC<2>{}, IC<1>{}, true, true, true);
         if constexpr (S > 3) tile_body(kt + 3, IC<3>{}, IC<1>{}, true, true, true);
+        if constexpr (S > 4) tile_body(kt + 4, IC<4>{}, IC<1>{}, true, true, true);
     }
     // tail: the remaining (at most 2S-1) tiles, with run-time existence checks and
     // a wait for all copies at each barrier
@@ -411,6 +416,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     tail_tile(kt + 2, IC<2 % S>{});
     if constexpr (S > 2) { tail_tile(kt + 3, IC<3 % S>{}); tail_tile(kt + 4, IC<4 % S>{}); }
     if constexpr (S > 3) { tail_tile(kt + 5, IC<5 % S>{}); tail_tile(kt + 6, IC<6 % S>{}); }
+    if constexpr (S > 4) { tail_tile(kt + 7, IC<7 % S>{}); tail_tile(kt + 8, IC<8 % S>{}); }
 
     // ---- epilogue
     const int m_wave = tm * BM + wm * Cfg::WM;
