@@ -31,20 +31,16 @@
 
 namespace pgk {
 
-template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int COPY_PARTS_, int STAGES_ = 2,
-          int WAVES_PER_SIMD_ = 1>
+template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
 struct MfmaCfg {
-    // depth of the LDS ring of K tiles (2..5): STAGES - 1 tiles are in flight or landed
-    // ahead of the one being multiplied
-    static constexpr int STAGES = STAGES_;
-    // waves the register allocation must leave room for on one SIMD
-    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
-    // The global -> LDS copy of one K tile is issued in COPY_PARTS_ equal parts, one
-    // part per operand-fetch step, so that the texture-address path (16 cycles per
-    // 1 KiB wave instruction) is never asked for more than it can take in a step.
-    static constexpr int COPY_PARTS = COPY_PARTS_;
     static constexpr bool BF16 = BF16_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
+    // LDS ring depth of the A tiles (2 or 3); the B tiles always have 2 stages.  With 3,
+    // the copy of an A tile is issued a whole K tile earlier than it is needed, so only
+    // the B half of the traffic has to land within one tile's worth of MFMAs.
+    static constexpr int A_STAGES = A_STAGES_;
+    // waves the register allocation must leave room for on one SIMD
+    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
     static constexpr int ES = BF16_ ? 2 : 4;       // element bytes
     static constexpr int NW = WGM * WGN;           // waves per workgroup
     static constexpr int NT = NW * 64;             // threads per workgroup
@@ -54,19 +50,19 @@ struct MfmaCfg {
     static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
     static constexpr int RB = BN * ES;             // LDS row bytes of the B tile
     static constexpr int A_BYTES = BM * RA, B_BYTES = BK * RB;
-    static constexpr int A_CPW = A_BYTES / 1024 / NW;  // 1 KiB chunks per wave
+    static constexpr int A_CPW = A_BYTES / 1024 / NW;  // 1 KiB copy instructions per wave
     static constexpr int B_CPW = B_BYTES / 1024 / NW;
     static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
     static constexpr int A_RPC = 1024 / RA, B_RPC = 1024 / RB;  // rows per 1 KiB
-    static constexpr int LDS_BYTES = STAGES * (A_BYTES + B_BYTES);
-    static_assert(STAGES >= 2 && STAGES <= 5 && LDS_BYTES <= 160 * 1024, "LDS ring size");
+    static constexpr int LDS_BYTES = A_STAGES * A_BYTES + 2 * B_BYTES;
+    static_assert(A_STAGES == 2 || A_STAGES == 3, "A ring depth");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
     static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
     static_assert(RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile / wave split");
     static_assert(BM <= NT, "row-sum combine uses one thread per tile row");
 };
 
-// Swizzles (in units of 16-byte chunks) applied to the chunk index of a row.
 // A tile: rows of CPR chunks; 16 consecutive rows read the same logical chunk
 // at once, so the 16 chunk slots of a 256-byte bank period must all differ.
 template <int CPR>
@@ -79,43 +75,89 @@ __device__ __forceinline__ int swz_b(int krow)
     return BF16 ? 4 * (krow & 3) : 8 * ((krow >> 2) & 1);
 }
 
-template <int ACT, bool OUT_BF16, int TM, int TN>
-__device__ __forceinline__ void epilogue_fused(f32x16 (&acc)[TM][TN], const GemmArgs& p,
-                                               size_t c_base, int m_wave, int n_wave, int lane,
-                                               float* rs_lds)
+// Epilogue, part 1: bias + activation on the accumulators, row-sum contribution, and
+// the output tile written to LDS in the output element type.  A lane's accumulators
+// are rows of C in runs of 4 consecutive columns (8 bytes as bf16, 16 bytes as fp32);
+// such a run is one "unit".  The tile is spread over the four operand buffers of
+// the main loop (each holds BM/4 rows of BN elements); inside a row the unit index is
+// XORed with twice the row index, so that the 32 rows a wave writes at once fall in
+// different banks, and so that the pair of units forming a 16-byte chunk stays
+// adjacent for part 2.
+template <int ACT, bool OUT_BF16, typename Cfg>
+__device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
+                                                int n_tile0, int wm, int wn, int lane,
+                                                unsigned char* const (&obj)[4], float* rs_lds)
 {
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int UB = OUT_BF16 ? 8 : 16;                 // bytes per unit
+    constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
+    constexpr int UNITS = ROW_BYTES / UB;                 // units per row
+    constexpr int ROWS_PER_OBJ = Cfg::BM / 4;
     const int half = lane >> 5;
     const int row_in = lane & 31;
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         float rs = 0.0f;
-        const size_t row_off = c_base + (size_t)(m_wave + 32 * i + row_in) * (size_t)p.N;
+        const int row = wm * Cfg::WM + 32 * i + row_in;   // row inside the tile
+        const int o = (wm * Cfg::WM + 32 * i) / ROWS_PER_OBJ;
+        unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
+                              (row % ROWS_PER_OBJ) * ROW_BYTES;
+        const int key = (2 * row) % UNITS;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
-                const int n = n_wave + 32 * j + 8 * g + 4 * half;
+                const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
                 f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (p.bias) bv = *(const f32x4*)(p.bias + n);
+                if (bias) bv = *(const f32x4*)(bias + n_tile0 + col);
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
                     rs += y[e];
                 }
+                unsigned char* dst = base + (((col >> 2) ^ key) * UB);
                 if constexpr (OUT_BF16) {
                     u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-                    *(u32x2*)((unsigned short*)p.C + row_off + n) = pk;
+                    *(u32x2*)dst = pk;
                 } else {
-                    f32x4 o = {y[0], y[1], y[2], y[3]};
-                    *(f32x4*)((float*)p.C + row_off + n) = o;
+                    f32x4 v = {y[0], y[1], y[2], y[3]};
+                    *(f32x4*)dst = v;
                 }
             }
         }
         if (rs_lds) {
             rs += __shfl_xor(rs, 32);
-            if (half == 0) rs_lds[32 * i + row_in] = rs;
+            if (half == 0) rs_lds[wn * Cfg::BM + row] = rs;
         }
+    }
+}
+
+// Epilogue, part 2: the staged tile goes to global memory as whole rows: a wave
+// instruction stores 64 x 16 bytes = complete 128-byte lines of consecutive rows.
+template <bool OUT_BF16, typename Cfg>
+__device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t ld_bytes, int tid,
+                                               unsigned char* const (&obj)[4])
+{
+    constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
+    constexpr int CPR = ROW_BYTES / 16;                   // 16-byte chunks per row
+    constexpr int UB = OUT_BF16 ? 8 : 16;
+    constexpr int UNITS = ROW_BYTES / UB;
+    constexpr int ROWS_PER_OBJ = Cfg::BM / 4;
+    constexpr int ROWS_PER_IT = Cfg::NT / CPR;
+    constexpr int ITERS = Cfg::BM / ROWS_PER_IT;
+    static_assert(ROWS_PER_OBJ % ROWS_PER_IT == 0, "an iteration stays inside one buffer");
+    const int c = tid % CPR;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int row = it * ROWS_PER_IT + tid / CPR;
+        const int o = (it * ROWS_PER_IT) / ROWS_PER_OBJ;  // compile-time after unrolling
+        const unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
+                                    (row % ROWS_PER_OBJ) * ROW_BYTES;
+        const int key = (2 * row) % UNITS;
+        const int unit = OUT_BF16 ? ((2 * c) ^ key) : (c ^ key);
+        u32x4 v = *(const u32x4*)(base + unit * UB);
+        *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v;
     }
 }
 
@@ -133,18 +175,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     // Separate LDS objects per stage and operand (not one array indexed by stage): the
     // compiler can then tell that a direct-to-LDS copy into one stage does not alias
-    // the operand reads of another stage, and does not wait for it.
-    constexpr int S = Cfg::STAGES;
+    // the operand reads of another stage, and does not make those reads wait for it.
+    constexpr int SA = Cfg::A_STAGES;
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a0[Cfg::A_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_a1[Cfg::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a2[S > 2 ? Cfg::A_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a3[S > 3 ? Cfg::A_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a4[S > 4 ? Cfg::A_BYTES : 16];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a2[SA > 2 ? Cfg::A_BYTES : 16];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b0[Cfg::B_BYTES];
     __shared__ __attribute__((aligned(1024))) unsigned char lds_b1[Cfg::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_b2[S > 2 ? Cfg::B_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_b3[S > 3 ? Cfg::B_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_b4[S > 4 ? Cfg::B_BYTES : 16];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -187,39 +224,29 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         voff_b[t] = (unsigned int)kr * (unsigned int)p.N * ES + (unsigned int)c * 16u;
     }
 
-    auto lds_a = [&](auto st) -> unsigned char* {
+    auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
         constexpr int v = decltype(st)::value;
-        if constexpr (v == 0) return lds_a0; else if constexpr (v == 1) return lds_a1;
-        else if constexpr (v == 2) return lds_a2; else if constexpr (v == 3) return lds_a3; else return lds_a4;
+        if constexpr (v == 0) return lds_a0; else if constexpr (v == 1) return lds_a1; else return lds_a2;
     };
-    auto lds_b = [&](auto st) -> unsigned char* {
-        constexpr int v = decltype(st)::value;
-        if constexpr (v == 0) return lds_b0; else if constexpr (v == 1) return lds_b1;
-        else if constexpr (v == 2) return lds_b2; else if constexpr (v == 3) return lds_b3; else return lds_b4;
+    auto lds_b = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
+        if constexpr (decltype(st)::value == 0) return lds_b0; else return lds_b1;
     };
 
-    // global -> LDS copy of K tile kt into stage st: instructions of part `part`
-    // (the A and B instructions of a wave are numbered together, A first)
-    constexpr int N_COPY = Cfg::A_CPW + Cfg::B_CPW;
-    constexpr int PER_PART = (N_COPY + Cfg::COPY_PARTS - 1) / Cfg::COPY_PARTS;
-    auto load_part = [&](int kt, auto st, int part) {
+    // global -> LDS copies of K tile kt: the A part into A stage `st`, the B part into
+    // B stage `st` (one contiguous 1 KiB of LDS per wave instruction)
+    auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
         const unsigned char* ga = Ag + (size_t)kt * a_step;
-        const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
+#pragma unroll
+        for (int t = 0; t < Cfg::A_CPW; ++t)
+            __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
+    };
+    auto copy_b = [&](int kt, auto st) __attribute__((always_inline)) {
+        const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
 #pragma unroll
-        for (int t = 0; t < N_COPY; ++t) {
-            if (t / PER_PART != part) continue;
-            if (t < Cfg::A_CPW)
-                __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
-            else
-                __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t - Cfg::A_CPW]),
-                                                 PGK_LDS(lb + (t - Cfg::A_CPW) * 1024), 16, 0, 0);
-        }
-    };
-    auto load_tile = [&](int kt, auto st) {
-#pragma unroll
-        for (int part = 0; part < Cfg::COPY_PARTS; ++part) load_part(kt, st, part);
+        for (int t = 0; t < Cfg::B_CPW; ++t)
+            __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t]), PGK_LDS(lb + t * 1024), 16, 0, 0);
     };
 
     // ---- per-lane LDS read offsets
@@ -257,9 +284,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     struct FragF32 { f32x4 a[TM]; float b[4][TN]; };
     using Frag = typename std::conditional<BF16, FragBF16, FragF32>::type;
 
-    auto read_frags = [&](auto st, int s, Frag& f) {
-        const unsigned char* as = lds_a(st);
-        const unsigned char* bs = lds_b(st);
+    auto read_frags = [&](auto sta, auto stb, int s, Frag& f) __attribute__((always_inline)) {
+        const unsigned char* as = lds_a(sta);
+        const unsigned char* bs = lds_b(stb);
         if constexpr (BF16) {
 #pragma unroll
             for (int j = 0; j < TN; ++j) {
@@ -294,7 +321,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    auto mfma_step = [&](const Frag& f) {
+    auto mfma_step = [&](const Frag& f) __attribute__((always_inline)) {
         if constexpr (BF16) {
 #pragma unroll
             for (int i = 0; i < TM; ++i)
@@ -315,58 +342,75 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // Wait until at most `allowed` of this wave's direct-to-LDS copy instructions are
     // still in flight (they complete in order), and for its own LDS reads; then meet
     // the other waves.  After the barrier the tile that has just landed is visible to
-    // everybody, and everybody has fetched its last operands from the stage that is
+    // everybody, and everybody has fetched its last operands from the stages that are
     // overwritten next.  The sched_barriers keep the compiler from moving MFMAs or
     // fetches across.
-    auto wait_copies_and_sync = [&](auto allowed) {
+    auto wait_copies_and_sync = [&](auto allowed) __attribute__((always_inline)) {
         __builtin_amdgcn_sched_barrier(0);
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(decltype(allowed)::value) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
-    // copy instructions per wave per tile; tiles kt+2 .. kt+S-1 may stay in flight
-    // while tile kt+1 is awaited
-    constexpr int STEADY_IN_FLIGHT = (S - 2) * N_COPY;
-    static_assert(STEADY_IN_FLIGHT <= 63, "vmcnt is a 6-bit counter");
+    // With a three-deep A ring the A copy issued in this tile's first step is for the
+    // tile after next and may still be in flight when the next tile is awaited.
+    constexpr int STEADY_IN_FLIGHT = (SA - 2) * Cfg::A_CPW;
 
     Frag frag[2];
 
-    // One K tile out of stage ST.  Operands of step s+1 are fetched while the MFMAs
-    // of step s run.  Before the MFMAs of the last step, when a next tile exists:
-    // wait for its copy, meet the other waves, fetch its first operands (next
-    // stage), and start the copy of tile kt+S into this stage, which nobody reads
-    // any more.  That copy is issued in parts: part 0 here, parts 1.. during the
-    // first steps of the next tile.  `steady` = every tile up to kt+S exists, so
-    // the in-flight count at the wait is the steady-state one; otherwise the wait
-    // is for all copies.
-    static_assert(Cfg::COPY_PARTS >= 1 && Cfg::COPY_PARTS <= NS, "one copy part per step");
-    auto tile_body = [&](int kt, auto st, auto steady_tag, bool has_next, bool has_copy, bool has_prev_copy) {
-        constexpr int ST = decltype(st)::value;
+    // One K tile: A operands from A stage kt % SA, B operands from B stage kt % 2.
+    //   * Operands of step s+1 are fetched while the MFMAs of step s issue.
+    //   * Before the MFMAs of the last step, when a next tile exists: wait for its
+    //     copies, meet the other waves, fetch its first operands, and issue the first
+    //     half of the copy of tile kt+2 into a stage of this tile, which nobody reads
+    //     any more.  The second half follows in the first step of the next tile.
+    //   * A rows are 128-byte pieces 2*K bytes apart and take longer to arrive than the
+    //     512-byte B rows, so the A half goes first.  Two-deep A ring: A(kt+2) after the
+    //     barrier, B(kt+1) in the first step.  Three-deep A ring: A(kt+2) already in
+    //     this tile's first step (its stage was last read by tile kt-1), B(kt+2) after
+    //     the barrier; the A copy then has a whole extra tile to land.
+    //   * Copy instructions are spaced evenly between the MFMAs of their step: a burst
+    //     would fill the texture-address path (about 16 cycles per 1 KiB instruction
+    //     for the whole CU) and stall the in-order waves.
+    // `steady`: every tile up to kt+SA-1 and kt+2 exists, so the in-flight count at the
+    // wait is the steady-state one; otherwise the wait is for all copies.
+    // has_a / has_b: tile kt+2 exists (its A / B copy is issued here).
+    auto tile_body = [&](int kt, auto sta, auto stb, auto steady_tag, bool has_next, bool has_a, bool has_b) __attribute__((always_inline)) {
+        constexpr int STA = decltype(sta)::value, STB = decltype(stb)::value;
         constexpr bool STEADY = decltype(steady_tag)::value != 0;
-        using StNext = IC<(ST + 1) % S>;
-        using StPrev = IC<(ST + S - 1) % S>;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            bool copy = false;
-            if (s + 1 < NS) {
-                read_frags(st, s + 1, frag[(s + 1) & 1]);
-                if (s + 1 < Cfg::COPY_PARTS && has_prev_copy) {
-                    // rest of the copy of tile kt-1+S, started in the previous tile's last step
-                    load_part(kt - 1 + S, StPrev{}, s + 1);
-                    copy = true;
+            int n_copy = 0;
+            if constexpr (SA == 3) {
+                if (s == 0 && has_a) {
+                    copy_a(kt + 2, IC<(STA + 2) % 3>{});
+                    n_copy = Cfg::A_CPW;
                 }
+            } else {
+                if (s == 0 && has_next) {
+                    copy_b(kt + 1, IC<(STB + 1) % 2>{});
+                    n_copy = Cfg::B_CPW;
+                }
+            }
+            if (s + 1 < NS) {
+                read_frags(sta, stb, s + 1, frag[(s + 1) & 1]);
             } else if (has_next) {
                 if constexpr (STEADY) wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
                 else wait_copies_and_sync(IC<0>{});
-                read_frags(StNext{}, 0, frag[0]);
-                if (has_copy) {
-                    load_part(kt + S, st, 0);
-                    copy = true;
+                read_frags(IC<(STA + 1) % SA>{}, IC<(STB + 1) % 2>{}, 0, frag[0]);
+                if constexpr (SA == 3) {
+                    if (has_b) {
+                        copy_b(kt + 2, stb);
+                        n_copy = Cfg::B_CPW;
+                    }
+                } else {
+                    if (has_a) {
+                        copy_a(kt + 2, sta);
+                        n_copy = Cfg::A_CPW;
+                    }
                 }
             }
             mfma_step(frag[s & 1]);
-            // Issue order inside this step: one LDS operand fetch after each MFMA, and
-            // the copy instructions of this step evenly spaced over its MFMAs, so the
-            // matrix pipe never waits for a burst of fetches.
+            // issue order of this step: one LDS operand fetch after each MFMA, the copy
+            // instructions evenly spaced
             constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
             constexpr int N_DS = BF16 ? TM + 2 * TN : TM + 4 * TN;
             const bool fetch = (s + 1 < NS) || has_next;
@@ -374,101 +418,123 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             for (int m = 0; m < N_MFMA; ++m) {
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
                 if (fetch && m < N_DS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if (copy && (m * PER_PART) / N_MFMA != ((m + 1) * PER_PART) / N_MFMA)
+                if ((m * n_copy) / N_MFMA != ((m + 1) * n_copy) / N_MFMA)
                     __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
             }
         }
     };
 
-    // prologue: tiles 0 .. S-2 are copied in full; part 0 of tile S-1 follows after
-    // the first barrier (its other parts are issued inside tile 0, like every later copy)
-    load_tile(0, IC<0>{});
-    if constexpr (S > 2) { if (KT > 1) load_tile(1, IC<1>{}); }
-    if constexpr (S > 3) { if (KT > 2) load_tile(2, IC<2>{}); }
-    if constexpr (S > 4) { if (KT > 3) load_tile(3, IC<3>{}); }
-    {
-        // tile 0 has landed once at most (tiles issued after it) x N_COPY are in flight
-        const int later = (KT - 1 < S - 2) ? KT - 1 : S - 2;
-        if (later == 3) wait_copies_and_sync(IC<3 * N_COPY>{});
-        else if (later == 2) wait_copies_and_sync(IC<2 * N_COPY>{});
-        else if (later == 1) wait_copies_and_sync(IC<N_COPY>{});
-        else wait_copies_and_sync(IC<0>{});
+    // prologue: tile 0 in full; what a tile body expects to find in flight follows
+    copy_a(0, IC<0>{});
+    copy_b(0, IC<0>{});
+    if constexpr (SA == 3) {
+        if (KT > 1) {
+            copy_a(1, IC<1>{});
+            wait_copies_and_sync(IC<Cfg::A_CPW>{});
+            copy_b(1, IC<1>{});
+        } else {
+            wait_copies_and_sync(IC<0>{});
+        }
+    } else {
+        wait_copies_and_sync(IC<0>{});
+        if (KT > 1) copy_a(1, IC<1>{});
     }
-    if (KT > S - 1) load_part(S - 1, IC<S - 1>{}, 0);
-    read_frags(IC<0>{}, 0, frag[0]);
+    read_frags(IC<0>{}, IC<0>{}, 0, frag[0]);
 
     int kt = 0;
-    // steady state: S tiles per trip, every tile up to kt+2S-1 exists, no conditionals
-    for (; kt + 2 * S - 1 < KT; kt += S) {
-        tile_body(kt, IC<0>{}, IC<1>{}, true, true, true);
-        tile_body(kt + 1, IC<1>{}, IC<1>{}, true, true, true);
-        if constexpr (S > 2) tile_body(kt + 2, IC<2>{}, IC<1>{}, true, true, true);
-        if constexpr (S > 3) tile_body(kt + 3, IC<3>{}, IC<1>{}, true, true, true);
-        if constexpr (S > 4) tile_body(kt + 4, IC<4>{}, IC<1>{}, true, true, true);
+    constexpr int UNROLL = SA == 3 ? 6 : 2;      // lcm of the two ring depths
+    constexpr int LOOKAHEAD = 2;
+    // steady state: every copy issued in the trip exists, no conditionals in the body
+    for (; kt + UNROLL - 1 + LOOKAHEAD < KT; kt += UNROLL) {
+        tile_body(kt, IC<0>{}, IC<0>{}, IC<1>{}, true, true, true);
+        tile_body(kt + 1, IC<1 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
+        if constexpr (SA == 3) {
+            tile_body(kt + 2, IC<2 % SA>{}, IC<0>{}, IC<1>{}, true, true, true);
+            tile_body(kt + 3, IC<3 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
+            tile_body(kt + 4, IC<4 % SA>{}, IC<0>{}, IC<1>{}, true, true, true);
+            tile_body(kt + 5, IC<5 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
+        }
     }
-    // tail: the remaining (at most 2S-1) tiles, with run-time existence checks and
-    // a wait for all copies at each barrier
-    auto tail_tile = [&](int t, auto st) {
-        if (t < KT) tile_body(t, st, IC<0>{}, t + 1 < KT, t + S < KT, t - 1 + S < KT);
+    // tail: the remaining tiles (fewer than UNROLL + LOOKAHEAD), with run-time
+    // existence checks and a wait for all copies at each barrier
+    auto tail_tile = [&](int t, auto sta, auto stb) __attribute__((always_inline)) {
+        if (t < KT) tile_body(t, sta, stb, IC<0>{}, t + 1 < KT, t + 2 < KT, t + 2 < KT);
     };
-    tail_tile(kt, IC<0>{});
-    tail_tile(kt + 1, IC<1 % S>{});
-    tail_tile(kt + 2, IC<2 % S>{});
-    if constexpr (S > 2) { tail_tile(kt + 3, IC<3 % S>{}); tail_tile(kt + 4, IC<4 % S>{}); }
-    if constexpr (S > 3) { tail_tile(kt + 5, IC<5 % S>{}); tail_tile(kt + 6, IC<6 % S>{}); }
-    if constexpr (S > 4) { tail_tile(kt + 7, IC<7 % S>{}); tail_tile(kt + 8, IC<8 % S>{}); }
+    tail_tile(kt, IC<0>{}, IC<0>{});
+    tail_tile(kt + 1, IC<1 % SA>{}, IC<1>{});
+    tail_tile(kt + 2, IC<2 % SA>{}, IC<0>{});
+    if constexpr (SA == 3) {
+        tail_tile(kt + 3, IC<3 % SA>{}, IC<1>{});
+        tail_tile(kt + 4, IC<4 % SA>{}, IC<0>{});
+        tail_tile(kt + 5, IC<5 % SA>{}, IC<1>{});
+        tail_tile(kt + 6, IC<6 % SA>{}, IC<0>{});
+    }
 
-    // ---- epilogue
-    const int m_wave = tm * BM + wm * Cfg::WM;
-    const int n_wave = tn * BN + wn * Cfg::WN;
+    // ---- epilogue: activation into LDS (the operand buffers are free now), then
+    // whole-row stores.  The row-sum exchange has a small buffer of its own.
+    static_assert(Cfg::A_BYTES == Cfg::B_BYTES && Cfg::A_BYTES == (BM / 4) * BN * (BF16 ? 2 : 4) &&
+                  (BM / 4) % 32 == 0,
+                  "four operand buffers hold the output tile, BM/4 rows each");
+    // row-sum exchange buffer: the third A stage when there is one, else a small array
+    __shared__ float rs_own[SA > 2 ? 1 : Cfg::WGN * BM];
+    float* rs_buf = SA > 2 ? (float*)lds_a2 : rs_own;
+    static_assert(Cfg::WGN * BM * 4 <= Cfg::A_BYTES, "row-sum buffer fits an A stage");
+    unsigned char* const obj[4] = {lds_a0, lds_a1, lds_b0, lds_b1};
+    __syncthreads();   // every wave is done with the operand tiles
     if (out_mode == 1) {
-        // split-K pass 1: raw fp32 partial products
-        float* w = p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N;
+        // split-K pass 1: raw fp32 partial products to the workspace slice
+        // (BF16 kernels stage half of the columns at a time: the fp32 tile is twice
+        // the size of the operand buffers)
+        unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
+                                            (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
+        if constexpr (!BF16) {
+            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, 0, wm, wn, lane, obj, nullptr);
+            __syncthreads();
+            epilogue_store<false, Cfg>(w, (size_t)p.N * 4, tid, obj);
+        } else {
 #pragma unroll
-        for (int i = 0; i < TM; ++i) {
-            const size_t row_off = (size_t)(m_wave + 32 * i + l32) * (size_t)p.N;
+            for (int i = 0; i < TM; ++i) {
+                const size_t row_off = (size_t)(wm * Cfg::WM + 32 * i + l32) * (size_t)p.N;
 #pragma unroll
-            for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < TN; ++j)
 #pragma unroll
-                for (int g = 0; g < 4; ++g) {
-                    const int n = n_wave + 32 * j + 8 * g + 4 * half;
-                    f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                    *(f32x4*)(w + row_off + n) = o;
-                }
+                    for (int g = 0; g < 4; ++g) {
+                        const int n = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;
+                        f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
+                        *(f32x4*)((float*)w + row_off + n) = o;
+                    }
+            }
         }
         return;
     }
 
-    float* rs_lds = nullptr;
-    if (p.rs_part) {
-        __syncthreads();  // every wave is done with the operand tiles; reuse LDS
-        rs_lds = (float*)lds_a0 + wn * BM + wm * Cfg::WM;
-    }
-    const size_t c_base = (size_t)b * p.M * p.N;
+    float* rs_lds = p.rs_part ? rs_buf : nullptr;
     switch (p.act) {
-    case ACT_RELU: epilogue_fused<ACT_RELU, BF16, TM, TN>(acc, p, c_base, m_wave, n_wave, lane, rs_lds); break;
-    case ACT_GELU_TANH: epilogue_fused<ACT_GELU_TANH, BF16, TM, TN>(acc, p, c_base, m_wave, n_wave, lane, rs_lds); break;
-    case ACT_SILU: epilogue_fused<ACT_SILU, BF16, TM, TN>(acc, p, c_base, m_wave, n_wave, lane, rs_lds); break;
-    default: epilogue_fused<ACT_NONE, BF16, TM, TN>(acc, p, c_base, m_wave, n_wave, lane, rs_lds); break;
+    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
+    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
+    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
+    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
     }
-    if (p.rs_part) {
-        __syncthreads();
-        if (tid < BM) {
-            const float* r = (const float*)lds_a0 + tid;
-            float s = r[0];
+    __syncthreads();
+    unsigned char* c_tile = (unsigned char*)p.C +
+        ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
+    epilogue_store<BF16, Cfg>(c_tile, (size_t)p.N * ES, tid, obj);
+    if (p.rs_part && tid < BM) {
+        // partial row sums of the waves that share a row, added in wave-column order
+        float s = rs_buf[tid];
 #pragma unroll
-            for (int w = 1; w < Cfg::WGN; ++w) s += r[w * BM];
-            p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
-        }
+        for (int w = 1; w < Cfg::WGN; ++w) s += rs_buf[w * BM + tid];
+        p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
     }
 }
 
-// Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, copy parts, stages, waves/SIMD>.
+// Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>.
 // bf16: 256x256x64 tile, eight waves of 64x128 (two per SIMD, so one wave's operand
-// fetches and barrier waits overlap the other's MFMAs), 128 KiB of LDS.
+// fetches and barrier waits overlap the other's MFMAs), A ring of 3 + B ring of 2 =
+// 160 KiB of LDS.
 // fp32: 128x128x32 tile, four waves of 64x64, 64 KiB of LDS, two workgroups per CU.
-using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 2, 2, 2>;
-using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 1, 2, 1>;
+using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>;
+using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 2, 1>;
 
 TileShape mfma_tile_shape(int dtype)
 {
