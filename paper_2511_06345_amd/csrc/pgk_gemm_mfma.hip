@@ -233,20 +233,24 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     };
 
     // global -> LDS copies of K tile kt: the A part into A stage `st`, the B part into
-    // B stage `st` (one contiguous 1 KiB of LDS per wave instruction)
-    auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
+    // B stage `st`; instruction t of this wave's share (one contiguous 1 KiB of LDS each)
+    auto copy_a_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
         const unsigned char* ga = Ag + (size_t)kt * a_step;
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
-#pragma unroll
-        for (int t = 0; t < Cfg::A_CPW; ++t)
-            __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
     };
-    auto copy_b = [&](int kt, auto st) __attribute__((always_inline)) {
+    auto copy_b_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
         const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
+        __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t]), PGK_LDS(lb + t * 1024), 16, 0, 0);
+    };
+    auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < Cfg::B_CPW; ++t)
-            __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t]), PGK_LDS(lb + t * 1024), 16, 0, 0);
+        for (int t = 0; t < Cfg::A_CPW; ++t) copy_a_op(kt, st, t);
+    };
+    auto copy_b = [&](int kt, auto st) __attribute__((always_inline)) {
+#pragma unroll
+        for (int t = 0; t < Cfg::B_CPW; ++t) copy_b_op(kt, st, t);
     };
 
     // ---- per-lane LDS read offsets
@@ -278,39 +282,40 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         }
     }
 
-    // Operand fragments for one step.  bf16: one step = one MFMA K (16).
-    // fp32: one step = 8 K values = four MFMAs per tile pair.
-    struct FragBF16 { bf16x8 a[TM]; bf16x8 b[TN]; };
+    // Operand fragments for one step.  bf16: one step = one MFMA K (16); the B
+    // operand arrives as two transposing 64-bit reads.  fp32: one step = 8 K values =
+    // four MFMAs per tile pair.
+    struct FragBF16 { bf16x8 a[TM]; s16x4 blo[TN], bhi[TN]; };
     struct FragF32 { f32x4 a[TM]; float b[4][TN]; };
     using Frag = typename std::conditional<BF16, FragBF16, FragF32>::type;
 
-    auto read_frags = [&](auto sta, auto stb, int s, Frag& f) __attribute__((always_inline)) {
+    // LDS fetches of one step, numbered in the order the MFMAs need them (the MFMAs
+    // run over the A fragments in the outer loop): A fragment 0, every B fragment,
+    // then the remaining A fragments.
+    constexpr int N_DS = BF16 ? TM + 2 * TN : TM + 4 * TN;
+    auto fetch_op = [&](auto sta, auto stb, int s, Frag& f, int q) __attribute__((always_inline)) {
         const unsigned char* as = lds_a(sta);
         const unsigned char* bs = lds_b(stb);
-        if constexpr (BF16) {
-#pragma unroll
-            for (int j = 0; j < TN; ++j) {
-                const unsigned char* q = bs + b_off[j] + (16 * s) * RB;
-                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4*)PGK_LDS(q));
-                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                    (__attribute__((address_space(3))) s16x4*)PGK_LDS(q + 4 * RB));
-                s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                f.b[j] = __builtin_bit_cast(bf16x8, both);
-            }
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+        constexpr int NB = BF16 ? 2 * TN : 4 * TN;
+        if (q == 0 || q > NB) {
+            const int i = q == 0 ? 0 : q - NB;
+            if constexpr (BF16)
                 f.a[i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
-        } else {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    f.b[t][j] = *(const __attribute__((address_space(3))) float*)PGK_LDS(bs + b_off[j] + (8 * s + t) * RB);
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
+            else
                 f.a[i] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
+        } else if constexpr (BF16) {
+            const int j = (q - 1) / 2, h = (q - 1) % 2;
+            const unsigned char* src = bs + b_off[j] + (16 * s + 4 * h) * RB;
+            s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)PGK_LDS(src));
+            if (h == 0) f.blo[j] = v; else f.bhi[j] = v;
+        } else {
+            const int t = (q - 1) / TN, j = (q - 1) % TN;
+            f.b[t][j] = *(const __attribute__((address_space(3))) float*)PGK_LDS(bs + b_off[j] + (8 * s + t) * RB);
         }
+    };
+    auto read_frags = [&](auto sta, auto stb, int s, Frag& f) __attribute__((always_inline)) {
+#pragma unroll
+        for (int q = 0; q < N_DS; ++q) fetch_op(sta, stb, s, f, q);
     };
 
     f32x16 acc[TM][TN];
@@ -321,21 +326,16 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
             for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
 
-    auto mfma_step = [&](const Frag& f) __attribute__((always_inline)) {
+    // MFMA number m of a step (A fragments in the outer loop)
+    constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
+    auto mfma_op = [&](const Frag& f, int m) __attribute__((always_inline)) {
         if constexpr (BF16) {
-#pragma unroll
-            for (int i = 0; i < TM; ++i)
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.b[j], f.a[i], acc[i][j], 0, 0, 0);
+            const int i = m / TN, j = m % TN;
+            const s16x8 both = __builtin_shufflevector(f.blo[j], f.bhi[j], 0, 1, 2, 3, 4, 5, 6, 7);
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), f.a[i], acc[i][j], 0, 0, 0);
         } else {
-#pragma unroll
-            for (int t = 0; t < 4; ++t)
-#pragma unroll
-                for (int i = 0; i < TM; ++i)
-#pragma unroll
-                    for (int j = 0; j < TN; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[t][j], f.a[i][t], acc[i][j], 0, 0, 0);
+            const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[t][j], f.a[i][t], acc[i][j], 0, 0, 0);
         }
     };
 
@@ -372,54 +372,55 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     //     for the whole CU) and stall the in-order waves.
     // `steady`: every tile up to kt+SA-1 and kt+2 exists, so the in-flight count at the
     // wait is the steady-state one; otherwise the wait is for all copies.
+    // The instruction order of a step is written out and pinned (a scheduling barrier
+    // after every MFMA slot): MFMA m, then the operand fetches and copy instructions
+    // that belong to slot m, spread evenly over the slots.  The compiler allocates
+    // registers and places the lgkmcnt waits; it does not reorder.
+    // The fetches go into the first three quarters of the slots, so that the last of
+    // them has the remaining MFMAs to come back before the next step needs it.
     // has_a / has_b: tile kt+2 exists (its A / B copy is issued here).
+    constexpr int DS_SLOTS = N_MFMA - N_MFMA / 4;
+    auto ds_first = [](int m) { return m >= DS_SLOTS ? N_DS : (m * N_DS) / DS_SLOTS; };
     auto tile_body = [&](int kt, auto sta, auto stb, auto steady_tag, bool has_next, bool has_a, bool has_b) __attribute__((always_inline)) {
         constexpr int STA = decltype(sta)::value, STB = decltype(stb)::value;
         constexpr bool STEADY = decltype(steady_tag)::value != 0;
+        using NextA = IC<(STA + 1) % SA>;
+        using NextB = IC<(STB + 1) % 2>;
 #pragma unroll
         for (int s = 0; s < NS; ++s) {
-            int n_copy = 0;
-            if constexpr (SA == 3) {
-                if (s == 0 && has_a) {
-                    copy_a(kt + 2, IC<(STA + 2) % 3>{});
-                    n_copy = Cfg::A_CPW;
-                }
-            } else {
-                if (s == 0 && has_next) {
-                    copy_b(kt + 1, IC<(STB + 1) % 2>{});
-                    n_copy = Cfg::B_CPW;
-                }
-            }
-            if (s + 1 < NS) {
-                read_frags(sta, stb, s + 1, frag[(s + 1) & 1]);
-            } else if (has_next) {
+            const bool last = s + 1 == NS;
+            // which copy (if any) is issued during this step
+            const bool early = s == 0 && (SA == 3 ? has_a : has_next);    // A(kt+2) or B(kt+1)
+            const bool late = last && has_next && (SA == 3 ? has_b : has_a);  // B(kt+2) or A(kt+2)
+            const int n_copy = early ? (SA == 3 ? Cfg::A_CPW : Cfg::B_CPW)
+                             : late ? (SA == 3 ? Cfg::B_CPW : Cfg::A_CPW) : 0;
+            const bool fetch = !last || has_next;
+            if (last && has_next) {
                 if constexpr (STEADY) wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
                 else wait_copies_and_sync(IC<0>{});
-                read_frags(IC<(STA + 1) % SA>{}, IC<(STB + 1) % 2>{}, 0, frag[0]);
-                if constexpr (SA == 3) {
-                    if (has_b) {
-                        copy_b(kt + 2, stb);
-                        n_copy = Cfg::B_CPW;
-                    }
-                } else {
-                    if (has_a) {
-                        copy_a(kt + 2, sta);
-                        n_copy = Cfg::A_CPW;
-                    }
-                }
             }
-            mfma_step(frag[s & 1]);
-            // issue order of this step: one LDS operand fetch after each MFMA, the copy
-            // instructions evenly spaced
-            constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
-            constexpr int N_DS = BF16 ? TM + 2 * TN : TM + 4 * TN;
-            const bool fetch = (s + 1 < NS) || has_next;
 #pragma unroll
             for (int m = 0; m < N_MFMA; ++m) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                if (fetch && m < N_DS) __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-                if ((m * n_copy) / N_MFMA != ((m + 1) * n_copy) / N_MFMA)
-                    __builtin_amdgcn_sched_group_barrier(0x020, 1, 0);
+                mfma_op(frag[s & 1], m);
+                if (fetch) {
+#pragma unroll
+                    for (int q = ds_first(m); q < ds_first(m + 1); ++q) {
+                        if (!last) fetch_op(sta, stb, s + 1, frag[(s + 1) & 1], q);
+                        else fetch_op(NextA{}, NextB{}, 0, frag[0], q);
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < (Cfg::A_CPW > Cfg::B_CPW ? Cfg::A_CPW : Cfg::B_CPW); ++t) {
+                    if (t < (m * n_copy) / N_MFMA || t >= ((m + 1) * n_copy) / N_MFMA) continue;
+                    if constexpr (SA == 3) {
+                        if (early) copy_a_op(kt + 2, IC<(STA + 2) % 3>{}, t);
+                        else copy_b_op(kt + 2, stb, t);
+                    } else {
+                        if (early) copy_b_op(kt + 1, NextB{}, t);
+                        else copy_a_op(kt + 2, sta, t);
+                    }
+                }
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
     };
