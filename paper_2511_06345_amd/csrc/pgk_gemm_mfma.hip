@@ -85,7 +85,7 @@ __device__ __forceinline__ int swz_b(int krow)
 // adjacent for part 2.
 template <int ACT, bool OUT_BF16, typename Cfg>
 __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
-                                                int n_tile0, int wm, int wn, int lane,
+                                                int n_tile0, int n_rem, int wm, int wn, int lane,
                                                 unsigned char* const (&obj)[4], float* rs_lds)
 {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -108,13 +108,16 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
+                // columns past the end of a ragged N: no bias read, nothing added to the
+                // row sum (N is a multiple of 4, so a run of 4 is all in or all out)
+                const bool in_n = col < n_rem;
                 f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (bias) bv = *(const f32x4*)(bias + n_tile0 + col);
+                if (bias && in_n) bv = *(const f32x4*)(bias + n_tile0 + col);
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
-                    rs += y[e];
+                    rs += in_n ? y[e] : 0.0f;
                 }
                 unsigned char* dst = base + (((col >> 2) ^ key) * UB);
                 if constexpr (OUT_BF16) {
@@ -137,7 +140,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
 // instruction stores 64 x 16 bytes = complete 128-byte lines of consecutive rows.
 template <bool OUT_BF16, typename Cfg>
 __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t ld_bytes, int tid,
-                                               unsigned char* const (&obj)[4])
+                                               int m_rem, int n_rem, unsigned char* const (&obj)[4])
 {
     constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
     constexpr int CPR = ROW_BYTES / 16;                   // 16-byte chunks per row
@@ -157,7 +160,8 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
         const int key = (2 * row) % UNITS;
         const int unit = OUT_BF16 ? ((2 * c) ^ key) : (c ^ key);
         u32x4 v = *(const u32x4*)(base + unit * UB);
-        *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v;
+        if (row < m_rem && c * (16 / (OUT_BF16 ? 2 : 4)) < n_rem)
+            *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v;
     }
 }
 
@@ -207,6 +211,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
     const size_t b_step = (size_t)BK * p.N * ES;       // bytes per K tile down B
 
+    // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
+    const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
+    const int n_rem = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
+
     // ---- per-lane byte offsets of the global chunks this lane copies
     unsigned int voff_a[Cfg::A_CPW], voff_b[Cfg::B_CPW];
 #pragma unroll
@@ -214,14 +222,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         const int ch = wave * Cfg::A_CPW + t;
         const int r = ch * Cfg::A_RPC + lane / Cfg::A_CPR;
         const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
-        voff_a[t] = (unsigned int)r * (unsigned int)p.K * ES + (unsigned int)c * 16u;
+        // rows past the end of A (last tile row of a ragged M) re-read the last valid row:
+        // they only feed output rows that are never stored
+        const int rg = r < m_rem ? r : m_rem - 1;
+        voff_a[t] = (unsigned int)rg * (unsigned int)p.K * ES + (unsigned int)c * 16u;
     }
 #pragma unroll
     for (int t = 0; t < Cfg::B_CPW; ++t) {
         const int ch = wave * Cfg::B_CPW + t;
         const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
         const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
-        voff_b[t] = (unsigned int)kr * (unsigned int)p.N * ES + (unsigned int)c * 16u;
+        // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
+        constexpr int EPC = 16 / ES;                      // elements per chunk
+        const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
+        voff_b[t] = (unsigned int)kr * (unsigned int)p.N * ES + (unsigned int)cg * 16u;
     }
 
     auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
@@ -489,9 +503,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
                                             (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
         if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, 0, wm, wn, lane, obj, nullptr);
+            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, 0, n_rem, wm, wn, lane, obj, nullptr);
             __syncthreads();
-            epilogue_store<false, Cfg>(w, (size_t)p.N * 4, tid, obj);
+            epilogue_store<false, Cfg>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
         } else {
 #pragma unroll
             for (int i = 0; i < TM; ++i) {
@@ -502,7 +516,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                     for (int g = 0; g < 4; ++g) {
                         const int n = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;
                         f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        *(f32x4*)((float*)w + row_off + n) = o;
+                        if (wm * Cfg::WM + 32 * i + l32 < m_rem && n < n_rem) *(f32x4*)((float*)w + row_off + n) = o;
                     }
             }
         }
@@ -511,16 +525,16 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     float* rs_lds = p.rs_part ? rs_buf : nullptr;
     switch (p.act) {
-    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
-    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
-    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
-    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, p.bias, tn * BN, wm, wn, lane, obj, rs_lds); break;
+    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
     }
     __syncthreads();
     unsigned char* c_tile = (unsigned char*)p.C +
         ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
-    epilogue_store<BF16, Cfg>(c_tile, (size_t)p.N * ES, tid, obj);
-    if (p.rs_part && tid < BM) {
+    epilogue_store<BF16, Cfg>(c_tile, (size_t)p.N * ES, tid, m_rem, n_rem, obj);
+    if (p.rs_part && tid < m_rem) {
         // partial row sums of the waves that share a row, added in wave-column order
         float s = rs_buf[tid];
 #pragma unroll

@@ -65,6 +65,9 @@ def check(got_c, got_rs, ref_c, ref_rs, dtype, what):
 # shapes: tiny and ragged (bounds-checked kernel), exact tile multiples with several
 # K-tile counts (matrix-core kernels), and mixes with a ragged tail in each dimension
 GUARDED_SHAPES = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (64, 64, 16, 1), (2, 300, 5, 1)]
+# K a whole number of K tiles, M and N ragged: matrix-core kernels with edge tiles
+F32_EDGE_SHAPES = [(100, 36, 64, 2), (129, 132, 96, 1), (300, 260, 32, 1), (17, 500, 128, 1), (250, 16, 64, 3)]
+BF16_EDGE_SHAPES = [(100, 40, 64, 2), (257, 264, 128, 1), (300, 520, 64, 1), (17, 1000, 192, 1), (700, 16, 64, 2)]
 F32_TILE_SHAPES = [(128, 128, 32, 1), (128, 128, 64, 1), (256, 128, 96, 1), (128, 384, 160, 2), (384, 256, 224, 1)]
 BF16_TILE_SHAPES = [(256, 256, 64, 1), (256, 256, 128, 1), (256, 512, 192, 1), (512, 256, 320, 2), (256, 256, 448, 1)]
 
@@ -80,7 +83,8 @@ def test_small_and_ragged_shapes(pgk, oracle, dtype, shape, act):
     check(got_c, got_rs, ref_c, ref_rs, dtype, f"guarded {shape} act {act}")
 
 
-@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES), (BF16, BF16_TILE_SHAPES)])
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES),
+                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES)])
 @pytest.mark.parametrize("act", [NONE, RELU, GELU, SILU])
 def test_tile_multiple_shapes(pgk, oracle, dtype, shapes, act):
     for shape in shapes:
@@ -96,7 +100,8 @@ def test_tile_multiple_shapes(pgk, oracle, dtype, shapes, act):
         check(got_c, None, ref_c, None, dtype, f"mfma {shape} act {act} no bias")
 
 
-@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + GUARDED_SHAPES), (BF16, BF16_TILE_SHAPES + GUARDED_SHAPES)])
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES + GUARDED_SHAPES),
+                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES + GUARDED_SHAPES)])
 def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
     """Entries in {-2..2}, identity activation: bit-exact against the oracle, for every
     K-tile count (catches stage / double-buffer hazards and index slips)."""
