@@ -36,7 +36,7 @@ int validate_common(const void* A, const void* B, const void* C, int64_t M, int6
     return PGK_OK;
 }
 
-int kstep_of(int dtype) { return pgk::mfma_tile_shape(dtype).bk; }
+int kstep_of(int dtype) { return pgk::mfma_tile_shape(dtype, false).bk; }
 
 // Split geometry shared by the workspace query and the launch: slice length L
 // and the number of non-empty slices.
@@ -44,7 +44,7 @@ struct SplitPlan { int splits; int k_slice; };
 
 bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
 {
-    const pgk::TileShape t = pgk::mfma_tile_shape(dtype);
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
     // K in whole K tiles; rows of B and C start on 16-byte boundaries.  M and N may be
     // ragged; tiny outputs are left to the bounds-checked kernel, which wastes less.
@@ -61,7 +61,7 @@ SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype,
     const int64_t ksteps = (K + ks - 1) / ks;
     int64_t s = splits;
     if (s == 0) {
-        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype) : pgk::guarded_tile_shape();
+        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype, false) : pgk::guarded_tile_shape();
         const long double tiles = (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
         s = 1;
         while (s < kMaxAutoSplits && s < ksteps && tiles * s < 2.0L * kNumCUs) ++s;
@@ -109,14 +109,20 @@ hipError_t scratch_get(hipStream_t stream, size_t bytes, float** out)
     return hipSuccess;
 }
 
-struct Path { bool mfma; pgk::TileShape tile; };
+struct Path { bool mfma; bool small; pgk::TileShape tile; };
 
+// `units` = batch entries x K splits: workgroups per output tile position.
 Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
-                 int64_t M, int64_t N, int64_t K, int dtype)
+                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units)
 {
     const bool ok = mfma_shape_ok(M, N, K, dtype) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
-    return ok ? Path{true, pgk::mfma_tile_shape(dtype)} : Path{false, pgk::guarded_tile_shape()};
+    if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
+    // the small tile when the large-tile grid would leave a quarter of the CUs idle
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
+    const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
+    const bool small = wgs < 0.75L * kNumCUs;
+    return Path{true, small, pgk::mfma_tile_shape(dtype, small)};
 }
 
 }  // namespace
@@ -130,7 +136,7 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     if (rc != PGK_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype);
+    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -153,7 +159,7 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
             a.rs_part = part;
         }
     }
-    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     if (part) {
         e = pgk::launch_rowsum_combine(part, rowsum, (int)M, (int)batch, (int)tiles_n, st);
@@ -194,7 +200,7 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     const SplitPlan plan = plan_splits(M, N, K, batch, dtype, splits);
-    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype);
+    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -207,7 +213,7 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
 
-    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     e = pgk::launch_splitk_reduce(a.ws, bias, C, rowsum, (int)M, (int)N, (int)batch, plan.splits, act, dtype, st);
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;

@@ -78,8 +78,8 @@ __device__ __forceinline__ int swz_b(int krow)
 // Epilogue, part 1: bias + activation on the accumulators, row-sum contribution, and
 // the output tile written to LDS in the output element type.  A lane's accumulators
 // are rows of C in runs of 4 consecutive columns (8 bytes as bf16, 16 bytes as fp32);
-// such a run is one "unit".  The tile is spread over the four operand buffers of
-// the main loop (each holds BM/4 rows of BN elements); inside a row the unit index is
+// such a run is one "unit".  The tile is spread over (up to) four operand buffers of
+// the main loop, whole rows of BN elements each; inside a row the unit index is
 // XORed with twice the row index, so that the 32 rows a wave writes at once fall in
 // different banks, and so that the pair of units forming a 16-byte chunk stays
 // adjacent for part 2.
@@ -92,7 +92,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     constexpr int UB = OUT_BF16 ? 8 : 16;                 // bytes per unit
     constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
     constexpr int UNITS = ROW_BYTES / UB;                 // units per row
-    constexpr int ROWS_PER_OBJ = Cfg::BM / 4;
+    constexpr int ROWS_PER_OBJ = Cfg::A_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     const int half = lane >> 5;
     const int row_in = lane & 31;
 #pragma unroll
@@ -146,7 +146,7 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
     constexpr int CPR = ROW_BYTES / 16;                   // 16-byte chunks per row
     constexpr int UB = OUT_BF16 ? 8 : 16;
     constexpr int UNITS = ROW_BYTES / UB;
-    constexpr int ROWS_PER_OBJ = Cfg::BM / 4;
+    constexpr int ROWS_PER_OBJ = Cfg::A_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     constexpr int ROWS_PER_IT = Cfg::NT / CPR;
     constexpr int ITERS = Cfg::BM / ROWS_PER_IT;
     static_assert(ROWS_PER_OBJ % ROWS_PER_IT == 0, "an iteration stays inside one buffer");
@@ -163,6 +163,16 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
         if (row < m_rem && c * (16 / (OUT_BF16 ? 2 : 4)) < n_rem)
             *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v;
     }
+}
+
+// Returns its argument through an empty asm, so that the 32 -> 64 bit extension of a
+// per-lane byte offset stays next to the copy instruction that uses it: the
+// instruction then takes "uniform 64-bit base + 32-bit lane offset" operands instead
+// of a 64-bit address per lane held in two registers across the main loop.
+__device__ __forceinline__ unsigned int keep32(unsigned int v)
+{
+    asm volatile("" : "+v"(v));
+    return v;
 }
 
 template <int V>
@@ -251,12 +261,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     auto copy_a_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
         const unsigned char* ga = Ag + (size_t)kt * a_step;
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
-        __builtin_amdgcn_global_load_lds(PGK_GLB(ga + voff_a[t]), PGK_LDS(la + t * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(PGK_GLB(ga + keep32(voff_a[t])), PGK_LDS(la + t * 1024), 16, 0, 0);
     };
     auto copy_b_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
         const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
-        __builtin_amdgcn_global_load_lds(PGK_GLB(gb + voff_b[t]), PGK_LDS(lb + t * 1024), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds(PGK_GLB(gb + keep32(voff_b[t])), PGK_LDS(lb + t * 1024), 16, 0, 0);
     };
     auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
@@ -487,9 +497,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     // ---- epilogue: activation into LDS (the operand buffers are free now), then
     // whole-row stores.  The row-sum exchange has a small buffer of its own.
-    static_assert(Cfg::A_BYTES == Cfg::B_BYTES && Cfg::A_BYTES == (BM / 4) * BN * (BF16 ? 2 : 4) &&
-                  (BM / 4) % 32 == 0,
-                  "four operand buffers hold the output tile, BM/4 rows each");
+    static_assert(Cfg::A_BYTES == Cfg::B_BYTES && 4 * Cfg::A_BYTES >= BM * BN * (BF16 ? 2 : 4) &&
+                  (Cfg::A_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
+                  "the first four operand buffers hold the output tile, whole 32-row blocks each");
     // row-sum exchange buffer: the third A stage when there is one, else a small array
     __shared__ float rs_own[SA > 2 ? 1 : Cfg::WGN * BM];
     float* rs_buf = SA > 2 ? (float*)lds_a2 : rs_own;
@@ -544,17 +554,26 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 }
 
 // Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>.
-// bf16: 256x256x64 tile, eight waves of 64x128 (two per SIMD, so one wave's operand
-// fetches and barrier waits overlap the other's MFMAs), A ring of 3 + B ring of 2 =
-// 160 KiB of LDS.
-// fp32: 128x128x32 tile, four waves of 64x64, 64 KiB of LDS, two workgroups per CU.
+// Large tiles for problems that fill the chip with them:
+//   bf16 256x256x64, eight waves of 64x128 (two per SIMD, so one wave's operand fetches
+//        and barrier waits overlap the other's MFMAs), A ring 3 + B ring 2 = 160 KiB LDS;
+//   fp32 128x128x32, four waves of 64x64, 64 KiB of LDS, two workgroups per CU.
+// Small tiles (a quarter of the area) for problems whose large-tile grid would leave
+// most of the 256 CUs idle:
+//   bf16 128x128x64, four waves of 64x64, 80 KiB of LDS, two workgroups per CU;
+//   fp32 64x64x32, four waves of 32x32, 32 KiB of LDS.
 using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>;
 using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 2, 1>;
+using CfgBF16Small = MfmaCfg<true, 128, 128, 64, 2, 2, 3, 2>;
+using CfgF32Small = MfmaCfg<false, 64, 64, 32, 2, 2, 2, 2>;
 
-TileShape mfma_tile_shape(int dtype)
+TileShape mfma_tile_shape(int dtype, bool small)
 {
-    if (dtype == DT_BF16) return {CfgBF16::BM, CfgBF16::BN, CfgBF16::BK};
-    return {CfgF32::BM, CfgF32::BN, CfgF32::BK};
+    if (dtype == DT_BF16)
+        return small ? TileShape{CfgBF16Small::BM, CfgBF16Small::BN, CfgBF16Small::BK}
+                     : TileShape{CfgBF16::BM, CfgBF16::BN, CfgBF16::BK};
+    return small ? TileShape{CfgF32Small::BM, CfgF32Small::BN, CfgF32Small::BK}
+                 : TileShape{CfgF32::BM, CfgF32::BN, CfgF32::BK};
 }
 
 template <typename Cfg>
@@ -566,10 +585,10 @@ static hipError_t launch_cfg(const GemmArgs& a, int out_mode, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int out_mode, hipStream_t s)
+hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s)
 {
-    if (dtype == DT_BF16) return launch_cfg<CfgBF16>(a, out_mode, s);
-    return launch_cfg<CfgF32>(a, out_mode, s);
+    if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16Small>(a, out_mode, s) : launch_cfg<CfgBF16>(a, out_mode, s);
+    return small ? launch_cfg<CfgF32Small>(a, out_mode, s) : launch_cfg<CfgF32>(a, out_mode, s);
 }
 
 }  // namespace pgk

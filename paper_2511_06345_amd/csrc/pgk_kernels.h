@@ -31,16 +31,17 @@ struct GemmArgs {
     int group_m;        // tile rows per scheduling group
 };
 
-// Tile geometry of the matrix-core kernels (one per element type).
+// Tile geometry of the matrix-core kernels: a large and a small tile per element
+// type (same K tile), the small one for grids that would not fill the chip.
 struct TileShape { int bm, bn, bk; };
-TileShape mfma_tile_shape(int dtype);
+TileShape mfma_tile_shape(int dtype, bool small);
 TileShape guarded_tile_shape();
 
 // Matrix-core kernels: require K % bk == 0, k_slice % bk == 0, N a multiple of the
 // 16-byte chunk (8 bf16 / 4 fp32 elements) and 16-byte aligned A, B, C, bias, ws.
 // M and N need not be tile multiples: edge tiles re-read valid rows / columns and
 // store only what exists.
-hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.
 hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);

@@ -122,6 +122,33 @@ def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
             assert np.array_equal(got_rs, ref_rs), f"splitk rowsum {shape} splits {splits}"
 
 
+# The library picks its small tile (64x64 fp32, 128x128 bf16) when the large-tile grid
+# would have fewer than 192 workgroups, so the shapes above run on the small tiles.  These
+# have enough batch entries to get the large tiles (128x128 fp32, 256x256 bf16), with
+# one to seven K tiles and ragged edges.
+LARGE_TILE_SHAPES = {F32: [(128, 128, 32, 192), (256, 128, 96, 100), (300, 260, 64, 40), (129, 140, 224, 70)],
+                     BF16: [(256, 256, 64, 192), (512, 256, 192, 100), (300, 520, 128, 40), (257, 264, 448, 50)]}
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_large_tiles_with_many_batch_entries(pgk, oracle, dtype):
+    for shape in LARGE_TILE_SHAPES[dtype]:
+        M, N, K, batch = shape
+        A, B = gen.make_int_inputs(dtype, M, N, K, batch, seed=3 * M + K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, None, NONE)
+        got_c, got_rs = run_fused(pgk, A, B, None, NONE, dtype)
+        if dtype == BF16:
+            ref_c = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref_c.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(got_c, ref_c), f"large tile {shape}"
+        assert np.array_equal(got_rs, ref_rs), f"large tile rowsum {shape}"
+        got_c, got_rs = run_splitk(pgk, A, B, None, NONE, dtype, splits=2)
+        assert np.array_equal(got_c, ref_c) and np.array_equal(got_rs, ref_rs), f"large tile split-K {shape}"
+        A, B, bias = random_case(dtype, M, N, K, batch, seed=M + K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, bias, GELU)
+        got_c, got_rs = run_fused(pgk, A, B, bias, GELU, dtype)
+        check(got_c, got_rs, ref_c, ref_rs, dtype, f"large tile {shape} GELU")
+
+
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("act", [NONE, SILU])
 def test_splitk_matches_oracle_and_is_deterministic(pgk, oracle, dtype, act):
