@@ -30,7 +30,7 @@ def _compile(src: str) -> str:
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *HIPCC_FLAGS, "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
-    if res.returncode != 0:
+    if res.returncode != 0 or "error:" in res.stderr:
         raise RuntimeError(f"hipcc failed for {src}:\n{res.stderr}")
     return obj
 
@@ -44,6 +44,9 @@ def build_library(verbose: bool = False) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
+    # every symbol must resolve: load the library the way the binding does
+    import ctypes
+    ctypes.CDLL(LIB, mode=getattr(os, "RTLD_NOW", 2))
     if verbose:
         print(f"built {LIB}")
     return LIB

@@ -165,22 +165,13 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
     }
 }
 
-// Returns its argument through an empty asm, so that the 32 -> 64 bit extension of a
-// per-lane byte offset stays next to the copy instruction that uses it: the
-// instruction then takes "uniform 64-bit base + 32-bit lane offset" operands instead
-// of a 64-bit address per lane held in two registers across the main loop.
-__device__ __forceinline__ unsigned int keep32(unsigned int v)
-{
-    asm volatile("" : "+v"(v));
-    return v;
-}
-
 template <int V>
 struct IC { static constexpr int value = V; };
 
 template <typename Cfg>
 __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel(const GemmArgs p, const int out_mode)
 {
+#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub (and has no buffer-resource type)
     constexpr bool BF16 = Cfg::BF16;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ES = Cfg::ES;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, RA = Cfg::RA, RB = Cfg::RB;
@@ -257,16 +248,22 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     };
 
     // global -> LDS copies of K tile kt: the A part into A stage `st`, the B part into
-    // B stage `st`; instruction t of this wave's share (one contiguous 1 KiB of LDS each)
+    // B stage `st`; instruction t of this wave's share (one contiguous 1 KiB of LDS each).
+    // Buffer addressing: a scalar resource whose base is this K tile of the workgroup's
+    // A (or B) panel, plus the lane's constant 32-bit byte offset -- no vector ALU work
+    // per copy.  The resource covers 4 GiB from its base; lane offsets stay below that
+    // (checked on the host).
     auto copy_a_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
-        const unsigned char* ga = Ag + (size_t)kt * a_step;
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
-        __builtin_amdgcn_global_load_lds(PGK_GLB(ga + keep32(voff_a[t])), PGK_LDS(la + t * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            __builtin_amdgcn_make_buffer_rsrc((void*)(Ag + (size_t)kt * a_step), 0, (int)0xffffffffu, 0x00020000),
+            PGK_LDS(la + t * 1024), 16, voff_a[t], 0, 0, 0);
     };
     auto copy_b_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
-        const unsigned char* gb = Bg + (size_t)kt * b_step;
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
-        __builtin_amdgcn_global_load_lds(PGK_GLB(gb + keep32(voff_b[t])), PGK_LDS(lb + t * 1024), 16, 0, 0);
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(
+            __builtin_amdgcn_make_buffer_rsrc((void*)(Bg + (size_t)kt * b_step), 0, (int)0xffffffffu, 0x00020000),
+            PGK_LDS(lb + t * 1024), 16, voff_b[t], 0, 0, 0);
     };
     auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
@@ -551,6 +548,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         for (int w = 1; w < Cfg::WGN; ++w) s += rs_buf[w * BM + tid];
         p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
     }
+#endif
 }
 
 // Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>.
