@@ -33,7 +33,7 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
 # profiles/.  Valid only for the kernel configuration named here; None otherwise.
-TRAFFIC_BYTES = {}   # re-measured at the end of a round for the shipping kernel (see profiles/)
+TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 786888 * 1024 * 2 + 131072 * 1024)}
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
