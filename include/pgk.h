@@ -68,10 +68,9 @@ typedef enum {
  * with the activation and reduction operators fused into its epilogue).
  *
  * M, N, K, batch > 0.  Any shape is accepted.  The matrix-core kernels take every
- * problem with K a multiple of the K tile (32 for float32, 64 for bfloat16), N a
- * multiple of 16 bytes of elements (4 / 8), M and N at least 16 and 16-byte aligned
- * pointers; M and N need not be tile multiples.  All other shapes go to a
- * bounds-checked kernel.  M, N, K must each be below 2^31 and
+ * problem with K and N multiples of 16 bytes of elements (4 for float32, 8 for
+ * bfloat16), M and N at least 16 and 16-byte aligned pointers; M, N and K need not be
+ * tile multiples.  All other shapes go to a bounds-checked kernel.  M, N, K must each be below 2^31 and
  * batch*M*N, batch*M*K, batch*K*N below 2^62 (else PGK_ERR_UNSUPPORTED).
  *
  * When rowsum is requested and N spans several tile columns the library keeps

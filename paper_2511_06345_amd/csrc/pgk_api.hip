@@ -46,9 +46,10 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
 {
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
-    // K in whole K tiles; rows of B and C start on 16-byte boundaries.  M and N may be
-    // ragged; tiny outputs are left to the bounds-checked kernel, which wastes less.
-    if (K % t.bk || N % (16 / es)) return false;
+    // rows of A, B and C start on 16-byte boundaries.  M, N and K may be ragged (K: the
+    // last K tile is partial); tiny outputs are left to the bounds-checked kernel, which
+    // wastes less.
+    if (K % (16 / es) || N % (16 / es)) return false;
     if (M < 16 || N < 16) return false;
     // per-lane 32-bit byte offsets inside one tile
     if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * N * es >= (1LL << 32)) return false;

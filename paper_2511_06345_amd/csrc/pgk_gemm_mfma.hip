@@ -203,7 +203,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const int sp = (int)(z - (unsigned int)b * (unsigned int)p.splits);
     const int k_begin = sp * p.k_slice;
     const int k_end = (k_begin + p.k_slice < p.K) ? (k_begin + p.k_slice) : p.K;
-    const int KT = (k_end - k_begin) / BK;
+    // K tiles of this slice; the last one may be partial (K need not be a multiple of BK,
+    // only of the 16-byte chunk): k_last of its BK columns exist
+    const int KT = (k_end - k_begin + BK - 1) / BK;
+    const int k_last = (k_end - k_begin) - (KT - 1) * BK;
+    const bool k_partial = k_last < BK;
 
     const unsigned char* Ag = (const unsigned char*)p.A +
         ((size_t)b * p.M * p.K + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
@@ -211,6 +215,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         ((size_t)b * p.K * p.N + (size_t)k_begin * p.N + (size_t)tn * BN) * ES;
     const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
     const size_t b_step = (size_t)BK * p.N * ES;       // bytes per K tile down B
+    // one past the last byte of A and of B: copies of a partial K tile run past the end of a
+    // row (into the next row, harmless) and, for the last row, past the end of the array,
+    // where the buffer resource's size check makes them read nothing
+    const unsigned char* const A_end = (const unsigned char*)p.A + (size_t)p.batch * p.M * p.K * ES;
+    const unsigned char* const B_end = (const unsigned char*)p.B + (size_t)p.batch * p.K * p.N * ES;
 
     // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
     const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
@@ -253,25 +262,54 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // A (or B) panel, plus the lane's constant 32-bit byte offset -- no vector ALU work
     // per copy.  The resource covers 4 GiB from its base; lane offsets stay below that
     // (checked on the host).
-    auto copy_a_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
+    // `bounded`: the resource ends where the array ends instead of 4 GiB after its base
+    // (partial last K tile only; out-of-range lanes then fetch nothing).
+    auto records = [](const unsigned char* base, const unsigned char* end, bool bounded) __attribute__((always_inline)) -> int {
+        const size_t left = (size_t)(end - base);
+        return (bounded && left < 0xffffffffull) ? (int)(unsigned int)left : (int)0xffffffffu;
+    };
+    auto copy_a_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
+        const unsigned char* base = Ag + (size_t)kt * a_step;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            __builtin_amdgcn_make_buffer_rsrc((void*)(Ag + (size_t)kt * a_step), 0, (int)0xffffffffu, 0x00020000),
+            __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, A_end, bounded), 0x00020000),
             PGK_LDS(la + t * 1024), 16, voff_a[t], 0, 0, 0);
     };
-    auto copy_b_op = [&](int kt, auto st, int t) __attribute__((always_inline)) {
+    auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
+        const unsigned char* base = Bg + (size_t)kt * b_step;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            __builtin_amdgcn_make_buffer_rsrc((void*)(Bg + (size_t)kt * b_step), 0, (int)0xffffffffu, 0x00020000),
+            __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, B_end, bounded), 0x00020000),
             PGK_LDS(lb + t * 1024), 16, voff_b[t], 0, 0, 0);
     };
     auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < Cfg::A_CPW; ++t) copy_a_op(kt, st, t);
+        for (int t = 0; t < Cfg::A_CPW; ++t) copy_a_op(kt, st, t, k_partial && kt == KT - 1);
     };
     auto copy_b = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
-        for (int t = 0; t < Cfg::B_CPW; ++t) copy_b_op(kt, st, t);
+        for (int t = 0; t < Cfg::B_CPW; ++t) copy_b_op(kt, st, t, k_partial && kt == KT - 1);
+    };
+    // The columns of a partial last K tile that do not exist: the copy has put whatever
+    // follows the row in memory there (A chunks at or beyond k_last, B rows at or beyond
+    // k_last).  Each lane clears the 16-byte pieces it copied itself; call after the wait
+    // for the copies and before the barrier that publishes the tile.
+    auto zero_k_tail = [&](auto sta, auto stb) __attribute__((always_inline)) {
+        constexpr int EPC = 16 / ES;
+        const u32x4 zero = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int t = 0; t < Cfg::A_CPW; ++t) {
+            const int r = (wave * Cfg::A_CPW + t) * Cfg::A_RPC + lane / Cfg::A_CPR;
+            const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
+            if (c * EPC >= k_last)
+                *(__attribute__((address_space(3))) u32x4*)PGK_LDS(lds_a(sta) + wave * (Cfg::A_CPW * 1024) + t * 1024 + lane * 16) = zero;
+        }
+#pragma unroll
+        for (int t = 0; t < Cfg::B_CPW; ++t) {
+            const int kr = (wave * Cfg::B_CPW + t) * Cfg::B_RPC + lane / Cfg::B_CPR;
+            if (kr >= k_last)
+                *(__attribute__((address_space(3))) u32x4*)PGK_LDS(lds_b(stb) + wave * (Cfg::B_CPW * 1024) + t * 1024 + lane * 16) = zero;
+        }
     };
 
     // ---- per-lane LDS read offsets
@@ -371,6 +409,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(decltype(allowed)::value) : "memory");
         __builtin_amdgcn_sched_barrier(0);
     };
+    // the same for a partial last K tile landing in stages sta / stb: all copies awaited,
+    // missing columns cleared, then the barrier
+    auto wait_clear_and_sync = [&](auto sta, auto stb) __attribute__((always_inline)) {
+        __builtin_amdgcn_sched_barrier(0);
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
+        zero_k_tail(sta, stb);
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+        __builtin_amdgcn_sched_barrier(0);
+    };
     // With a three-deep A ring the A copy issued in this tile's first step is for the
     // tile after next and may still be in flight when the next tile is awaited.
     constexpr int STEADY_IN_FLIGHT = (SA - 2) * Cfg::A_CPW;
@@ -417,8 +464,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                              : late ? (SA == 3 ? Cfg::B_CPW : Cfg::A_CPW) : 0;
             const bool fetch = !last || has_next;
             if (last && has_next) {
-                if constexpr (STEADY) wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
-                else wait_copies_and_sync(IC<0>{});
+                if constexpr (STEADY) {
+                    wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
+                } else {
+                    if (k_partial && kt + 2 == KT) wait_clear_and_sync(NextA{}, NextB{});
+                    else wait_copies_and_sync(IC<0>{});
+                }
             }
 #pragma unroll
             for (int m = 0; m < N_MFMA; ++m) {
@@ -433,12 +484,14 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
                 for (int t = 0; t < (Cfg::A_CPW > Cfg::B_CPW ? Cfg::A_CPW : Cfg::B_CPW); ++t) {
                     if (t < (m * n_copy) / N_MFMA || t >= ((m + 1) * n_copy) / N_MFMA) continue;
+                    // steady tiles never copy the last K tile when that one is partial
+                    const bool b1 = !STEADY && k_partial && kt + 2 == KT, b2 = !STEADY && k_partial && kt + 3 == KT;
                     if constexpr (SA == 3) {
-                        if (early) copy_a_op(kt + 2, IC<(STA + 2) % 3>{}, t);
-                        else copy_b_op(kt + 2, stb, t);
+                        if (early) copy_a_op(kt + 2, IC<(STA + 2) % 3>{}, t, b2);
+                        else copy_b_op(kt + 2, stb, t, b2);
                     } else {
-                        if (early) copy_b_op(kt + 1, NextB{}, t);
-                        else copy_a_op(kt + 2, sta, t);
+                        if (early) copy_b_op(kt + 1, NextB{}, t, b1);
+                        else copy_a_op(kt + 2, sta, t, b2);
                     }
                 }
                 __builtin_amdgcn_sched_barrier(0);
@@ -454,11 +507,14 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             copy_a(1, IC<1>{});
             wait_copies_and_sync(IC<Cfg::A_CPW>{});
             copy_b(1, IC<1>{});
+        } else if (k_partial) {
+            wait_clear_and_sync(IC<0>{}, IC<0>{});
         } else {
             wait_copies_and_sync(IC<0>{});
         }
     } else {
-        wait_copies_and_sync(IC<0>{});
+        if (k_partial && KT == 1) wait_clear_and_sync(IC<0>{}, IC<0>{});
+        else wait_copies_and_sync(IC<0>{});
         if (KT > 1) copy_a(1, IC<1>{});
     }
     read_frags(IC<0>{}, IC<0>{}, 0, frag[0]);
@@ -467,7 +523,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     constexpr int UNROLL = SA == 3 ? 6 : 2;      // lcm of the two ring depths
     constexpr int LOOKAHEAD = 2;
     // steady state: every copy issued in the trip exists, no conditionals in the body
-    for (; kt + UNROLL - 1 + LOOKAHEAD < KT; kt += UNROLL) {
+    const int KT_full = KT - (k_partial ? 1 : 0);   // the steady loop leaves a partial tile to the tail
+    for (; kt + UNROLL - 1 + LOOKAHEAD < KT_full; kt += UNROLL) {
         tile_body(kt, IC<0>{}, IC<0>{}, IC<1>{}, true, true, true);
         tile_body(kt + 1, IC<1 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
         if constexpr (SA == 3) {
@@ -477,7 +534,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             tile_body(kt + 5, IC<5 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
         }
     }
-    // tail: the remaining tiles (fewer than UNROLL + LOOKAHEAD), with run-time
+    // tail: the remaining tiles (at most UNROLL + LOOKAHEAD), with run-time
     // existence checks and a wait for all copies at each barrier
     auto tail_tile = [&](int t, auto sta, auto stb) __attribute__((always_inline)) {
         if (t < KT) tile_body(t, sta, stb, IC<0>{}, t + 1 < KT, t + 2 < KT, t + 2 < KT);
@@ -485,11 +542,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     tail_tile(kt, IC<0>{}, IC<0>{});
     tail_tile(kt + 1, IC<1 % SA>{}, IC<1>{});
     tail_tile(kt + 2, IC<2 % SA>{}, IC<0>{});
+    tail_tile(kt + 3, IC<3 % SA>{}, IC<1>{});
     if constexpr (SA == 3) {
-        tail_tile(kt + 3, IC<3 % SA>{}, IC<1>{});
         tail_tile(kt + 4, IC<4 % SA>{}, IC<0>{});
         tail_tile(kt + 5, IC<5 % SA>{}, IC<1>{});
         tail_tile(kt + 6, IC<6 % SA>{}, IC<0>{});
+        tail_tile(kt + 7, IC<7 % SA>{}, IC<1>{});
     }
 
     // ---- epilogue: activation into LDS (the operand buffers are free now), then

@@ -37,10 +37,10 @@ struct TileShape { int bm, bn, bk; };
 TileShape mfma_tile_shape(int dtype, bool small);
 TileShape guarded_tile_shape();
 
-// Matrix-core kernels: require K % bk == 0, k_slice % bk == 0, N a multiple of the
-// 16-byte chunk (8 bf16 / 4 fp32 elements) and 16-byte aligned A, B, C, bias, ws.
-// M and N need not be tile multiples: edge tiles re-read valid rows / columns and
-// store only what exists.
+// Matrix-core kernels: require k_slice % bk == 0, K and N multiples of the 16-byte
+// chunk (8 bf16 / 4 fp32 elements) and 16-byte aligned A, B, C, bias, ws.
+// M, N and K need not be tile multiples: edge tiles re-read valid rows / columns and
+// store only what exists; the missing columns of a partial last K tile are cleared in LDS.
 hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.

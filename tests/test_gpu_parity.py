@@ -68,6 +68,10 @@ GUARDED_SHAPES = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3
 # K a whole number of K tiles, M and N ragged: matrix-core kernels with edge tiles
 F32_EDGE_SHAPES = [(100, 36, 64, 2), (129, 132, 96, 1), (300, 260, 32, 1), (17, 500, 128, 1), (250, 16, 64, 3)]
 BF16_EDGE_SHAPES = [(100, 40, 64, 2), (257, 264, 128, 1), (300, 520, 64, 1), (17, 1000, 192, 1), (700, 16, 64, 2)]
+# K a multiple of the 16-byte chunk only (4 fp32 / 8 bf16 elements): the last K tile is
+# partial, with one to sixteen full tiles before it
+F32_KTAIL_SHAPES = [(128, 128, 36, 1), (100, 36, 4, 2), (129, 132, 100, 1), (256, 128, 60, 2), (64, 64, 200, 3), (70, 200, 524, 1)]
+BF16_KTAIL_SHAPES = [(256, 256, 72, 1), (100, 40, 8, 2), (257, 264, 200, 1), (300, 520, 120, 2), (128, 128, 456, 2), (256, 128, 520, 1), (130, 72, 1032, 1)]
 F32_TILE_SHAPES = [(128, 128, 32, 1), (128, 128, 64, 1), (256, 128, 96, 1), (128, 384, 160, 2), (384, 256, 224, 1)]
 BF16_TILE_SHAPES = [(256, 256, 64, 1), (256, 256, 128, 1), (256, 512, 192, 1), (512, 256, 320, 2), (256, 256, 448, 1)]
 
@@ -83,8 +87,8 @@ def test_small_and_ragged_shapes(pgk, oracle, dtype, shape, act):
     check(got_c, got_rs, ref_c, ref_rs, dtype, f"guarded {shape} act {act}")
 
 
-@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES),
-                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES)])
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES + F32_KTAIL_SHAPES),
+                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES + BF16_KTAIL_SHAPES)])
 @pytest.mark.parametrize("act", [NONE, RELU, GELU, SILU])
 def test_tile_multiple_shapes(pgk, oracle, dtype, shapes, act):
     for shape in shapes:
@@ -100,8 +104,8 @@ def test_tile_multiple_shapes(pgk, oracle, dtype, shapes, act):
         check(got_c, None, ref_c, None, dtype, f"mfma {shape} act {act} no bias")
 
 
-@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES + GUARDED_SHAPES),
-                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES + GUARDED_SHAPES)])
+@pytest.mark.parametrize("dtype,shapes", [(F32, F32_TILE_SHAPES + F32_EDGE_SHAPES + F32_KTAIL_SHAPES + GUARDED_SHAPES),
+                                          (BF16, BF16_TILE_SHAPES + BF16_EDGE_SHAPES + BF16_KTAIL_SHAPES + GUARDED_SHAPES)])
 def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
     """Entries in {-2..2}, identity activation: bit-exact against the oracle, for every
     K-tile count (catches stage / double-buffer hazards and index slips)."""
@@ -126,8 +130,10 @@ def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
 # would have fewer than 192 workgroups, so the shapes above run on the small tiles.  These
 # have enough batch entries to get the large tiles (128x128 fp32, 256x256 bf16), with
 # one to seven K tiles and ragged edges.
-LARGE_TILE_SHAPES = {F32: [(128, 128, 32, 192), (256, 128, 96, 100), (300, 260, 64, 40), (129, 140, 224, 70)],
-                     BF16: [(256, 256, 64, 192), (512, 256, 192, 100), (300, 520, 128, 40), (257, 264, 448, 50)]}
+LARGE_TILE_SHAPES = {F32: [(128, 128, 32, 192), (256, 128, 96, 100), (300, 260, 64, 40), (129, 140, 224, 70),
+                           (128, 128, 36, 192), (300, 260, 100, 40), (129, 140, 300, 70)],
+                     BF16: [(256, 256, 64, 192), (512, 256, 192, 100), (300, 520, 128, 40), (257, 264, 448, 50),
+                            (256, 256, 72, 192), (300, 520, 200, 40), (257, 264, 520, 50), (256, 256, 1032, 48)]}
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -164,6 +170,30 @@ def test_splitk_matches_oracle_and_is_deterministic(pgk, oracle, dtype, act):
             assert np.array_equal(got_c, again_c) and np.array_equal(got_rs, again_rs)
         fused_c, fused_rs = run_fused(pgk, A, B, bias, act, dtype)
         check(fused_c, fused_rs, ref_c, ref_rs, dtype, f"fused {shape}")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("batch", [2, 48])
+def test_k_tail_ignores_what_follows_a_row(pgk, oracle, dtype, batch):
+    """K not a multiple of the K tile: the columns of the last tile that do not exist lie,
+    in memory, over the start of the next row of A and over the next batch entry of B.
+    NaNs planted there must not reach the rows / batch entries before them."""
+    M, N, K = 260, 264, 200 if dtype == BF16 else 100
+    A, B, bias = random_case(dtype, M, N, K, batch, seed=77)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, NONE)
+    nan = np.uint16(0x7FC0) if dtype == BF16 else np.float32(np.nan)
+    bad_row, bad_batch = 131, batch - 1
+    A2, B2 = A.copy(), B.copy()
+    A2[:, bad_row, :16] = nan           # what the tail columns of row 130 run into
+    B2[bad_batch, :16, :] = nan         # what the tail rows of B of the batch entry before run into
+    got_c, got_rs = run_fused(pgk, A2, B2, bias, NONE, dtype)
+    keep = np.ones((batch, M), dtype=bool)
+    keep[:, bad_row] = False
+    keep[bad_batch, :] = False
+    assert np.all(np.isfinite(got_c[keep])) and np.all(np.isfinite(got_rs[keep]))
+    assert np.all(np.isnan(got_c[~keep]))
+    for b in range(batch - 1):
+        check(got_c[b][keep[b]], got_rs[b][keep[b]], ref_c[b][keep[b]], ref_rs[b][keep[b]], dtype, f"batch {b}")
 
 
 def test_identity_operand_passes_b_through(pgk, oracle):
