@@ -47,6 +47,9 @@ def _load():
         lib.oracle_act.restype = ctypes.c_double
         lib.oracle_act.argtypes = [ctypes.c_double, ctypes.c_int]
         lib.oracle_num_threads.restype = ctypes.c_int
+        lib.oracle_reduce_max.restype = ctypes.c_int
+        lib.oracle_reduce_max.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
+                                          ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -106,3 +109,32 @@ def gemm_fused(A: np.ndarray, B: np.ndarray, bias, act_kind: int, rows=None,
     if rc != 0:
         raise ValueError("oracle_gemm_fused rejected its arguments")
     return C, rs
+
+
+def reduce_max(X: np.ndarray, dim: int, want_idx: bool = True):
+    """Maximum of X over dimension `dim` and the first position attaining it.
+
+    X: float32, or uint16 holding bfloat16 bit patterns; any number of dimensions.
+    Returns (values float32 with `dim` removed, indices int32 or None).  A NaN in a
+    slice gives NaN and the position of the first NaN.
+    """
+    lib = _load()
+    X = np.ascontiguousarray(X)
+    if X.dtype == np.float32:
+        dtype = F32
+    elif X.dtype == np.uint16:
+        dtype = BF16
+    else:
+        raise TypeError("X must be float32 or uint16 (bf16 bits)")
+    dim = dim % X.ndim
+    outer = int(np.prod(X.shape[:dim], dtype=np.int64))
+    red = int(X.shape[dim])
+    inner = int(np.prod(X.shape[dim + 1:], dtype=np.int64))
+    shape = X.shape[:dim] + X.shape[dim + 1:]
+    out = np.empty(outer * inner, dtype=np.float32)
+    idx = np.empty(outer * inner, dtype=np.int32) if want_idx else None
+    rc = lib.oracle_reduce_max(X.ctypes.data, dtype, outer, red, inner, out.ctypes.data,
+                               idx.ctypes.data if want_idx else None)
+    if rc != 0:
+        raise ValueError("oracle_reduce_max rejected its arguments")
+    return out.reshape(shape), (idx.reshape(shape) if want_idx else None)

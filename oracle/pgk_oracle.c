@@ -29,6 +29,14 @@
  * float64 library matmul on random shapes, and tabulated activation values.
  * No function in this file is "parity unpinned".
  *
+ * Second operator: maximum over one dimension (the paper's GPU case study,
+ * Section 4.4 "Max reduction over a dimension"; the paper gives no formula or
+ * shape).  oracle_reduce_max below is the definition written out as one scan
+ * per output element.  Pins (see tests): agreement with numpy's max / argmax,
+ * hand cases, "attained, not exceeded, nothing equal before it", invariance
+ * of the value under permutation of the reduced axis, reduced length 1, ties
+ * between +0 and -0, NaN and infinity cases.
+ *
  * Loop order is (b, i, k, j) with one row of N double accumulators, so the
  * inner loop is stride-1 in B; rows are independent and are shared among
  * OpenMP threads.  No blocking, no fusion beyond the definition.
@@ -151,6 +159,41 @@ int oracle_gemm_fused(const void *A, const void *B, const float *bias,
 }
 
 /* Number of threads the parallel region above will use. */
+/*
+ * Maximum over the middle dimension of X viewed as [outer][red][inner]
+ * (row-major, contiguous), which covers a reduction over any one dimension of a
+ * contiguous tensor:
+ *
+ *     out[o][i] = max_{r} X[o][r][i]
+ *     idx[o][i] = the smallest r with X[o][r][i] == out[o][i]
+ *
+ * under IEEE comparison (+0 and -0 compare equal, so the earlier one is
+ * returned).  If the slice holds a NaN the result is that NaN and idx the
+ * position of the first NaN.  Values are returned widened to float (exact for
+ * both storage types), idx may be NULL.  Returns 0, or -1 for bad arguments.
+ */
+int oracle_reduce_max(const void *X, int dtype, int64_t outer, int64_t red, int64_t inner,
+                      float *out, int32_t *idx)
+{
+    if (!X || !out || outer <= 0 || red <= 0 || inner <= 0 || red > 2147483647LL) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+#pragma omp parallel for schedule(static)
+    for (int64_t o = 0; o < outer; ++o) {
+        for (int64_t i = 0; i < inner; ++i) {
+            const int64_t base = o * red * inner + i;
+            float best = (float)load_elem(X, dtype, base);
+            int64_t at = 0;
+            for (int64_t r = 1; r < red && best == best; ++r) {      /* a NaN ends the scan */
+                const float x = (float)load_elem(X, dtype, base + r * inner);
+                if (x != x || x > best) { best = x; at = r; }
+            }
+            out[o * inner + i] = best;
+            if (idx) idx[o * inner + i] = (int32_t)at;
+        }
+    }
+    return 0;
+}
+
 int oracle_num_threads(void)
 {
 #ifdef _OPENMP
