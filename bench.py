@@ -34,6 +34,7 @@ PEAK_HBM_GBS = 8000.0
 # (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
 # profiles/.  Valid only for the kernel configuration named here; None otherwise.
 TRAFFIC_BYTES = {}   # counters are taken again for the kernel as shipped (see profiles/)
+REDUCE_TRAFFIC_BYTES = {}
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
@@ -41,6 +42,14 @@ DESCR = {
     "c3": "c3: bf16 GEMM 8192x8192x8192 (fp32 accumulate), bias + SiLU, bf16 out",
     "c4": "c4: bf16 GEMM 16384x1024x4096, bias + ReLU + fp32 rowsum, bf16 out",
     "c5": "c5: fp32 split-K GEMM 256x256x65536 x16, identity + rowsum",
+}
+
+
+REDUCE_DESCR = {
+    "r1": "r1: fp32 max over dim 1 of [64, 4096, 1024] (strided), values + positions",
+    "r2": "r2: fp32 max over dim 2 of [64, 4096, 1024] (contiguous rows of 1024), values + positions",
+    "r3": "r3: bf16 max over dim 1 of [32, 4096, 4096] (strided), values + positions",
+    "r4": "r4: fp32 max over dim 1 of [16, 2^24] (few long rows, two passes), values + positions",
 }
 
 
@@ -107,6 +116,95 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
     return res
 
 
+def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
+    """Times `steps` calls of pgk_reduce_max on reduction workload `name`; returns a dict."""
+    w = gen.REDUCE_WORKLOADS[name]
+    t0 = time.time()
+    X = gen.make_reduce_input(w)
+    dX = (torch.from_numpy(X.view(np.int16)).cuda().view(torch.bfloat16) if w.dtype == gen.BF16
+          else torch.from_numpy(X).cuda())
+    log(f"[{name}] input generated and copied in {time.time() - t0:.1f} s")
+    shape = tuple(d for i, d in enumerate(w.shape) if i != w.dim)
+    vals = torch.empty(shape, dtype=dX.dtype, device="cuda")
+    idx = torch.empty(shape, dtype=torch.int32, device="cuda")
+
+    def step():
+        pgk.reduce_max(dX, w.dim, want_idx=True, out=vals, idx_out=idx)
+
+    for _ in range(warmup):
+        step()
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t_start = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        step()
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])
+    ms_per_step = wall * 1e3 / steps
+    res = {
+        "workload": REDUCE_DESCR[name],
+        "ms_per_step": ms_per_step,
+        "gbs": w.algorithmic_bytes / (ms_per_step * 1e-3) / 1e9,
+        "call_ms_avg": float(per.mean()),
+        "call_ms_median": float(np.median(per)),
+        "call_ms_min": float(per.min()),
+        "algorithmic_gbs": w.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
+    }
+    res["hbm_frac_algorithmic"] = res["algorithmic_gbs"] / PEAK_HBM_GBS
+    if keep_host:
+        res["_host"] = X
+    return res
+
+
+def reduce_main(args, name, pgk, gen, torch):
+    """One JSON line for a reduction workload (bound: HBM)."""
+    w = gen.REDUCE_WORKLOADS[name]
+    head = run_reduce_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True)
+    X = head.pop("_host")
+    out = {
+        "metric": "max-reduction algorithmic GB/s on 1 MI355X",
+        "value": head["gbs"],
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"],
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == gen.BF16 else "f32",
+        "data": "synthetic (seeded SplitMix64 block of 2^24 uniform values repeated, resident in HBM before timing)",
+        "config": {"workload": REDUCE_DESCR[name], "shape": list(w.shape), "dim": w.dim,
+                   "algorithmic_bytes_per_step": w.algorithmic_bytes},
+        "roofline": {
+            "bound": "hbm",
+            "kernel": "pgk::reduce_max_rows_kernel / reduce_max_cols_kernel (+ reduce_max_finish_kernel)",
+            "achieved": head["algorithmic_gbs"],
+            "peak": PEAK_HBM_GBS,
+            "unit": "GB/s",
+            "frac": head["algorithmic_gbs"] / PEAK_HBM_GBS,
+            "launch_ms_avg": head["call_ms_avg"],
+            "traffic": REDUCE_TRAFFIC_BYTES.get(name),
+            "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
+        },
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        oracle.reduce_max(X[:1], w.dim)   # loads the library before the timed call
+        t0 = time.perf_counter()
+        oracle.reduce_max(X, w.dim)
+        dt = time.perf_counter() - t0
+        out["cpu_baseline"] = {
+            "value": w.algorithmic_bytes / dt / 1e9, "unit": "GB/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"the whole {name} tensor ({w.elements} elements in {dt * 1e3:.0f} ms, one scan per output, gcc -O2 -fopenmp)",
+        }
+    print(json.dumps(out), flush=True)
+
+
 def cpu_baseline(w, host, gen, budget_s=15.0):
     """The CPU oracle, as it stands, on a bounded sample of whole rows of the workload."""
     import oracle
@@ -138,9 +236,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=sorted(DESCR))
+    ap.add_argument("--workload", default="c3", choices=sorted(DESCR) + sorted(REDUCE_DESCR),
+                    help="c1..c5: fused GEMM workloads (c3 is the headline); r1..r4: max-reduction workloads")
     ap.add_argument("--others", action="store_true",
-                    help="also time the other four workloads (reported under 'others')")
+                    help="also time the other GEMM workloads and the reduction workloads (reported under 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch plain 1 GiB device-to-device copies and exit (run under rocprofv3 --pmc "
@@ -168,6 +267,9 @@ def main():
     pgk.load_library()   # no fallback: fails here if libpgk.so is not built
 
     name = args.workload
+    if name in REDUCE_DESCR:
+        reduce_main(args, name, pgk, gen, torch)
+        return
     w = gen.WORKLOADS[name]
     head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True)
     host = head.pop("_host")
@@ -220,6 +322,9 @@ def main():
             r["mfma_frac"] = ow.flops / (r["call_ms_avg"] * 1e-3) / 1e12 / pk
             r["hbm_frac_algorithmic"] = r["algorithmic_gbs"] / PEAK_HBM_GBS
             others[other] = r
+            torch.cuda.empty_cache()
+        for other in sorted(REDUCE_DESCR):
+            others[other] = run_reduce_workload(other, args.steps, args.warmup, pgk, gen, torch)
             torch.cuda.empty_cache()
         out["others"] = others
     print(json.dumps(out), flush=True)

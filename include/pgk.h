@@ -117,6 +117,34 @@ size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch
 int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch,
                            int dtype, int splits);
 
+/*
+ * pgk_reduce_max -- maximum over one dimension (the reduction operator of the
+ * paper's GPU case study, Section 4.4; no formula is given there, so this is the
+ * plain definition).  X is a dense row-major tensor viewed as [outer][red][inner]
+ * -- reducing dimension d of a contiguous tensor means outer = product of the sizes
+ * before d, red = size of d, inner = product of the sizes after d:
+ *
+ *     out[o][i] = max over r of X[o][r][i]
+ *     idx[o][i] = the smallest r with X[o][r][i] == out[o][i]
+ *
+ * under IEEE comparison (+0 and -0 tie; the earlier one is returned, bit for bit).
+ * A slice that holds a NaN gives that NaN and the position of the first NaN.
+ *
+ *     X    [outer][red][inner]  float32 or bfloat16 (dtype), device pointer
+ *     out  [outer][inner]       same element type as X, device pointer
+ *     idx  [outer][inner]       int32 device pointer, or NULL = positions not wanted
+ *
+ * outer, red, inner > 0; red at most 2^31 - 1024, outer * inner below 2^62, else
+ * PGK_ERR_UNSUPPORTED.  Any shape and alignment is accepted (16-byte loads are used when
+ * X is 16-byte aligned and the contiguous extent is a multiple of 16 bytes).  When there
+ * are few outputs and a long reduced dimension the range is reduced in segments and a
+ * second small kernel combines them; the segment results live in the same per
+ * (device, stream) scratch buffer as the row-sum partials (hipMalloc on first use).
+ * The result does not depend on how the work was split and is bit-reproducible.
+ */
+int pgk_reduce_max(const void* X, void* out, int32_t* idx,
+                   int64_t outer, int64_t red, int64_t inner, int dtype, void* stream);
+
 /* Frees the row-sum scratch buffers of the current process (synchronises the
  * devices that own them).  Optional; safe to call when none exist. */
 int pgk_release_scratch(void);

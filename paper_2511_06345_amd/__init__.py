@@ -1,11 +1,11 @@
-"""libpgk: fused GEMM + bias/activation/row-sum kernels for AMD MI355X (gfx950).
+"""libpgk: fused GEMM + bias/activation/row-sum kernels and a max reduction for AMD MI355X (gfx950).
 
 ``inputs`` (seeded synthetic workloads) imports nothing but numpy; the GPU
-binding is loaded lazily on first use of ``gemm_fused`` / ``gemm_splitk``.
+binding is loaded lazily on first use of ``gemm_fused`` / ``gemm_splitk`` / ``reduce_max``.
 """
 from . import inputs  # noqa: F401
 
-_LAZY = {"gemm_fused", "gemm_splitk", "splitk_workspace_bytes", "splitk_auto_splits",
+_LAZY = {"gemm_fused", "gemm_splitk", "reduce_max", "splitk_workspace_bytes", "splitk_auto_splits",
          "status_string", "version", "load_library", "release_scratch", "PgkError"}
 
 

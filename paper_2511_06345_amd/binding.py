@@ -19,7 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
 EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_splitk_workspace_bytes",
-           "pgk_splitk_auto_splits", "pgk_release_scratch", "pgk_status_string", "pgk_version")
+           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_release_scratch", "pgk_status_string",
+           "pgk_version")
 
 _lib = None
 
@@ -50,6 +51,8 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_splitk_auto_splits.restype = ci
     lib.pgk_splitk_auto_splits.argtypes = [i64, i64, i64, i64, ci, ci]
+    lib.pgk_reduce_max.restype = ci
+    lib.pgk_reduce_max.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp]
     lib.pgk_release_scratch.restype = ci
     lib.pgk_release_scratch.argtypes = []
     lib.pgk_status_string.restype = ctypes.c_char_p
@@ -162,3 +165,36 @@ def gemm_splitk(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], 
     if rc != 0:
         raise PgkError(rc, "pgk_gemm_splitk")
     return C, rs
+
+
+def reduce_max(X: torch.Tensor, dim: int, want_idx: bool = True, out: Optional[torch.Tensor] = None,
+               idx_out: Optional[torch.Tensor] = None, stream=None):
+    """Maximum of X over dimension ``dim`` and the first position attaining it
+    (pgk_reduce_max).  X: contiguous float32 or bfloat16 device tensor.  Returns
+    (values in the dtype of X with ``dim`` removed, int32 positions or None)."""
+    lib = load_library()
+    if not (X.is_cuda and X.is_contiguous()):
+        raise ValueError("X must be a contiguous device tensor")
+    if X.dtype == torch.float32:
+        dtype = F32
+    elif X.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("X must be float32 or bfloat16")
+    dim = dim % X.dim()
+    outer = inner = 1
+    for d in X.shape[:dim]:
+        outer *= int(d)
+    for d in X.shape[dim + 1:]:
+        inner *= int(d)
+    red = int(X.shape[dim])
+    shape = tuple(X.shape[:dim]) + tuple(X.shape[dim + 1:])
+    vals = out if out is not None else torch.empty(shape, dtype=X.dtype, device=X.device)
+    idx = None
+    if want_idx:
+        idx = idx_out if idx_out is not None else torch.empty(shape, dtype=torch.int32, device=X.device)
+    rc = lib.pgk_reduce_max(X.data_ptr(), vals.data_ptr(), idx.data_ptr() if idx is not None else None,
+                            outer, red, inner, dtype, _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_reduce_max")
+    return vals, idx

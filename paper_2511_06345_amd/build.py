@@ -10,7 +10,7 @@ CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpgk.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 
-SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip"]
+SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed fp32 VALU ops

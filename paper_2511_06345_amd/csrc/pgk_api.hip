@@ -220,6 +220,27 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
+int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_t red, int64_t inner,
+                   int dtype, void* stream)
+{
+    if (!X || !out || outer <= 0 || red <= 0 || inner <= 0) return PGK_ERR_INVALID_ARG;
+    if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return PGK_ERR_INVALID_ARG;
+    if (red > (1LL << 31) - 1024) return PGK_ERR_UNSUPPORTED;
+    if ((long double)outer * (long double)inner >= 4.6e18L ||
+        (long double)outer * (long double)inner * (long double)red >= 4.6e18L) return PGK_ERR_UNSUPPORTED;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const pgk::ReducePlan pl = pgk::plan_reduce_max(outer, red, inner, dtype, aligned16(X));
+    if (pl.blocks <= 0 || pl.blocks > 0x7fffffffLL) return PGK_ERR_UNSUPPORTED;
+    float* pv = nullptr;
+    int* pi = nullptr;
+    if (pl.partial_elems) {
+        if (scratch_get(st, pl.partial_elems * 8, &pv) != hipSuccess) return PGK_ERR_HIP;
+        pi = reinterpret_cast<int*>(pv + pl.partial_elems);
+    }
+    const hipError_t e = pgk::launch_reduce_max(pl, X, out, idx, pv, pi, outer, red, inner, dtype, st);
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
 int pgk_release_scratch(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);

@@ -55,5 +55,21 @@ hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, flo
                                 int M, int N, int batch, int splits, int act, int dtype,
                                 hipStream_t s);
 
+// Maximum over the middle dimension of X viewed as [outer][red][inner]; see
+// pgk_reduce_max.hip.  The plan is pure host arithmetic: vector width (elements per
+// 16-byte load, or 1 for the unaligned fallback), lanes per row (inner == 1), number of
+// segments the reduced range is cut into and their length (in chunks for inner == 1, in
+// r otherwise), workgroups, and the number of (value, position) partials for the second
+// pass (0 when there is a single segment).
+struct ReducePlan {
+    int vec, group, segs, per_seg, tiles_i;
+    long long blocks;
+    size_t partial_elems;
+};
+ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int dtype, bool x_aligned);
+// pv / pi: partial_elems floats / ints of scratch (unused when partial_elems == 0).
+hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int* idx, float* pv, int* pi,
+                             long long outer, long long red, long long inner, int dtype, hipStream_t s);
+
 }  // namespace pgk
 #endif

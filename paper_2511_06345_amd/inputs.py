@@ -227,3 +227,59 @@ def make_int_inputs(dtype: int, M: int, N: int, K: int, batch: int, seed: int):
         A = f32_to_bf16_bits(A)
         B = f32_to_bf16_bits(B)
     return A.reshape(batch, M, K), B.reshape(batch, K, N)
+
+
+# ---- workloads of the max reduction (maximum over one dimension of a dense tensor) ----
+
+@dataclass(frozen=True)
+class ReduceWorkload:
+    name: str
+    index: int           # part of the seed
+    dtype: int           # F32 | BF16
+    shape: Tuple[int, ...]
+    dim: int             # the reduced dimension
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == BF16 else 4
+
+    @property
+    def elements(self) -> int:
+        n = 1
+        for d in self.shape:
+            n *= d
+        return n
+
+    @property
+    def outputs(self) -> int:
+        return self.elements // self.shape[self.dim]
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        """Read X once, write the values and the int32 positions once."""
+        return float(self.elements * self.elem_bytes + self.outputs * (self.elem_bytes + 4))
+
+
+# 1 GiB of input each: a strided reduction, the same tensor reduced along its contiguous
+# dimension (short rows), a bf16 tensor, and a few very long rows.
+REDUCE_WORKLOADS = {
+    "r1": ReduceWorkload("r1", 11, F32, (64, 4096, 1024), 1),
+    "r2": ReduceWorkload("r2", 12, F32, (64, 4096, 1024), 2),
+    "r3": ReduceWorkload("r3", 13, BF16, (32, 4096, 4096), 1),
+    "r4": ReduceWorkload("r4", 14, F32, (16, 1 << 24), 1),
+}
+
+_REDUCE_BLOCK = 1 << 24
+
+
+def make_reduce_input(w: ReduceWorkload, salt: int = 0) -> np.ndarray:
+    """Input tensor of a reduction workload: one seeded block of 2**24 values, uniform in
+    [-1, 1), repeated to fill the tensor (so equal values recur 2**24 elements apart, which
+    exercises the first-position rule across the whole reduced range).  float32, or uint16
+    bf16 bit patterns."""
+    n = w.elements
+    block = uniform(tensor_seed(w.index, 1, salt), min(n, _REDUCE_BLOCK), -1.0, 1.0)
+    if w.dtype == BF16:
+        block = f32_to_bf16_bits(block)
+    reps = (n + block.size - 1) // block.size
+    return np.tile(block, reps)[:n].reshape(w.shape)

@@ -95,6 +95,17 @@ def test_split_plan_arithmetic(lib):
     assert binding.splitk_workspace_bytes(8, 8, 8, 1, F32, 9) == 0
 
 
+def test_reduce_max_rejects_bad_arguments_on_the_host(lib):
+    def call(X=0x1000, out=0x2000, idx=None, outer=2, red=3, inner=4, dtype=0):
+        return lib.pgk_reduce_max(X, out, idx, outer, red, inner, dtype, None)
+    assert call(X=None) == INVALID
+    assert call(out=None) == INVALID
+    for bad in ({"outer": 0}, {"red": 0}, {"inner": -3}, {"dtype": 2}):
+        assert call(**bad) == INVALID, bad
+    assert call(red=1 << 31) == UNSUPPORTED
+    assert call(outer=1 << 40, inner=1 << 40) == UNSUPPORTED
+
+
 def test_python_binding_validates_before_calling(lib):
     import torch
     a = torch.zeros(2, 3)
@@ -102,6 +113,8 @@ def test_python_binding_validates_before_calling(lib):
         binding.gemm_fused(a, torch.zeros(3, 2), None, 0)      # host tensors are refused
     with pytest.raises(ValueError):
         binding._shape(torch.zeros(2, 3), torch.zeros(4, 2))
+    with pytest.raises(ValueError):
+        binding.reduce_max(torch.zeros(2, 3), 0)
 
 
 def test_release_scratch_without_any(lib):
