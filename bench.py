@@ -33,8 +33,8 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
 # profiles/.  Valid only for the kernel configuration named here; None otherwise.
-TRAFFIC_BYTES = {}   # counters are taken again for the kernel as shipped (see profiles/)
-REDUCE_TRAFFIC_BYTES = {}
+TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745882063)}
+REDUCE_TRAFFIC_BYTES = {"r1": 1082777332, "r3": 1091557567}   # both kernels of a call
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
@@ -244,7 +244,20 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch plain 1 GiB device-to-device copies and exit (run under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE to get the counters' scale factor)")
+    ap.add_argument("--profile", action="store_true",
+                    help="run the workload under rocprofv3 (kernel trace, then counter runs) and print the "
+                         "per-kernel metric set as one JSON line instead of timing it here")
+    ap.add_argument("--extra-counters", nargs="*", default=[], help="with --profile: further counter names")
+    ap.add_argument("--record", default=None, help="with --profile: JSON file keeping the best profile so far")
     args = ap.parse_args()
+    if args.profile:
+        # the measurements are child processes (this bench again, without --profile); this process
+        # stays off the GPU
+        from paper_2511_06345_amd import profile
+        argv = ["--workload", args.workload, "--extra", *args.extra_counters]
+        if args.record:
+            argv += ["--record", args.record]
+        sys.exit(profile.main(argv))
     if args.gpus != 1:
         sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (nothing here uses a second GPU)")
 

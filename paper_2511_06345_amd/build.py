@@ -1,7 +1,9 @@
 """Builds libpgk.so (HIP, gfx950 only) next to this file."""
 from __future__ import annotations
 
+import json
 import os
+import re
 import subprocess
 from concurrent.futures import ThreadPoolExecutor
 
@@ -9,6 +11,9 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libpgk.so")
 OBJ_DIR = os.path.join(HERE, "_build")
+# what the compiler reports per kernel (registers, scratch, LDS, waves per SIMD), written at
+# build time next to the library; the profile harness reads it
+RESOURCES = os.path.join(HERE, "kernel_resources.json")
 
 SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip"]
 HIPCC_FLAGS = [
@@ -16,6 +21,8 @@ HIPCC_FLAGS = [
     # keep the compiler from forming packed fp32 VALU ops
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-Wno-unused-command-line-argument",
+    # one remark block per kernel with its register, scratch and LDS use
+    "-Rpass-analysis=kernel-resource-usage",
 ]
 
 
@@ -26,20 +33,57 @@ def _hipcc() -> str:
     return "hipcc"
 
 
-def _compile(src: str) -> str:
+_REMARK = re.compile(r"remark:\s+(Function Name|TotalSGPRs|VGPRs|AGPRs|ScratchSize \[bytes/lane\]|"
+                     r"Occupancy \[waves/SIMD\]|SGPRs Spill|VGPRs Spill|LDS Size \[bytes/block\]):\s+(\S+)")
+_REMARK_KEY = {"TotalSGPRs": "sgprs", "VGPRs": "vgprs", "AGPRs": "agprs", "ScratchSize [bytes/lane]": "scratch_bytes_per_lane",
+               "Occupancy [waves/SIMD]": "waves_per_simd", "SGPRs Spill": "sgpr_spills", "VGPRs Spill": "vgpr_spills",
+               "LDS Size [bytes/block]": "lds_bytes_per_workgroup"}
+
+
+def parse_resource_remarks(text: str) -> dict:
+    """{mangled kernel name: {vgprs, agprs, sgprs, ...}} from -Rpass-analysis=kernel-resource-usage output."""
+    out, cur = {}, None
+    for key, val in _REMARK.findall(text):
+        if key == "Function Name":
+            cur = out.setdefault(val, {})
+        elif cur is not None:
+            cur[_REMARK_KEY[key]] = int(val)
+    return out
+
+
+def _demangle(names):
+    for tool in ("/opt/rocm/llvm/bin/llvm-cxxfilt", "llvm-cxxfilt", "c++filt"):
+        try:
+            res = subprocess.run([tool], input="\n".join(names), capture_output=True, text=True)
+        except OSError:
+            continue
+        if res.returncode == 0:
+            return res.stdout.splitlines()
+    return list(names)
+
+
+def _compile(src: str):
     obj = os.path.join(OBJ_DIR, os.path.splitext(src)[0] + ".o")
     cmd = [_hipcc(), *HIPCC_FLAGS, "-I", CSRC, "-c", os.path.join(CSRC, src), "-o", obj]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0 or "error:" in res.stderr:
         raise RuntimeError(f"hipcc failed for {src}:\n{res.stderr}")
-    return obj
+    return obj, parse_resource_remarks(res.stderr)
 
 
 def build_library(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link libpgk.so.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
     with ThreadPoolExecutor(max_workers=4) as ex:
-        objs = list(ex.map(_compile, SOURCES))
+        compiled = list(ex.map(_compile, SOURCES))
+    objs = [c[0] for c in compiled]
+    resources = {}
+    for _, r in compiled:
+        resources.update(r)
+    mangled = sorted(resources)
+    table = {plain: dict(resources[m], mangled=m) for m, plain in zip(mangled, _demangle(mangled))}
+    with open(RESOURCES, "w") as f:
+        json.dump(table, f, indent=1, sort_keys=True)
     cmd = [_hipcc(), "--offload-arch=gfx950", "-shared", "-fPIC", "-o", LIB, *objs]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
