@@ -68,35 +68,43 @@ def device_inputs(w, gen, torch):
     return (A, B, bias), (dA, dB, dbias)
 
 
-def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
-    """Times `steps` calls of the hot path on workload `name`; returns a dict."""
+def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
+    """Times `steps` calls of the hot path on workload `name`; returns a dict.
+
+    Cache hygiene: the calls rotate through `sets` separate copies of the inputs and outputs
+    (same values, different addresses), so that consecutive calls do not find their operands
+    in the 256 MB memory-side cache; every copy is resident in HBM before timing starts."""
     w = gen.WORKLOADS[name]
     t0 = time.time()
     host, (dA, dB, dbias) = device_inputs(w, gen, torch)
     log(f"[{name}] inputs generated and copied in {time.time() - t0:.1f} s")
     out_dt = torch.bfloat16 if w.dtype == gen.BF16 else torch.float32
-    C = torch.empty((w.batch, w.M, w.N), dtype=out_dt, device="cuda")
-    rs = torch.empty((w.batch, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None
-    kw = {}
-    if w.call == "splitk":
-        need = pgk.splitk_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, 0)
-        kw["workspace"] = torch.empty(need, dtype=torch.uint8, device="cuda")
-        fn = pgk.gemm_splitk
-    else:
-        fn = pgk.gemm_fused
+    fn = pgk.gemm_splitk if w.call == "splitk" else pgk.gemm_fused
+    bufs = []
+    for i in range(max(1, sets)):
+        kw = {}
+        if w.call == "splitk":
+            need = pgk.splitk_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, 0)
+            kw["workspace"] = torch.empty(need, dtype=torch.uint8, device="cuda")
+        bufs.append(dict(
+            A=dA if i == 0 else dA.clone(), B=dB if i == 0 else dB.clone(),
+            bias=dbias if (i == 0 or dbias is None) else dbias.clone(),
+            C=torch.empty((w.batch, w.M, w.N), dtype=out_dt, device="cuda"),
+            rs=torch.empty((w.batch, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None, kw=kw))
 
-    def step():
-        fn(dA, dB, dbias, w.act, rowsum=w.rowsum, out=C, rowsum_out=rs, **kw)
+    def step(i):
+        b = bufs[i % len(bufs)]
+        fn(b["A"], b["B"], b["bias"], w.act, rowsum=w.rowsum, out=b["C"], rowsum_out=b["rs"], **b["kw"])
 
-    for _ in range(warmup):
-        step()
+    for i in range(warmup):
+        step(i)
     torch.cuda.synchronize()
     # events are recorded on torch's current stream, the stream the kernels are launched on
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t_start = time.perf_counter()
     ev[0].record()
     for i in range(steps):
-        step()
+        step(warmup + i)
         ev[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
@@ -110,14 +118,16 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
         "call_ms_median": float(np.median(per)),
         "call_ms_min": float(per.min()),
         "algorithmic_gbs": w.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
+        "buffer_sets": len(bufs),
     }
     if keep_host:
         res["_host"] = host
     return res
 
 
-def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
-    """Times `steps` calls of pgk_reduce_max on reduction workload `name`; returns a dict."""
+def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
+    """Times `steps` calls of pgk_reduce_max on reduction workload `name`; returns a dict.
+    The calls rotate through `sets` copies of the input at different addresses."""
     w = gen.REDUCE_WORKLOADS[name]
     t0 = time.time()
     X = gen.make_reduce_input(w)
@@ -127,18 +137,19 @@ def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
     shape = tuple(d for i, d in enumerate(w.shape) if i != w.dim)
     vals = torch.empty(shape, dtype=dX.dtype, device="cuda")
     idx = torch.empty(shape, dtype=torch.int32, device="cuda")
+    copies = [dX] + [dX.clone() for _ in range(max(1, sets) - 1)]
 
-    def step():
-        pgk.reduce_max(dX, w.dim, want_idx=True, out=vals, idx_out=idx)
+    def step(i):
+        pgk.reduce_max(copies[i % len(copies)], w.dim, want_idx=True, out=vals, idx_out=idx)
 
-    for _ in range(warmup):
-        step()
+    for i in range(warmup):
+        step(i)
     torch.cuda.synchronize()
     ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     t_start = time.perf_counter()
     ev[0].record()
     for i in range(steps):
-        step()
+        step(warmup + i)
         ev[i + 1].record()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t_start
@@ -152,6 +163,7 @@ def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
         "call_ms_median": float(np.median(per)),
         "call_ms_min": float(per.min()),
         "algorithmic_gbs": w.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
+        "buffer_sets": len(copies),
     }
     res["hbm_frac_algorithmic"] = res["algorithmic_gbs"] / PEAK_HBM_GBS
     if keep_host:
@@ -162,7 +174,7 @@ def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False):
 def reduce_main(args, name, pgk, gen, torch):
     """One JSON line for a reduction workload (bound: HBM)."""
     w = gen.REDUCE_WORKLOADS[name]
-    head = run_reduce_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True)
+    head = run_reduce_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
     X = head.pop("_host")
     out = {
         "metric": "max-reduction algorithmic GB/s on 1 MI355X",
@@ -205,6 +217,41 @@ def reduce_main(args, name, pgk, gen, torch):
     print(json.dumps(out), flush=True)
 
 
+def measured_ceilings(pgk, gen, torch):
+    """What this chip sustains under its power limit (library probes, timed with events on the
+    launch stream): the matrix instruction alone with zero and with random operands, and a
+    streaming read of 2 GiB.  Context for the roofline fractions; the published peaks stay the
+    denominators."""
+    sink = torch.zeros(4, dtype=torch.float32, device="cuda")
+
+    def timed(fn, reps=5):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        ev[0].record()
+        for i in range(reps):
+            fn()
+            ev[i + 1].record()
+        torch.cuda.synchronize()
+        return float(np.median([ev[i].elapsed_time(ev[i + 1]) for i in range(reps)])) * 1e-3
+
+    out = {}
+    for key, dtype, rnd in (("mfma_bf16_zero_operands_tflops", gen.BF16, False), ("mfma_bf16_random_operands_tflops", gen.BF16, True),
+                            ("mfma_f32_random_operands_tflops", gen.F32, True)):
+        flops = [0.0]
+
+        def launch():
+            flops[0] = pgk.probe_mfma(dtype, rnd, 2000, sink)
+        t = timed(launch)
+        out[key] = flops[0] / t / 1e12
+    buf = torch.ones(1 << 29, dtype=torch.float32, device="cuda")       # 2 GiB
+    t = timed(lambda: pgk.probe_stream_read(buf, sink))
+    out["hbm_stream_read_gbs"] = buf.numel() * 4 / t / 1e9
+    del buf
+    return out
+
+
 def cpu_baseline(w, host, gen, budget_s=15.0):
     """The CPU oracle, as it stands, on a bounded sample of whole rows of the workload."""
     import oracle
@@ -241,6 +288,8 @@ def main():
     ap.add_argument("--others", action="store_true",
                     help="also time the other GEMM workloads and the reduction workloads (reported under 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--buffer-sets", type=int, default=4,
+                    help="copies of the inputs/outputs the timed calls rotate through (cache hygiene)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="launch plain 1 GiB device-to-device copies and exit (run under rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE to get the counters' scale factor)")
@@ -284,7 +333,7 @@ def main():
         reduce_main(args, name, pgk, gen, torch)
         return
     w = gen.WORKLOADS[name]
-    head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True)
+    head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
     host = head.pop("_host")
 
     dtype_key = "bf16" if w.dtype == gen.BF16 else "f32"
@@ -315,11 +364,16 @@ def main():
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": dtype_key,
-        "data": "synthetic (seeded SplitMix64 generator, resident in HBM before timing)",
+        "data": "synthetic (seeded SplitMix64 generator, resident in HBM before timing; calls rotate through "
+                f"{head['buffer_sets']} copies of the buffers)",
         "config": {"workload": DESCR[name], "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
                    "call": w.call, "flops_per_step": w.flops, "algorithmic_bytes_per_step": w.algorithmic_bytes},
         "roofline": roofline,
     }
+    out["measured_ceilings"] = measured_ceilings(pgk, gen, torch)
+    mc = out["measured_ceilings"]
+    key = "mfma_bf16_random_operands_tflops" if w.dtype == gen.BF16 else "mfma_f32_random_operands_tflops"
+    roofline["frac_of_measured_ceiling"] = achieved / mc[key]
     if not args.no_cpu_baseline:
         log("[cpu_baseline] timing the oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w, host, gen)
@@ -329,7 +383,7 @@ def main():
         for other in sorted(DESCR):
             if other == name:
                 continue
-            r = run_workload(other, args.steps, args.warmup, pgk, gen, torch)
+            r = run_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
             ow = gen.WORKLOADS[other]
             pk = PEAK_TFLOPS["bf16" if ow.dtype == gen.BF16 else "f32"]
             r["mfma_frac"] = ow.flops / (r["call_ms_avg"] * 1e-3) / 1e12 / pk
@@ -337,7 +391,7 @@ def main():
             others[other] = r
             torch.cuda.empty_cache()
         for other in sorted(REDUCE_DESCR):
-            others[other] = run_reduce_workload(other, args.steps, args.warmup, pgk, gen, torch)
+            others[other] = run_reduce_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
             torch.cuda.empty_cache()
         out["others"] = others
     print(json.dumps(out), flush=True)

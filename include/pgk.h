@@ -145,6 +145,23 @@ int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch,
 int pgk_reduce_max(const void* X, void* out, int32_t* idx,
                    int64_t outer, int64_t red, int64_t inner, int dtype, void* stream);
 
+/*
+ * pgk_probe_mfma / pgk_probe_stream_read -- measurement aids, not operators: what the chip
+ * sustains under its power limit, to read a kernel's numbers against (the paper's Section 3.2
+ * lists matrix-unit activity and memory throughput among a performance engineer's evidence).
+ *
+ * pgk_probe_mfma launches 512 workgroups (two per CU, two waves per SIMD) in which every wave
+ * issues iters * 32 matrix instructions of `dtype` on register operands -- all zero
+ * (random_operands = 0: nothing toggles, the clock stays high) or random finite values
+ * (random_operands = 1: what a real GEMM's operands do to the clock).  *flops_out (host
+ * pointer, may be NULL) receives the floating-point operations of one launch.
+ * pgk_probe_stream_read reads `bytes` (a multiple of 16, 16-byte aligned device memory at
+ * `src`) once with 16-byte loads.  `sink` is one float of device memory for both; it is not
+ * written in practice.  Time the calls with events on `stream`.  iters in [1, 2^20].
+ */
+int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream);
+int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
+
 /* Frees the row-sum scratch buffers of the current process (synchronises the
  * devices that own them).  Optional; safe to call when none exist. */
 int pgk_release_scratch(void);

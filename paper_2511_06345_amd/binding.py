@@ -19,8 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
 EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_splitk_workspace_bytes",
-           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_release_scratch", "pgk_status_string",
-           "pgk_version")
+           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_probe_mfma", "pgk_probe_stream_read",
+           "pgk_release_scratch", "pgk_status_string", "pgk_version")
 
 _lib = None
 
@@ -53,6 +53,10 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_splitk_auto_splits.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_reduce_max.restype = ci
     lib.pgk_reduce_max.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp]
+    lib.pgk_probe_mfma.restype = ci
+    lib.pgk_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.pgk_probe_stream_read.restype = ci
+    lib.pgk_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.pgk_release_scratch.restype = ci
     lib.pgk_release_scratch.argtypes = []
     lib.pgk_status_string.restype = ctypes.c_char_p
@@ -198,3 +202,22 @@ def reduce_max(X: torch.Tensor, dim: int, want_idx: bool = True, out: Optional[t
     if rc != 0:
         raise PgkError(rc, "pgk_reduce_max")
     return vals, idx
+
+
+def probe_mfma(dtype: int, random_operands: bool, iters: int, sink: torch.Tensor, stream=None) -> float:
+    """Enqueues the matrix-instruction-only loop (pgk_probe_mfma); returns its flop count."""
+    flops = ctypes.c_double(0.0)
+    rc = load_library().pgk_probe_mfma(int(dtype), int(bool(random_operands)), int(iters), sink.data_ptr(),
+                                       ctypes.byref(flops), _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_probe_mfma")
+    return float(flops.value)
+
+
+def probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int:
+    """Enqueues one streaming read of the whole of `src` (pgk_probe_stream_read); returns its bytes."""
+    nbytes = src.numel() * src.element_size()
+    rc = load_library().pgk_probe_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_probe_stream_read")
+    return nbytes

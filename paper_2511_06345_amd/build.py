@@ -15,7 +15,8 @@ OBJ_DIR = os.path.join(HERE, "_build")
 # build time next to the library; the profile harness reads it
 RESOURCES = os.path.join(HERE, "kernel_resources.json")
 
-SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip"]
+SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
+           "pgk_probe.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed fp32 VALU ops

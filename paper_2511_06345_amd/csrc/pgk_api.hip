@@ -17,6 +17,7 @@ using pgk::GemmArgs;
 
 constexpr int64_t kMaxDim = 0x7fffffffLL;
 constexpr int kNumCUs = 256;          // MI355X
+constexpr int64_t kFusedCombineMaxWorkgroups = 64;
 constexpr int kMaxAutoSplits = 32;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -110,6 +111,34 @@ hipError_t scratch_get(hipStream_t stream, size_t bytes, float** out)
     return hipSuccess;
 }
 
+// ---- tile-row counters of the fused row-sum combine: one grow-only array per (device, stream),
+// zero when handed out (cleared on the stream when allocated; every kernel leaves it zero)
+std::map<std::pair<int, hipStream_t>, Scratch> g_counters;
+
+hipError_t counters_get(hipStream_t stream, size_t count, unsigned int** out)
+{
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    std::lock_guard<std::mutex> lk(g_mu);
+    Scratch& s = g_counters[{dev, stream}];
+    const size_t bytes = count * sizeof(unsigned int);
+    if (s.bytes < bytes) {
+        size_t want = bytes < (1u << 16) ? (1u << 16) : bytes;
+        if (want < 2 * s.bytes) want = 2 * s.bytes;
+        void* p = nullptr;
+        e = hipMalloc(&p, want);
+        if (e != hipSuccess) return e;
+        e = hipMemsetAsync(p, 0, want, stream);
+        if (e != hipSuccess) { (void)hipFree(p); return e; }
+        if (s.ptr) g_retired.push_back(s.ptr);
+        s.ptr = p;
+        s.bytes = want;
+    }
+    *out = static_cast<unsigned int*>(s.ptr);
+    return hipSuccess;
+}
+
 struct Path { bool mfma; bool small; pgk::TileShape tile; };
 
 // `units` = batch entries x K splits: workgroups per output tile position.
@@ -158,6 +187,15 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
             const size_t bytes = (size_t)batch * (size_t)tiles_n * (size_t)M * sizeof(float);
             if (scratch_get(st, bytes, &part) != hipSuccess) return PGK_ERR_HIP;
             a.rs_part = part;
+            // Small grids (latency-bound): the matrix-core kernel adds the partials itself, in the
+            // last workgroup of a tile row, and the second launch is saved.  Its device-scope
+            // fences write the whole L2 back, which on a large grid costs far more than the
+            // 4 us combine kernel (measured on the 16384 x 1024 x 4096 workload: 182 us against 139 us).
+            if (path.mfma && tiles_m * tiles_n * batch <= kFusedCombineMaxWorkgroups) {
+                if (counters_get(st, (size_t)batch * (size_t)tiles_m, &a.rs_counter) != hipSuccess) return PGK_ERR_HIP;
+                a.rowsum = rowsum;
+                part = nullptr;
+            }
         }
     }
     hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
@@ -241,12 +279,36 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
+int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream)
+{
+    if (!sink || iters < 1 || iters > (1 << 20)) return PGK_ERR_INVALID_ARG;
+    if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return PGK_ERR_INVALID_ARG;
+    const int workgroups = 2 * kNumCUs;
+    if (flops_out) {
+        const double per_instruction = dtype == PGK_DTYPE_BF16 ? 2.0 * 32 * 32 * 16 : 2.0 * 32 * 32 * 2;
+        *flops_out = per_instruction * 32.0 * iters * 4.0 * workgroups;
+    }
+    const hipError_t e = pgk::launch_probe_mfma(dtype, random_operands != 0, iters, workgroups, sink,
+                                                static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
+int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream)
+{
+    if (!src || !sink || bytes == 0 || bytes % 16 || !aligned16(src)) return PGK_ERR_INVALID_ARG;
+    const hipError_t e = pgk::launch_probe_stream_read(src, bytes, sink, static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
 int pgk_release_scratch(void)
 {
     std::lock_guard<std::mutex> lk(g_mu);
     int rc = PGK_OK;
     for (auto& kv : g_scratch)
         if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
+    for (auto& kv : g_counters)
+        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
+    g_counters.clear();
     for (void* p : g_retired)
         if (hipFree(p) != hipSuccess) rc = PGK_ERR_HIP;
     g_scratch.clear();

@@ -606,6 +606,35 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         for (int w = 1; w < Cfg::WGN; ++w) s += rs_buf[w * BM + tid];
         p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
     }
+    // Several tile columns: the workgroup that finishes a tile row last adds the row's
+    // partials, always in tile-column order, so the sum does not depend on which one that is.
+    // Each workgroup publishes its partials (device-scope fence), then counts itself in; the
+    // one that sees the count complete reads all of them (fence again: other XCDs' partials
+    // come through memory, not through this XCD's L2) and puts the counter back to zero for
+    // the next call on the stream.
+    if (p.rs_counter) {
+        // the flag lives in the first word of an operand buffer: after the barrier nobody reads
+        // the staged output tile any more (LDS has no room for another object)
+        int* const is_last = (int*)lds_a0;
+        __threadfence();
+        __syncthreads();
+        if (tid == 0) {
+            const unsigned int seen = atomicAdd(p.rs_counter + (size_t)b * p.tiles_m + tm, 1u);
+            *is_last = seen + 1u == (unsigned int)p.tiles_n;
+        }
+        __syncthreads();
+        if (*is_last) {
+            __threadfence();
+            if (tid < m_rem) {
+                const size_t row = (size_t)tm * BM + tid;
+                const volatile float* part = p.rs_part + (size_t)b * p.tiles_n * (size_t)p.M + row;
+                float s = part[0];
+                for (int t = 1; t < p.tiles_n; ++t) s += part[(size_t)t * p.M];
+                p.rowsum[(size_t)b * p.M + row] = s;
+            }
+            if (tid == 0) p.rs_counter[(size_t)b * p.tiles_m + tm] = 0u;
+        }
+    }
 #endif
 }
 

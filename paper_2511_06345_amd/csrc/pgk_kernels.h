@@ -22,6 +22,9 @@ struct GemmArgs {
     void* C;            // [batch][M][N]
     float* rs_part;     // row-sum partials [batch][tiles_n][M], or final [batch][M]
                         // when tiles_n == 1; nullptr = no row-sum
+    float* rowsum;      // final row sums [batch][M], written by the last workgroup of a tile row
+                        // when rs_counter != nullptr (matrix-core kernels, tiles_n > 1)
+    unsigned int* rs_counter;  // [batch][tiles_m], zero before the launch and again after it
     float* ws;          // split-K partial products [batch][splits][M][N]
     int M, N, K, batch;
     int act;
@@ -70,6 +73,12 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
 // pv / pi: partial_elems floats / ints of scratch (unused when partial_elems == 0).
 hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int* idx, float* pv, int* pi,
                              long long outer, long long red, long long inner, int dtype, hipStream_t s);
+
+// Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
+// threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming
+// read of `bytes` (16-byte aligned).  `sink`: one float the kernels never really write.
+hipError_t launch_probe_mfma(int dtype, int random_operands, int iters, int workgroups, float* sink, hipStream_t s);
+hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 
 }  // namespace pgk
 #endif

@@ -106,6 +106,15 @@ def test_reduce_max_rejects_bad_arguments_on_the_host(lib):
     assert call(outer=1 << 40, inner=1 << 40) == UNSUPPORTED
 
 
+def test_probes_reject_bad_arguments_on_the_host(lib):
+    assert lib.pgk_probe_mfma(0, 1, 10, None, None, None) == INVALID
+    assert lib.pgk_probe_mfma(5, 1, 10, 0x1000, None, None) == INVALID
+    assert lib.pgk_probe_mfma(0, 1, 0, 0x1000, None, None) == INVALID
+    assert lib.pgk_probe_stream_read(None, 1024, 0x1000, None) == INVALID
+    assert lib.pgk_probe_stream_read(0x2000, 1000, 0x1000, None) == INVALID     # not a multiple of 16
+    assert lib.pgk_probe_stream_read(0x2004, 1024, 0x1000, None) == INVALID     # misaligned
+
+
 def test_python_binding_validates_before_calling(lib):
     import torch
     a = torch.zeros(2, 3)
