@@ -50,6 +50,9 @@ def _load():
         lib.oracle_reduce_max.restype = ctypes.c_int
         lib.oracle_reduce_max.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_int64, ctypes.c_int64,
                                           ctypes.c_int64, ctypes.c_void_p, ctypes.c_void_p]
+        lib.oracle_conv1d.restype = ctypes.c_int64
+        lib.oracle_conv1d.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int] + \
+            [ctypes.c_int64] * 8 + [ctypes.c_int, ctypes.c_void_p]
         _lib = lib
     return _lib
 
@@ -138,3 +141,41 @@ def reduce_max(X: np.ndarray, dim: int, want_idx: bool = True):
     if rc != 0:
         raise ValueError("oracle_reduce_max rejected its arguments")
     return out.reshape(shape), (idx.reshape(shape) if want_idx else None)
+
+
+def conv1d_out_len(L: int, Kw: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
+    return (L + 2 * pad - dilation * (Kw - 1) - 1) // stride + 1
+
+
+def conv1d(x: np.ndarray, w: np.ndarray, bias, act_kind: int = ACT_NONE, stride: int = 1, pad: int = 0,
+           dilation: int = 1) -> np.ndarray:
+    """y = act(conv1d(x, w) + bias) in double.  x [B, Cin, L], w [Cout, Cin, Kw]: float32, or
+    uint16 holding bfloat16 bits; bias float32 [Cout] or None.  Cross-correlation with zero
+    padding, as in deep-learning frameworks.  Returns float64 [B, Cout, Lout]."""
+    lib = _load()
+    x, w = np.ascontiguousarray(x), np.ascontiguousarray(w)
+    if x.dtype == np.float32 and w.dtype == np.float32:
+        dtype = F32
+    elif x.dtype == np.uint16 and w.dtype == np.uint16:
+        dtype = BF16
+    else:
+        raise TypeError("x and w must both be float32 or both uint16 (bf16 bits)")
+    if x.ndim != 3 or w.ndim != 3 or x.shape[1] != w.shape[1]:
+        raise ValueError("expected x [B, Cin, L] and w [Cout, Cin, Kw]")
+    B, Cin, L = x.shape
+    Cout, _, Kw = w.shape
+    bias_p = None
+    if bias is not None:
+        bias = np.ascontiguousarray(bias, dtype=np.float32)
+        if bias.shape != (Cout,):
+            raise ValueError("bias must have shape [Cout]")
+        bias_p = bias.ctypes.data
+    Lout = conv1d_out_len(L, Kw, stride, pad, dilation)
+    if Lout <= 0:
+        raise ValueError("empty output")
+    y = np.empty((B, Cout, Lout), dtype=np.float64)
+    rc = lib.oracle_conv1d(x.ctypes.data, w.ctypes.data, bias_p, dtype, B, Cin, L, Cout, Kw,
+                           stride, pad, dilation, int(act_kind), y.ctypes.data)
+    if rc != Lout:
+        raise ValueError("oracle_conv1d rejected its arguments")
+    return y

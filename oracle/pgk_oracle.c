@@ -37,6 +37,15 @@
  * of the value under permutation of the reduced axis, reduced length 1, ties
  * between +0 and -0, NaN and infinity cases.
  *
+ * Third operator: one-dimensional convolution (the paper's second case study,
+ * Section 4.4 "Conv Standard 1D"; again no formula or shape is given).
+ * oracle_conv1d is the definition as used by deep-learning frameworks
+ * (cross-correlation with zero padding, stride and dilation), four nested loops
+ * in double.  Pins (see tests): numpy's correlate on every channel pair, a
+ * kernel of width one against the matrix product, unit-impulse kernels (pure
+ * shifts), the all-ones closed form that counts the taps inside the input,
+ * linearity, shift equivariance, integer-exact agreement with int64.
+ *
  * Loop order is (b, i, k, j) with one row of N double accumulators, so the
  * inner loop is stride-1 in B; rows are independent and are shared among
  * OpenMP threads.  No blocking, no fusion beyond the definition.
@@ -192,6 +201,48 @@ int oracle_reduce_max(const void *X, int dtype, int64_t outer, int64_t red, int6
         }
     }
     return 0;
+}
+
+/*
+ * One-dimensional convolution with bias and activation:
+ *
+ *     y[b][co][l] = act( bias[co] + sum_{ci} sum_{k} w[co][ci][k] * x[b][ci][l*stride + k*dilation - pad] )
+ *
+ * where x outside [0, L) counts as zero, and
+ *     Lout = floor((L + 2 pad - dilation (Kw - 1) - 1) / stride) + 1.
+ *   x [B][Cin][L], w [Cout][Cin][Kw] row-major, float32 or bfloat16 bits (dtype);
+ *   bias [Cout] float32 or NULL; y_out [B][Cout][Lout] double, nothing rounded.
+ * Returns Lout, or -1 for bad arguments (including Lout <= 0).
+ */
+int64_t oracle_conv1d(const void *x, const void *w, const float *bias, int dtype,
+                      int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw,
+                      int64_t stride, int64_t pad, int64_t dilation, int act, double *y_out)
+{
+    if (!x || !w || !y_out || B <= 0 || Cin <= 0 || L <= 0 || Cout <= 0 || Kw <= 0) return -1;
+    if (stride <= 0 || pad < 0 || dilation <= 0) return -1;
+    if (dtype != ORACLE_F32 && dtype != ORACLE_BF16) return -1;
+    if (act < ORACLE_ACT_NONE || act > ORACLE_ACT_SILU) return -1;
+    const int64_t span = L + 2 * pad - dilation * (Kw - 1) - 1;
+    if (span < 0) return -1;
+    const int64_t Lout = span / stride + 1;
+#pragma omp parallel for collapse(2) schedule(static)
+    for (int64_t b = 0; b < B; ++b) {
+        for (int64_t co = 0; co < Cout; ++co) {
+            for (int64_t l = 0; l < Lout; ++l) {
+                double acc = bias ? (double)bias[co] : 0.0;
+                for (int64_t ci = 0; ci < Cin; ++ci) {
+                    for (int64_t k = 0; k < Kw; ++k) {
+                        const int64_t pos = l * stride + k * dilation - pad;
+                        if (pos < 0 || pos >= L) continue;
+                        acc += load_elem(w, dtype, (co * Cin + ci) * Kw + k) *
+                               load_elem(x, dtype, (b * Cin + ci) * L + pos);
+                    }
+                }
+                y_out[(b * Cout + co) * Lout + l] = oracle_act(acc, act);
+            }
+        }
+    }
+    return Lout;
 }
 
 int oracle_num_threads(void)
