@@ -174,6 +174,7 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     GemmArgs a{};
     a.A = A; a.B = B; a.bias = bias; a.C = C; a.ws = nullptr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
+    pgk::fill_plain_views(a);
     a.act = act; a.splits = 1;
     a.k_slice = (int)(((K + path.tile.bk - 1) / path.tile.bk) * path.tile.bk);
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
@@ -248,6 +249,7 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     a.A = A; a.B = B; a.bias = nullptr; a.C = nullptr; a.rs_part = nullptr;
     a.ws = static_cast<float*>(workspace);
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
+    pgk::fill_plain_views(a);
     a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);

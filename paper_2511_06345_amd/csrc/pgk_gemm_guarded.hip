@@ -45,8 +45,8 @@ __global__ __launch_bounds__(256) void gemm_guarded_kernel(const GemmArgs p, con
     const int k_end = (k_begin + p.k_slice < p.K) ? (k_begin + p.k_slice) : p.K;
 
     const int m0 = tm * GT, n0 = tn * GT;
-    const size_t a_base = (size_t)b * p.M * p.K;
-    const size_t b_base = (size_t)b * p.K * p.N;
+    const size_t a_base = (size_t)b * (size_t)p.a_batch_stride;
+    const size_t b_base = (size_t)b * (size_t)p.b_batch_stride;
 
     float acc[4][4];
 #pragma unroll
@@ -72,7 +72,17 @@ __global__ __launch_bounds__(256) void gemm_guarded_kernel(const GemmArgs p, con
             const int kk = idx >> 6, nn = idx & 63;
             const int gk = k0 + kk, gn = n0 + nn;
             float v = 0.0f;
-            if (gk < k_end && gn < p.N) v = load_elem<BF16>(p.B, b_base + (size_t)gk * p.N + gn);
+            if (gk < k_end && gn < p.N) {
+                if (p.conv_kw > 0) {
+                    // convolution read in place: row gk is (input channel, tap), column gn an output position
+                    const int ci = gk / p.conv_kw, tap = gk - ci * p.conv_kw;
+                    const long long pos = (long long)gn * p.conv_stride + (long long)tap * p.conv_dil - p.conv_pad;
+                    if (pos >= 0 && pos < p.conv_len)
+                        v = load_elem<BF16>(p.B, b_base + (size_t)ci * (size_t)p.conv_len + (size_t)pos);
+                } else {
+                    v = load_elem<BF16>(p.B, b_base + (size_t)gk * p.ldb + gn);
+                }
+            }
             Bs[kk][nn] = v;
         }
         __syncthreads();
@@ -115,7 +125,7 @@ __global__ __launch_bounds__(256) void gemm_guarded_kernel(const GemmArgs p, con
         for (int j = 0; j < 4; ++j) {
             const int gn = n0 + tx * 4 + j;
             if (gm < p.M && gn < p.N) {
-                const float x = acc[i][j] + (p.bias ? p.bias[gn] : 0.0f);
+                const float x = acc[i][j] + (p.bias ? p.bias[p.bias_per_row ? gm : gn] : 0.0f);
                 const float y = activate_dyn(x, p.act);
                 rs += y;
                 const size_t o = c_base + (size_t)gm * p.N + gn;

@@ -85,6 +85,7 @@ __device__ __forceinline__ int swz_b(int krow)
 // adjacent for part 2.
 template <int ACT, bool OUT_BF16, typename Cfg>
 __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
+                                                const float* bias_row, int m_rem,
                                                 int n_tile0, int n_rem, int wm, int wn, int lane,
                                                 unsigned char* const (&obj)[4], float* rs_lds)
 {
@@ -103,6 +104,8 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
         unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
                               (row % ROWS_PER_OBJ) * ROW_BYTES;
         const int key = (2 * row) % UNITS;
+        // bias added to rows instead of columns (bias_row points at this tile's first row)
+        const float br = (bias_row && row < m_rem) ? bias_row[row] : 0.0f;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
 #pragma unroll
@@ -116,7 +119,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
+                    y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e] + br);
                     rs += in_n ? y[e] : 0.0f;
                 }
                 unsigned char* dst = base + (((col >> 2) ^ key) * UB);
@@ -210,16 +213,18 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const bool k_partial = k_last < BK;
 
     const unsigned char* Ag = (const unsigned char*)p.A +
-        ((size_t)b * p.M * p.K + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
+        ((size_t)b * (size_t)p.a_batch_stride + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
     const unsigned char* Bg = (const unsigned char*)p.B +
-        ((size_t)b * p.K * p.N + (size_t)k_begin * p.N + (size_t)tn * BN) * ES;
+        ((size_t)b * (size_t)p.b_batch_stride + (size_t)k_begin * p.ldb + (size_t)tn * BN) * ES;
     const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
-    const size_t b_step = (size_t)BK * p.N * ES;       // bytes per K tile down B
+    const size_t b_step = (size_t)BK * p.ldb * ES;     // bytes per K tile down B
     // one past the last byte of A and of B: copies of a partial K tile run past the end of a
     // row (into the next row, harmless) and, for the last row, past the end of the array,
     // where the buffer resource's size check makes them read nothing
-    const unsigned char* const A_end = (const unsigned char*)p.A + (size_t)p.batch * p.M * p.K * ES;
-    const unsigned char* const B_end = (const unsigned char*)p.B + (size_t)p.batch * p.K * p.N * ES;
+    const unsigned char* const A_end = (const unsigned char*)p.A +
+        ((size_t)(p.batch - 1) * (size_t)p.a_batch_stride + (size_t)p.M * p.K) * ES;
+    const unsigned char* const B_end = (const unsigned char*)p.B +
+        ((size_t)(p.batch - 1) * (size_t)p.b_batch_stride + (size_t)p.K * p.ldb) * ES;
 
     // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
     const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
@@ -245,7 +250,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
         constexpr int EPC = 16 / ES;                      // elements per chunk
         const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
-        voff_b[t] = (unsigned int)kr * (unsigned int)p.N * ES + (unsigned int)cg * 16u;
+        voff_b[t] = (unsigned int)kr * (unsigned int)p.ldb * ES + (unsigned int)cg * 16u;
     }
 
     auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
@@ -275,12 +280,27 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, A_end, bounded), 0x00020000),
             PGK_LDS(la + t * 1024), 16, voff_a[t], 0, 0, 0);
     };
+    // B tiles are copied in K order, one after the other, so where the next one starts is
+    // kept as running state: b_step further down, except that after every b_tiles_per_tap
+    // tiles (never, for a plain GEMM) the rows start over and the columns move on by
+    // b_tap_step elements -- a convolution read as a sum of shifted GEMMs, tap after tap.
+    size_t b_next_off = 0;
+    int b_next_row_tile = 0;
+    const long long b_tap_jump = (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step;
     auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
-        const unsigned char* base = Bg + (size_t)kt * b_step;
+        const unsigned char* base = Bg + b_next_off;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, B_end, bounded), 0x00020000),
             PGK_LDS(lb + t * 1024), 16, voff_b[t], 0, 0, 0);
+        if (t == Cfg::B_CPW - 1) {        // the tile's last piece: move on to the next tile
+            b_next_off += b_step;
+            if (++b_next_row_tile == p.b_tiles_per_tap) {
+                b_next_row_tile = 0;
+                b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
+            }
+        }
+        (void)kt;
     };
     auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll
@@ -568,7 +588,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
                                             (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
         if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, 0, n_rem, wm, wn, lane, obj, nullptr);
+            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, nullptr, m_rem, 0, n_rem, wm, wn, lane, obj, nullptr);
             __syncthreads();
             epilogue_store<false, Cfg>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
         } else {
@@ -589,11 +609,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     }
 
     float* rs_lds = p.rs_part ? rs_buf : nullptr;
+    const float* const bias_col = p.bias_per_row ? nullptr : p.bias;
+    const float* const bias_row = (p.bias_per_row && p.bias) ? p.bias + (size_t)tm * BM : nullptr;
     switch (p.act) {
-    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, p.bias, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
     }
     __syncthreads();
     unsigned char* c_tile = (unsigned char*)p.C +

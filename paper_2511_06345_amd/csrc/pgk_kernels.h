@@ -27,12 +27,36 @@ struct GemmArgs {
     unsigned int* rs_counter;  // [batch][tiles_m], zero before the launch and again after it
     float* ws;          // split-K partial products [batch][splits][M][N]
     int M, N, K, batch;
+    // Operand views.  Plain GEMM: a_batch_stride = M*K, b_batch_stride = K*N, ldb = N,
+    // b_tiles_per_tap = INT_MAX (fill_plain_views sets these).  a_batch_stride = 0 shares A
+    // between the batch entries.
+    long long a_batch_stride, b_batch_stride;   // elements between batch entries of A and of B
+    int ldb;                 // elements between rows of B
+    int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows
+    // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
+    // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
+    int b_tiles_per_tap, b_tap_step;
+    // Bounds-checked kernel, convolution read in place: conv_kw > 0 means B is the input
+    // x [batch][K / conv_kw][conv_len] and B[k][n] stands for
+    // x[k / conv_kw][n * conv_stride + (k % conv_kw) * conv_dil - conv_pad], zero outside.
+    int conv_kw, conv_stride, conv_pad, conv_dil, conv_len;
     int act;
     int splits;         // >= 1
     int k_slice;        // K elements per split (multiple of the K tile)
     int tiles_m, tiles_n;
     int group_m;        // tile rows per scheduling group
 };
+
+inline void fill_plain_views(GemmArgs& a)
+{
+    a.a_batch_stride = (long long)a.M * a.K;
+    a.b_batch_stride = (long long)a.K * a.N;
+    a.ldb = a.N;
+    a.bias_per_row = 0;
+    a.b_tiles_per_tap = 0x7fffffff;
+    a.b_tap_step = 0;
+    a.conv_kw = 0; a.conv_stride = 1; a.conv_pad = 0; a.conv_dil = 1; a.conv_len = 0;
+}
 
 // Tile geometry of the matrix-core kernels: a large and a small tile per element
 // type (same K tile), the small one for grids that would not fill the chip.
