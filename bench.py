@@ -53,6 +53,13 @@ REDUCE_DESCR = {
 }
 
 
+CONV_DESCR = {
+    "v1": "v1: fp32 conv1d [16, 64, 65536] * [128, 64, 3], stride 1, pad 1, bias + ReLU (matrix-core path)",
+    "v2": "v2: bf16 conv1d [8, 256, 16384] * [256, 256, 5], stride 1, pad 4, dilation 2, bias + SiLU (matrix-core path)",
+    "v3": "v3: fp32 conv1d [4, 48, 32768] * [64, 48, 5], stride 2, pad 2, bias (bounds-checked path)",
+}
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -171,6 +178,99 @@ def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, s
     return res
 
 
+def run_conv_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
+    """Times `steps` calls of pgk_conv1d on convolution workload `name`; returns a dict.
+    The calls rotate through `sets` copies of input and output at different addresses."""
+    cw = gen.CONV_WORKLOADS[name]
+    t0 = time.time()
+    x, w, bias = gen.make_conv_inputs(cw)
+    if cw.dtype == gen.BF16:
+        dx = torch.from_numpy(x.view(np.int16)).cuda().view(torch.bfloat16)
+        dw = torch.from_numpy(w.view(np.int16)).cuda().view(torch.bfloat16)
+    else:
+        dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    dbias = torch.from_numpy(bias).cuda()
+    log(f"[{name}] inputs generated and copied in {time.time() - t0:.1f} s")
+    need = pgk.conv1d_workspace_bytes(cw.B, cw.Cin, cw.L, cw.Cout, cw.Kw, cw.stride, cw.pad, cw.dilation, cw.dtype)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    xs = [dx] + [dx.clone() for _ in range(max(1, sets) - 1)]
+    ys = [torch.empty((cw.B, cw.Cout, cw.Lout), dtype=dx.dtype, device="cuda") for _ in xs]
+
+    def step(i):
+        pgk.conv1d(xs[i % len(xs)], dw, dbias, cw.act, cw.stride, cw.pad, cw.dilation, out=ys[i % len(xs)], workspace=ws)
+
+    for i in range(warmup):
+        step(i)
+    torch.cuda.synchronize()
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    t_start = time.perf_counter()
+    ev[0].record()
+    for i in range(steps):
+        step(warmup + i)
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t_start
+    per = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(steps)])
+    ms_per_step = wall * 1e3 / steps
+    res = {
+        "workload": CONV_DESCR[name],
+        "ms_per_step": ms_per_step,
+        "tflops": cw.flops / (ms_per_step * 1e-3) / 1e12,
+        "call_ms_avg": float(per.mean()),
+        "call_ms_median": float(np.median(per)),
+        "call_ms_min": float(per.min()),
+        "algorithmic_gbs": cw.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
+        "workspace_bytes": need,
+        "buffer_sets": len(xs),
+    }
+    res["hbm_frac_algorithmic"] = res["algorithmic_gbs"] / PEAK_HBM_GBS
+    if keep_host:
+        res["_host"] = (x, w, bias)
+    return res
+
+
+def conv_main(args, name, pgk, gen, torch):
+    """One JSON line for a convolution workload."""
+    cw = gen.CONV_WORKLOADS[name]
+    head = run_conv_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
+    x, w, bias = head.pop("_host")
+    dtype_key = "bf16" if cw.dtype == gen.BF16 else "f32"
+    fast = head["workspace_bytes"] > 0
+    # the matrix-core path is priced against the matrix peak of its type, the bounds-checked
+    # path (plain fp32 FMA) against the fp32 vector peak
+    peak = PEAK_TFLOPS[dtype_key] if fast else 157.3
+    achieved = cw.flops / (head["call_ms_avg"] * 1e-3) / 1e12
+    out = {
+        "metric": "conv1d+epilogue TFLOP/s on 1 MI355X",
+        "value": head["tflops"], "unit": "TFLOP/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": dtype_key,
+        "data": f"synthetic (seeded SplitMix64 generator, resident in HBM before timing; calls rotate through {head['buffer_sets']} copies)",
+        "config": {"workload": CONV_DESCR[name], "B": cw.B, "Cin": cw.Cin, "L": cw.L, "Cout": cw.Cout, "Kw": cw.Kw,
+                   "stride": cw.stride, "pad": cw.pad, "dilation": cw.dilation, "flops_per_step": cw.flops,
+                   "algorithmic_bytes_per_step": cw.algorithmic_bytes, "workspace_bytes": head["workspace_bytes"]},
+        "roofline": {"bound": "mfma" if fast else "alu",
+                     "kernel": "pgk::gemm_mfma_kernel on shifted views (+ pad and weight regrouping kernels)" if fast
+                               else "pgk::gemm_guarded_kernel reading the input in place",
+                     "achieved": achieved, "peak": peak, "unit": "TFLOP/s", "frac": achieved / peak,
+                     "launch_ms_avg": head["call_ms_avg"], "traffic": None,
+                     "hbm_frac_algorithmic": head["hbm_frac_algorithmic"]},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        oracle.build()
+        nb, nco = 1, min(cw.Cout, 16)
+        oracle.conv1d(x[:1, :, :64 + cw.Kw * cw.dilation], w[:1], None)      # loads the library
+        t0 = time.perf_counter()
+        oracle.conv1d(x[:nb], w[:nco], bias[:nco], cw.act, cw.stride, cw.pad, cw.dilation)
+        dt = time.perf_counter() - t0
+        fl = 2.0 * nb * nco * cw.Lout * cw.Cin * cw.Kw
+        out["cpu_baseline"] = {"value": fl / dt / 1e12, "unit": "TFLOP/s", "cores": oracle.num_threads(), "kind": "oracle",
+                               "sample": f"{nb} batch entry x {nco} output channels of {name} ({fl:.3e} flop in {dt:.2f} s, "
+                                         "direct loops in double, gcc -O2 -fopenmp)"}
+    print(json.dumps(out), flush=True)
+
+
 def reduce_main(args, name, pgk, gen, torch):
     """One JSON line for a reduction workload (bound: HBM)."""
     w = gen.REDUCE_WORKLOADS[name]
@@ -283,8 +383,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="c3", choices=sorted(DESCR) + sorted(REDUCE_DESCR),
-                    help="c1..c5: fused GEMM workloads (c3 is the headline); r1..r4: max-reduction workloads")
+    ap.add_argument("--workload", default="c3", choices=sorted(DESCR) + sorted(REDUCE_DESCR) + sorted(CONV_DESCR),
+                    help="c1..c5: fused GEMM workloads (c3 is the headline); r1..r4: max-reduction workloads; "
+                         "v1..v3: conv1d workloads")
     ap.add_argument("--others", action="store_true",
                     help="also time the other GEMM workloads and the reduction workloads (reported under 'others')")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -331,6 +432,9 @@ def main():
     name = args.workload
     if name in REDUCE_DESCR:
         reduce_main(args, name, pgk, gen, torch)
+        return
+    if name in CONV_DESCR:
+        conv_main(args, name, pgk, gen, torch)
         return
     w = gen.WORKLOADS[name]
     head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
@@ -392,6 +496,9 @@ def main():
             torch.cuda.empty_cache()
         for other in sorted(REDUCE_DESCR):
             others[other] = run_reduce_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
+            torch.cuda.empty_cache()
+        for other in sorted(CONV_DESCR):
+            others[other] = run_conv_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
             torch.cuda.empty_cache()
         out["others"] = others
     print(json.dumps(out), flush=True)

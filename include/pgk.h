@@ -146,6 +146,45 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx,
                    int64_t outer, int64_t red, int64_t inner, int dtype, void* stream);
 
 /*
+ * pgk_conv1d -- one-dimensional convolution with fused bias and activation (the paper's second
+ * case study, Section 4.4 "Conv Standard 1D"; no formula is given there, so this is the
+ * operator as deep-learning frameworks define it: cross-correlation with zero padding):
+ *
+ *     y[b][co][l] = act( bias[co] + sum_ci sum_k w[co][ci][k] * x[b][ci][l*stride + k*dilation - pad] )
+ *     Lout = floor((L + 2 pad - dilation (Kw - 1) - 1) / stride) + 1      (x outside [0, L) is 0)
+ *
+ *     x    [B][Cin][L]       float32 or bfloat16 (dtype), device pointer
+ *     w    [Cout][Cin][Kw]   same element type
+ *     bias [Cout]            float32, NULL = 0
+ *     y    [B][Cout][Lout]   same element type as x (bf16: round-to-nearest-even), fully overwritten
+ *
+ * Accumulation is float32.  Every size > 0, stride, dilation >= 1, pad >= 0, Lout >= 1, sizes
+ * within the index ranges of pgk_gemm_fused (else PGK_ERR_INVALID_ARG / PGK_ERR_UNSUPPORTED).
+ *
+ * With stride 1 the convolution runs on the matrix cores as a sum over the taps of GEMMs on
+ * shifted views of the input (no unfolded copy of the input is made), provided Cin is a
+ * multiple of the K tile (32 float32 / 64 bfloat16), Cout and Lout are at least 16, Lout is a
+ * multiple of 16 bytes of elements, for bfloat16 the dilation is even (or Kw = 1), and the pointers are
+ * 16-byte aligned.  That path needs `workspace` (device memory, 256-byte aligned, contents
+ * destroyed) of pgk_conv1d_workspace_bytes(...) bytes: the weights regrouped tap by tap and,
+ * when pad > 0 or L is not a multiple of 16 bytes, a zero-padded copy of the input.  Too small
+ * or NULL gives PGK_ERR_WORKSPACE.  Every other case is computed by a bounds-checked kernel
+ * that reads the input in place and needs no workspace (the query then returns 0).
+ */
+int pgk_conv1d(const void* x, const void* w, const float* bias, void* y,
+               int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw,
+               int64_t stride, int64_t pad, int64_t dilation, int act, int dtype,
+               void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace pgk_conv1d needs for this problem (0: none).  Pure host arithmetic,
+ * assuming 16-byte aligned pointers; 0 also for invalid arguments. */
+size_t pgk_conv1d_workspace_bytes(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw,
+                                  int64_t stride, int64_t pad, int64_t dilation, int dtype);
+
+/* Output length of the convolution, or 0 when the arguments give none.  Host arithmetic. */
+int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, int64_t dilation);
+
+/*
  * pgk_probe_mfma / pgk_probe_stream_read -- measurement aids, not operators: what the chip
  * sustains under its power limit, to read a kernel's numbers against (the paper's Section 3.2
  * lists matrix-unit activity and memory throughput among a performance engineer's evidence).

@@ -19,7 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
 EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_splitk_workspace_bytes",
-           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_probe_mfma", "pgk_probe_stream_read",
+           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_conv1d", "pgk_conv1d_workspace_bytes",
+           "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
            "pgk_release_scratch", "pgk_status_string", "pgk_version")
 
 _lib = None
@@ -53,6 +54,12 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_splitk_auto_splits.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_reduce_max.restype = ci
     lib.pgk_reduce_max.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp]
+    lib.pgk_conv1d.restype = ci
+    lib.pgk_conv1d.argtypes = [vp, vp, vp, vp] + [i64] * 8 + [ci, ci, vp, ctypes.c_size_t, vp]
+    lib.pgk_conv1d_workspace_bytes.restype = ctypes.c_size_t
+    lib.pgk_conv1d_workspace_bytes.argtypes = [i64] * 8 + [ci]
+    lib.pgk_conv1d_out_len.restype = i64
+    lib.pgk_conv1d_out_len.argtypes = [i64] * 5
     lib.pgk_probe_mfma.restype = ci
     lib.pgk_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.pgk_probe_stream_read.restype = ci
@@ -221,3 +228,47 @@ def probe_stream_read(src: torch.Tensor, sink: torch.Tensor, stream=None) -> int
     if rc != 0:
         raise PgkError(rc, "pgk_probe_stream_read")
     return nbytes
+
+
+def conv1d_out_len(L: int, Kw: int, stride: int = 1, pad: int = 0, dilation: int = 1) -> int:
+    return int(load_library().pgk_conv1d_out_len(L, Kw, stride, pad, dilation))
+
+
+def conv1d_workspace_bytes(B: int, Cin: int, L: int, Cout: int, Kw: int, stride: int, pad: int, dilation: int,
+                           dtype: int) -> int:
+    return int(load_library().pgk_conv1d_workspace_bytes(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype))
+
+
+def conv1d(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], act: int = ACT_NONE, stride: int = 1,
+           pad: int = 0, dilation: int = 1, out: Optional[torch.Tensor] = None,
+           workspace: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """y = act(conv1d(x, w) + bias) via pgk_conv1d.  x [B, Cin, L], w [Cout, Cin, Kw]: contiguous
+    float32 or bfloat16 device tensors; bias float32 [Cout] or None.  ``workspace``: uint8 device
+    tensor of at least ``conv1d_workspace_bytes(...)`` bytes, allocated here when None."""
+    lib = load_library()
+    if x.dim() != 3 or w.dim() != 3 or x.shape[1] != w.shape[1]:
+        raise ValueError("expected x [B, Cin, L] and w [Cout, Cin, Kw]")
+    if not (x.is_cuda and w.is_cuda and x.is_contiguous() and w.is_contiguous()):
+        raise ValueError("x and w must be contiguous device tensors")
+    if x.dtype == torch.float32 and w.dtype == torch.float32:
+        dtype = F32
+    elif x.dtype == torch.bfloat16 and w.dtype == torch.bfloat16:
+        dtype = BF16
+    else:
+        raise TypeError("x and w must both be float32 or both bfloat16")
+    B, Cin, L = (int(d) for d in x.shape)
+    Cout, _, Kw = (int(d) for d in w.shape)
+    Lout = conv1d_out_len(L, Kw, stride, pad, dilation)
+    if Lout <= 0:
+        raise ValueError("the convolution has no output for these sizes")
+    need = conv1d_workspace_bytes(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype)
+    if workspace is None and need:
+        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
+    y = out if out is not None else torch.empty((B, Cout, Lout), dtype=x.dtype, device=x.device)
+    rc = lib.pgk_conv1d(x.data_ptr(), w.data_ptr(), _check_bias(bias, Cout) or None, y.data_ptr(),
+                        B, Cin, L, Cout, Kw, stride, pad, dilation, int(act), dtype,
+                        workspace.data_ptr() if workspace is not None else None,
+                        workspace.numel() if workspace is not None else 0, _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_conv1d")
+    return y

@@ -281,6 +281,134 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
+}  // extern "C"
+
+namespace {
+
+struct ConvPlan {
+    bool valid;          // arguments make sense
+    bool fast;           // matrix-core path
+    int64_t Lout;
+    int64_t Lp;          // row length of the padded input copy (fast path), 0 = the input is used as it is
+    size_t w_bytes, x_bytes;   // workspace parts (fast path): regrouped weights, padded input
+};
+
+size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw, int64_t stride, int64_t pad,
+                     int64_t dilation, int dtype)
+{
+    ConvPlan pl{};
+    if (B <= 0 || Cin <= 0 || L <= 0 || Cout <= 0 || Kw <= 0 || stride <= 0 || pad < 0 || dilation <= 0) return pl;
+    if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return pl;
+    if (B > kMaxDim || Cin > kMaxDim || L > kMaxDim || Cout > kMaxDim || Kw > kMaxDim || pad > kMaxDim ||
+        dilation > kMaxDim || stride > kMaxDim) return pl;
+    const int64_t span = L + 2 * pad - dilation * (Kw - 1) - 1;
+    if (span < 0) return pl;
+    pl.Lout = span / stride + 1;
+    if (Cin * Kw > kMaxDim) return pl;
+    pl.valid = true;
+    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = 16 / es;
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
+    const int64_t K = Cin * Kw;
+    const bool needs_copy = pad > 0 || L % epc != 0;
+    const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
+    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 &&
+              (dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1) &&
+              (int64_t)t.bm * K * es < (1LL << 32) && (int64_t)t.bk * Lp * es + dilation * Kw * es < (1LL << 32);
+    if (pl.fast) {
+        pl.Lp = needs_copy ? Lp : 0;
+        pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
+        pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es, 256) : 0;
+    }
+    return pl;
+}
+
+}  // namespace
+
+extern "C" {
+
+int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, int64_t dilation)
+{
+    if (L <= 0 || Kw <= 0 || stride <= 0 || pad < 0 || dilation <= 0) return 0;
+    const int64_t span = L + 2 * pad - dilation * (Kw - 1) - 1;
+    return span < 0 ? 0 : span / stride + 1;
+}
+
+size_t pgk_conv1d_workspace_bytes(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw, int64_t stride,
+                                  int64_t pad, int64_t dilation, int dtype)
+{
+    const ConvPlan pl = plan_conv1d(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype);
+    return (pl.valid && pl.fast) ? pl.w_bytes + pl.x_bytes : 0;
+}
+
+int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t B, int64_t Cin, int64_t L,
+               int64_t Cout, int64_t Kw, int64_t stride, int64_t pad, int64_t dilation, int act, int dtype,
+               void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !w || !y) return PGK_ERR_INVALID_ARG;
+    if (act < PGK_ACT_NONE || act > PGK_ACT_SILU) return PGK_ERR_INVALID_ARG;
+    ConvPlan pl = plan_conv1d(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype);
+    if (!pl.valid) {
+        // tell "out of range" from "makes no sense"
+        if (B > 0 && Cin > 0 && L > 0 && Cout > 0 && Kw > 0 && stride > 0 && pad >= 0 && dilation > 0 &&
+            (dtype == PGK_DTYPE_F32 || dtype == PGK_DTYPE_BF16) && pgk_conv1d_out_len(L, Kw, stride, pad, dilation) > 0)
+            return PGK_ERR_UNSUPPORTED;
+        return PGK_ERR_INVALID_ARG;
+    }
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
+    if ((long double)B * Cout * pl.Lout >= 4.6e18L || (long double)B * Cin * L >= 4.6e18L) return PGK_ERR_UNSUPPORTED;
+    if (pl.fast && !(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(bias))) pl.fast = false;
+
+    GemmArgs a{};
+    a.bias = bias; a.C = y; a.ws = nullptr; a.rs_part = nullptr;
+    a.M = (int)Cout; a.N = (int)pl.Lout; a.K = (int)(Cin * Kw); a.batch = (int)B;
+    pgk::fill_plain_views(a);
+    a.a_batch_stride = 0;                 // the weights are shared by the batch entries
+    a.bias_per_row = 1;                   // one bias per output channel = per row
+    a.act = act; a.splits = 1;
+
+    if (pl.fast) {
+        if (!workspace || (reinterpret_cast<uintptr_t>(workspace) & 255u) || workspace_bytes < pl.w_bytes + pl.x_bytes)
+            return PGK_ERR_WORKSPACE;
+        unsigned char* wr = static_cast<unsigned char*>(workspace);
+        unsigned char* xp = wr + pl.w_bytes;
+        if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+        const void* bsrc = x;
+        int64_t ldb = L;
+        if (pl.Lp) {
+            if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+            bsrc = xp;
+            ldb = pl.Lp;
+        }
+        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B);
+        if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked everything the kernel needs
+        a.A = wr; a.B = bsrc;
+        a.b_batch_stride = Cin * ldb;
+        a.ldb = (int)ldb;
+        a.b_tiles_per_tap = (int)(Cin / path.tile.bk);
+        a.b_tap_step = (int)dilation;
+        a.k_slice = a.K;
+        a.tiles_m = (int)((Cout + path.tile.bm - 1) / path.tile.bm);
+        a.tiles_n = (int)((pl.Lout + path.tile.bn - 1) / path.tile.bn);
+        if ((long double)a.tiles_m * a.tiles_n * B > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+        a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+        return pgk::launch_gemm_mfma(a, dtype, path.small, 0, st) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+    }
+    // bounds-checked kernel, input read in place
+    const pgk::TileShape t = pgk::guarded_tile_shape();
+    a.A = w; a.B = x;
+    a.b_batch_stride = Cin * L;
+    a.conv_kw = (int)Kw; a.conv_stride = (int)stride; a.conv_pad = (int)pad; a.conv_dil = (int)dilation; a.conv_len = (int)L;
+    a.k_slice = (int)(((a.K + t.bk - 1) / t.bk) * t.bk);
+    a.tiles_m = (int)((Cout + t.bm - 1) / t.bm);
+    a.tiles_n = (int)((pl.Lout + t.bn - 1) / t.bn);
+    if ((long double)a.tiles_m * a.tiles_n * B > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+    return pgk::launch_gemm_guarded(a, dtype, 0, st) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
 int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream)
 {
     if (!sink || iters < 1 || iters > (1 << 20)) return PGK_ERR_INVALID_ARG;

@@ -1,0 +1,90 @@
+// Helpers of the one-dimensional convolution (PRAGMA's second case study, Section 4.4
+// "Conv Standard 1D"; the operator is the usual cross-correlation with zero padding).
+// The convolution itself runs in the GEMM kernels: with stride 1,
+//     y[b] (Cout x Lout) = sum over taps k of  W_k (Cout x Cin)  *  x[b] shifted by k * dilation - pad,
+// so a K loop that walks tap after tap over the input channels reads, for each K tile, a plain
+// sub-block of the padded input as its B operand.  What is needed beside that:
+//   * conv_pad_input: the input with `pad` zeros in front of every row and zeros after it
+//     up to a row length that keeps rows 16-byte aligned (skipped when there is no padding
+//     and the rows are aligned already);
+//   * conv_repack_weights: w[Cout][Cin][Kw] -> w'[Cout][Kw][Cin], so that the K index runs
+//     over the channels inside a tap.
+// Both are streaming copies.
+#include <hip/hip_runtime.h>
+
+#include "pgk_device.h"
+#include "pgk_kernels.h"
+
+namespace pgk {
+
+namespace {
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp,
+                                                             long long rows, int L, int Lp, int pad)
+{
+    // one workgroup row-slab: blockIdx.y = row (batch entry x channel), blockIdx.x = slab of 1024 outputs
+    const long long row = blockIdx.y;
+    if (row >= rows) return;
+    const int j0 = blockIdx.x * 1024 + threadIdx.x;
+    const T* src = x + (size_t)row * (size_t)L;
+    T* dst = xp + (size_t)row * (size_t)Lp;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int j = j0 + 256 * u;
+        if (j < Lp) {
+            const int s = j - pad;
+            dst[j] = (s >= 0 && s < L) ? src[s] : T(0);
+        }
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __restrict__ w, T* __restrict__ wr,
+                                                                  int Cout, int Cin, int Kw)
+{
+    const long long total = (long long)Cout * Cin * Kw;
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;     // index into wr: (co, k, ci)
+    if (t >= total) return;
+    const int ci = (int)(t % Cin);
+    const long long r = t / Cin;
+    const int k = (int)(r % Kw);
+    const long long co = r / Kw;
+    wr[t] = w[(co * Cin + ci) * Kw + k];
+}
+
+}  // namespace
+
+hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s)
+{
+    if (rows <= 0 || rows > 65535LL * 65535LL) return hipErrorInvalidValue;
+    // grid.y is limited to 65535: fold the rows when there are more
+    const unsigned int slabs = (unsigned int)((Lp + 1023) / 1024);
+    for (long long r0 = 0; r0 < rows; r0 += 65535) {
+        const long long n = rows - r0 < 65535 ? rows - r0 : 65535;
+        const dim3 grid(slabs, (unsigned int)n);
+        if (dtype == DT_BF16)
+            hipLaunchKernelGGL(conv_pad_input_kernel<unsigned short>, grid, dim3(256), 0, s,
+                               (const unsigned short*)x + (size_t)r0 * L, (unsigned short*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
+        else
+            hipLaunchKernelGGL(conv_pad_input_kernel<float>, grid, dim3(256), 0, s,
+                               (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
+    }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s)
+{
+    const long long total = (long long)Cout * Cin * Kw;
+    const long long blocks = (total + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(conv_repack_weights_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw);
+    else
+        hipLaunchKernelGGL(conv_repack_weights_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const float*)w, (float*)wr, Cout, Cin, Kw);
+    return hipGetLastError();
+}
+
+}  // namespace pgk

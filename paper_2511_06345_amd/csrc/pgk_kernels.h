@@ -98,6 +98,11 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
 hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int* idx, float* pv, int* pi,
                              long long outer, long long red, long long inner, int dtype, hipStream_t s);
 
+// Convolution helpers (pgk_conv.hip): xp[row][j] = x[row][j - pad] inside [0, L), else 0, for
+// `rows` rows of length L -> Lp; wr[co][k][ci] = w[co][ci][k].
+hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s);
+hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s);
+
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming
 // read of `bytes` (16-byte aligned).  `sink`: one float the kernels never really write.

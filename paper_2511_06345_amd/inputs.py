@@ -283,3 +283,64 @@ def make_reduce_input(w: ReduceWorkload, salt: int = 0) -> np.ndarray:
         block = f32_to_bf16_bits(block)
     reps = (n + block.size - 1) // block.size
     return np.tile(block, reps)[:n].reshape(w.shape)
+
+
+# ---- workloads of the one-dimensional convolution ----
+
+@dataclass(frozen=True)
+class ConvWorkload:
+    name: str
+    index: int
+    dtype: int
+    B: int
+    Cin: int
+    L: int
+    Cout: int
+    Kw: int
+    stride: int
+    pad: int
+    dilation: int
+    act: int
+
+    @property
+    def elem_bytes(self) -> int:
+        return 2 if self.dtype == BF16 else 4
+
+    @property
+    def Lout(self) -> int:
+        return (self.L + 2 * self.pad - self.dilation * (self.Kw - 1) - 1) // self.stride + 1
+
+    @property
+    def flops(self) -> float:
+        return 2.0 * self.B * self.Cout * self.Lout * self.Cin * self.Kw
+
+    @property
+    def algorithmic_bytes(self) -> float:
+        """Read x, w and bias once, write y once."""
+        e = self.elem_bytes
+        return float((self.B * self.Cin * self.L + self.Cout * self.Cin * self.Kw + self.B * self.Cout * self.Lout) * e
+                     + self.Cout * 4)
+
+
+# A long-sequence fp32 convolution with "same" padding, a channel-heavy bf16 one (even
+# dilation), and a strided one that takes the general path.
+CONV_WORKLOADS = {
+    "v1": ConvWorkload("v1", 21, F32, 16, 64, 65536, 128, 3, 1, 1, 1, ACT_RELU),
+    "v2": ConvWorkload("v2", 22, BF16, 8, 256, 16384, 256, 5, 1, 4, 2, ACT_SILU),
+    "v3": ConvWorkload("v3", 23, F32, 4, 48, 32768, 64, 5, 2, 2, 1, ACT_NONE),
+}
+
+
+def make_conv_inputs(cw: ConvWorkload, salt: int = 0):
+    """(x [B, Cin, L], w [Cout, Cin, Kw], bias [Cout]): x uniform in [-1, 1) (one seeded block of
+    2**24 values repeated when the tensor is larger), w normal with standard deviation
+    1/sqrt(Cin Kw), bias normal 0.1.  float32, or uint16 bf16 bit patterns for x and w."""
+    n = cw.B * cw.Cin * cw.L
+    block = uniform(tensor_seed(cw.index, 1, salt), min(n, _REDUCE_BLOCK), -1.0, 1.0)
+    x = np.tile(block, (n + block.size - 1) // block.size)[:n].reshape(cw.B, cw.Cin, cw.L)
+    w = normal(tensor_seed(cw.index, 2, salt), cw.Cout * cw.Cin * cw.Kw, _inv_sqrt(cw.Cin * cw.Kw))
+    w = w.reshape(cw.Cout, cw.Cin, cw.Kw)
+    bias = normal(tensor_seed(cw.index, 3, salt), cw.Cout, 0.1)
+    if cw.dtype == BF16:
+        x, w = f32_to_bf16_bits(x), f32_to_bf16_bits(w)
+    return x, w, bias

@@ -106,6 +106,36 @@ def test_reduce_max_rejects_bad_arguments_on_the_host(lib):
     assert call(outer=1 << 40, inner=1 << 40) == UNSUPPORTED
 
 
+def test_conv1d_host_arithmetic_and_validation(lib):
+    F32, BF16 = gen.F32, gen.BF16
+    assert binding.conv1d_out_len(4, 3) == 2 and binding.conv1d_out_len(4, 3, 2, 1, 1) == 2
+    assert binding.conv1d_out_len(5, 3, 1, 0, 3) == 0 and binding.conv1d_out_len(0, 3) == 0
+    # matrix-core path: regrouped weights + padded input copy (rows rounded up to 16 bytes)
+    need = binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, F32)
+    assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1004 * 4
+    # no padding and aligned rows: only the weights
+    assert binding.conv1d_workspace_bytes(2, 64, 1024, 32, 3, 1, 0, 2, F32) == 32 * 64 * 3 * 4
+    # stride 2, channels not a multiple of the K tile, odd dilation in bf16, odd output length: in place, no workspace
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 2, 1, 1, F32) == 0
+    assert binding.conv1d_workspace_bytes(2, 48, 1000, 32, 3, 1, 1, 1, F32) == 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, BF16) == 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 2, 2, BF16) > 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 0
+
+    def call(x=0x1000, w=0x2000, y=0x3000, B=1, Cin=4, L=16, Cout=4, Kw=3, stride=1, pad=0, dil=1, act=0, dtype=0,
+             ws=None, ws_bytes=0):
+        return lib.pgk_conv1d(x, w, None, y, B, Cin, L, Cout, Kw, stride, pad, dil, act, dtype, ws, ws_bytes, None)
+    assert call(x=None) == INVALID and call(w=None) == INVALID and call(y=None) == INVALID
+    for bad in ({"B": 0}, {"Cin": 0}, {"Kw": 0}, {"stride": 0}, {"pad": -1}, {"dil": 0}, {"act": 9}, {"dtype": 3},
+                {"L": 2, "Kw": 3}):
+        assert call(**bad) == INVALID, bad
+    assert call(Cin=1 << 20, Kw=1 << 20, L=1 << 21) == UNSUPPORTED
+    # matrix-core shape without its workspace
+    assert call(B=2, Cin=64, L=1024, Cout=32, Kw=3, pad=1) == WORKSPACE
+    assert call(B=2, Cin=64, L=1024, Cout=32, Kw=3, pad=1, ws=0x10000, ws_bytes=100) == WORKSPACE
+    assert call(B=2, Cin=64, L=1024, Cout=32, Kw=3, pad=1, ws=0x10010, ws_bytes=1 << 30) == WORKSPACE     # misaligned
+
+
 def test_probes_reject_bad_arguments_on_the_host(lib):
     assert lib.pgk_probe_mfma(0, 1, 10, None, None, None) == INVALID
     assert lib.pgk_probe_mfma(5, 1, 10, 0x1000, None, None) == INVALID

@@ -1,0 +1,138 @@
+"""GPU parity of conv1d: the HIP path (through the C ABI) against the CPU oracle on the same
+seeded inputs.  Error bar as for the GEMM it is computed by: max |g - r| / max(|r|, RMS(r))
+<= 1e-4 for fp32 and <= 2e-2 for bf16 with fp32 accumulation; integer-valued inputs with the
+identity activation must match exactly."""
+import numpy as np
+import pytest
+
+from paper_2511_06345_amd import inputs as gen
+from util import TOL, c_to_numpy, rel_err, to_device
+
+pytestmark = pytest.mark.gpu
+NONE, RELU, GELU, SILU = gen.ACT_NONE, gen.ACT_RELU, gen.ACT_GELU_TANH, gen.ACT_SILU
+F32, BF16 = gen.F32, gen.BF16
+
+
+@pytest.fixture(scope="module")
+def pgk():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    from paper_2511_06345_amd import binding
+    binding.load_library()
+    return binding
+
+
+def run(pgk, x, w, bias, act, dtype, stride, pad, dilation):
+    import torch
+    dx, dw = to_device(x, dtype), to_device(w, dtype)
+    db = torch.from_numpy(bias).cuda() if bias is not None else None
+    y = pgk.conv1d(dx, dw, db, act, stride, pad, dilation)
+    torch.cuda.synchronize()
+    return c_to_numpy(y, dtype)
+
+
+def random_case(dtype, B, Cin, L, Cout, Kw, seed):
+    x = gen.uniform(gen.tensor_seed(98, 1, seed), B * Cin * L, -1.0, 1.0).reshape(B, Cin, L)
+    w = gen.uniform(gen.tensor_seed(98, 2, seed), Cout * Cin * Kw, -1.0, 1.0).reshape(Cout, Cin, Kw)
+    bias = gen.normal(gen.tensor_seed(98, 3, seed), Cout, 0.5)
+    if dtype == BF16:
+        x, w = gen.f32_to_bf16_bits(x), gen.f32_to_bf16_bits(w)
+    return x, w, bias
+
+
+def int_case(dtype, B, Cin, L, Cout, Kw, seed):
+    x = gen.small_ints(gen.tensor_seed(98, 4, seed), B * Cin * L).reshape(B, Cin, L)
+    w = gen.small_ints(gen.tensor_seed(98, 5, seed), Cout * Cin * Kw).reshape(Cout, Cin, Kw)
+    if dtype == BF16:
+        x, w = gen.f32_to_bf16_bits(x), gen.f32_to_bf16_bits(w)
+    return x, w
+
+
+# (B, Cin, L, Cout, Kw, stride, pad, dilation).  FAST: stride 1, channels a multiple of the K
+# tile, output length a multiple of 16 bytes -> matrix-core path (shifted views, several
+# taps, padded copy or not, small and large tiles, ragged Cout and Lout tiles).
+FAST = {
+    F32: [(2, 32, 256, 32, 3, 1, 1, 1), (1, 64, 1024, 48, 5, 1, 2, 1), (3, 32, 520, 130, 3, 1, 1, 1),
+          (2, 96, 300, 64, 1, 1, 0, 1), (2, 32, 1028, 20, 4, 1, 3, 2), (1, 32, 1024, 64, 7, 1, 9, 3),
+          (40, 64, 2048, 128, 3, 1, 1, 1), (2, 64, 4096, 256, 3, 1, 0, 2)],
+    BF16: [(2, 64, 256, 32, 3, 1, 2, 2), (1, 128, 1024, 48, 5, 1, 4, 2), (3, 64, 520, 130, 1, 1, 0, 1),
+           (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8)],
+}
+# everything else: the bounds-checked kernel reading the input in place
+GENERAL = [(1, 1, 9, 1, 3, 1, 0, 1), (2, 3, 17, 4, 3, 1, 1, 1), (2, 5, 50, 7, 5, 2, 2, 1), (1, 2, 130, 70, 4, 3, 5, 2),
+           (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (1, 7, 300, 5, 9, 1, 0, 3), (2, 64, 256, 8, 3, 1, 1, 1)]
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("act", [NONE, SILU])
+def test_matrix_core_path(pgk, oracle, dtype, act):
+    for cfg in FAST[dtype]:
+        B, Cin, L, Cout, Kw, stride, pad, dilation = cfg
+        assert pgk.conv1d_workspace_bytes(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype) > 0, cfg
+        x, w, bias = random_case(dtype, B, Cin, L, Cout, Kw, seed=L + Kw)
+        ref = oracle.conv1d(x, w, bias, act, stride, pad, dilation)
+        got = run(pgk, x, w, bias, act, dtype, stride, pad, dilation)
+        assert got.shape == ref.shape
+        e = rel_err(got, ref)
+        assert e <= TOL[dtype], f"{cfg} act {act}: error {e:.3e}"
+        xi, wi = int_case(dtype, B, Cin, L, Cout, Kw, seed=L)
+        ref = oracle.conv1d(xi, wi, None, NONE, stride, pad, dilation)
+        got = run(pgk, xi, wi, None, NONE, dtype, stride, pad, dilation)
+        if dtype == BF16:
+            ref = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(got, ref), f"{cfg}: integer inputs"
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("act", [NONE, RELU, GELU])
+def test_general_path(pgk, oracle, dtype, act):
+    for cfg in GENERAL:
+        B, Cin, L, Cout, Kw, stride, pad, dilation = cfg
+        assert pgk.conv1d_workspace_bytes(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype) == 0, cfg
+        x, w, bias = random_case(dtype, B, Cin, L, Cout, Kw, seed=L + 3 * Kw)
+        ref = oracle.conv1d(x, w, bias, act, stride, pad, dilation)
+        got = run(pgk, x, w, bias, act, dtype, stride, pad, dilation)
+        e = rel_err(got, ref)
+        assert e <= TOL[dtype], f"{cfg} act {act}: error {e:.3e}"
+        xi, wi = int_case(dtype, B, Cin, L, Cout, Kw, seed=L)
+        ref = oracle.conv1d(xi, wi, None, NONE, stride, pad, dilation)
+        got = run(pgk, xi, wi, None, NONE, dtype, stride, pad, dilation)
+        if dtype == BF16:
+            ref = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref.astype(np.float32))).astype(np.float64)
+        assert np.array_equal(got, ref), f"{cfg}: integer inputs"
+
+
+def test_both_paths_agree_and_are_deterministic(pgk):
+    """The same problem through the matrix-core path and, made ineligible by a misaligned
+    input pointer, through the bounds-checked kernel."""
+    import torch
+    B, Cin, L, Cout, Kw = 2, 32, 512, 40, 3
+    x, w = int_case(F32, B, Cin, L, Cout, Kw, seed=3)
+    dx, dw = torch.from_numpy(x).cuda(), torch.from_numpy(w).cuda()
+    a = pgk.conv1d(dx, dw, None, NONE, 1, 1, 1)
+    a2 = pgk.conv1d(dx, dw, None, NONE, 1, 1, 1)
+    flat = torch.cat([torch.zeros(1, device="cuda"), dx.reshape(-1)])
+    off = flat[1:].view(B, Cin, L)
+    b = pgk.conv1d(off, dw, None, NONE, 1, 1, 1)
+    torch.cuda.synchronize()
+    assert torch.equal(a, a2) and torch.equal(a, b)
+
+
+@pytest.mark.parametrize("name", sorted(gen.CONV_WORKLOADS))
+def test_conv_workloads_sampled(pgk, oracle, name):
+    """The benchmark's convolution workloads at full size; the oracle evaluates a seeded sample
+    of batch entries and output channels in full."""
+    import torch
+    cw = gen.CONV_WORKLOADS[name]
+    x, w, bias = gen.make_conv_inputs(cw)
+    dx, dw = to_device(x, cw.dtype), to_device(w, cw.dtype)
+    y = pgk.conv1d(dx, dw, torch.from_numpy(bias).cuda(), cw.act, cw.stride, cw.pad, cw.dilation)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    bs = sorted(set([0, cw.B - 1] + rng.integers(0, cw.B, 1).tolist()))
+    cos = sorted(set([0, cw.Cout - 1] + rng.integers(0, cw.Cout, 6).tolist()))
+    for b in bs:
+        ref = oracle.conv1d(x[b:b + 1], w[cos], bias[cos], cw.act, cw.stride, cw.pad, cw.dilation)[0]
+        got = c_to_numpy(y[b][cos], cw.dtype)
+        e = rel_err(got, ref)
+        assert e <= TOL[cw.dtype], f"{name} batch {b}: error {e:.3e}"
