@@ -289,8 +289,20 @@ struct ConvPlan {
     bool valid;          // arguments make sense
     bool fast;           // matrix-core path
     int64_t Lout;
-    int64_t Lp;          // row length of the padded input copy (fast path), 0 = the input is used as it is
-    size_t w_bytes, x_bytes;   // workspace parts (fast path): regrouped weights, padded input
+    // matrix-core path, where the B operand comes from:
+    //   strips: the input itself; the tile columns whose reads would leave a row (listed in
+    //           edge_tn) read zero-padded strips of edge_w columns instead;
+    //   else:   a zero-padded copy of the whole input with rows of Lp elements (Lp = 0: the
+    //           input as it is -- no padding and aligned rows)
+    bool strips;
+    int n_edges;
+    int edge_tn[3];
+    int edge_first_col[3];
+    int64_t edge_w;
+    int64_t Lp;
+    bool small_tile;
+    pgk::TileShape tile;
+    size_t w_bytes, x_bytes;   // workspace parts: regrouped weights; padded input or strips
 };
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -313,12 +325,36 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     const int64_t K = Cin * Kw;
     const bool needs_copy = pad > 0 || L % epc != 0;
     const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
-    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 &&
-              (dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1) &&
+    const bool taps_even = dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1;
+    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 && taps_even &&
               (int64_t)t.bm * K * es < (1LL << 32) && (int64_t)t.bk * Lp * es + dilation * Kw * es < (1LL << 32);
-    if (pl.fast) {
+    if (!pl.fast) return pl;
+    // the tile shape the GEMM will use (same rule as for a plain GEMM)
+    const long double wgs = (long double)((Cout + t.bm - 1) / t.bm) * ((pl.Lout + t.bn - 1) / t.bn) * B;
+    pl.small_tile = wgs < 0.75L * kNumCUs;
+    pl.tile = pgk::mfma_tile_shape(dtype, pl.small_tile);
+    pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
+    // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
+    // halo and the padding no wider than a tile, and few enough rows for one strip launch.
+    const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
+    pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && B * Cin <= 65535;
+    if (pl.strips) {
+        const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
+        pl.edge_w = (int64_t)round_up((size_t)(bn + halo), (size_t)epc);
+        pl.n_edges = 0;
+        if (pad > 0) {
+            const int64_t r0 = pl.Lout > pad ? (pl.Lout - pad) / bn : 0;     // first tile column reading past the end
+            for (int64_t tn = 0; tn < tiles_n; ++tn)
+                if (tn == 0 || tn >= r0) {
+                    pl.edge_tn[pl.n_edges] = (int)tn;
+                    pl.edge_first_col[pl.n_edges] = (int)(tn * bn - pad);
+                    ++pl.n_edges;
+                }
+        }
+        pl.x_bytes = round_up((size_t)pl.n_edges * (size_t)B * (size_t)Cin * (size_t)pl.edge_w * (size_t)es, 256);
+        pl.Lp = 0;
+    } else {
         pl.Lp = needs_copy ? Lp : 0;
-        pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
         pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es, 256) : 0;
     }
     return pl;
@@ -377,13 +413,25 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
         if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
         const void* bsrc = x;
         int64_t ldb = L;
-        if (pl.Lp) {
+        if (pl.strips) {
+            if (pl.n_edges > 0) {
+                if (pgk::launch_conv_edge_strips(x, xp, B * Cin, (int)L, (int)pl.edge_w, pl.n_edges, pl.edge_first_col,
+                                                 dtype, st) != hipSuccess) return PGK_ERR_HIP;
+                for (int e = 0; e < pl.n_edges; ++e) {
+                    a.edge_tn[e] = pl.edge_tn[e];
+                    a.edge_B[e] = xp + (size_t)e * (size_t)(B * Cin) * (size_t)pl.edge_w * (size_t)es;
+                }
+                a.edge_ldb = (int)pl.edge_w;
+                a.edge_batch_stride = Cin * pl.edge_w;
+            }
+            a.b_col_shift = -(int)pad;
+        } else if (pl.Lp) {
             if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, dtype, st) != hipSuccess) return PGK_ERR_HIP;
             bsrc = xp;
             ldb = pl.Lp;
         }
         const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B);
-        if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked everything the kernel needs
+        if (!path.mfma || path.small != pl.small_tile) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
         a.b_batch_stride = Cin * ldb;
         a.ldb = (int)ldb;

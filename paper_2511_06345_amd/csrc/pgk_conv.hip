@@ -39,6 +39,21 @@ __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict
     }
 }
 
+struct EdgeCols { int first[3]; };
+
+// strips[e][row][j] = x[row][first[e] + j] inside [0, L), else 0; blockIdx.y = row, blockIdx.z = e
+template <typename T>
+__global__ __launch_bounds__(256) void conv_edge_strips_kernel(const T* __restrict__ x, T* __restrict__ strips,
+                                                               long long rows, int L, int W, EdgeCols cols)
+{
+    const long long row = blockIdx.y;
+    const int e = blockIdx.z;
+    const int j = blockIdx.x * 256 + threadIdx.x;
+    if (row >= rows || j >= W) return;
+    const long long s = (long long)cols.first[e] + j;
+    strips[((size_t)e * (size_t)rows + (size_t)row) * (size_t)W + j] = (s >= 0 && s < L) ? x[(size_t)row * (size_t)L + (size_t)s] : T(0);
+}
+
 template <typename T>
 __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __restrict__ w, T* __restrict__ wr,
                                                                   int Cout, int Cin, int Kw)
@@ -70,6 +85,21 @@ hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L,
             hipLaunchKernelGGL(conv_pad_input_kernel<float>, grid, dim3(256), 0, s,
                                (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_edge_strips(const void* x, void* strips, long long rows, int L, int W, int n_edges,
+                                   const int* first_col, int dtype, hipStream_t s)
+{
+    if (rows <= 0 || rows > 65535 || n_edges < 1 || n_edges > 3) return hipErrorInvalidValue;
+    EdgeCols cols{};
+    for (int e = 0; e < n_edges; ++e) cols.first[e] = first_col[e];
+    const dim3 grid((unsigned int)((W + 255) / 256), (unsigned int)rows, (unsigned int)n_edges);
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(conv_edge_strips_kernel<unsigned short>, grid, dim3(256), 0, s, (const unsigned short*)x,
+                           (unsigned short*)strips, rows, L, W, cols);
+    else
+        hipLaunchKernelGGL(conv_edge_strips_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)strips, rows, L, W, cols);
     return hipGetLastError();
 }
 

@@ -214,10 +214,25 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     const unsigned char* Ag = (const unsigned char*)p.A +
         ((size_t)b * (size_t)p.a_batch_stride + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
-    const unsigned char* Bg = (const unsigned char*)p.B +
-        ((size_t)b * (size_t)p.b_batch_stride + (size_t)k_begin * p.ldb + (size_t)tn * BN) * ES;
+    // where this tile column's B operand lives: the B array itself, its columns shifted by
+    // b_col_shift (0 for a GEMM), or, for an edge tile column of a convolution, a strip
+    const unsigned char* b_src = (const unsigned char*)p.B;
+    int ldb = p.ldb;
+    long long b_batch_stride = p.b_batch_stride;
+    long long b_col0 = (long long)tn * BN + p.b_col_shift;
+#pragma unroll
+    for (int e = 0; e < 3; ++e) {
+        if (p.edge_B[e] && p.edge_tn[e] == tn) {
+            b_src = (const unsigned char*)p.edge_B[e];
+            ldb = p.edge_ldb;
+            b_batch_stride = p.edge_batch_stride;
+            b_col0 = 0;
+        }
+    }
+    const unsigned char* Bg = b_src +
+        ((long long)b * b_batch_stride + (long long)k_begin * ldb + b_col0) * ES;
     const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
-    const size_t b_step = (size_t)BK * p.ldb * ES;     // bytes per K tile down B
+    const size_t b_step = (size_t)BK * ldb * ES;       // bytes per K tile down B
     // one past the last byte of A and of B: copies of a partial K tile run past the end of a
     // row (into the next row, harmless) and, for the last row, past the end of the array,
     // where the buffer resource's size check makes them read nothing
@@ -250,7 +265,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
         constexpr int EPC = 16 / ES;                      // elements per chunk
         const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
-        voff_b[t] = (unsigned int)kr * (unsigned int)p.ldb * ES + (unsigned int)cg * 16u;
+        voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
     }
 
     auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {

@@ -36,6 +36,15 @@ struct GemmArgs {
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
     // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
     int b_tiles_per_tap, b_tap_step;
+    // Matrix-core kernels, convolution without a padded copy of the input: the columns a tile
+    // reads start b_col_shift (= -pad) before its output columns; the (at most three) tile
+    // columns whose reads would leave the rows read a small zero-padded strip instead:
+    // edge_B[e] [batch][rows][edge_ldb], holding the columns of tile column edge_tn[e].
+    int b_col_shift;
+    const void* edge_B[3];
+    int edge_tn[3];
+    int edge_ldb;
+    long long edge_batch_stride;
     // Bounds-checked kernel, convolution read in place: conv_kw > 0 means B is the input
     // x [batch][K / conv_kw][conv_len] and B[k][n] stands for
     // x[k / conv_kw][n * conv_stride + (k % conv_kw) * conv_dil - conv_pad], zero outside.
@@ -55,6 +64,10 @@ inline void fill_plain_views(GemmArgs& a)
     a.bias_per_row = 0;
     a.b_tiles_per_tap = 0x7fffffff;
     a.b_tap_step = 0;
+    a.b_col_shift = 0;
+    for (int e = 0; e < 3; ++e) { a.edge_B[e] = nullptr; a.edge_tn[e] = -1; }
+    a.edge_ldb = 0;
+    a.edge_batch_stride = 0;
     a.conv_kw = 0; a.conv_stride = 1; a.conv_pad = 0; a.conv_dil = 1; a.conv_len = 0;
 }
 
@@ -101,6 +114,9 @@ hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int
 // Convolution helpers (pgk_conv.hip): xp[row][j] = x[row][j - pad] inside [0, L), else 0, for
 // `rows` rows of length L -> Lp; wr[co][k][ci] = w[co][ci][k].
 hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s);
+// strip e (e < n_edges) of S[e][row][j], j < W: x[row][first_col[e] + j] inside [0, L), else 0
+hipError_t launch_conv_edge_strips(const void* x, void* strips, long long rows, int L, int W, int n_edges,
+                                   const int* first_col, int dtype, hipStream_t s);
 hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s);
 
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256

@@ -110,9 +110,13 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     F32, BF16 = gen.F32, gen.BF16
     assert binding.conv1d_out_len(4, 3) == 2 and binding.conv1d_out_len(4, 3, 2, 1, 1) == 2
     assert binding.conv1d_out_len(5, 3, 1, 0, 3) == 0 and binding.conv1d_out_len(0, 3) == 0
-    # matrix-core path: regrouped weights + padded input copy (rows rounded up to 16 bytes)
+    # matrix-core path: regrouped weights + zero-padded strips for the first and the last tile
+    # column (64-column tiles on this small grid, halo 2, rounded up to 16 bytes: 68 columns)
     need = binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, F32)
-    assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1004 * 4
+    assert need == 32 * 64 * 3 * 4 + 2 * (2 * 64) * 68 * 4
+    # padding wider than a tile: a padded copy of the whole input instead (rows of 1000 + 2 * 101, rounded up)
+    need = binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 101, 1, F32)
+    assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1204 * 4
     # no padding and aligned rows: only the weights
     assert binding.conv1d_workspace_bytes(2, 64, 1024, 32, 3, 1, 0, 2, F32) == 32 * 64 * 3 * 4
     # stride 2, channels not a multiple of the K tile, odd dilation in bf16, odd output length: in place, no workspace

@@ -54,9 +54,13 @@ def int_case(dtype, B, Cin, L, Cout, Kw, seed):
 FAST = {
     F32: [(2, 32, 256, 32, 3, 1, 1, 1), (1, 64, 1024, 48, 5, 1, 2, 1), (3, 32, 520, 130, 3, 1, 1, 1),
           (2, 96, 300, 64, 1, 1, 0, 1), (2, 32, 1028, 20, 4, 1, 3, 2), (1, 32, 1024, 64, 7, 1, 9, 3),
-          (40, 64, 2048, 128, 3, 1, 1, 1), (2, 64, 4096, 256, 3, 1, 0, 2)],
+          (40, 64, 2048, 128, 3, 1, 1, 1), (2, 64, 4096, 256, 3, 1, 0, 2),
+          # one tile column that is first and last at once; right edge spread over two tile columns;
+          # padding wider than a tile (padded copy of the whole input); halo wider than a tile
+          (2, 32, 60, 32, 5, 1, 2, 1), (2, 32, 1024, 32, 9, 1, 6, 1), (2, 32, 500, 32, 3, 1, 101, 1), (1, 32, 2000, 32, 5, 1, 0, 40)],
     BF16: [(2, 64, 256, 32, 3, 1, 2, 2), (1, 128, 1024, 48, 5, 1, 4, 2), (3, 64, 520, 130, 1, 1, 0, 1),
-           (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8)],
+           (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8),
+           (2, 64, 120, 32, 5, 1, 4, 2), (2, 64, 1030, 32, 3, 1, 3, 2), (2, 64, 1036, 32, 9, 1, 6, 2)],
 }
 # everything else: the bounds-checked kernel reading the input in place
 GENERAL = [(1, 1, 9, 1, 3, 1, 0, 1), (2, 3, 17, 4, 3, 1, 1, 1), (2, 5, 50, 7, 5, 2, 2, 1), (1, 2, 130, 70, 4, 3, 5, 2),
