@@ -83,10 +83,14 @@ __device__ __forceinline__ int swz_b(int krow)
 // XORed with twice the row index, so that the 32 rows a wave writes at once fall in
 // different banks, and so that the pair of units forming a 16-byte chunk stays
 // adjacent for part 2.
-template <int ACT, bool OUT_BF16, typename Cfg>
+// `bias` / `bias_row`: this tile's column or row biases, already in LDS (see the kernel).
+// PLAIN: no row bias and no row sum (the caller guarantees bias_row == rs_lds == nullptr), so
+// the per-element work is one add, the activation and the rounding -- the large GEMMs' case.
+// HAS_BIAS false: `bias` is not read (the split-K partial products).
+template <int ACT, bool OUT_BF16, bool PLAIN, typename Cfg, bool HAS_BIAS = true>
 __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
-                                                const float* bias_row, int m_rem,
-                                                int n_tile0, int n_rem, int wm, int wn, int lane,
+                                                const float* bias_row,
+                                                int n_rem, int wm, int wn, int lane,
                                                 unsigned char* const (&obj)[4], float* rs_lds)
 {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
@@ -96,6 +100,11 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     constexpr int ROWS_PER_OBJ = Cfg::A_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     const int half = lane >> 5;
     const int row_in = lane & 31;
+    // per accumulator block row: where its output row is staged, its row bias, its row sum
+    // Block by block (32 rows x 32 columns of the wave's part): the lane's sixteen column
+    // biases of the block are fetched together, one LDS round trip per block instead of one
+    // per group of four outputs.  `bias` always points at staged values, zero when the call has
+    // no column bias.
 #pragma unroll
     for (int i = 0; i < TM; ++i) {
         float rs = 0.0f;
@@ -104,23 +113,32 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
         unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
                               (row % ROWS_PER_OBJ) * ROW_BYTES;
         const int key = (2 * row) % UNITS;
-        // bias added to rows instead of columns (bias_row points at this tile's first row)
-        const float br = (bias_row && row < m_rem) ? bias_row[row] : 0.0f;
+        // bias added to rows instead of columns: staged in LDS, zero past the edge
+        const float br = (!PLAIN && bias_row) ? bias_row[row] : 0.0f;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
+            f32x4 bvs[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if constexpr (HAS_BIAS) bvs[g] = *(const f32x4*)(bias + wn * Cfg::WN + 32 * j + 8 * g + 4 * half);
+                else bvs[g] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
-                // columns past the end of a ragged N: no bias read, nothing added to the
-                // row sum (N is a multiple of 4, so a run of 4 is all in or all out)
+                // columns past the end of a ragged N add nothing to the row sum (N is a
+                // multiple of 4, so a run of 4 is all in or all out)
                 const bool in_n = col < n_rem;
-                f32x4 bv = {0.f, 0.f, 0.f, 0.f};
-                if (bias && in_n) bv = *(const f32x4*)(bias + n_tile0 + col);
+                const f32x4 bv = bvs[g];
                 float y[4];
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
-                    y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e] + br);
-                    rs += in_n ? y[e] : 0.0f;
+                    if constexpr (PLAIN) {
+                        y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
+                    } else {
+                        y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e] + br);
+                        rs += in_n ? y[e] : 0.0f;
+                    }
                 }
                 unsigned char* dst = base + (((col >> 2) ^ key) * UB);
                 if constexpr (OUT_BF16) {
@@ -131,8 +149,11 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                     *(f32x4*)dst = v;
                 }
             }
+            // keeps the next block's bias fetches below this block's work: hoisting all of
+            // them to the top would cost 64 registers
+            asm volatile("" ::: "memory");
         }
-        if (rs_lds) {
+        if (!PLAIN && rs_lds) {
             rs += __shfl_xor(rs, 32);
             if (half == 0) rs_lds[wn * Cfg::BM + row] = rs;
         }
@@ -244,6 +265,16 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
     const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
     const int n_rem = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
+
+    // this tile's biases (one per column, or one per row), one value per thread, fetched now
+    // and handed out through LDS in the epilogue
+    constexpr int BIAS_N = BM > BN ? BM : BN;
+    static_assert(BIAS_N <= Cfg::NT, "one thread per bias value");
+    float bias_pre = 0.0f;
+    if (p.bias && out_mode == 0) {
+        if (p.bias_per_row) { if (tid < m_rem) bias_pre = p.bias[(size_t)tm * BM + tid]; }
+        else if (tid < n_rem) bias_pre = p.bias[(size_t)tn * BN + tid];
+    }
 
     // ---- per-lane byte offsets of the global chunks this lane copies
     unsigned int voff_a[Cfg::A_CPW], voff_b[Cfg::B_CPW];
@@ -591,9 +622,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                   (Cfg::A_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
                   "the first four operand buffers hold the output tile, whole 32-row blocks each");
     // row-sum exchange buffer: the third A stage when there is one, else a small array
-    __shared__ float rs_own[SA > 2 ? 1 : Cfg::WGN * BM];
+    // (followed by the tile's biases, BIAS_N floats)
+    __shared__ __attribute__((aligned(16))) float rs_own[SA > 2 ? 4 : Cfg::WGN * BM + 2 * BIAS_N];
     float* rs_buf = SA > 2 ? (float*)lds_a2 : rs_own;
-    static_assert(Cfg::WGN * BM * 4 <= Cfg::A_BYTES, "row-sum buffer fits an A stage");
+    static_assert((Cfg::WGN * BM + 2 * BIAS_N) * 4 <= Cfg::A_BYTES, "row-sum and bias buffers fit an A stage");
     unsigned char* const obj[4] = {lds_a0, lds_a1, lds_b0, lds_b1};
     __syncthreads();   // every wave is done with the operand tiles
     if (out_mode == 1) {
@@ -603,7 +635,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
                                             (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
         if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, false, Cfg>(acc, nullptr, nullptr, m_rem, 0, n_rem, wm, wn, lane, obj, nullptr);
+            epilogue_to_lds<ACT_NONE, false, true, Cfg, false>(acc, nullptr, nullptr, n_rem, wm, wn, lane, obj, nullptr);
             __syncthreads();
             epilogue_store<false, Cfg>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
         } else {
@@ -624,13 +656,33 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     }
 
     float* rs_lds = p.rs_part ? rs_buf : nullptr;
-    const float* const bias_col = p.bias_per_row ? nullptr : p.bias;
-    const float* const bias_row = (p.bias_per_row && p.bias) ? p.bias + (size_t)tm * BM : nullptr;
-    switch (p.act) {
-    case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
-    default: epilogue_to_lds<ACT_NONE, BF16, Cfg>(acc, bias_col, bias_row, m_rem, tn * BN, n_rem, wm, wn, lane, obj, rs_lds); break;
+    // the tile's biases, fetched at kernel start, go through LDS to the lanes that need them
+    // (sixteen dependent global loads per lane at this point cost 12 000 cycles per tile)
+    float* const bias_lds = rs_buf + Cfg::WGN * BM;
+    // (row biases go to a second array; the column array then holds zeros, and so it does
+    // when the call has no bias)
+    float* const bias_lds_row = bias_lds + BIAS_N;
+    if (tid < BIAS_N) {
+        bias_lds[tid] = p.bias_per_row ? 0.0f : bias_pre;
+        if (p.bias_per_row) bias_lds_row[tid] = bias_pre;
+    }
+    __syncthreads();
+    const float* const bias_col = bias_lds;
+    const float* const bias_row = (p.bias && p.bias_per_row) ? bias_lds_row : nullptr;
+    if (!bias_row && !rs_lds) {
+        switch (p.act) {
+        case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
+        case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
+        case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
+        default: epilogue_to_lds<ACT_NONE, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
+        }
+    } else {
+        switch (p.act) {
+        case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
+        case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
+        case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
+        default: epilogue_to_lds<ACT_NONE, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
+        }
     }
     __syncthreads();
     unsigned char* c_tile = (unsigned char*)p.C +
