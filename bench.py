@@ -399,6 +399,7 @@ def main():
                          "per-kernel metric set as one JSON line instead of timing it here")
     ap.add_argument("--extra-counters", nargs="*", default=[], help="with --profile: further counter names")
     ap.add_argument("--record", default=None, help="with --profile: JSON file keeping the best profile so far")
+    ap.add_argument("--markdown", default=None, help="with --profile: also write a short text summary to this file")
     args = ap.parse_args()
     if args.profile:
         # the measurements are child processes (this bench again, without --profile); this process
@@ -407,6 +408,8 @@ def main():
         argv = ["--workload", args.workload, "--extra", *args.extra_counters]
         if args.record:
             argv += ["--record", args.record]
+        if args.markdown:
+            argv += ["--markdown", args.markdown]
         sys.exit(profile.main(argv))
     if args.gpus != 1:
         sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (nothing here uses a second GPU)")

@@ -337,6 +337,40 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
     }
 
 
+def to_markdown(prof: dict, command: str) -> str:
+    """A short text summary of one profile (what profiles/*_metric_set.md hold)."""
+    w = prof["workload"]
+    sc = prof["counter_scale"]
+    out = [f"# Metric set of workload {w} (per kernel) — profile harness over rocprofv3\n",
+           "Command (one MI355X; the harness starts one rocprofv3 run for the kernel trace, one per counter group —",
+           ", ".join(f"`{g}` = {' '.join(names)}" for g, names in DEFAULT_GROUPS) + " —",
+           f"and two calibration runs on a plain 1 GiB copy):\n",
+           f"    {command}\n",
+           f"Counter scale factors ({sc['source']}): FETCH_SIZE x {sc['FETCH_SIZE']:.4f}, WRITE_SIZE x {sc['WRITE_SIZE']:.4f}.",
+           f"Step time (sum of the library's kernels, profiler attached): {prof['step_time_us']:.1f} us.\n"]
+    for k in prof["kernels"]:
+        r, l, o, m = k["registers"], k["lds"], k["occupancy"], k.get("memory", {})
+        out += [f"## `{k['kernel']}`\n", "| metric | value |", "|---|---|",
+                f"| time per launch | {k['time_us']:.1f} us (min {k['time_us_min']:.1f}, max {k['time_us_max']:.1f}; {k['calls']} launches) |",
+                f"| launch | {k['workgroups']} workgroups of {k['workgroup_size']} threads |",
+                f"| registers ({r['source']}) | {r['vgprs']} VGPR + {r['agprs']} AGPR, {r['sgprs']} SGPR, scratch "
+                f"{r['scratch_bytes_per_lane']} B/lane, spills {r.get('vgpr_spills', 0)} VGPR / {r.get('sgpr_spills', 0)} SGPR |",
+                f"| LDS | {l['bytes_per_workgroup']} B per workgroup = {100 * l['fraction_of_cu']:.0f} % of a CU; busy "
+                f"{l.get('busy_percent', 0):.1f} %, bank-conflict stall {l.get('bank_conflict_percent', 0):.2f} % |",
+                f"| occupancy | {o['waves_per_simd']} of {o['max_waves_per_simd']} waves per SIMD fit (registers allow "
+                f"{o['by_registers']}, LDS {o['by_lds']}); measured {o.get('measured_percent', 0):.1f} % |",
+                f"| matrix unit busy (MfmaUtil) | {k.get('matrix_unit_busy_percent', 0):.1f} % |",
+                f"| vector ALU busy | {k.get('vector_alu_busy_percent', 0):.1f} % |"]
+        if "gb_per_s" in m:
+            out.append(f"| memory traffic (L2 <-> fabric) | read {m['read_bytes'] / 1e6:.1f} MB + written {m['written_bytes'] / 1e6:.1f} MB "
+                       f"per launch = {m['gb_per_s']:.0f} GB/s ({100 * m['fraction_of_hbm_peak']:.1f} % of 8 TB/s); L2 hit rate "
+                       f"{m.get('l2_hit_percent', 0):.1f} % |")
+        for name, v in sorted(k.get("extra_counters", {}).items()):
+            out.append(f"| {name} | {v:.6g} |")
+        out.append("")
+    return "\n".join(out)
+
+
 def main(argv: Optional[Iterable[str]] = None) -> int:
     ap = argparse.ArgumentParser(description=__doc__.split("\n\n")[0])
     ap.add_argument("--workload", default="c3")
@@ -347,11 +381,17 @@ def main(argv: Optional[Iterable[str]] = None) -> int:
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--no-calibration", action="store_true")
     ap.add_argument("--all-kernels", action="store_true", help="also report kernels that are not the library's")
+    ap.add_argument("--markdown", default=None, help="also write a short text summary of the profile to this file")
     args = ap.parse_args(list(argv) if argv is not None else None)
     prof = profile_workload(args.workload, os.path.join(args.out, args.workload), args.extra, args.steps, args.warmup,
                             not args.no_calibration, all_kernels=args.all_kernels)
     if args.record:
         prof["against_best"] = update_record(args.record, args.workload, {k: prof[k] for k in ("workload", "when", "step_time_us", "kernels")})
+    if args.markdown:
+        cmd = f"python3 bench.py --profile --workload {args.workload}" + (" --extra-counters " + " ".join(args.extra) if args.extra else "")
+        os.makedirs(os.path.dirname(os.path.abspath(args.markdown)), exist_ok=True)
+        with open(args.markdown, "w") as f:
+            f.write(to_markdown(prof, cmd))
     print(json.dumps(prof), flush=True)
     return 0
 

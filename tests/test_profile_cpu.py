@@ -95,6 +95,16 @@ def test_merge_fills_the_metric_set():
     assert len(profile.merge(trace, counters, resources, 2.0, 1.0, all_kernels=True)) == 3
 
 
+def test_markdown_summary_names_the_command_and_every_kernel():
+    trace = profile.parse_kernel_trace(os.path.join(GOLD, "c4_kernel_trace.csv"))
+    kernels = profile.merge(trace, {MFMA: {"FETCH_SIZE": 1000.0, "WRITE_SIZE": 500.0, "MfmaUtil": 61.0}}, {}, 2.0, 1.0)
+    prof = {"workload": "c4", "step_time_us": 120.0, "kernels": kernels,
+            "counter_scale": {"FETCH_SIZE": 2.0, "WRITE_SIZE": 1.0, "source": "test"}}
+    text = profile.to_markdown(prof, "python3 bench.py --profile --workload c4")
+    assert "python3 bench.py --profile --workload c4" in text and "MfmaUtil" in text
+    assert text.count("## `") == 2 and "61.0 %" in text and "FETCH_SIZE x 2.0000" in text
+
+
 def test_best_so_far_record(tmp_path):
     path = str(tmp_path / "best.json")
     a = {"workload": "c3", "when": "t0", "step_time_us": 900.0, "kernels": [{"kernel": "k", "time_us": 900.0}]}
