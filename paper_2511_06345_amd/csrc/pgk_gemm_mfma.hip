@@ -175,6 +175,9 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
     constexpr int ITERS = Cfg::BM / ROWS_PER_IT;
     static_assert(ROWS_PER_OBJ % ROWS_PER_IT == 0, "an iteration stays inside one buffer");
     const int c = tid % CPR;
+    // all of the thread's chunks are read from LDS first (one round trip), then stored; the
+    // scheduling barrier keeps the compiler from sinking each read into its store's branch
+    u32x4 v[ITERS];
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int row = it * ROWS_PER_IT + tid / CPR;
@@ -183,9 +186,15 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
                                     (row % ROWS_PER_OBJ) * ROW_BYTES;
         const int key = (2 * row) % UNITS;
         const int unit = OUT_BF16 ? ((2 * c) ^ key) : (c ^ key);
-        u32x4 v = *(const u32x4*)(base + unit * UB);
-        if (row < m_rem && c * (16 / (OUT_BF16 ? 2 : 4)) < n_rem)
-            *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v;
+        v[it] = *(const u32x4*)(base + unit * UB);
+    }
+    __builtin_amdgcn_sched_barrier(0);
+    const bool col_ok = c * (16 / (OUT_BF16 ? 2 : 4)) < n_rem;
+#pragma unroll
+    for (int it = 0; it < ITERS; ++it) {
+        const int row = it * ROWS_PER_IT + tid / CPR;
+        if (row < m_rem && col_ok)
+            *(u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16) = v[it];
     }
 }
 
