@@ -73,10 +73,14 @@ typedef enum {
  * tile multiples.  All other shapes go to a bounds-checked kernel.  M, N, K must each be below 2^31 and
  * batch*M*N, batch*M*K, batch*K*N below 2^62 (else PGK_ERR_UNSUPPORTED).
  *
- * When rowsum is requested and N spans several tile columns the library keeps
- * a small device scratch buffer per (device, stream) for the per-tile partial
- * sums; it is allocated on first use (hipMalloc; PGK_ERR_HIP if that fails),
- * reused afterwards, and released by pgk_release_scratch().
+ * The library keeps a device scratch buffer per (device, stream), allocated on first
+ * use (hipMalloc; PGK_ERR_HIP if that fails), grown when needed, reused afterwards and
+ * released by pgk_release_scratch().  It holds the per-tile partial row sums when rowsum
+ * is requested and N spans several tile columns, and -- for problems with few output
+ * tiles and a long K (fewer than 192 tiles, K of at least 16 K tiles; skinny or small
+ * outputs) -- the partial products of an automatic K split, computed exactly as by
+ * pgk_gemm_splitk with splits = 0 (at most 256 MiB; larger cases are not split).  Which
+ * route a problem takes depends on its shape only, so results stay bit-reproducible.
  */
 int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
                    int64_t M, int64_t N, int64_t K, int64_t batch,

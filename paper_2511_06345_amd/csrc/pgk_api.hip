@@ -18,6 +18,7 @@ using pgk::GemmArgs;
 constexpr int64_t kMaxDim = 0x7fffffffLL;
 constexpr int kNumCUs = 256;          // MI355X
 constexpr int64_t kFusedCombineMaxWorkgroups = 64;
+constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // scratch pgk_gemm_fused may take for an automatic split
 constexpr int kMaxAutoSplits = 32;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
@@ -57,13 +58,22 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
     return true;
 }
 
+// A large tile at least half of which would lie outside the matrix (skinny M or N): the small
+// tile wastes less matrix work and fewer operand loads.
+bool large_tile_mostly_empty(int64_t M, int64_t N, int dtype)
+{
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
+    return 2 * M <= big.bm || 2 * N <= big.bn;
+}
+
 SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
 {
     const int ks = kstep_of(dtype);
     const int64_t ksteps = (K + ks - 1) / ks;
     int64_t s = splits;
     if (s == 0) {
-        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype, false) : pgk::guarded_tile_shape();
+        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype, large_tile_mostly_empty(M, N, dtype))
+                                                         : pgk::guarded_tile_shape();
         const long double tiles = (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
         s = 1;
         while (s < kMaxAutoSplits && s < ksteps && tiles * s < 2.0L * kNumCUs) ++s;
@@ -148,11 +158,49 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
     const bool ok = mfma_shape_ok(M, N, K, dtype) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
-    // the small tile when the large-tile grid would leave a quarter of the CUs idle
+    // the small tile when the large-tile grid would leave a quarter of the CUs idle, or when
+    // half of a large tile would be empty
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    const bool small = wgs < 0.75L * kNumCUs;
+    const bool small = wgs < 0.75L * kNumCUs || large_tile_mostly_empty(M, N, dtype);
     return Path{true, small, pgk::mfma_tile_shape(dtype, small)};
+}
+
+// The two passes of the split-K path.  `workspace`: batch * plan.splits * M * N floats;
+// `part`: batch * nseg * M floats when rowsum != nullptr and the second pass uses nseg > 1
+// column segments (nseg from splitk_reduce_segments), else unused.
+int run_split_passes(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
+                     int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, float* workspace,
+                     float* part, hipStream_t st)
+{
+    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits);
+    const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
+    const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
+    if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+
+    GemmArgs a{};
+    a.A = A; a.B = B; a.bias = nullptr; a.C = nullptr; a.rs_part = nullptr;
+    a.ws = workspace;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
+    pgk::fill_plain_views(a);
+    a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
+    if (e != hipSuccess) return PGK_ERR_HIP;
+    const int nseg = pgk::splitk_reduce_segments((int)M, (int)N, (int)batch);
+    float* rs_part = (rowsum && nseg > 1) ? part : nullptr;
+    e = pgk::launch_splitk_reduce(a.ws, bias, C, rowsum, rs_part, nseg, (int)M, (int)N, (int)batch, plan.splits, act, dtype, st);
+    if (e != hipSuccess) return PGK_ERR_HIP;
+    if (rs_part) e = pgk::launch_rowsum_combine(rs_part, rowsum, (int)M, (int)batch, nseg, st);
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
+size_t split_part_bytes(int64_t M, int64_t N, int64_t batch, bool rowsum)
+{
+    const int nseg = pgk::splitk_reduce_segments((int)M, (int)N, (int)batch);
+    return (rowsum && nseg > 1) ? (size_t)batch * (size_t)nseg * (size_t)M * sizeof(float) : 0;
 }
 
 }  // namespace
@@ -170,6 +218,21 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+
+    // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
+    // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
+    // partial products in the library's scratch buffer.  The choice depends on the shape only.
+    if (path.mfma && tiles_m * tiles_n * batch < (3 * kNumCUs) / 4 && K >= 16 * path.tile.bk) {
+        const SplitPlan plan = plan_splits(M, N, K, batch, dtype, 0);
+        const long double ws_bytes = (long double)batch * plan.splits * M * N * sizeof(float);
+        if (plan.splits > 1 && ws_bytes <= (long double)kAutoSplitMaxWorkspace) {
+            const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
+            float* buf = nullptr;
+            if (scratch_get(st, (size_t)ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
+            return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, buf,
+                                    buf + (size_t)ws_bytes / sizeof(float), st);
+        }
+    }
 
     GemmArgs a{};
     a.A = A; a.B = B; a.bias = bias; a.C = C; a.ws = nullptr;
@@ -240,24 +303,10 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     hipStream_t st = static_cast<hipStream_t>(stream);
 
     const SplitPlan plan = plan_splits(M, N, K, batch, dtype, splits);
-    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits);
-    const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
-    const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
-    if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
-
-    GemmArgs a{};
-    a.A = A; a.B = B; a.bias = nullptr; a.C = nullptr; a.rs_part = nullptr;
-    a.ws = static_cast<float*>(workspace);
-    a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
-    pgk::fill_plain_views(a);
-    a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
-    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
-    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
-
-    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
-    if (e != hipSuccess) return PGK_ERR_HIP;
-    e = pgk::launch_splitk_reduce(a.ws, bias, C, rowsum, (int)M, (int)N, (int)batch, plan.splits, act, dtype, st);
-    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+    float* part = nullptr;
+    const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
+    if (part_bytes && scratch_get(st, part_bytes, &part) != hipSuccess) return PGK_ERR_HIP;
+    return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, static_cast<float*>(workspace), part, st);
 }
 
 int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_t red, int64_t inner,

@@ -90,10 +90,13 @@ hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipSt
 hipError_t launch_rowsum_combine(const float* part, float* rowsum, int M, int batch,
                                  int tiles_n, hipStream_t s);
 
-// Split-K pass 2: C = act(sum_s ws[b][s] + bias), s ascending; optional rowsum.
-hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, float* rowsum,
-                                int M, int N, int batch, int splits, int act, int dtype,
-                                hipStream_t s);
+// Split-K pass 2: C = act(sum_s ws[b][s] + bias), s ascending; optional rowsum.  The columns
+// are cut into `nseg` segments (splitk_reduce_segments) so that skinny outputs still fill the
+// chip; with nseg > 1 the row sums go to rs_part[batch][nseg][M] and are to be added in
+// segment order (launch_rowsum_combine with tiles_n = nseg).
+int splitk_reduce_segments(int M, int N, int batch);
+hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, float* rowsum, float* rs_part,
+                                int nseg, int M, int N, int batch, int splits, int act, int dtype, hipStream_t s);
 
 // Maximum over the middle dimension of X viewed as [outer][red][inner]; see
 // pgk_reduce_max.hip.  The plan is pure host arithmetic: vector width (elements per

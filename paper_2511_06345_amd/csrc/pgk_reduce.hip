@@ -36,24 +36,31 @@ hipError_t launch_rowsum_combine(const float* part, float* rowsum, int M, int ba
     return hipGetLastError();
 }
 
-// One wave per output row.  VEC = 4 when N % 4 == 0 and the buffers are 16-byte
-// aligned (each lane handles 4 consecutive columns per trip), else 1.
+// One wave per output row and column segment (blockIdx.y; segments of seg_cols columns, so
+// that skinny outputs still give enough waves).  VEC = 4 when N % 4 == 0 and the buffers are
+// 16-byte aligned (each lane handles 4 consecutive columns per trip), else 1.  With several
+// segments the row sums are per-segment partials rs_part[b][segment][m], to be added in
+// segment order by rowsum_combine_kernel.
 template <int VEC, bool OUT_BF16>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restrict__ ws,
                                                             const float* __restrict__ bias,
                                                             void* __restrict__ C, float* __restrict__ rowsum,
+                                                            float* __restrict__ rs_part, int seg_cols,
                                                             int M, int N, int batch, int splits, int act)
 {
     const int lane = threadIdx.x & 63;
     const size_t row = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);   // b * M + m
     if (row >= (size_t)M * batch) return;
+    const int seg = blockIdx.y, nseg = gridDim.y;
+    const int n_begin = seg * seg_cols;
+    const int n_end = n_begin + seg_cols < N ? n_begin + seg_cols : N;
     const size_t b = row / M, m = row - b * M;
     const size_t slice = (size_t)M * N;
     const float* src = ws + b * (size_t)splits * slice + m * (size_t)N;
     const size_t out = row * (size_t)N;
 
     float rs = 0.0f;
-    for (int n = lane * VEC; n < N; n += 64 * VEC) {
+    for (int n = n_begin + lane * VEC; n < n_end; n += 64 * VEC) {
         float x[VEC];
         if constexpr (VEC == 4) {
             f32x4 v = *(const f32x4*)(src + n);
@@ -91,25 +98,38 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float* __restr
         // fixed butterfly over the 64 lanes
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) rs += __shfl_xor(rs, off);
-        if (lane == 0) rowsum[row] = rs;
+        if (lane == 0) {
+            if (nseg == 1) rowsum[row] = rs;
+            else rs_part[(b * nseg + seg) * (size_t)M + m] = rs;
+        }
     }
 }
 
-hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, float* rowsum, int M, int N,
-                                int batch, int splits, int act, int dtype, hipStream_t s)
+int splitk_reduce_segments(int M, int N, int batch)
+{
+    // about 4096 waves, segments of whole 256-column trips
+    const long long rows = (long long)M * batch;
+    long long want = (4096 + rows - 1) / rows;
+    const long long most = (N + 255) / 256;
+    if (want > most) want = most;
+    if (want < 1) want = 1;
+    const long long cols = (((N + want - 1) / want) + 255) / 256 * 256;
+    return (int)((N + cols - 1) / cols);
+}
+
+hipError_t launch_splitk_reduce(const float* ws, const float* bias, void* C, float* rowsum, float* rs_part,
+                                int nseg, int M, int N, int batch, int splits, int act, int dtype, hipStream_t s)
 {
     const size_t rows = (size_t)M * batch;
     const size_t blocks = (rows + 3) / 4;
-    if (blocks == 0 || blocks > 0x7fffffffULL) return hipErrorInvalidValue;
+    if (blocks == 0 || blocks > 0x7fffffffULL || nseg < 1 || nseg > 65535) return hipErrorInvalidValue;
+    const int seg_cols = (((N + nseg - 1) / nseg) + 255) / 256 * 256;
     const bool vec = (N % 4 == 0) && (((uintptr_t)ws | (uintptr_t)C | (uintptr_t)bias) % 16 == 0);
-    const dim3 g((unsigned int)blocks), t(256);
-    if (dtype == DT_BF16) {
-        if (vec) hipLaunchKernelGGL((splitk_reduce_kernel<4, true>), g, t, 0, s, ws, bias, C, rowsum, M, N, batch, splits, act);
-        else hipLaunchKernelGGL((splitk_reduce_kernel<1, true>), g, t, 0, s, ws, bias, C, rowsum, M, N, batch, splits, act);
-    } else {
-        if (vec) hipLaunchKernelGGL((splitk_reduce_kernel<4, false>), g, t, 0, s, ws, bias, C, rowsum, M, N, batch, splits, act);
-        else hipLaunchKernelGGL((splitk_reduce_kernel<1, false>), g, t, 0, s, ws, bias, C, rowsum, M, N, batch, splits, act);
-    }
+    const dim3 g((unsigned int)blocks, (unsigned int)nseg), t(256);
+#define PGK_RED(V, BF) hipLaunchKernelGGL((splitk_reduce_kernel<V, BF>), g, t, 0, s, ws, bias, C, rowsum, rs_part, seg_cols, M, N, batch, splits, act)
+    if (dtype == DT_BF16) { if (vec) PGK_RED(4, true); else PGK_RED(1, true); }
+    else { if (vec) PGK_RED(4, false); else PGK_RED(1, false); }
+#undef PGK_RED
     return hipGetLastError();
 }
 

@@ -158,7 +158,9 @@ def test_large_tiles_with_many_batch_entries(pgk, oracle, dtype):
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("act", [NONE, SILU])
 def test_splitk_matches_oracle_and_is_deterministic(pgk, oracle, dtype, act):
-    shapes = [(128, 128, 1024, 3), (256, 256, 2048, 2), (100, 36, 1000, 2)]
+    # the last two are skinny: the second pass cuts their columns into segments and the row
+    # sums are combined from per-segment partials
+    shapes = [(128, 128, 1024, 3), (256, 256, 2048, 2), (100, 36, 1000, 2), (20, 2056, 512, 1), (16, 4096, 256, 2)]
     for shape in shapes:
         M, N, K, batch = shape
         A, B, bias = random_case(dtype, M, N, K, batch, seed=5 * M + K)
@@ -194,6 +196,19 @@ def test_k_tail_ignores_what_follows_a_row(pgk, oracle, dtype, batch):
     assert np.all(np.isnan(got_c[~keep]))
     for b in range(batch - 1):
         check(got_c[b][keep[b]], got_rs[b][keep[b]], ref_c[b][keep[b]], ref_rs[b][keep[b]], dtype, f"batch {b}")
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+def test_skinny_splitk_is_exact_on_integers(pgk, oracle, dtype):
+    for shape in [(16, 4096, 512, 1), (40, 1288, 256, 3), (7, 3000, 128, 2)]:
+        M, N, K, batch = shape
+        A, B = gen.make_int_inputs(dtype, M, N, K, batch, seed=M + N)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, None, NONE)
+        if dtype == BF16:
+            ref_c = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref_c.astype(np.float32))).astype(np.float64)
+        for splits in (0, 2, 5):
+            got_c, got_rs = run_splitk(pgk, A, B, None, NONE, dtype, splits=splits)
+            assert np.array_equal(got_c, ref_c) and np.array_equal(got_rs, ref_rs), f"{shape} splits {splits}"
 
 
 def test_identity_operand_passes_b_through(pgk, oracle):
