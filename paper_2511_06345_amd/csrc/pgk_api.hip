@@ -18,6 +18,7 @@ using pgk::GemmArgs;
 constexpr int64_t kMaxDim = 0x7fffffffLL;
 constexpr int kNumCUs = 256;          // MI355X
 constexpr int64_t kFusedCombineMaxWorkgroups = 64;
+constexpr int kMinStepsPerSlice = 16;
 constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // scratch pgk_gemm_fused may take for an automatic split
 constexpr int kMaxAutoSplits = 32;
 
@@ -58,12 +59,37 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
     return true;
 }
 
-// A large tile at least half of which would lie outside the matrix (skinny M or N): the small
-// tile wastes less matrix work and fewer operand loads.
+// A large tile three quarters of which would lie outside the matrix (skinny M or N): the
+// small tile wastes less matrix work and fewer operand loads.  (At one half the two are
+// level: 128 x 65536 x 1024 bf16 took 37 us with the large tile and 39 us with the small one.)
 bool large_tile_mostly_empty(int64_t M, int64_t N, int dtype)
 {
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
-    return 2 * M <= big.bm || 2 * N <= big.bn;
+    return 4 * M <= big.bm || 4 * N <= big.bn;
+}
+
+// Automatic choice (splits == 0): slices of at least kMinStepsPerSlice K steps (shorter ones
+// are all prologue and epilogue), at most kMaxAutoSplits of them, and the smallest count that
+// gives 2 x 256 workgroups.  The tile the count is made with: the large one if it can reach
+// 1.5 x 256 workgroups within those limits and is not mostly empty, else the small one.
+struct AutoPlan { int splits; bool small_tile; };
+
+AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
+{
+    const int ks = kstep_of(dtype);
+    const int64_t ksteps = (K + ks - 1) / ks;
+    int64_t s_max = ksteps / kMinStepsPerSlice;
+    if (s_max < 1) s_max = 1;
+    if (s_max > kMaxAutoSplits) s_max = kMaxAutoSplits;
+    auto tiles_of = [&](bool small) {
+        const pgk::TileShape t = pgk::mfma_tile_shape(dtype, small);
+        return (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
+    };
+    const bool small = large_tile_mostly_empty(M, N, dtype) || tiles_of(false) * s_max < 1.5L * kNumCUs;
+    const long double tiles = tiles_of(small);
+    int64_t s = 1;
+    while (s < s_max && tiles * s < 2.0L * kNumCUs) ++s;
+    return {(int)s, small};
 }
 
 SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
@@ -72,11 +98,14 @@ SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype,
     const int64_t ksteps = (K + ks - 1) / ks;
     int64_t s = splits;
     if (s == 0) {
-        pgk::TileShape t = mfma_shape_ok(M, N, K, dtype) ? pgk::mfma_tile_shape(dtype, large_tile_mostly_empty(M, N, dtype))
-                                                         : pgk::guarded_tile_shape();
-        const long double tiles = (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
-        s = 1;
-        while (s < kMaxAutoSplits && s < ksteps && tiles * s < 2.0L * kNumCUs) ++s;
+        if (mfma_shape_ok(M, N, K, dtype)) {
+            s = auto_split(M, N, K, batch, dtype).splits;
+        } else {
+            const pgk::TileShape t = pgk::guarded_tile_shape();
+            const long double tiles = (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
+            s = 1;
+            while (s < kMaxAutoSplits && s < ksteps && tiles * s < 2.0L * kNumCUs) ++s;
+        }
     }
     if (s > ksteps) s = ksteps;
     const int64_t per = (ksteps + s - 1) / s;     // K steps per slice
@@ -152,8 +181,9 @@ hipError_t counters_get(hipStream_t stream, size_t count, unsigned int** out)
 struct Path { bool mfma; bool small; pgk::TileShape tile; };
 
 // `units` = batch entries x K splits: workgroups per output tile position.
+// small_tile_forced: -1 = by the grid size, 0 / 1 = the caller (an automatic split plan) decides
 Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
-                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units)
+                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int small_tile_forced = -1)
 {
     const bool ok = mfma_shape_ok(M, N, K, dtype) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
@@ -162,7 +192,8 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
     // half of a large tile would be empty
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    const bool small = wgs < 0.75L * kNumCUs || large_tile_mostly_empty(M, N, dtype);
+    const bool small = small_tile_forced >= 0 ? small_tile_forced != 0
+                                              : (wgs < 0.75L * kNumCUs || large_tile_mostly_empty(M, N, dtype));
     return Path{true, small, pgk::mfma_tile_shape(dtype, small)};
 }
 
@@ -170,10 +201,10 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
 // `part`: batch * nseg * M floats when rowsum != nullptr and the second pass uses nseg > 1
 // column segments (nseg from splitk_reduce_segments), else unused.
 int run_split_passes(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
-                     int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, float* workspace,
-                     float* part, hipStream_t st)
+                     int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, int small_tile,
+                     float* workspace, float* part, hipStream_t st)
 {
-    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits);
+    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits, small_tile);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -222,14 +253,15 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
     // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
     // partial products in the library's scratch buffer.  The choice depends on the shape only.
-    if (path.mfma && tiles_m * tiles_n * batch < (3 * kNumCUs) / 4 && K >= 16 * path.tile.bk) {
+    if (path.mfma && tiles_m * tiles_n * batch < (3 * kNumCUs) / 4) {
         const SplitPlan plan = plan_splits(M, N, K, batch, dtype, 0);
+        const int small_tile = (int)auto_split(M, N, K, batch, dtype).small_tile;
         const long double ws_bytes = (long double)batch * plan.splits * M * N * sizeof(float);
         if (plan.splits > 1 && ws_bytes <= (long double)kAutoSplitMaxWorkspace) {
             const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
             float* buf = nullptr;
             if (scratch_get(st, (size_t)ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
-            return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, buf,
+            return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile, buf,
                                     buf + (size_t)ws_bytes / sizeof(float), st);
         }
     }
@@ -306,7 +338,10 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     float* part = nullptr;
     const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
     if (part_bytes && scratch_get(st, part_bytes, &part) != hipSuccess) return PGK_ERR_HIP;
-    return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, static_cast<float*>(workspace), part, st);
+    // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
+    const int small_tile = (splits == 0 && mfma_shape_ok(M, N, K, dtype)) ? (int)auto_split(M, N, K, batch, dtype).small_tile : -1;
+    return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile,
+                            static_cast<float*>(workspace), part, st);
 }
 
 int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_t red, int64_t inner,
