@@ -294,7 +294,7 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
                      calibrate: bool = True, limit_s: int = 240, all_kernels: bool = False) -> dict:
     os.makedirs(out_dir, exist_ok=True)
     program = ["python3", BENCH, "--workload", workload, "--steps", str(steps), "--warmup", str(warmup),
-               "--no-cpu-baseline"]
+               "--no-cpu-baseline", "--no-ceilings"]
     t_dir = os.path.join(out_dir, "trace")
     trace_run(t_dir, program, limit_s)
     trace = parse_kernel_trace(_find(t_dir, "kernel_trace.csv"), warmup_calls=warmup)
