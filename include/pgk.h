@@ -77,7 +77,8 @@ typedef enum {
  * use (hipMalloc; PGK_ERR_HIP if that fails), grown when needed, reused afterwards and
  * released by pgk_release_scratch().  It holds the per-tile partial row sums when rowsum
  * is requested and N spans several tile columns, and -- for problems with few output
- * tiles and a long K (fewer than 192 tiles, K of at least 16 K tiles; skinny or small
+ * tiles and a long K (fewer than 192 tiles of the shape in use and K of at least 32 K
+ * tiles, or fewer than 192 large tiles and K of at least 512 K tiles; skinny or small
  * outputs) -- the partial products of an automatic K split, computed exactly as by
  * pgk_gemm_splitk with splits = 0 (at most 256 MiB; larger cases are not split).  Which
  * route a problem takes depends on its shape only, so results stay bit-reproducible.
@@ -111,6 +112,26 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
                     int64_t M, int64_t N, int64_t K, int64_t batch,
                     int act, int dtype, int splits,
                     void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * pgk_gemm_fused_bt / pgk_gemm_splitk_bt -- the same two calls with the second factor
+ * given transposed: Bt [batch][N][K], K contiguous (how a linear layer's weight
+ * [out_features][in_features] is stored), so that C = act(A * Bt^T + bias).  This is the
+ * "pre-transposed B" form of the matmul operator (Sections 1 / 4.2; same definition, only
+ * the storage of one operand differs).  Every other argument, the layouts of A, bias, C
+ * and rowsum, ownership, the scratch buffer, the split rule, the workspace size
+ * (pgk_splitk_workspace_bytes does not depend on the layout of B) and the errors are as
+ * for pgk_gemm_fused / pgk_gemm_splitk.  The matrix-core kernels take these calls under
+ * the same conditions (K and N multiples of 16 bytes of elements, M and N at least 16,
+ * 16-byte aligned pointers); they read Bt in place -- no transposed copy is made.
+ */
+int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
+                      int64_t M, int64_t N, int64_t K, int64_t batch,
+                      int act, int dtype, void* stream);
+int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
+                       int64_t M, int64_t N, int64_t K, int64_t batch,
+                       int act, int dtype, int splits,
+                       void* workspace, size_t workspace_bytes, void* stream);
 
 /* Bytes of workspace pgk_gemm_splitk needs for this problem (splits = 0: the
  * automatic choice).  Pure host arithmetic; returns 0 for invalid arguments. */

@@ -114,6 +114,13 @@ def gemm_fused(A: np.ndarray, B: np.ndarray, bias, act_kind: int, rows=None,
     return C, rs
 
 
+def gemm_fused_bt(A: np.ndarray, Bt: np.ndarray, bias, act_kind: int, **kw):
+    """The same operator with the second factor given transposed, Bt [batch, N, K] or [N, K]:
+    C = act(A @ Bt^T + bias).  By definition: transpose, then the plain evaluation."""
+    Bt = np.asarray(Bt)
+    return gemm_fused(A, np.ascontiguousarray(np.swapaxes(Bt, -1, -2)), bias, act_kind, **kw)
+
+
 def reduce_max(X: np.ndarray, dim: int, want_idx: bool = True):
     """Maximum of X over dimension `dim` and the first position attaining it.
 

@@ -5,7 +5,7 @@ binding is loaded lazily on first use of ``gemm_fused`` / ``gemm_splitk`` / ``re
 """
 from . import inputs  # noqa: F401
 
-_LAZY = {"gemm_fused", "gemm_splitk", "reduce_max", "conv1d", "splitk_workspace_bytes", "splitk_auto_splits",
+_LAZY = {"gemm_fused", "gemm_splitk", "gemm_fused_bt", "gemm_splitk_bt", "reduce_max", "conv1d", "splitk_workspace_bytes", "splitk_auto_splits",
          "status_string", "version", "load_library", "release_scratch", "PgkError"}
 
 

@@ -18,7 +18,8 @@ from .inputs import ACT_GELU_TANH, ACT_NONE, ACT_RELU, ACT_SILU, BF16, F32  # no
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
-EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_splitk_workspace_bytes",
+EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_splitk_bt",
+           "pgk_splitk_workspace_bytes",
            "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_conv1d", "pgk_conv1d_workspace_bytes",
            "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
            "pgk_release_scratch", "pgk_status_string", "pgk_version")
@@ -48,6 +49,10 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_gemm_splitk.restype = ci
     lib.pgk_gemm_splitk.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp,
                                     ctypes.c_size_t, vp]
+    lib.pgk_gemm_fused_bt.restype = ci
+    lib.pgk_gemm_fused_bt.argtypes = lib.pgk_gemm_fused.argtypes
+    lib.pgk_gemm_splitk_bt.restype = ci
+    lib.pgk_gemm_splitk_bt.argtypes = lib.pgk_gemm_splitk.argtypes
     lib.pgk_splitk_workspace_bytes.restype = ctypes.c_size_t
     lib.pgk_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_splitk_auto_splits.restype = ci
@@ -96,13 +101,14 @@ def release_scratch() -> None:
         raise PgkError(rc, "pgk_release_scratch")
 
 
-def _shape(A: torch.Tensor, B: torch.Tensor) -> Tuple[int, int, int, int, int]:
+def _shape(A: torch.Tensor, B: torch.Tensor, b_transposed: bool = False) -> Tuple[int, int, int, int, int]:
     if A.dim() == 2:
         A = A.unsqueeze(0)
     if B.dim() == 2:
         B = B.unsqueeze(0)
-    if A.dim() != 3 or B.dim() != 3 or A.shape[0] != B.shape[0] or A.shape[2] != B.shape[1]:
-        raise ValueError("expected A [batch, M, K] and B [batch, K, N]")
+    kdim, ndim = (2, 1) if b_transposed else (1, 2)
+    if A.dim() != 3 or B.dim() != 3 or A.shape[0] != B.shape[0] or A.shape[2] != B.shape[kdim]:
+        raise ValueError("expected A [batch, M, K] and B [batch, K, N] (transposed: [batch, N, K])")
     if not (A.is_cuda and B.is_cuda and A.is_contiguous() and B.is_contiguous()):
         raise ValueError("A and B must be contiguous device tensors")
     if A.dtype == torch.float32 and B.dtype == torch.float32:
@@ -112,7 +118,7 @@ def _shape(A: torch.Tensor, B: torch.Tensor) -> Tuple[int, int, int, int, int]:
     else:
         raise TypeError("A and B must both be float32 or both bfloat16")
     batch, M, K = A.shape
-    return int(batch), int(M), int(B.shape[2]), int(K), dtype
+    return int(batch), int(M), int(B.shape[ndim]), int(K), dtype
 
 
 def _check_bias(bias: Optional[torch.Tensor], N: int) -> int:
@@ -130,36 +136,45 @@ def _stream_ptr(stream) -> int:
 
 def gemm_fused(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
                rowsum: bool = True, out: Optional[torch.Tensor] = None,
-               rowsum_out: Optional[torch.Tensor] = None, stream=None):
+               rowsum_out: Optional[torch.Tensor] = None, stream=None, b_transposed: bool = False):
     """C = act(A @ B + bias) and (optionally) rowsum = C.sum(-1) in fp32 via pgk_gemm_fused.
 
     Returns (C, rowsum) with C [batch, M, N] in the dtype of A and rowsum
     [batch, M] float32 (None when ``rowsum`` is False).  Asynchronous on the
-    current (or given) torch stream.
+    current (or given) torch stream.  ``b_transposed``: B is [batch, N, K] and the call is
+    pgk_gemm_fused_bt.
     """
     lib = load_library()
-    batch, M, N, K, dtype = _shape(A, B)
+    batch, M, N, K, dtype = _shape(A, B, b_transposed)
+    entry = lib.pgk_gemm_fused_bt if b_transposed else lib.pgk_gemm_fused
     C = out if out is not None else torch.empty((batch, M, N), dtype=A.dtype, device=A.device)
     rs = None
     if rowsum:
         rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
                                                                    device=A.device)
-    rc = lib.pgk_gemm_fused(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
-                            rs.data_ptr() if rs is not None else None,
-                            M, N, K, batch, int(act), dtype, _stream_ptr(stream) or None)
+    rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
+               rs.data_ptr() if rs is not None else None,
+               M, N, K, batch, int(act), dtype, _stream_ptr(stream) or None)
     if rc != 0:
-        raise PgkError(rc, "pgk_gemm_fused")
+        raise PgkError(rc, "pgk_gemm_fused_bt" if b_transposed else "pgk_gemm_fused")
     return C, rs
+
+
+def gemm_fused_bt(A: torch.Tensor, Bt: torch.Tensor, bias: Optional[torch.Tensor], act: int, **kw):
+    """C = act(A @ Bt^T + bias) with Bt [batch, N, K] read in place (pgk_gemm_fused_bt)."""
+    return gemm_fused(A, Bt, bias, act, b_transposed=True, **kw)
 
 
 def gemm_splitk(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
                 splits: int = 0, rowsum: bool = True, out: Optional[torch.Tensor] = None,
                 rowsum_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
-                stream=None):
-    """Two-pass split-K variant (pgk_gemm_splitk).  ``workspace`` is a uint8 device
-    tensor of at least ``splitk_workspace_bytes(...)`` bytes; allocated here when None."""
+                stream=None, b_transposed: bool = False):
+    """Two-pass split-K variant (pgk_gemm_splitk; pgk_gemm_splitk_bt when ``b_transposed``).
+    ``workspace`` is a uint8 device tensor of at least ``splitk_workspace_bytes(...)`` bytes;
+    allocated here when None."""
     lib = load_library()
-    batch, M, N, K, dtype = _shape(A, B)
+    batch, M, N, K, dtype = _shape(A, B, b_transposed)
+    entry = lib.pgk_gemm_splitk_bt if b_transposed else lib.pgk_gemm_splitk
     need = splitk_workspace_bytes(M, N, K, batch, dtype, splits)
     if workspace is None:
         workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=A.device)
@@ -168,14 +183,19 @@ def gemm_splitk(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], 
     if rowsum:
         rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
                                                                    device=A.device)
-    rc = lib.pgk_gemm_splitk(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
-                             rs.data_ptr() if rs is not None else None,
-                             M, N, K, batch, int(act), dtype, int(splits),
-                             workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-                             _stream_ptr(stream) or None)
+    rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
+               rs.data_ptr() if rs is not None else None,
+               M, N, K, batch, int(act), dtype, int(splits),
+               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
+               _stream_ptr(stream) or None)
     if rc != 0:
-        raise PgkError(rc, "pgk_gemm_splitk")
+        raise PgkError(rc, "pgk_gemm_splitk_bt" if b_transposed else "pgk_gemm_splitk")
     return C, rs
+
+
+def gemm_splitk_bt(A: torch.Tensor, Bt: torch.Tensor, bias: Optional[torch.Tensor], act: int, **kw):
+    """Split-K variant with Bt [batch, N, K] read in place (pgk_gemm_splitk_bt)."""
+    return gemm_splitk(A, Bt, bias, act, b_transposed=True, **kw)
 
 
 def reduce_max(X: torch.Tensor, dim: int, want_idx: bool = True, out: Optional[torch.Tensor] = None,

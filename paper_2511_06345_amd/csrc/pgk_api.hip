@@ -21,6 +21,7 @@ constexpr int64_t kFusedCombineMaxWorkgroups = 64;
 constexpr int kMinStepsPerSlice = 16;
 constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // scratch pgk_gemm_fused may take for an automatic split
 constexpr int kMaxAutoSplits = 32;
+constexpr int64_t kLongKSteps = 512;
 
 bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -45,7 +46,7 @@ int kstep_of(int dtype) { return pgk::mfma_tile_shape(dtype, false).bk; }
 // and the number of non-empty slices.
 struct SplitPlan { int splits; int k_slice; };
 
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = false)
 {
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
@@ -55,7 +56,8 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype)
     if (K % (16 / es) || N % (16 / es)) return false;
     if (M < 16 || N < 16) return false;
     // per-lane 32-bit byte offsets inside one tile
-    if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * N * es >= (1LL << 32)) return false;
+    if ((int64_t)t.bm * K * es >= (1LL << 32)) return false;
+    if ((b_trans ? (int64_t)t.bn * K : (int64_t)t.bk * N) * es >= (1LL << 32)) return false;
     return true;
 }
 
@@ -183,9 +185,10 @@ struct Path { bool mfma; bool small; pgk::TileShape tile; };
 // `units` = batch entries x K splits: workgroups per output tile position.
 // small_tile_forced: -1 = by the grid size, 0 / 1 = the caller (an automatic split plan) decides
 Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
-                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int small_tile_forced = -1)
+                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int small_tile_forced = -1,
+                 bool b_trans = false)
 {
-    const bool ok = mfma_shape_ok(M, N, K, dtype) && aligned16(A) && aligned16(B) && aligned16(C) &&
+    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
     // the small tile when the large-tile grid would leave a quarter of the CUs idle, or when
@@ -202,9 +205,9 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
 // column segments (nseg from splitk_reduce_segments), else unused.
 int run_split_passes(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
                      int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, int small_tile,
-                     float* workspace, float* part, hipStream_t st)
+                     float* workspace, float* part, hipStream_t st, bool b_trans)
 {
-    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits, small_tile);
+    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits, small_tile, b_trans);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -214,6 +217,7 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
     a.ws = workspace;
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
     pgk::fill_plain_views(a);
+    if (b_trans) pgk::set_b_transposed(a);
     a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
@@ -234,18 +238,15 @@ size_t split_part_bytes(int64_t M, int64_t N, int64_t batch, bool rowsum)
     return (rowsum && nseg > 1) ? (size_t)batch * (size_t)nseg * (size_t)M * sizeof(float) : 0;
 }
 
-}  // namespace
-
-extern "C" {
-
-int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
-                   int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+// pgk_gemm_fused and pgk_gemm_fused_bt (b_trans: B given as [batch][N][K])
+int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream, bool b_trans)
 {
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch);
+    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch, -1, b_trans);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -253,7 +254,14 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
     // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
     // partial products in the library's scratch buffer.  The choice depends on the shape only.
-    if (path.mfma && tiles_m * tiles_n * batch < (3 * kNumCUs) / 4) {
+    // (Also when only the small-tile grid fills the chip and K is very long: 256 x 256 x 65536 x 16
+    // fp32 took 1536 us on 256 small tiles and 1083 us split; below 512 K tiles the split's extra
+    // pass costs more than it gains -- 2048 x 2048 x 16384 bf16: 130 us against 152 us.)
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
+    const int64_t big_tiles = ((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * batch;
+    const bool few_tiles = tiles_m * tiles_n * batch < (3 * kNumCUs) / 4;
+    const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
+    if (path.mfma && (few_tiles || long_k)) {
         const SplitPlan plan = plan_splits(M, N, K, batch, dtype, 0);
         const int small_tile = (int)auto_split(M, N, K, batch, dtype).small_tile;
         const long double ws_bytes = (long double)batch * plan.splits * M * N * sizeof(float);
@@ -262,7 +270,7 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
             float* buf = nullptr;
             if (scratch_get(st, (size_t)ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
             return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile, buf,
-                                    buf + (size_t)ws_bytes / sizeof(float), st);
+                                    buf + (size_t)ws_bytes / sizeof(float), st, b_trans);
         }
     }
 
@@ -270,6 +278,7 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     a.A = A; a.B = B; a.bias = bias; a.C = C; a.ws = nullptr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
     pgk::fill_plain_views(a);
+    if (b_trans) pgk::set_b_transposed(a);
     a.act = act; a.splits = 1;
     a.k_slice = (int)(((K + path.tile.bk - 1) / path.tile.bk) * path.tile.bk);
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
@@ -303,6 +312,22 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
     return PGK_OK;
 }
 
+}  // namespace
+
+extern "C" {
+
+int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                   int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+{
+    return gemm_fused_impl(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, stream, false);
+}
+
+int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
+                      int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+{
+    return gemm_fused_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, stream, true);
+}
+
 int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
 {
     if (M <= 0 || N <= 0 || K <= 0 || batch <= 0) return 0;
@@ -321,9 +346,13 @@ size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch
     return (size_t)batch * (size_t)s * (size_t)M * (size_t)N * sizeof(float);
 }
 
-int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, float* rowsum,
-                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, int splits,
-                    void* workspace, size_t workspace_bytes, void* stream)
+}  // extern "C"
+
+namespace {
+
+int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                     int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, int splits,
+                     void* workspace, size_t workspace_bytes, void* stream, bool b_trans)
 {
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
@@ -341,7 +370,27 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
     // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
     const int small_tile = (splits == 0 && mfma_shape_ok(M, N, K, dtype)) ? (int)auto_split(M, N, K, batch, dtype).small_tile : -1;
     return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile,
-                            static_cast<float*>(workspace), part, st);
+                            static_cast<float*>(workspace), part, st, b_trans);
+}
+
+}  // namespace
+
+extern "C" {
+
+int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, int splits,
+                    void* workspace, size_t workspace_bytes, void* stream)
+{
+    return gemm_splitk_impl(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, splits, workspace, workspace_bytes,
+                            stream, false);
+}
+
+int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
+                       int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, int splits,
+                       void* workspace, size_t workspace_bytes, void* stream)
+{
+    return gemm_splitk_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, splits, workspace, workspace_bytes,
+                            stream, true);
 }
 
 int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_t red, int64_t inner,

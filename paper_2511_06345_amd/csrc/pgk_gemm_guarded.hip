@@ -65,11 +65,11 @@ __global__ __launch_bounds__(256) void gemm_guarded_kernel(const GemmArgs p, con
             if (gm < p.M && gk < k_end) v = load_elem<BF16>(p.A, a_base + (size_t)gm * p.K + gk);
             As[kk][mm] = v;
         }
-        // B tile: 16 k x 64 cols
+        // B tile: 16 k x 64 cols (k fastest across threads when B is given transposed)
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
             const int idx = tid + 256 * e;
-            const int kk = idx >> 6, nn = idx & 63;
+            const int kk = p.b_trans ? (idx & 15) : (idx >> 6), nn = p.b_trans ? (idx >> 4) : (idx & 63);
             const int gk = k0 + kk, gn = n0 + nn;
             float v = 0.0f;
             if (gk < k_end && gn < p.N) {
@@ -79,6 +79,8 @@ __global__ __launch_bounds__(256) void gemm_guarded_kernel(const GemmArgs p, con
                     const long long pos = (long long)gn * p.conv_stride + (long long)tap * p.conv_dil - p.conv_pad;
                     if (pos >= 0 && pos < p.conv_len)
                         v = load_elem<BF16>(p.B, b_base + (size_t)ci * (size_t)p.conv_len + (size_t)pos);
+                } else if (p.b_trans) {
+                    v = load_elem<BF16>(p.B, b_base + (size_t)gn * p.ldb + gk);
                 } else {
                     v = load_elem<BF16>(p.B, b_base + (size_t)gk * p.ldb + gn);
                 }

@@ -31,9 +31,12 @@
 
 namespace pgk {
 
-template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
-struct MfmaCfg {
+template <bool BT_, bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
+struct MfmaCfgBase {
     static constexpr bool BF16 = BF16_;
+    // B given transposed, [N][K] with K contiguous (a linear layer's weight as stored): its
+    // tile then sits in LDS like the A tile, [BN][BK], and is fetched like it
+    static constexpr bool BT = BT_;
     static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
     // LDS ring depth of the A tiles (2 or 3); the B tiles always have 2 stages.  With 3,
     // the copy of an A tile is issued a whole K tile earlier than it is needed, so only
@@ -48,8 +51,8 @@ struct MfmaCfg {
     static constexpr int WN = BN / WGN;            // cols per wave
     static constexpr int TM = WM / 32, TN = WN / 32;
     static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
-    static constexpr int RB = BN * ES;             // LDS row bytes of the B tile
-    static constexpr int A_BYTES = BM * RA, B_BYTES = BK * RB;
+    static constexpr int RB = BT ? BK * ES : BN * ES;   // LDS row bytes of the B tile
+    static constexpr int A_BYTES = BM * RA, B_BYTES = BN * BK * ES;
     static constexpr int A_CPW = A_BYTES / 1024 / NW;  // 1 KiB copy instructions per wave
     static constexpr int B_CPW = B_BYTES / 1024 / NW;
     static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
@@ -58,10 +61,16 @@ struct MfmaCfg {
     static_assert(A_STAGES == 2 || A_STAGES == 3, "A ring depth");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
     static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
-    static_assert(RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
+    static_assert(BT || RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
     static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile / wave split");
     static_assert(BM <= NT, "row-sum combine uses one thread per tile row");
 };
+// <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>: B as [K][N] ...
+template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
+struct MfmaCfg : MfmaCfgBase<false, BF16_, BM_, BN_, BK_, WGM_, WGN_, A_STAGES_, WAVES_PER_SIMD_> {};
+// ... and B given transposed, [N][K]
+template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
+struct MfmaCfgBt : MfmaCfgBase<true, BF16_, BM_, BN_, BK_, WGM_, WGN_, A_STAGES_, WAVES_PER_SIMD_> {};
 
 // A tile: rows of CPR chunks; 16 consecutive rows read the same logical chunk
 // at once, so the 16 chunk slots of a 256-byte bank period must all differ.
@@ -259,17 +268,19 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             b_col0 = 0;
         }
     }
+    // (transposed B: rows are tile columns, K runs along them)
     const unsigned char* Bg = b_src +
-        ((long long)b * b_batch_stride + (long long)k_begin * ldb + b_col0) * ES;
+        (Cfg::BT ? ((long long)b * b_batch_stride + b_col0 * ldb + (long long)k_begin) * ES
+                 : ((long long)b * b_batch_stride + (long long)k_begin * ldb + b_col0) * ES);
     const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
-    const size_t b_step = (size_t)BK * ldb * ES;       // bytes per K tile down B
+    const size_t b_step = Cfg::BT ? (size_t)BK * ES : (size_t)BK * ldb * ES;   // bytes per K tile of B
     // one past the last byte of A and of B: copies of a partial K tile run past the end of a
     // row (into the next row, harmless) and, for the last row, past the end of the array,
     // where the buffer resource's size check makes them read nothing
     const unsigned char* const A_end = (const unsigned char*)p.A +
         ((size_t)(p.batch - 1) * (size_t)p.a_batch_stride + (size_t)p.M * p.K) * ES;
     const unsigned char* const B_end = (const unsigned char*)p.B +
-        ((size_t)(p.batch - 1) * (size_t)p.b_batch_stride + (size_t)p.K * p.ldb) * ES;
+        ((size_t)(p.batch - 1) * (size_t)p.b_batch_stride + (size_t)(Cfg::BT ? p.N : p.K) * p.ldb) * ES;
 
     // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
     const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
@@ -300,12 +311,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
     for (int t = 0; t < Cfg::B_CPW; ++t) {
         const int ch = wave * Cfg::B_CPW + t;
-        const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
-        const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
-        // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
-        constexpr int EPC = 16 / ES;                      // elements per chunk
-        const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
-        voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
+        if constexpr (Cfg::BT) {
+            // rows of the transposed B are tile columns: same scheme as for A
+            const int r = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
+            const int c = (lane % Cfg::B_CPR) ^ swz_a<Cfg::B_CPR>(r);
+            const int rg = r < n_rem ? r : n_rem - 1;
+            voff_b[t] = (unsigned int)rg * (unsigned int)ldb * ES + (unsigned int)c * 16u;
+        } else {
+            const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
+            const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
+            // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
+            constexpr int EPC = 16 / ES;                      // elements per chunk
+            const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
+            voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
+        }
     }
 
     auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
@@ -382,7 +401,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
         for (int t = 0; t < Cfg::B_CPW; ++t) {
             const int kr = (wave * Cfg::B_CPW + t) * Cfg::B_RPC + lane / Cfg::B_CPR;
-            if (kr >= k_last)
+            const int cb = (lane % Cfg::B_CPR) ^ swz_a<Cfg::B_CPR>(kr);   // transposed B: kr is a tile column
+            if (Cfg::BT ? cb * EPC >= k_last : kr >= k_last)
                 *(__attribute__((address_space(3))) u32x4*)PGK_LDS(lds_b(stb) + wave * (Cfg::B_CPW * 1024) + t * 1024 + lane * 16) = zero;
         }
     };
@@ -396,8 +416,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
     for (int s = 0; s < NS; ++s) a_koff[s] = a_row_off + (((2 * s + half) ^ swz_a<Cfg::A_CPR>(l32)) * 16);
     // B columns (MFMA "A" operand)
-    int b_off[TN];
-    if constexpr (BF16) {
+    int b_off[Cfg::BT ? NS : TN];
+    if constexpr (Cfg::BT) {
+        // transposed B: column n of B is row n of the LDS tile; per step like a_koff
+#pragma unroll
+        for (int s = 0; s < NS; ++s)
+            b_off[s] = (wn * Cfg::WN + l32) * RB + (((2 * s + half) ^ swz_a<Cfg::B_CPR>(l32)) * 16);
+    } else if constexpr (BF16) {
         const int grp = lane >> 4, pl = lane & 15;
 #pragma unroll
         for (int j = 0; j < TN; ++j) {
@@ -419,24 +444,34 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // Operand fragments for one step.  bf16: one step = one MFMA K (16); the B
     // operand arrives as two transposing 64-bit reads.  fp32: one step = 8 K values =
     // four MFMAs per tile pair.
+    // Transposed B: its fragments look like A's (one 128-bit read per 32 columns and step).
     struct FragBF16 { bf16x8 a[TM]; s16x4 blo[TN], bhi[TN]; };
     struct FragF32 { f32x4 a[TM]; float b[4][TN]; };
-    using Frag = typename std::conditional<BF16, FragBF16, FragF32>::type;
+    struct FragBF16T { bf16x8 a[TM]; bf16x8 bt[TN]; };
+    struct FragF32T { f32x4 a[TM]; f32x4 bt[TN]; };
+    using Frag = typename std::conditional<Cfg::BT, typename std::conditional<BF16, FragBF16T, FragF32T>::type,
+                                           typename std::conditional<BF16, FragBF16, FragF32>::type>::type;
 
     // LDS fetches of one step, numbered in the order the MFMAs need them (the MFMAs
     // run over the A fragments in the outer loop): A fragment 0, every B fragment,
     // then the remaining A fragments.
-    constexpr int N_DS = BF16 ? TM + 2 * TN : TM + 4 * TN;
+    constexpr int N_DS = Cfg::BT ? TM + TN : BF16 ? TM + 2 * TN : TM + 4 * TN;
     auto fetch_op = [&](auto sta, auto stb, int s, Frag& f, int q) __attribute__((always_inline)) {
         const unsigned char* as = lds_a(sta);
         const unsigned char* bs = lds_b(stb);
-        constexpr int NB = BF16 ? 2 * TN : 4 * TN;
+        constexpr int NB = Cfg::BT ? TN : BF16 ? 2 * TN : 4 * TN;
         if (q == 0 || q > NB) {
             const int i = q == 0 ? 0 : q - NB;
             if constexpr (BF16)
                 f.a[i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
             else
                 f.a[i] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
+        } else if constexpr (Cfg::BT) {
+            const int j = q - 1;
+            if constexpr (BF16)
+                f.bt[j] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
+            else
+                f.bt[j] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
         } else if constexpr (BF16) {
             const int j = (q - 1) / 2, h = (q - 1) % 2;
             const unsigned char* src = bs + b_off[j] + (16 * s + 4 * h) * RB;
@@ -463,7 +498,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // MFMA number m of a step (A fragments in the outer loop)
     constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
     auto mfma_op = [&](const Frag& f, int m) __attribute__((always_inline)) {
-        if constexpr (BF16) {
+        if constexpr (Cfg::BT && BF16) {
+            const int i = m / TN, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.bt[j], f.a[i], acc[i][j], 0, 0, 0);
+        } else if constexpr (Cfg::BT) {
+            const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
+            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.bt[j][t], f.a[i][t], acc[i][j], 0, 0, 0);
+        } else if constexpr (BF16) {
             const int i = m / TN, j = m % TN;
             const s16x8 both = __builtin_shufflevector(f.blo[j], f.bhi[j], 0, 1, 2, 3, 4, 5, 6, 7);
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), f.a[i], acc[i][j], 0, 0, 0);
@@ -749,6 +790,11 @@ using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>;
 using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 2, 1>;
 using CfgBF16Small = MfmaCfg<true, 128, 128, 64, 2, 2, 3, 2>;
 using CfgF32Small = MfmaCfg<false, 64, 64, 32, 2, 2, 2, 2>;
+// the same four for B given transposed ([N][K])
+using CfgBF16T = MfmaCfgBt<true, 256, 256, 64, 4, 2, 3, 2>;
+using CfgF32T = MfmaCfgBt<false, 128, 128, 32, 2, 2, 2, 1>;
+using CfgBF16SmallT = MfmaCfgBt<true, 128, 128, 64, 2, 2, 3, 2>;
+using CfgF32SmallT = MfmaCfgBt<false, 64, 64, 32, 2, 2, 2, 2>;
 
 TileShape mfma_tile_shape(int dtype, bool small)
 {
@@ -770,6 +816,12 @@ static hipError_t launch_cfg(const GemmArgs& a, int out_mode, hipStream_t s)
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s)
 {
+    if (a.b_trans) {
+        // the operand views of the convolution path assume B as [K][N]
+        if (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0]) return hipErrorInvalidValue;
+        if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16SmallT>(a, out_mode, s) : launch_cfg<CfgBF16T>(a, out_mode, s);
+        return small ? launch_cfg<CfgF32SmallT>(a, out_mode, s) : launch_cfg<CfgF32T>(a, out_mode, s);
+    }
     if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16Small>(a, out_mode, s) : launch_cfg<CfgBF16>(a, out_mode, s);
     return small ? launch_cfg<CfgF32Small>(a, out_mode, s) : launch_cfg<CfgF32>(a, out_mode, s);
 }

@@ -32,6 +32,7 @@ struct GemmArgs {
     // between the batch entries.
     long long a_batch_stride, b_batch_stride;   // elements between batch entries of A and of B
     int ldb;                 // elements between rows of B
+    int b_trans;             // 1: B is given transposed, [batch][N][ldb >= K], K contiguous
     int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
     // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
@@ -61,6 +62,7 @@ inline void fill_plain_views(GemmArgs& a)
     a.a_batch_stride = (long long)a.M * a.K;
     a.b_batch_stride = (long long)a.K * a.N;
     a.ldb = a.N;
+    a.b_trans = 0;
     a.bias_per_row = 0;
     a.b_tiles_per_tap = 0x7fffffff;
     a.b_tap_step = 0;
@@ -69,6 +71,13 @@ inline void fill_plain_views(GemmArgs& a)
     a.edge_ldb = 0;
     a.edge_batch_stride = 0;
     a.conv_kw = 0; a.conv_stride = 1; a.conv_pad = 0; a.conv_dil = 1; a.conv_len = 0;
+}
+
+// B given as [batch][N][K] (call after fill_plain_views)
+inline void set_b_transposed(GemmArgs& a)
+{
+    a.b_trans = 1;
+    a.ldb = a.K;
 }
 
 // Tile geometry of the matrix-core kernels: a large and a small tile per element

@@ -45,6 +45,35 @@ def test_hand_non_square_detects_transposition(oracle):
     assert rs[0].tolist() == [127.0, 148.0]
 
 
+def test_hand_transposed_second_factor(oracle):
+    # the same product with the second factor handed over as its transpose [N][K]
+    A = f32([[1, 2, 3], [4, 5, 6]])
+    Bt = f32([[1, 0, 3], [0, 2, 1]])
+    C, rs = oracle.gemm_fused_bt(A, Bt, f32([10, 100]), NONE)
+    assert C[0].tolist() == [[20.0, 107.0], [32.0, 116.0]]
+    assert rs[0].tolist() == [127.0, 148.0]
+    # a linear layer by hand: y = x W^T + b with W [out=3][in=2]
+    x = f32([[1, -1]])
+    W = f32([[2, 3], [5, 7], [-1, 4]])
+    C, _ = oracle.gemm_fused_bt(x, W, f32([0.5, 0, 1]), RELU)
+    assert C[0].tolist() == [[0.0, 0.0, 0.0]]
+    C, _ = oracle.gemm_fused_bt(x, W, f32([1.5, 0, 6]), NONE)
+    assert C[0].tolist() == [[0.5, -2.0, 1.0]]
+
+
+@pytest.mark.parametrize("seed,shape", [(10, (33, 17, 65, 2)), (11, (8, 128, 40, 1))])
+def test_transposed_against_numpy_float64(oracle, seed, shape):
+    M, N, K, batch = shape
+    rng = np.random.default_rng(seed)
+    A = rng.uniform(-1, 1, (batch, M, K)).astype(np.float32)
+    Bt = rng.uniform(-1, 1, (batch, N, K)).astype(np.float32)
+    bias = rng.standard_normal(N).astype(np.float32)
+    ref = np.einsum("bmk,bnk->bmn", A.astype(np.float64), Bt.astype(np.float64)) + bias.astype(np.float64)
+    C, rs = oracle.gemm_fused_bt(A, Bt, bias, NONE)
+    assert np.max(np.abs(C - ref)) <= 1e-12 * max(np.sqrt(np.mean(ref ** 2)), 1.0)
+    assert np.max(np.abs(rs - ref.sum(axis=2))) <= 1e-11 * np.sqrt(N) * max(np.sqrt(np.mean(ref ** 2)), 1.0)
+
+
 def test_degenerate_shapes(oracle):
     C, rs = oracle.gemm_fused(f32([[3]]), f32([[-2]]), f32([1]), NONE)       # 1x1x1
     assert C.ravel().tolist() == [-5.0] and rs.ravel().tolist() == [-5.0]
