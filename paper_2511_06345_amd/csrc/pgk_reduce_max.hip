@@ -297,7 +297,40 @@ __global__ __launch_bounds__(256) void reduce_max_finish_kernel(const float* __r
     if (idx) idx[t] = p;
 }
 
+// The same with one wave per output, for many segments (few outputs, long rows): the lanes
+// take every 64th segment, then the pairs are combined across the lanes.  The combine picks
+// by (value, then earlier position), so the order it is applied in does not matter.
+template <bool BF16>
+__global__ __launch_bounds__(256) void reduce_max_finish_wave_kernel(const float* __restrict__ pv, const int* __restrict__ pi,
+                                                                     void* __restrict__ out, int* __restrict__ idx,
+                                                                     long long outer, long long inner, int segs)
+{
+    const int lane = threadIdx.x & 63;
+    const long long t = (long long)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (t >= outer * inner) return;          // whole waves leave together
+    const long long o = t / inner, i = t - o * inner;
+    const size_t base = (size_t)o * segs * (size_t)inner + (size_t)i;
+    float v = kNegInf;
+    int p = kNoPos;
+    for (int s = lane; s < segs; s += 64) {
+        const float ov = pv[base + (size_t)s * (size_t)inner];
+        const int op = pi[base + (size_t)s * (size_t)inner];
+        if (beats(ov, op, v, p)) { v = ov; p = op; }
+    }
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(v, off, 64);
+        const int op = __shfl_xor(p, off, 64);
+        if (beats(ov, op, v, p)) { v = ov; p = op; }
+    }
+    if (lane == 0) {
+        store_one<BF16>(out, (size_t)t, v);
+        if (idx) idx[t] = p;
+    }
+}
+
 constexpr int kTargetWorkgroups = 2048;           // eight per CU
+constexpr int kWaveFinishMinSegs = 16;
 
 }  // namespace
 
@@ -367,6 +400,13 @@ hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || pl.segs == 1) return e;
     const long long outs = outer * inner;
+    if (pl.segs >= kWaveFinishMinSegs) {
+        const long long wb = (outs + 3) / 4;
+        if (wb > 0x7fffffffLL) return hipErrorInvalidValue;
+        if (bf) hipLaunchKernelGGL(reduce_max_finish_wave_kernel<true>, dim3((unsigned int)wb), block, 0, s, pv, pi, out, idx, outer, inner, pl.segs);
+        else hipLaunchKernelGGL(reduce_max_finish_wave_kernel<false>, dim3((unsigned int)wb), block, 0, s, pv, pi, out, idx, outer, inner, pl.segs);
+        return hipGetLastError();
+    }
     const long long fb = (outs + 255) / 256;
     if (fb > 0x7fffffffLL) return hipErrorInvalidValue;
     if (bf) hipLaunchKernelGGL(reduce_max_finish_kernel<true>, dim3((unsigned int)fb), block, 0, s, pv, pi, out, idx, outer, inner, pl.segs);
