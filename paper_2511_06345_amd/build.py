@@ -5,6 +5,7 @@ import json
 import os
 import re
 import subprocess
+import sys
 from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
@@ -89,9 +90,13 @@ def build_library(verbose: bool = False) -> str:
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"link failed:\n{res.stderr}")
-    # every symbol must resolve: load the library the way the binding does
-    import ctypes
-    ctypes.CDLL(LIB, mode=getattr(os, "RTLD_NOW", 2))
+    # every symbol must resolve: load the library with immediate binding -- in a child process,
+    # so that this process does not end up with the system's HIP runtime loaded ahead of the one
+    # torch brings along (two runtimes in one process: launches then fail)
+    check = "import ctypes, os, sys; ctypes.CDLL(sys.argv[1], mode=getattr(os, 'RTLD_NOW', 2))"
+    res = subprocess.run([sys.executable, "-c", check, LIB], capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError(f"{LIB} does not load:\n{res.stderr}")
     if verbose:
         print(f"built {LIB}")
     return LIB
