@@ -211,6 +211,49 @@ def test_skinny_splitk_is_exact_on_integers(pgk, oracle, dtype):
             assert np.array_equal(got_c, ref_c) and np.array_equal(got_rs, ref_rs), f"{shape} splits {splits}"
 
 
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("which", ["A", "B", "C", "bias", "workspace"])
+def test_pointers_off_the_16_byte_grid(pgk, oracle, dtype, which):
+    """A tile-friendly shape with one pointer a single element past a 16-byte boundary: the
+    matrix-core kernels cannot take it, the bounds-checked kernel must, with the same result."""
+    import torch
+    M, N, K, batch = 128, 256, 192, 2
+    A, B, bias = random_case(dtype, M, N, K, batch, seed=41)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, SILU)
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+
+    def shifted(t):
+        flat = torch.empty(t.numel() + 1, dtype=t.dtype, device="cuda")
+        v = flat[1:].view(t.shape)
+        v.copy_(t)
+        assert v.data_ptr() % 16 != 0 and v.is_contiguous()
+        return v
+
+    dA, dB, dbias = to_device(A, dtype), to_device(B, dtype), torch.from_numpy(bias).cuda()
+    C = torch.empty((batch, M, N), dtype=tdt, device="cuda")
+    if which == "A":
+        dA = shifted(dA)
+    elif which == "B":
+        dB = shifted(dB)
+    elif which == "C":
+        C = shifted(C)
+    elif which == "bias":
+        dbias = shifted(dbias)
+    if which == "workspace":
+        need = pgk.splitk_workspace_bytes(M, N, K, batch, dtype, 2)
+        ws = torch.empty(need + 16, dtype=torch.uint8, device="cuda")[4:]
+        with pytest.raises(pgk.PgkError) as ei:      # the workspace is the caller's: it must be aligned
+            pgk.gemm_splitk(dA, dB, dbias, SILU, splits=2, out=C, workspace=ws)
+        assert ei.value.status == -3
+        return
+    C, rs = pgk.gemm_fused(dA, dB, dbias, SILU, out=C)
+    torch.cuda.synchronize()
+    check(c_to_numpy(C, dtype), rs.cpu().numpy().astype(np.float64), ref_c, ref_rs, dtype, f"misaligned {which}")
+    C2, rs2 = pgk.gemm_splitk(dA, dB, dbias, SILU, splits=3, out=torch.empty_like(C))
+    torch.cuda.synchronize()
+    check(c_to_numpy(C2, dtype), rs2.cpu().numpy().astype(np.float64), ref_c, ref_rs, dtype, f"misaligned {which}, split")
+
+
 def test_identity_operand_passes_b_through(pgk, oracle):
     # A = I: C = act(B + bias) -- exercises operand roles (a transposed B would fail)
     n = 256
