@@ -180,7 +180,26 @@ hipError_t counters_get(hipStream_t stream, size_t count, unsigned int** out)
     return hipSuccess;
 }
 
-struct Path { bool mfma; bool small; pgk::TileShape tile; };
+struct Path { bool mfma; int kind; pgk::TileShape tile; };
+
+// Half of a large tile (tall: half as wide; wide: half as high) when that takes away at least
+// a third of the padded area the large tiles would compute -- the last tile column or row at
+// most half full and few of them -- and still gives a grid that fills the chip.  (With less
+// padding to save the large tile's better main loop wins: a half tile moves three quarters of
+// the operand bytes per K tile for half the matrix work.)
+int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
+{
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, pgk::TILE_LARGE);
+    const long double area_large = (long double)((M + big.bm - 1) / big.bm * big.bm) * ((N + big.bn - 1) / big.bn * big.bn);
+    for (int kind : {pgk::TILE_TALL, pgk::TILE_WIDE}) {
+        if (!pgk::mfma_has_tile(dtype, kind, b_trans)) continue;
+        const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
+        const int64_t tm = (M + t.bm - 1) / t.bm, tn = (N + t.bn - 1) / t.bn;
+        const long double area = (long double)(tm * t.bm) * (tn * t.bn);
+        if (3 * area <= 2 * area_large && (long double)tm * tn * units >= 0.75L * kNumCUs) return kind;
+    }
+    return -1;
+}
 
 // `units` = batch entries x K splits: workgroups per output tile position.
 // small_tile_forced: -1 = by the grid size, 0 / 1 = the caller (an automatic split plan) decides
@@ -195,9 +214,17 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
     // half of a large tile would be empty
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    const bool small = small_tile_forced >= 0 ? small_tile_forced != 0
-                                              : (wgs < 0.75L * kNumCUs || large_tile_mostly_empty(M, N, dtype));
-    return Path{true, small, pgk::mfma_tile_shape(dtype, small)};
+    int kind;
+    if (small_tile_forced >= 0) {
+        kind = small_tile_forced != 0 ? pgk::TILE_SMALL : pgk::TILE_LARGE;
+    } else if (large_tile_mostly_empty(M, N, dtype)) {
+        kind = pgk::TILE_SMALL;
+    } else if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) {
+        kind = half;
+    } else {
+        kind = wgs < 0.75L * kNumCUs ? pgk::TILE_SMALL : pgk::TILE_LARGE;
+    }
+    return Path{true, kind, pgk::mfma_tile_shape(dtype, kind)};
 }
 
 // The two passes of the split-K path.  `workspace`: batch * plan.splits * M * N floats;
@@ -222,7 +249,7 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
 
-    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.kind, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     const int nseg = pgk::splitk_reduce_segments((int)M, (int)N, (int)batch);
     float* rs_part = (rowsum && nseg > 1) ? part : nullptr;
@@ -303,7 +330,7 @@ int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, fl
             }
         }
     }
-    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.small, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
+    hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.kind, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     if (part) {
         e = pgk::launch_rowsum_combine(part, rowsum, (int)M, (int)batch, (int)tiles_n, st);
@@ -563,8 +590,8 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
             bsrc = xp;
             ldb = pl.Lp;
         }
-        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B);
-        if (!path.mfma || path.small != pl.small_tile) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
+        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B, (int)pl.small_tile);
+        if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
         a.b_batch_stride = Cin * ldb;
         a.ldb = (int)ldb;
@@ -575,7 +602,7 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
         a.tiles_n = (int)((pl.Lout + path.tile.bn - 1) / path.tile.bn);
         if ((long double)a.tiles_m * a.tiles_n * B > 2.0e9L) return PGK_ERR_UNSUPPORTED;
         a.group_m = group_m_for(a.tiles_m, a.tiles_n);
-        return pgk::launch_gemm_mfma(a, dtype, path.small, 0, st) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+        return pgk::launch_gemm_mfma(a, dtype, path.kind, 0, st) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
     }
     // bounds-checked kernel, input read in place
     const pgk::TileShape t = pgk::guarded_tile_shape();

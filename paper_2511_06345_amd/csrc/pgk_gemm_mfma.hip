@@ -668,9 +668,13 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     // ---- epilogue: activation into LDS (the operand buffers are free now), then
     // whole-row stores.  The row-sum exchange has a small buffer of its own.
-    static_assert(Cfg::A_BYTES == Cfg::B_BYTES && 4 * Cfg::A_BYTES >= BM * BN * (BF16 ? 2 : 4) &&
+    // the output tile is staged in pieces of A_BYTES, whole 32-row blocks each, in the two A
+    // stages and, when it needs more than two pieces, the two B stages
+    constexpr int OUT_PIECES = BM * BN * (BF16 ? 2 : 4) / Cfg::A_BYTES;
+    static_assert(OUT_PIECES * Cfg::A_BYTES == BM * BN * (BF16 ? 2 : 4) && OUT_PIECES <= 4 &&
+                  (OUT_PIECES <= 2 || Cfg::B_BYTES >= Cfg::A_BYTES) &&
                   (Cfg::A_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
-                  "the first four operand buffers hold the output tile, whole 32-row blocks each");
+                  "the operand buffers hold the output tile, whole 32-row blocks each");
     // row-sum exchange buffer: the third A stage when there is one, else a small array
     // (followed by the tile's biases, BIAS_N floats)
     __shared__ __attribute__((aligned(16))) float rs_own[SA > 2 ? 4 : Cfg::WGN * BM + 2 * BIAS_N];
@@ -790,19 +794,32 @@ using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>;
 using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 2, 1>;
 using CfgBF16Small = MfmaCfg<true, 128, 128, 64, 2, 2, 3, 2>;
 using CfgF32Small = MfmaCfg<false, 64, 64, 32, 2, 2, 2, 2>;
+// Halves of the large bf16 tile, eight waves of 64x64, for outputs whose last tile column (tall,
+// 256x128) or last tile row (wide, 128x256) would be at most half full with the large tile:
+using CfgBF16Tall = MfmaCfg<true, 256, 128, 64, 4, 2, 3, 2>;
+using CfgBF16Wide = MfmaCfg<true, 128, 256, 64, 2, 4, 3, 2>;
 // the same four for B given transposed ([N][K])
 using CfgBF16T = MfmaCfgBt<true, 256, 256, 64, 4, 2, 3, 2>;
 using CfgF32T = MfmaCfgBt<false, 128, 128, 32, 2, 2, 2, 1>;
 using CfgBF16SmallT = MfmaCfgBt<true, 128, 128, 64, 2, 2, 3, 2>;
 using CfgF32SmallT = MfmaCfgBt<false, 64, 64, 32, 2, 2, 2, 2>;
 
-TileShape mfma_tile_shape(int dtype, bool small)
+bool mfma_has_tile(int dtype, int kind, bool b_trans)
 {
-    if (dtype == DT_BF16)
-        return small ? TileShape{CfgBF16Small::BM, CfgBF16Small::BN, CfgBF16Small::BK}
-                     : TileShape{CfgBF16::BM, CfgBF16::BN, CfgBF16::BK};
-    return small ? TileShape{CfgF32Small::BM, CfgF32Small::BN, CfgF32Small::BK}
-                 : TileShape{CfgF32::BM, CfgF32::BN, CfgF32::BK};
+    if (kind == TILE_LARGE || kind == TILE_SMALL) return true;
+    return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16 && !b_trans;
+}
+
+TileShape mfma_tile_shape(int dtype, int kind)
+{
+    if (dtype == DT_BF16) {
+        if (kind == TILE_TALL) return TileShape{CfgBF16Tall::BM, CfgBF16Tall::BN, CfgBF16Tall::BK};
+        if (kind == TILE_WIDE) return TileShape{CfgBF16Wide::BM, CfgBF16Wide::BN, CfgBF16Wide::BK};
+        return kind == TILE_SMALL ? TileShape{CfgBF16Small::BM, CfgBF16Small::BN, CfgBF16Small::BK}
+                                  : TileShape{CfgBF16::BM, CfgBF16::BN, CfgBF16::BK};
+    }
+    return kind == TILE_SMALL ? TileShape{CfgF32Small::BM, CfgF32Small::BN, CfgF32Small::BK}
+                              : TileShape{CfgF32::BM, CfgF32::BN, CfgF32::BK};
 }
 
 template <typename Cfg>
@@ -814,8 +831,12 @@ static hipError_t launch_cfg(const GemmArgs& a, int out_mode, hipStream_t s)
     return hipGetLastError();
 }
 
-hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s)
+hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s)
 {
+    if (!mfma_has_tile(dtype, kind, a.b_trans != 0)) return hipErrorInvalidValue;
+    const bool small = kind == TILE_SMALL;
+    if (kind == TILE_TALL) return launch_cfg<CfgBF16Tall>(a, out_mode, s);
+    if (kind == TILE_WIDE) return launch_cfg<CfgBF16Wide>(a, out_mode, s);
     if (a.b_trans) {
         // the operand views of the convolution path assume B as [K][N]
         if (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0]) return hipErrorInvalidValue;

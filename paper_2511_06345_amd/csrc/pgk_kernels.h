@@ -80,17 +80,21 @@ inline void set_b_transposed(GemmArgs& a)
     a.ldb = a.K;
 }
 
-// Tile geometry of the matrix-core kernels: a large and a small tile per element
-// type (same K tile), the small one for grids that would not fill the chip.
+// Tile geometry of the matrix-core kernels: a large and a small tile per element type (same
+// K tile), the small one for grids that would not fill the chip; for bf16 also the two halves
+// of the large tile (tall = half as wide, wide = half as high) for outputs whose last tile
+// column / row would be at most half full.  A kind the type does not have gives the large tile.
 struct TileShape { int bm, bn, bk; };
-TileShape mfma_tile_shape(int dtype, bool small);
+enum { TILE_LARGE = 0, TILE_SMALL = 1, TILE_TALL = 2, TILE_WIDE = 3 };
+TileShape mfma_tile_shape(int dtype, int kind);
+bool mfma_has_tile(int dtype, int kind, bool b_trans);
 TileShape guarded_tile_shape();
 
 // Matrix-core kernels: require k_slice % bk == 0, K and N multiples of the 16-byte
 // chunk (8 bf16 / 4 fp32 elements) and 16-byte aligned A, B, C, bias, ws.
 // M, N and K need not be tile multiples: edge tiles re-read valid rows / columns and
 // store only what exists; the missing columns of a partial last K tile are cleared in LDS.
-hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, bool small, int out_mode, hipStream_t s);
+hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.
 hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);

@@ -133,7 +133,10 @@ def test_integer_inputs_are_exact(pgk, oracle, dtype, shapes):
 LARGE_TILE_SHAPES = {F32: [(128, 128, 32, 192), (256, 128, 96, 100), (300, 260, 64, 40), (129, 140, 224, 70),
                            (128, 128, 36, 192), (300, 260, 100, 40), (129, 140, 300, 70)],
                      BF16: [(256, 256, 64, 192), (512, 256, 192, 100), (300, 520, 128, 40), (257, 264, 448, 50),
-                            (256, 256, 72, 192), (300, 520, 200, 40), (257, 264, 520, 50), (256, 256, 1032, 48)]}
+                            (256, 256, 72, 192), (300, 520, 200, 40), (257, 264, 520, 50), (256, 256, 1032, 48),
+                            # last tile column / row at most half full: the 256x128 and 128x256 tiles
+                            (512, 128, 192, 100), (300, 100, 200, 100), (256, 128, 1032, 192), (1024, 72, 64, 50),
+                            (128, 512, 192, 100), (100, 300, 520, 100), (128, 256, 72, 192), (72, 1024, 448, 50)]}
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
@@ -336,6 +339,22 @@ def test_workload_c4_sampled_rows(pgk, oracle):
 
 def test_workload_c5_sampled_rows(pgk, oracle):
     _workload_case(pgk, oracle, "c5", 24)
+
+
+@pytest.mark.parametrize("shape", [(65536, 128, 1024), (128, 65536, 1024)])
+def test_skinny_full_size_sampled_rows(pgk, oracle, shape):
+    """One dimension of 128: the half-width / half-height bf16 tiles at full size (256 workgroups)."""
+    import torch
+    M, N, K = shape
+    A = gen.f32_to_bf16_bits(gen.normal(gen.tensor_seed(94, 1, M), M * K, 1.0).reshape(1, M, K))
+    B = gen.f32_to_bf16_bits(gen.normal(gen.tensor_seed(94, 2, M), K * N, 1.0 / 32).reshape(1, K, N))
+    bias = gen.normal(gen.tensor_seed(94, 3, M), N, 0.5)
+    rows = sample_rows(M, 128, 32, seed=3)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, GELU, rows=rows)
+    C, rs = pgk.gemm_fused(to_device(A, BF16), to_device(B, BF16), torch.from_numpy(bias).cuda(), GELU)
+    torch.cuda.synchronize()
+    drows = torch.from_numpy(rows).cuda()
+    check(c_to_numpy(C[:, drows], BF16), rs[:, drows].cpu().numpy().astype(np.float64), ref_c, ref_rs, BF16, f"skinny {shape}")
 
 
 def test_workload_c3_without_bias_or_activation(pgk, oracle):
