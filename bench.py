@@ -33,10 +33,10 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
 # profiles/.  Valid only for the kernel configuration named here; None otherwise.
-TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745925602),
-                 "c4": ("MfmaCfg<true,256,256,64,4,2,3,2>", 235676098),
-                 "c2": ("MfmaCfg<false,128,128,32,2,2,2,1>", 1204777242)}
-REDUCE_TRAFFIC_BYTES = {"r1": 1082787077, "r3": 1091703547, "r4": 1073967935}   # both kernels of a call
+TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745612876),
+                 "c4": ("MfmaCfg<true,256,256,64,4,2,3,2>", 235692862),
+                 "c2": ("MfmaCfg<false,128,128,32,2,2,2,1>", 1203942020)}
+REDUCE_TRAFFIC_BYTES = {"r1": 1082787626, "r3": 1091693187, "r4": 1073967611}   # both kernels of a call
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
