@@ -133,6 +133,21 @@ int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C
                        int act, int dtype, int splits,
                        void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * pgk_gemm_plan -- what pgk_gemm_fused (b_transposed = 0) or pgk_gemm_fused_bt (1) runs for a
+ * problem whose pointers are all 16-byte aligned: the tile-shape table and the split rule as a
+ * pure host function, for callers that want to know and for tests (the paper, Section 4.2, credits
+ * its matmul gains to tile candidates chosen from profile data; this is the static form of such
+ * a table).  `out` is a HOST array of six int32:
+ *   out[0]  1 = matrix-core kernel, 0 = bounds-checked kernel
+ *   out[1..3]  tile rows, tile columns, K tile
+ *   out[4]  K slices (1 = one pass; more = the automatic two-pass split)
+ *   out[5]  workgroups of the GEMM launch
+ * Returns PGK_OK, or the error pgk_gemm_fused would return for these sizes; out == NULL is
+ * PGK_ERR_INVALID_ARG.  Nothing is launched.
+ */
+int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_transposed, int32_t* out);
+
 /* Bytes of workspace pgk_gemm_splitk needs for this problem (splits = 0: the
  * automatic choice).  Pure host arithmetic; returns 0 for invalid arguments. */
 size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch,

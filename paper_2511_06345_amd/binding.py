@@ -18,7 +18,7 @@ from .inputs import ACT_GELU_TANH, ACT_NONE, ACT_RELU, ACT_SILU, BF16, F32  # no
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
-EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_splitk_bt",
+EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_splitk_bt", "pgk_gemm_plan",
            "pgk_splitk_workspace_bytes",
            "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_conv1d", "pgk_conv1d_workspace_bytes",
            "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
@@ -53,6 +53,8 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_gemm_fused_bt.argtypes = lib.pgk_gemm_fused.argtypes
     lib.pgk_gemm_splitk_bt.restype = ci
     lib.pgk_gemm_splitk_bt.argtypes = lib.pgk_gemm_splitk.argtypes
+    lib.pgk_gemm_plan.restype = ci
+    lib.pgk_gemm_plan.argtypes = [i64, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
     lib.pgk_splitk_workspace_bytes.restype = ctypes.c_size_t
     lib.pgk_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_splitk_auto_splits.restype = ci
@@ -93,6 +95,15 @@ def splitk_workspace_bytes(M: int, N: int, K: int, batch: int, dtype: int, split
 
 def splitk_auto_splits(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0) -> int:
     return int(load_library().pgk_splitk_auto_splits(M, N, K, batch, dtype, splits))
+
+
+def gemm_plan(M: int, N: int, K: int, batch: int, dtype: int, b_transposed: bool = False) -> dict:
+    """What the fused call runs for this shape (pgk_gemm_plan): kernel, tile, K slices, workgroups."""
+    out = (ctypes.c_int32 * 6)()
+    rc = load_library().pgk_gemm_plan(M, N, K, batch, dtype, int(b_transposed), out)
+    if rc != 0:
+        raise PgkError(rc, "pgk_gemm_plan")
+    return {"matrix_core": bool(out[0]), "tile": (out[1], out[2], out[3]), "slices": out[4], "workgroups": out[5]}
 
 
 def release_scratch() -> None:

@@ -265,6 +265,41 @@ size_t split_part_bytes(int64_t M, int64_t N, int64_t batch, bool rowsum)
     return (rowsum && nseg > 1) ? (size_t)batch * (size_t)nseg * (size_t)M * sizeof(float) : 0;
 }
 
+// What pgk_gemm_fused does with a problem: the kernel and tile of the single-pass route, and
+// whether the K range is split instead (then `slices` and the tile that goes with them).
+struct FusedPlan {
+    Path path;
+    bool split;
+    SplitPlan slices;
+    int split_small_tile;
+};
+
+FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void* C, int64_t M, int64_t N, int64_t K,
+                     int64_t batch, int dtype, bool b_trans)
+{
+    FusedPlan fp{};
+    fp.path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch, -1, b_trans);
+    const int64_t tiles_m = (M + fp.path.tile.bm - 1) / fp.path.tile.bm;
+    const int64_t tiles_n = (N + fp.path.tile.bn - 1) / fp.path.tile.bn;
+    // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
+    // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
+    // partial products in the library's scratch buffer.  The choice depends on the shape only.
+    // (Also when only the small-tile grid fills the chip and K is very long: 256 x 256 x 65536 x 16
+    // fp32 took 1536 us on 256 small tiles and 1083 us split; below 512 K tiles the split's extra
+    // pass costs more than it gains -- 2048 x 2048 x 16384 bf16: 130 us against 152 us.)
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
+    const long double big_tiles = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * batch;
+    const bool few_tiles = (long double)tiles_m * tiles_n * batch < (3 * kNumCUs) / 4;
+    const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
+    if (fp.path.mfma && (few_tiles || long_k)) {
+        fp.slices = plan_splits(M, N, K, batch, dtype, 0);
+        fp.split_small_tile = (int)auto_split(M, N, K, batch, dtype).small_tile;
+        const long double ws_bytes = (long double)batch * fp.slices.splits * M * N * sizeof(float);
+        fp.split = fp.slices.splits > 1 && ws_bytes <= (long double)kAutoSplitMaxWorkspace;
+    }
+    return fp;
+}
+
 // pgk_gemm_fused and pgk_gemm_fused_bt (b_trans: B given as [batch][N][K])
 int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, float* rowsum,
                     int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream, bool b_trans)
@@ -273,32 +308,19 @@ int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, fl
     if (rc != PGK_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
 
-    const Path path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch, -1, b_trans);
+    const FusedPlan fp = plan_fused(A, B, bias, C, M, N, K, batch, dtype, b_trans);
+    const Path& path = fp.path;
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
 
-    // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
-    // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
-    // partial products in the library's scratch buffer.  The choice depends on the shape only.
-    // (Also when only the small-tile grid fills the chip and K is very long: 256 x 256 x 65536 x 16
-    // fp32 took 1536 us on 256 small tiles and 1083 us split; below 512 K tiles the split's extra
-    // pass costs more than it gains -- 2048 x 2048 x 16384 bf16: 130 us against 152 us.)
-    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
-    const int64_t big_tiles = ((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * batch;
-    const bool few_tiles = tiles_m * tiles_n * batch < (3 * kNumCUs) / 4;
-    const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
-    if (path.mfma && (few_tiles || long_k)) {
-        const SplitPlan plan = plan_splits(M, N, K, batch, dtype, 0);
-        const int small_tile = (int)auto_split(M, N, K, batch, dtype).small_tile;
-        const long double ws_bytes = (long double)batch * plan.splits * M * N * sizeof(float);
-        if (plan.splits > 1 && ws_bytes <= (long double)kAutoSplitMaxWorkspace) {
-            const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
-            float* buf = nullptr;
-            if (scratch_get(st, (size_t)ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
-            return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile, buf,
-                                    buf + (size_t)ws_bytes / sizeof(float), st, b_trans);
-        }
+    if (fp.split) {
+        const size_t ws_bytes = (size_t)batch * (size_t)fp.slices.splits * (size_t)M * (size_t)N * sizeof(float);
+        const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
+        float* buf = nullptr;
+        if (scratch_get(st, ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
+        return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, fp.slices, fp.split_small_tile, buf,
+                                buf + ws_bytes / sizeof(float), st, b_trans);
     }
 
     GemmArgs a{};
@@ -353,6 +375,29 @@ int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C,
                       int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
 {
     return gemm_fused_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, stream, true);
+}
+
+int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_transposed, int32_t* out)
+{
+    if (!out) return PGK_ERR_INVALID_ARG;
+    const void* ok = reinterpret_cast<const void*>(uintptr_t{256});   // stands for any 16-byte aligned pointer
+    const int rc = validate_common(ok, ok, ok, M, N, K, batch, PGK_ACT_NONE, dtype);
+    if (rc != PGK_OK) return rc;
+    const FusedPlan fp = plan_fused(ok, ok, nullptr, ok, M, N, K, batch, dtype, b_transposed != 0);
+    Path path = fp.path;
+    int slices = 1;
+    if (fp.split) {
+        slices = fp.slices.splits;
+        path = choose_path(ok, ok, nullptr, ok, ok, M, N, K, dtype, batch * slices, fp.split_small_tile, b_transposed != 0);
+    }
+    const long double wgs = (long double)((M + path.tile.bm - 1) / path.tile.bm) * ((N + path.tile.bn - 1) / path.tile.bn) *
+                            batch * slices;
+    if (wgs > 2.0e9L) return PGK_ERR_UNSUPPORTED;
+    out[0] = path.mfma ? 1 : 0;
+    out[1] = path.tile.bm; out[2] = path.tile.bn; out[3] = path.tile.bk;
+    out[4] = slices;
+    out[5] = (int32_t)wgs;
+    return PGK_OK;
 }
 
 int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)

@@ -95,6 +95,56 @@ def test_split_plan_arithmetic(lib):
     assert binding.splitk_workspace_bytes(8, 8, 8, 1, F32, 9) == 0
 
 
+def test_tile_table_and_split_rule(lib):
+    """pgk_gemm_plan: the host's choice of kernel, tile and K slices, pinned on the five
+    workloads and on the shapes each rule was measured on."""
+    F32, BF16 = gen.F32, gen.BF16
+    plan = binding.gemm_plan
+
+    def expect(shape, dtype, tile, slices, wgs, matrix_core=True, bt=False):
+        got = plan(*shape, dtype, b_transposed=bt)
+        assert got == {"matrix_core": matrix_core, "tile": tile, "slices": slices, "workgroups": wgs}, (shape, dtype, got)
+
+    # the five workloads (c5 through the fused call: same plan as the split call's automatic one)
+    expect((256, 256, 256, 1), F32, (64, 64, 32), 1, 16)
+    expect((4096, 4096, 4096, 1), F32, (128, 128, 32), 1, 1024)
+    expect((8192, 8192, 8192, 1), BF16, (256, 256, 64), 1, 1024)
+    expect((16384, 1024, 4096, 1), BF16, (256, 256, 64), 1, 256)
+    expect((256, 256, 65536, 16), F32, (128, 128, 32), 8, 512)
+    assert lib.pgk_splitk_auto_splits(256, 256, 65536, 16, F32, 0) == 8
+    # last tile column / row at most half full: half tiles (bf16, plain layout only)
+    expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256)
+    expect((128, 65536, 1024, 1), BF16, (128, 256, 64), 1, 256)
+    expect((65536, 128, 1024, 1), BF16, (256, 256, 64), 1, 256, bt=True)
+    expect((65536, 384, 1024, 1), BF16, (256, 256, 64), 1, 512)          # a quarter of padding: large tile stays
+    expect((65536, 128, 1024, 1), F32, (128, 128, 32), 1, 512)
+    # three quarters of a large tile empty, or a grid below 192 workgroups: small tile
+    expect((64, 65536, 1024, 1), BF16, (128, 128, 64), 1, 512)
+    expect((1024, 1024, 1024, 1), BF16, (128, 128, 64), 1, 64)
+    expect((2048, 2048, 2048, 1), BF16, (128, 128, 64), 1, 256)
+    # few tiles and a long K: slices of at least 16 K tiles, the fewest that give 512 workgroups
+    expect((32, 8192, 8192, 1), BF16, (128, 128, 64), 8, 512)
+    expect((1024, 1024, 8192, 1), BF16, (128, 128, 64), 8, 512)
+    expect((256, 256, 65536, 1), BF16, (128, 128, 64), 32, 128)
+    expect((256, 256, 1024, 1), BF16, (128, 128, 64), 1, 4)                 # 16 K tiles: not worth a second pass
+    # only the small-tile grid fills the chip: split from 512 K tiles on
+    expect((2048, 2048, 16384, 1), BF16, (128, 128, 64), 1, 256)
+    expect((2048, 2048, 65536, 1), BF16, (256, 256, 64), 8, 512)
+    # K or N off the 16-byte grid, or a tiny output: bounds-checked kernel
+    expect((4096, 4096, 4098, 1), F32, (64, 64, 16), 1, 4096, matrix_core=False)
+    expect((4096, 4100, 4096, 1), BF16, (64, 64, 16), 1, 64 * 65, matrix_core=False)
+    expect((4096, 4100, 4096, 1), F32, (128, 128, 32), 1, 32 * 33)
+    expect((8, 4096, 4096, 1), BF16, (64, 64, 16), 1, 64, matrix_core=False)
+    # ragged everything on the matrix cores
+    expect((3000, 5000, 4104, 1), BF16, (256, 256, 64), 1, 12 * 20)
+    # invalid sizes
+    out = (ctypes.c_int32 * 6)()
+    assert lib.pgk_gemm_plan(0, 4, 4, 1, F32, 0, out) == -1
+    assert lib.pgk_gemm_plan(4, 4, 4, 1, 7, 0, out) == -1
+    assert lib.pgk_gemm_plan(4, 4, 4, 1, F32, 0, None) == -1
+    assert lib.pgk_gemm_plan(1 << 31, 4, 4, 1, F32, 0, out) == -2
+
+
 def test_reduce_max_rejects_bad_arguments_on_the_host(lib):
     def call(X=0x1000, out=0x2000, idx=None, outer=2, red=3, inner=4, dtype=0):
         return lib.pgk_reduce_max(X, out, idx, outer, red, inner, dtype, None)
