@@ -540,9 +540,9 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     pl.tile = pgk::mfma_tile_shape(dtype, pl.small_tile);
     pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
     // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
-    // halo and the padding no wider than a tile, and few enough rows for one strip launch.
+    // halo and the padding no wider than a tile.
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
-    pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && B * Cin <= 65535;
+    pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
     if (pl.strips) {
         const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
         pl.edge_w = (int64_t)round_up((size_t)(bn + halo), (size_t)epc);
@@ -615,13 +615,13 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
             return PGK_ERR_WORKSPACE;
         unsigned char* wr = static_cast<unsigned char*>(workspace);
         unsigned char* xp = wr + pl.w_bytes;
-        if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
         const void* bsrc = x;
         int64_t ldb = L;
         if (pl.strips) {
+            // strips and regrouped weights in one launch
+            if (pgk::launch_conv_prepare(x, xp, B * Cin, (int)L, (int)pl.edge_w, pl.n_edges, pl.edge_first_col, w, wr,
+                                         (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
             if (pl.n_edges > 0) {
-                if (pgk::launch_conv_edge_strips(x, xp, B * Cin, (int)L, (int)pl.edge_w, pl.n_edges, pl.edge_first_col,
-                                                 dtype, st) != hipSuccess) return PGK_ERR_HIP;
                 for (int e = 0; e < pl.n_edges; ++e) {
                     a.edge_tn[e] = pl.edge_tn[e];
                     a.edge_B[e] = xp + (size_t)e * (size_t)(B * Cin) * (size_t)pl.edge_w * (size_t)es;
@@ -630,7 +630,10 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
                 a.edge_batch_stride = Cin * pl.edge_w;
             }
             a.b_col_shift = -(int)pad;
-        } else if (pl.Lp) {
+        } else {
+            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+        }
+        if (!pl.strips && pl.Lp) {
             if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, dtype, st) != hipSuccess) return PGK_ERR_HIP;
             bsrc = xp;
             ldb = pl.Lp;

@@ -8,8 +8,10 @@
 //     up to a row length that keeps rows 16-byte aligned (skipped when there is no padding
 //     and the rows are aligned already);
 //   * conv_repack_weights: w[Cout][Cin][Kw] -> w'[Cout][Kw][Cin], so that the K index runs
-//     over the channels inside a tap.
-// Both are streaming copies.
+//     over the channels inside a tap;
+//   * conv_prepare: the regrouped weights together with the zero-padded strips that the tile
+//     columns at the ends of the rows read when the input is used in place.
+// All are streaming copies.
 #include <hip/hip_runtime.h>
 
 #include "pgk_device.h"
@@ -41,19 +43,6 @@ __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict
 
 struct EdgeCols { int first[3]; };
 
-// strips[e][row][j] = x[row][first[e] + j] inside [0, L), else 0; blockIdx.y = row, blockIdx.z = e
-template <typename T>
-__global__ __launch_bounds__(256) void conv_edge_strips_kernel(const T* __restrict__ x, T* __restrict__ strips,
-                                                               long long rows, int L, int W, EdgeCols cols)
-{
-    const long long row = blockIdx.y;
-    const int e = blockIdx.z;
-    const int j = blockIdx.x * 256 + threadIdx.x;
-    if (row >= rows || j >= W) return;
-    const long long s = (long long)cols.first[e] + j;
-    strips[((size_t)e * (size_t)rows + (size_t)row) * (size_t)W + j] = (s >= 0 && s < L) ? x[(size_t)row * (size_t)L + (size_t)s] : T(0);
-}
-
 template <typename T>
 __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __restrict__ w, T* __restrict__ wr,
                                                                   int Cout, int Cin, int Kw)
@@ -68,7 +57,60 @@ __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __res
     wr[t] = w[(co * Cin + ci) * Kw + k];
 }
 
+// Both preparations of the in-place path in one launch (each is a few microseconds of work;
+// a second launch costs as much again).  Workgroups [0, strip_blocks) fill the strips,
+// strips[e][row][j] = x[row][first[e] + j] inside [0, L), else 0, numbered as (slab of 256
+// columns, row, edge) with the slab fastest; the rest regroup the weights.
+template <typename T>
+__global__ __launch_bounds__(256) void conv_prepare_kernel(const T* __restrict__ x, T* __restrict__ strips, long long rows,
+                                                           int L, int W, int slabs, EdgeCols cols, unsigned int strip_blocks,
+                                                           const T* __restrict__ w, T* __restrict__ wr, int Cout, int Cin, int Kw)
+{
+    if (blockIdx.x < strip_blocks) {
+        const unsigned int slab = blockIdx.x % (unsigned int)slabs;
+        const unsigned int r = blockIdx.x / (unsigned int)slabs;
+        const long long row = (long long)(r % (unsigned long long)rows);
+        const int e = (int)(r / (unsigned long long)rows);
+        const int j = (int)slab * 256 + (int)threadIdx.x;
+        if (j >= W) return;
+        const long long s = (long long)cols.first[e] + j;
+        strips[((size_t)e * (size_t)rows + (size_t)row) * (size_t)W + j] =
+            (s >= 0 && s < L) ? x[(size_t)row * (size_t)L + (size_t)s] : T(0);
+        return;
+    }
+    const long long total = (long long)Cout * Cin * Kw;
+    const long long t = (long long)(blockIdx.x - strip_blocks) * 256 + threadIdx.x;     // index into wr: (co, k, ci)
+    if (t >= total) return;
+    const int ci = (int)(t % Cin);
+    const long long q = t / Cin;
+    const int k = (int)(q % Kw);
+    const long long co = q / Kw;
+    wr[t] = w[(co * Cin + ci) * Kw + k];
+}
+
 }  // namespace
+
+hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int L, int W, int n_edges, const int* first_col,
+                               const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s)
+{
+    if (rows <= 0 || n_edges < 0 || n_edges > 3) return hipErrorInvalidValue;
+    EdgeCols cols{};
+    for (int e = 0; e < n_edges; ++e) cols.first[e] = first_col[e];
+    const int slabs = (W + 255) / 256;
+    const long long strip_blocks = n_edges > 0 ? (long long)slabs * rows * n_edges : 0;
+    const long long repack_blocks = ((long long)Cout * Cin * Kw + 255) / 256;
+    const long long blocks = strip_blocks + repack_blocks;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(conv_prepare_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const unsigned short*)x, (unsigned short*)strips, rows, L, W, slabs > 0 ? slabs : 1, cols,
+                           (unsigned int)strip_blocks, (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw);
+    else
+        hipLaunchKernelGGL(conv_prepare_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)x,
+                           (float*)strips, rows, L, W, slabs > 0 ? slabs : 1, cols, (unsigned int)strip_blocks,
+                           (const float*)w, (float*)wr, Cout, Cin, Kw);
+    return hipGetLastError();
+}
 
 hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s)
 {
@@ -85,21 +127,6 @@ hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L,
             hipLaunchKernelGGL(conv_pad_input_kernel<float>, grid, dim3(256), 0, s,
                                (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
     }
-    return hipGetLastError();
-}
-
-hipError_t launch_conv_edge_strips(const void* x, void* strips, long long rows, int L, int W, int n_edges,
-                                   const int* first_col, int dtype, hipStream_t s)
-{
-    if (rows <= 0 || rows > 65535 || n_edges < 1 || n_edges > 3) return hipErrorInvalidValue;
-    EdgeCols cols{};
-    for (int e = 0; e < n_edges; ++e) cols.first[e] = first_col[e];
-    const dim3 grid((unsigned int)((W + 255) / 256), (unsigned int)rows, (unsigned int)n_edges);
-    if (dtype == DT_BF16)
-        hipLaunchKernelGGL(conv_edge_strips_kernel<unsigned short>, grid, dim3(256), 0, s, (const unsigned short*)x,
-                           (unsigned short*)strips, rows, L, W, cols);
-    else
-        hipLaunchKernelGGL(conv_edge_strips_kernel<float>, grid, dim3(256), 0, s, (const float*)x, (float*)strips, rows, L, W, cols);
     return hipGetLastError();
 }
 

@@ -130,10 +130,11 @@ hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int
 // Convolution helpers (pgk_conv.hip): xp[row][j] = x[row][j - pad] inside [0, L), else 0, for
 // `rows` rows of length L -> Lp; wr[co][k][ci] = w[co][ci][k].
 hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s);
-// strip e (e < n_edges) of S[e][row][j], j < W: x[row][first_col[e] + j] inside [0, L), else 0
-hipError_t launch_conv_edge_strips(const void* x, void* strips, long long rows, int L, int W, int n_edges,
-                                   const int* first_col, int dtype, hipStream_t s);
 hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s);
+// the regrouped weights and, in the same launch, strip e (e < n_edges, may be 0) of
+// S[e][row][j], j < W: x[row][first_col[e] + j] inside [0, L), else 0
+hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int L, int W, int n_edges, const int* first_col,
+                               const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s);
 
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming
