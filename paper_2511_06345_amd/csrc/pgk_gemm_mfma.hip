@@ -809,11 +809,14 @@ using CfgBF16T = MfmaCfgBt<true, 256, 256, 64, 4, 2, 3, 2>;
 using CfgF32T = MfmaCfgBt<false, 128, 128, 32, 2, 2, 2, 1>;
 using CfgBF16SmallT = MfmaCfgBt<true, 128, 128, 64, 2, 2, 3, 2>;
 using CfgF32SmallT = MfmaCfgBt<false, 64, 64, 32, 2, 2, 2, 2>;
+using CfgBF16TallT = MfmaCfgBt<true, 256, 128, 64, 4, 2, 3, 2>;
+using CfgBF16WideT = MfmaCfgBt<true, 128, 256, 64, 2, 4, 3, 2>;
 
 bool mfma_has_tile(int dtype, int kind, bool b_trans)
 {
     if (kind == TILE_LARGE || kind == TILE_SMALL) return true;
-    return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16 && !b_trans;
+    (void)b_trans;   // both layouts of B have every bf16 shape
+    return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16;
 }
 
 TileShape mfma_tile_shape(int dtype, int kind)
@@ -841,11 +844,11 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
 {
     if (!mfma_has_tile(dtype, kind, a.b_trans != 0)) return hipErrorInvalidValue;
     const bool small = kind == TILE_SMALL;
-    if (kind == TILE_TALL) return launch_cfg<CfgBF16Tall>(a, out_mode, s);
-    if (kind == TILE_WIDE) return launch_cfg<CfgBF16Wide>(a, out_mode, s);
+    // the operand views of the convolution path assume B as [K][N]
+    if (a.b_trans && (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0])) return hipErrorInvalidValue;
+    if (kind == TILE_TALL) return a.b_trans ? launch_cfg<CfgBF16TallT>(a, out_mode, s) : launch_cfg<CfgBF16Tall>(a, out_mode, s);
+    if (kind == TILE_WIDE) return a.b_trans ? launch_cfg<CfgBF16WideT>(a, out_mode, s) : launch_cfg<CfgBF16Wide>(a, out_mode, s);
     if (a.b_trans) {
-        // the operand views of the convolution path assume B as [K][N]
-        if (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0]) return hipErrorInvalidValue;
         if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16SmallT>(a, out_mode, s) : launch_cfg<CfgBF16T>(a, out_mode, s);
         return small ? launch_cfg<CfgF32SmallT>(a, out_mode, s) : launch_cfg<CfgF32T>(a, out_mode, s);
     }

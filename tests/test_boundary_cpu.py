@@ -112,10 +112,10 @@ def test_tile_table_and_split_rule(lib):
     expect((16384, 1024, 4096, 1), BF16, (256, 256, 64), 1, 256)
     expect((256, 256, 65536, 16), F32, (128, 128, 32), 8, 512)
     assert lib.pgk_splitk_auto_splits(256, 256, 65536, 16, F32, 0) == 8
-    # last tile column / row at most half full: half tiles (bf16, plain layout only)
+    # last tile column / row at most half full: half tiles (bf16, either layout of B)
     expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256)
     expect((128, 65536, 1024, 1), BF16, (128, 256, 64), 1, 256)
-    expect((65536, 128, 1024, 1), BF16, (256, 256, 64), 1, 256, bt=True)
+    expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256, bt=True)
     expect((65536, 384, 1024, 1), BF16, (256, 256, 64), 1, 512)          # a quarter of padding: large tile stays
     expect((65536, 128, 1024, 1), F32, (128, 128, 32), 1, 512)
     # three quarters of a large tile empty, or a grid below 192 workgroups: small tile

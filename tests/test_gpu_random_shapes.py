@@ -15,6 +15,7 @@ pytestmark = pytest.mark.gpu
 
 F32, BF16 = gen.F32, gen.BF16
 ACTS = [gen.ACT_NONE, gen.ACT_RELU, gen.ACT_GELU_TANH, gen.ACT_SILU]
+CALLS = ["fused", "fused_bt", "splitk", "splitk_bt"]
 
 
 @pytest.fixture(scope="module")
@@ -78,7 +79,7 @@ def run(pgk, call, A, B, bias, act, dtype, rowsum, splits):
 def test_random_shape(pgk, oracle, n):
     dtype, M, N, K, batch = CASES[n]
     rng = np.random.default_rng(1000 + n)
-    call = ["fused", "fused_bt", "splitk", "splitk_bt"][int(rng.integers(4))]
+    call = CALLS[(n // 6) % 4]      # every size class meets every call twice
     splits = int(rng.choice([0, 1, 2, 3, 5]))
     if splits > K:
         splits = 0
@@ -114,9 +115,15 @@ def test_cases_reach_every_path(pgk):
     """The drawn shapes do cover what they are meant to: every tile shape of both types, the
     bounds-checked kernel and the automatic split (asked of the library's own plan query)."""
     seen = set()
-    for dtype, M, N, K, batch in CASES:
+    for n, (dtype, M, N, K, batch) in enumerate(CASES):
         p = pgk.gemm_plan(M, N, K, batch, dtype)
         seen.add((dtype, p["matrix_core"], p["tile"][:2], p["slices"] > 1))
+        if p["tile"][:2] in ((256, 128), (128, 256)):     # which layout of B the half-tile cases run with
+            call = CALLS[(n // 6) % 4]
+            seen.add(("half tile, transposed B" if call.endswith("_bt") else "half tile, plain B", p["tile"][:2]))
+    assert {("half tile, transposed B", (256, 128)), ("half tile, transposed B", (128, 256)),
+            ("half tile, plain B", (256, 128)), ("half tile, plain B", (128, 256))} <= seen
+    seen = {s for s in seen if len(s) == 4}
     tiles = {(d, t) for d, mc, t, s in seen if mc}
     assert {(F32, (128, 128)), (F32, (64, 64)), (BF16, (256, 256)), (BF16, (128, 128)), (BF16, (256, 128)), (BF16, (128, 256))} <= tiles
     assert any(not mc for d, mc, t, s in seen) and any(s for d, mc, t, s in seen)
