@@ -25,8 +25,8 @@
  *
  * Ownership.  The caller owns every buffer.  Outputs are fully overwritten
  * (no accumulate-into-C).  Calls enqueue work on `stream` and return without
- * synchronising it.  Results are deterministic: no atomics are used, every
- * reduction has a fixed order, so equal inputs give bit-equal outputs.
+ * synchronising it.  Results are deterministic: no value is accumulated with an
+ * atomic, every reduction has a fixed order, so equal inputs give bit-equal outputs.
  *
  * Errors.  Every entry point returns a pgk_status_t as int.  Arguments are
  * validated on the host before any device work is enqueued, so an error return
