@@ -357,6 +357,53 @@ def test_skinny_full_size_sampled_rows(pgk, oracle, shape):
     check(c_to_numpy(C[:, drows], BF16), rs[:, drows].cpu().numpy().astype(np.float64), ref_c, ref_rs, BF16, f"skinny {shape}")
 
 
+@pytest.mark.parametrize("dtype,K", [(F32, 256), (BF16, 512)])
+def test_output_larger_than_4_gib_of_offsets(pgk, oracle, dtype, K):
+    """C of 32768 x 32768: 2^30 elements, 4 GiB as fp32 -- element and byte offsets of the last
+    rows do not fit 32 bits.  Sampled rows (first, last, tile boundaries, random), C and row sums."""
+    import torch
+    M = N = 32768
+    A = gen.uniform(gen.tensor_seed(97, 1, K), M * K, -1.0, 1.0).reshape(1, M, K)
+    B = gen.uniform(gen.tensor_seed(97, 2, K), K * N, -1.0, 1.0).reshape(1, K, N)
+    bias = gen.normal(gen.tensor_seed(97, 3, K), N, 0.5)
+    if dtype == BF16:
+        A, B = gen.f32_to_bf16_bits(A), gen.f32_to_bf16_bits(B)
+    rows = sample_rows(M, 256, 24, seed=K)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, RELU, rows=rows)
+    C, rs = pgk.gemm_fused(to_device(A, dtype), to_device(B, dtype), torch.from_numpy(bias).cuda(), RELU)
+    torch.cuda.synchronize()
+    drows = torch.from_numpy(rows).cuda()
+    check(c_to_numpy(C[:, drows], dtype), rs[:, drows].cpu().numpy().astype(np.float64), ref_c, ref_rs, dtype,
+          f"large output dtype {dtype}")
+    del C, rs
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.parametrize("N", [64, 512])      # small tiles / large tiles
+def test_operand_larger_than_4_gib(pgk, oracle, N):
+    """A of 66560 x 32776 bf16 (4.36 GB; a seeded block of 1024 rows repeated): byte offsets of
+    its last rows exceed 32 bits, K has a partial last tile, and the copies of that tile for the
+    last rows run up to the end of the array.  Sampled rows against the oracle."""
+    import torch
+    rows_block, reps, K = 1024, 65, 32776
+    M = rows_block * reps
+    block = gen.f32_to_bf16_bits(gen.uniform(gen.tensor_seed(98, 1, 0), rows_block * K, -1.0, 1.0).reshape(rows_block, K))
+    B = gen.f32_to_bf16_bits(gen.uniform(gen.tensor_seed(98, 2, 0), K * N, -1.0, 1.0).reshape(1, K, N))
+    dblock = to_device(block, BF16)
+    dA = dblock.repeat(reps, 1).reshape(1, M, K)
+    assert dA.numel() * 2 > (1 << 32)
+    C, rs = pgk.gemm_fused(dA, to_device(B, BF16), None, NONE)
+    torch.cuda.synchronize()
+    rows = np.unique(np.concatenate([sample_rows(M, 256, 16, seed=1), np.arange(M - 8, M)]))
+    ref_c, ref_rs = oracle.gemm_fused(block[rows % rows_block][None], B, None, NONE)
+    drows = torch.from_numpy(rows).cuda()
+    check(c_to_numpy(C[:, drows], BF16), rs[:, drows].cpu().numpy().astype(np.float64), ref_c, ref_rs, BF16, "large A")
+    # equal rows of A give equal rows of C, wherever they lie
+    assert torch.equal(C[0, :rows_block].view(torch.int16), C[0, M - rows_block:].view(torch.int16))
+    del dA, C
+    torch.cuda.empty_cache()
+
+
 def test_workload_c3_without_bias_or_activation(pgk, oracle):
     """The large bf16 workload is bias dominated; check the bare product too."""
     import torch
