@@ -140,3 +140,22 @@ def test_conv_workloads_sampled(pgk, oracle, name):
         got = c_to_numpy(y[b][cos], cw.dtype)
         e = rel_err(got, ref)
         assert e <= TOL[cw.dtype], f"{name} batch {b}: error {e:.3e}"
+
+
+def test_input_larger_than_4_gib(pgk, oracle):
+    """x [132, 256, 65536] bf16 = 4.4 GB, one seeded batch entry repeated: byte offsets of the
+    later entries exceed 32 bits.  Matrix-core path (stride 1, padded, dilated); every entry
+    must equal the oracle's result for the one entry, on sampled output channels."""
+    import torch
+    B, Cin, L, Cout, Kw, pad, dil = 132, 256, 65536, 64, 3, 2, 2
+    x1, w, bias = random_case(BF16, 1, Cin, L, Cout, Kw, seed=77)
+    dx = to_device(x1, BF16).expand(B, -1, -1).contiguous()
+    assert dx.numel() * 2 > (1 << 32)
+    y = pgk.conv1d(dx, to_device(w, BF16), torch.from_numpy(bias).cuda(), RELU, 1, pad, dil)
+    torch.cuda.synchronize()
+    assert pgk.conv1d_workspace_bytes(B, Cin, L, Cout, Kw, 1, pad, dil, BF16) > 0, "expected the matrix-core path"
+    ref = oracle.conv1d(x1, w, bias, RELU, 1, pad, dil)
+    for b in (0, 66, 131):
+        e = rel_err(c_to_numpy(y[b:b + 1], BF16), ref)
+        assert e <= TOL[BF16], f"batch entry {b}: error {e:.3e}"
+    assert torch.equal(y.view(torch.int16), y[:1].view(torch.int16).expand(B, -1, -1))

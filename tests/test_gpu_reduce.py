@@ -137,3 +137,21 @@ def test_reduce_workloads_full_size(pgk, oracle, name):
     w = gen.REDUCE_WORKLOADS[name]
     X = gen.make_reduce_input(w)
     run_and_compare(pgk, oracle, X, w.dtype, w.dim, name)
+
+
+@pytest.mark.parametrize("dim", [1, 2])
+def test_tensor_larger_than_4_gib(pgk, oracle, dim):
+    """[72, 4096, 4100] fp32 = 4.8 GB, a seeded [4096, 4100] block repeated along the first
+    dimension: element offsets of the later entries exceed 32 bits; every entry must reduce
+    like the block does (strided and contiguous dimension; rows of 4100 are not tile multiples)."""
+    import torch
+    block = make(F32, (4096, 4100), 31, "ties")
+    ref_v, ref_i = oracle.reduce_max(block, dim - 1)
+    X = to_device(block, F32)[None].expand(72, -1, -1).contiguous()
+    assert X.numel() * 4 > (1 << 32)
+    v, i = pgk.reduce_max(X, dim)
+    torch.cuda.synchronize()
+    for o in (0, 1, 35, 71):
+        same_bits(v[o].cpu().numpy(), ref_v, f"entry {o} dim {dim}")
+        assert np.array_equal(i[o].cpu().numpy(), ref_i), f"positions of entry {o} dim {dim}"
+    assert torch.equal(v, v[:1].expand_as(v)) and torch.equal(i, i[:1].expand_as(i))
