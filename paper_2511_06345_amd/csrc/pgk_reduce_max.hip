@@ -331,7 +331,11 @@ __global__ __launch_bounds__(256) void reduce_max_finish_wave_kernel(const float
     }
 }
 
-constexpr int kTargetWorkgroups = 2048;           // eight per CU
+// Workgroups a launch is cut into when the outputs alone give fewer: two per CU for fp32, four
+// for bf16 (more vector ALU work per byte).  More, shorter segments stream worse -- measured on
+// 1 GiB tensors, fp32 strided 6800 GB/s at 512 workgroups, 6500 at 1024, 6370 at 2048; bf16
+// strided 5080 / 6450 / 5970; fp32 long rows 6940 / 6670 / 6620.
+constexpr int target_workgroups(int dtype) { return dtype == DT_BF16 ? 1024 : 512; }
 constexpr int kWaveFinishMinSegs = 16;
 
 }  // namespace
@@ -346,8 +350,8 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
         const long long nch = red / pl.vec;
         pl.group = nch <= 64 * 8 ? 64 : 256;       // short rows: one wave each
         pl.segs = 1;
-        if (pl.group == 256 && outer < kTargetWorkgroups) {
-            const long long want = (kTargetWorkgroups + outer - 1) / outer;
+        if (pl.group == 256 && outer < target_workgroups(dtype)) {
+            const long long want = (target_workgroups(dtype) + outer - 1) / outer;
             const long long most = nch / (256 * 8) > 0 ? nch / (256 * 8) : 1;   // eight sweeps per segment at least
             pl.segs = (int)(want < most ? want : most);
         }
@@ -362,8 +366,8 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
         pl.tiles_i = (int)((inner + 64 * pl.vec - 1) / (64 * pl.vec));
         const long long wg0 = outer * pl.tiles_i;
         pl.segs = 1;
-        if (wg0 < kTargetWorkgroups) {
-            const long long want = (kTargetWorkgroups + wg0 - 1) / wg0;
+        if (wg0 < target_workgroups(dtype)) {
+            const long long want = (target_workgroups(dtype) + wg0 - 1) / wg0;
             const long long most = red / 32 > 0 ? red / 32 : 1;                 // eight r per wave at least
             pl.segs = (int)(want < most ? want : most);
         }
