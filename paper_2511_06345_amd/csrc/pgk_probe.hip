@@ -90,7 +90,10 @@ hipError_t launch_probe_mfma(int dtype, int random_operands, int iters, int work
 
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s)
 {
-    hipLaunchKernelGGL(probe_stream_read_kernel, dim3(256 * 8), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
+    // two workgroups per CU, all sweeping the buffer together: 7.0 TB/s on a 2 GiB buffer; one per
+    // CU gives 6.3, four 5.9, and one contiguous segment per workgroup 5.9 -- how much is in flight
+    // decides, not contiguity
+    hipLaunchKernelGGL(probe_stream_read_kernel, dim3(256 * 2), dim3(256), 0, s, (const u32x4*)src, bytes / 16, sink);
     return hipGetLastError();
 }
 
