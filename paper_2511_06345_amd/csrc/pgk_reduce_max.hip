@@ -278,6 +278,162 @@ __global__ __launch_bounds__(256) void reduce_max_cols_kernel(const void* __rest
     }
 }
 
+// ---------------------------------------------------------------------------------
+// inner == 1, short rows (at most 128 chunks): a wave per row would leave most lanes idle,
+// so g = 1, 2, ... 32 lanes (a power of two, 1 << lg) share a row and a wave takes 64 / g
+// rows; every lane has at most four chunks, fetched together.  No segments.
+template <bool BF16, int VEC>
+__global__ __launch_bounds__(256) void reduce_max_short_rows_kernel(const void* __restrict__ X, void* __restrict__ out,
+                                                                    int* __restrict__ idx, long long outer, int red, int lg)
+{
+    const int tid = threadIdx.x;
+    const int g = 1 << lg;
+    const int gl = tid & (g - 1);
+    const long long row = (long long)blockIdx.x * (256 >> lg) + (tid >> lg);
+    const bool active = row < outer;              // whole groups only
+    const int nch = red / VEC;
+    const size_t row_base = (size_t)(active ? row : 0) * (size_t)red;
+
+    float x[4][VEC];
+    bool have[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int c = gl + u * g;
+        have[u] = active && c < nch;
+        if constexpr (VEC > 1) {
+            u32x4 w = {0u, 0u, 0u, 0u};
+            if (have[u]) w = __builtin_nontemporal_load((const u32x4*)((const unsigned char*)X + row_base * Elem<BF16>::BYTES) + c);
+            unpack<BF16>(w, x[u]);
+        } else {
+            x[u][0] = have[u] ? load_one<BF16>(X, row_base + c) : 0.0f;
+        }
+    }
+    // this lane's best over its chunks, in increasing position; the first one it has starts the scan
+    float v = kNegInf;
+    int p = kNoPos;
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) {
+            const int pos = (gl + u * g) * VEC + e;
+            if (have[u] && (p == kNoPos || replaces(x[u][e], v))) { v = x[u][e]; p = pos; }
+        }
+    }
+    // across the g lanes of the row
+    for (int off = g >> 1; off > 0; off >>= 1) {
+        const float ov = __shfl_xor(v, off, 64);
+        const int op = __shfl_xor(p, off, 64);
+        if (beats(ov, op, v, p)) { v = ov; p = op; }
+    }
+    if (gl == 0 && active) {
+        store_one<BF16>(out, (size_t)row, v);
+        if (idx) idx[row] = p;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// 1 < inner <= 64.  The strided kernel below would use inner / VEC of its 64 lanes.  Here
+// one wave owns one outer index (and the r range of one segment) and sweeps that contiguous
+// block of red x inner elements: R = 64 / inner consecutive r at a time, lane l at inner
+// position l % inner of r number l / inner of the sweep -- 64 (or R * inner) consecutive
+// elements per load instruction, eight sweeps in flight.  The lanes that share an inner
+// position are then combined through LDS.
+template <bool BF16>
+__global__ __launch_bounds__(256) void reduce_max_small_inner_kernel(const void* __restrict__ X, void* __restrict__ out,
+                                                                     int* __restrict__ idx, float* __restrict__ pv,
+                                                                     int* __restrict__ pi, long long outer, int red,
+                                                                     int inner, int segs, int r_per_seg)
+{
+    constexpr int UNROLL = 8;
+    __shared__ float sv[4][64];
+    __shared__ int si[4][64];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const long long unit = (long long)blockIdx.x * 4 + wave;        // o * segs + seg
+    const bool active = unit < outer * segs;                        // uniform per wave
+    const long long o = active ? unit / segs : 0;
+    const int seg = active ? (int)(unit - o * segs) : 0;
+    const int R = 64 / inner, L = R * inner;
+    const int i = lane % inner, rr = lane / inner;
+    const bool lane_ok = active && lane < L;
+    const int r0 = seg * r_per_seg;
+    const int r1 = active ? (r0 + r_per_seg < red ? r0 + r_per_seg : red) : r0;
+    const size_t base = (size_t)o * (size_t)red * (size_t)inner + (size_t)i;
+
+    float bv = kNegInf;
+    int bp = kNoPos;
+    int r = r0 + rr;
+    if (lane_ok && r < r1) { bv = load_one<BF16>(X, base + (size_t)r * inner); bp = r; }   // starts the scan
+    r += R;
+    for (; r - rr + (UNROLL - 1) * R < r1; r += UNROLL * R) {       // uniform: all UNROLL sweeps start inside the range
+        float x[UNROLL];
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u) {
+            const int ru = r + u * R;
+            x[u] = (lane_ok && ru < r1) ? load_one<BF16>(X, base + (size_t)ru * inner) : kNegInf;
+        }
+#pragma unroll
+        for (int u = 0; u < UNROLL; ++u)
+            if (lane_ok && r + u * R < r1 && replaces(x[u], bv)) { bv = x[u]; bp = r + u * R; }
+    }
+    for (; r - rr < r1; r += R) {
+        if (lane_ok && r < r1) {
+            const float x = load_one<BF16>(X, base + (size_t)r * inner);
+            if (replaces(x, bv)) { bv = x; bp = r; }
+        }
+    }
+    sv[wave][lane] = bv;
+    si[wave][lane] = bp;
+    __syncthreads();
+    if (active && lane < inner) {
+        float v = sv[wave][lane];
+        int p = si[wave][lane];
+        for (int q = 1; q < R; ++q) {
+            const float ov = sv[wave][q * inner + lane];
+            const int op = si[wave][q * inner + lane];
+            if (beats(ov, op, v, p)) { v = ov; p = op; }
+        }
+        if (segs == 1) {
+            store_one<BF16>(out, (size_t)o * inner + lane, v);
+            if (idx) idx[(size_t)o * inner + lane] = p;
+        } else {
+            const size_t at = ((size_t)o * segs + seg) * (size_t)inner + lane;
+            pv[at] = v;
+            pi[at] = p;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// inner > 1 and red x inner <= 128: the block of one outer index is smaller than a wave's
+// worth of work.  A workgroup takes Q = 256 / (red x inner) outer indices: its threads load
+// the Q blocks (contiguous in memory) into LDS, one element each, then one thread per output
+// scans its red values in order.
+template <bool BF16>
+__global__ __launch_bounds__(256) void reduce_max_tiny_block_kernel(const void* __restrict__ X, void* __restrict__ out,
+                                                                    int* __restrict__ idx, long long outer, int red, int inner)
+{
+    __shared__ float vals[256];
+    const int tid = threadIdx.x;
+    const int block = red * inner, Q = 256 / block;
+    const long long o0 = (long long)blockIdx.x * Q;
+    const int q_mine = tid / block;
+    if (q_mine < Q && o0 + q_mine < outer) vals[tid] = load_one<BF16>(X, (size_t)o0 * (size_t)block + (size_t)tid);
+    __syncthreads();
+    const int q = tid / inner, i = tid - q * inner;
+    if (q < Q && o0 + q < outer) {
+        const float* mine = vals + q * block + i;
+        float v = mine[0];
+        int p = 0;
+        for (int r = 1; r < red; ++r) {
+            const float x = mine[r * inner];
+            if (replaces(x, v)) { v = x; p = r; }
+        }
+        const size_t at = (size_t)(o0 + q) * (size_t)inner + (size_t)i;
+        store_one<BF16>(out, at, v);
+        if (idx) idx[at] = p;
+    }
+}
+
 // Second pass: one thread per output, the segment results taken in order.
 template <bool BF16>
 __global__ __launch_bounds__(256) void reduce_max_finish_kernel(const float* __restrict__ pv, const int* __restrict__ pi,
@@ -337,6 +493,9 @@ __global__ __launch_bounds__(256) void reduce_max_finish_wave_kernel(const float
 // strided 5080 / 6450 / 5970; fp32 long rows 6940 / 6670 / 6620.
 constexpr int target_workgroups(int dtype) { return dtype == DT_BF16 ? 1024 : 512; }
 constexpr int kWaveFinishMinSegs = 16;
+constexpr long long kShortRowChunks = 128;        // rows of at most this many chunks: several rows per wave
+constexpr long long kSmallInner = 64;             // inner dimensions up to this: the flattened-sweep kernel
+constexpr long long kTinyBlock = 128;             // red x inner up to this: several outer indices per workgroup
 
 }  // namespace
 
@@ -348,6 +507,17 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
     if (inner == 1) {
         pl.vec = (x_aligned && red % vec16 == 0) ? vec16 : 1;
         const long long nch = red / pl.vec;
+        if (nch <= kShortRowChunks) {              // very short rows: g lanes each, at most four chunks per lane
+            int g = 1;
+            while (4 * g < nch) g *= 2;
+            pl.group = g;
+            pl.segs = 1;
+            pl.per_seg = (int)nch;
+            pl.tiles_i = 1;
+            pl.blocks = (outer + 256 / g - 1) / (256 / g);
+            pl.partial_elems = 0;
+            return pl;
+        }
         pl.group = nch <= 64 * 8 ? 64 : 256;       // short rows: one wave each
         pl.segs = 1;
         if (pl.group == 256 && outer < target_workgroups(dtype)) {
@@ -360,6 +530,31 @@ ReducePlan plan_reduce_max(long long outer, long long red, long long inner, int 
         const long long units = outer * pl.segs, per_wg = 256 / pl.group;
         pl.blocks = (units + per_wg - 1) / per_wg;
         pl.tiles_i = 1;
+    } else if (red * inner <= kTinyBlock) {
+        // several outer indices per workgroup; group = -1 marks this kernel
+        pl.vec = 1;
+        pl.group = -1;
+        pl.tiles_i = 1;
+        pl.segs = 1;
+        pl.per_seg = (int)red;
+        const long long q = 256 / (red * inner);
+        pl.blocks = (outer + q - 1) / q;
+    } else if (inner <= kSmallInner) {
+        // one wave per (outer index, segment); group = 0 marks this kernel
+        pl.vec = 1;
+        pl.group = 0;
+        pl.tiles_i = 1;
+        pl.segs = 1;
+        const long long waves = 4LL * target_workgroups(dtype);
+        if (outer < waves) {
+            const long long want = (waves + outer - 1) / outer;
+            const long long sweep = 64 / inner;                                  // r per sweep
+            const long long most = red / (8 * sweep) > 0 ? red / (8 * sweep) : 1;   // eight sweeps per segment at least
+            pl.segs = (int)(want < most ? want : most);
+        }
+        pl.per_seg = (int)((red + pl.segs - 1) / pl.segs);
+        pl.segs = (int)((red + pl.per_seg - 1) / pl.per_seg);
+        pl.blocks = (outer * pl.segs + 3) / 4;
     } else {
         pl.vec = (x_aligned && inner % vec16 == 0) ? vec16 : 1;
         pl.group = 256;
@@ -385,7 +580,21 @@ hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int
     if (pl.blocks <= 0 || pl.blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     const dim3 grid((unsigned int)pl.blocks), block(256);
     const bool bf = dtype == DT_BF16;
-    if (inner == 1) {
+    if (inner == 1 && pl.group < 64) {
+        int lg = 0;
+        while ((1 << lg) < pl.group) ++lg;
+#define PGK_SHORT(BF, VEC) \
+    hipLaunchKernelGGL((reduce_max_short_rows_kernel<BF, VEC>), grid, block, 0, s, X, out, idx, outer, (int)red, lg)
+        if (bf) { if (pl.vec > 1) PGK_SHORT(true, 8); else PGK_SHORT(true, 1); }
+        else { if (pl.vec > 1) PGK_SHORT(false, 4); else PGK_SHORT(false, 1); }
+#undef PGK_SHORT
+    } else if (inner > 1 && pl.group == -1) {
+        if (bf) hipLaunchKernelGGL(reduce_max_tiny_block_kernel<true>, grid, block, 0, s, X, out, idx, outer, (int)red, (int)inner);
+        else hipLaunchKernelGGL(reduce_max_tiny_block_kernel<false>, grid, block, 0, s, X, out, idx, outer, (int)red, (int)inner);
+    } else if (inner > 1 && pl.group == 0) {
+        if (bf) hipLaunchKernelGGL(reduce_max_small_inner_kernel<true>, grid, block, 0, s, X, out, idx, pv, pi, outer, (int)red, (int)inner, pl.segs, pl.per_seg);
+        else hipLaunchKernelGGL(reduce_max_small_inner_kernel<false>, grid, block, 0, s, X, out, idx, pv, pi, outer, (int)red, (int)inner, pl.segs, pl.per_seg);
+    } else if (inner == 1) {
 #define PGK_ROWS(BF, VEC, G) \
     hipLaunchKernelGGL((reduce_max_rows_kernel<BF, VEC, G>), grid, block, 0, s, X, out, idx, pv, pi, outer, (int)red, pl.segs, pl.per_seg)
         if (bf) {

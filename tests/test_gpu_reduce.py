@@ -83,6 +83,14 @@ SHAPES = [
     ((37, 4096), 1), ((6, 40000), 1), ((3, 1 << 20), 1), ((2, 1000003), 1), ((700, 2052), 1),
     ((4, 9, 512), 1), ((3, 1000, 1032), 1), ((2, 5000, 72), 1), ((1, 30000, 8), 1), ((5, 77, 333), 1),
     ((4096, 40), 0), ((70000, 6), 0), ((9, 4, 5, 6), 2), ((2, 3, 4, 2048), 1),
+    # very short rows (several rows per wave: 1 ... 32 lanes each, vector and scalar loads)
+    ((1000, 8), 1), ((5000, 32), 1), ((777, 100), 1), ((333, 512), 1), ((2000, 3), 1), ((401, 128), 1), ((300, 129), 1),
+    ((65, 1024), 1), ((100, 33), 1),
+    # small inner extents (one wave per outer index sweeping the flattened block; with and without segments)
+    ((300, 50, 3), 1), ((7, 1000, 5), 1), ((2, 100000, 2), 1), ((5, 77, 33), 1), ((64, 64, 64), 1), ((9, 4, 5, 6), 1),
+    ((3, 40000, 40), 1), ((1000, 7, 5), 1), ((50000, 2), 0), ((1, 3, 64), 1),
+    # blocks of red x inner <= 128 elements (several outer indices per workgroup)
+    ((100000, 7, 5), 1), ((1001, 2, 64), 1), ((37, 64, 2), 1), ((5, 1, 100), 1), ((3000, 3, 3), 1), ((2, 43, 3), 0),
 ]
 
 
