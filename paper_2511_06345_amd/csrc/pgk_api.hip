@@ -505,6 +505,10 @@ struct ConvPlan {
     int edge_first_col[3];
     int64_t edge_w;
     int64_t Lp;
+    // bf16 with odd dilation: taps at odd column offsets would put tile bases on 2-byte
+    // boundaries, so the padded input is written twice, the second copy shifted by one element,
+    // and the taps are walked as two groups (even offsets from the first copy, odd from the second)
+    bool two_copies;
     bool small_tile;
     pgk::TileShape tile;
     size_t w_bytes, x_bytes;   // workspace parts: regrouped weights; padded input or strips
@@ -528,10 +532,10 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = 16 / es;
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     const int64_t K = Cin * Kw;
-    const bool needs_copy = pad > 0 || L % epc != 0;
+    pl.two_copies = dtype == PGK_DTYPE_BF16 && dilation % 2 != 0 && Kw > 1;
+    const bool needs_copy = pad > 0 || L % epc != 0 || pl.two_copies;
     const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
-    const bool taps_even = dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1;
-    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 && taps_even &&
+    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 &&
               (int64_t)t.bm * K * es < (1LL << 32) && (int64_t)t.bk * Lp * es + dilation * Kw * es < (1LL << 32);
     if (!pl.fast) return pl;
     // the tile shape the GEMM will use (same rule as for a plain GEMM)
@@ -542,7 +546,7 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
     // halo and the padding no wider than a tile.
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
-    pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
+    pl.strips = !pl.two_copies && halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
     if (pl.strips) {
         const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
         pl.edge_w = (int64_t)round_up((size_t)(bn + halo), (size_t)epc);
@@ -560,7 +564,7 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
         pl.Lp = 0;
     } else {
         pl.Lp = needs_copy ? Lp : 0;
-        pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es, 256) : 0;
+        pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es * (pl.two_copies ? 2 : 1), 256) : 0;
     }
     return pl;
 }
@@ -631,10 +635,12 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
             }
             a.b_col_shift = -(int)pad;
         } else {
-            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, pl.two_copies ? 1 : 0, dtype, st) != hipSuccess)
+                return PGK_ERR_HIP;
         }
         if (!pl.strips && pl.Lp) {
-            if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+            if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, pl.two_copies ? 2 : 1, dtype, st) != hipSuccess)
+                return PGK_ERR_HIP;
             bsrc = xp;
             ldb = pl.Lp;
         }
@@ -645,6 +651,14 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
         a.ldb = (int)ldb;
         a.b_tiles_per_tap = (int)(Cin / path.tile.bk);
         a.b_tap_step = (int)dilation;
+        if (pl.two_copies) {
+            // slots 0 .. n_even-1 hold the taps 0, 2, 4, ... (column offsets 0, 2 dil, ... in the first
+            // copy), the rest the taps 1, 3, ... (offsets dil - 1, 3 dil - 1, ... in the shifted copy)
+            const int64_t n_even = (Kw + 1) / 2;
+            a.b_tap_step = (int)(2 * dilation);
+            a.b_group_taps = (int)n_even;
+            a.b_group_jump = (B * Cin * ldb + (dilation - 1) - n_even * 2 * dilation) * es;
+        }
         a.k_slice = a.K;
         a.tiles_m = (int)((Cout + path.tile.bm - 1) / path.tile.bm);
         a.tiles_n = (int)((pl.Lout + path.tile.bn - 1) / path.tile.bn);

@@ -23,7 +23,7 @@ namespace {
 
 template <typename T>
 __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp,
-                                                             long long rows, int L, int Lp, int pad)
+                                                             long long rows, int L, int Lp, int pad, long long second)
 {
     // one workgroup row-slab: blockIdx.y = row (batch entry x channel), blockIdx.x = slab of 1024 outputs
     const long long row = blockIdx.y;
@@ -37,6 +37,8 @@ __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict
         if (j < Lp) {
             const int s = j - pad;
             dst[j] = (s >= 0 && s < L) ? src[s] : T(0);
+            // the copy shifted left by one element, `second` elements further on
+            if (second) dst[second + j] = (j + 1 < Lp && s + 1 >= 0 && s + 1 < L) ? src[s + 1] : T(0);
         }
     }
 }
@@ -45,15 +47,18 @@ struct EdgeCols { int first[3]; };
 
 template <typename T>
 __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __restrict__ w, T* __restrict__ wr,
-                                                                  int Cout, int Cin, int Kw)
+                                                                  int Cout, int Cin, int Kw, int even_first)
 {
     const long long total = (long long)Cout * Cin * Kw;
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;     // index into wr: (co, k, ci)
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;     // index into wr: (co, slot, ci)
     if (t >= total) return;
     const int ci = (int)(t % Cin);
     const long long r = t / Cin;
-    const int k = (int)(r % Kw);
+    const int slot = (int)(r % Kw);
     const long long co = r / Kw;
+    // which tap sits in this slot: in order, or the even taps followed by the odd ones
+    const int n_even = (Kw + 1) / 2;
+    const int k = !even_first ? slot : slot < n_even ? 2 * slot : 2 * (slot - n_even) + 1;
     wr[t] = w[(co * Cin + ci) * Kw + k];
 }
 
@@ -112,9 +117,10 @@ hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int 
     return hipGetLastError();
 }
 
-hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s)
+hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int copies, int dtype, hipStream_t s)
 {
-    if (rows <= 0 || rows > 65535LL * 65535LL) return hipErrorInvalidValue;
+    if (rows <= 0 || rows > 65535LL * 65535LL || copies < 1 || copies > 2) return hipErrorInvalidValue;
+    const long long second = copies == 2 ? rows * (long long)Lp : 0;    // elements between the two copies
     // grid.y is limited to 65535: fold the rows when there are more
     const unsigned int slabs = (unsigned int)((Lp + 1023) / 1024);
     for (long long r0 = 0; r0 < rows; r0 += 65535) {
@@ -122,25 +128,25 @@ hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L,
         const dim3 grid(slabs, (unsigned int)n);
         if (dtype == DT_BF16)
             hipLaunchKernelGGL(conv_pad_input_kernel<unsigned short>, grid, dim3(256), 0, s,
-                               (const unsigned short*)x + (size_t)r0 * L, (unsigned short*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
+                               (const unsigned short*)x + (size_t)r0 * L, (unsigned short*)xp + (size_t)r0 * Lp, n, L, Lp, pad, second);
         else
             hipLaunchKernelGGL(conv_pad_input_kernel<float>, grid, dim3(256), 0, s,
-                               (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
+                               (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad, second);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s)
+hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int even_taps_first, int dtype, hipStream_t s)
 {
     const long long total = (long long)Cout * Cin * Kw;
     const long long blocks = (total + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(conv_repack_weights_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw);
+                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw, even_taps_first);
     else
         hipLaunchKernelGGL(conv_repack_weights_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const float*)w, (float*)wr, Cout, Cin, Kw);
+                           (const float*)w, (float*)wr, Cout, Cin, Kw, even_taps_first);
     return hipGetLastError();
 }
 

@@ -365,7 +365,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // tiles (never, for a plain GEMM) the rows start over and the columns move on by
     // b_tap_step elements -- a convolution read as a sum of shifted GEMMs, tap after tap.
     size_t b_next_off = 0;
-    int b_next_row_tile = 0;
+    int b_next_row_tile = 0, b_taps_done = 0;
     const long long b_tap_jump = (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step;
     auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
@@ -378,6 +378,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             if (++b_next_row_tile == p.b_tiles_per_tap) {
                 b_next_row_tile = 0;
                 b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
+                if (++b_taps_done == p.b_group_taps) b_next_off = (size_t)((long long)b_next_off + p.b_group_jump);
             }
         }
         (void)kt;

@@ -169,11 +169,12 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1204 * 4
     # no padding and aligned rows: only the weights
     assert binding.conv1d_workspace_bytes(2, 64, 1024, 32, 3, 1, 0, 2, F32) == 32 * 64 * 3 * 4
-    # stride 2, channels not a multiple of the K tile, odd dilation in bf16, odd output length: in place, no workspace
+    # stride 2, channels not a multiple of the K tile, odd output length: in place, no workspace
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 2, 1, 1, F32) == 0
     assert binding.conv1d_workspace_bytes(2, 48, 1000, 32, 3, 1, 1, 1, F32) == 0
-    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, BF16) == 0
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 2, 2, BF16) > 0
+    # bf16 with odd dilation: weights + two padded copies of the input (rows of 1002, rounded up to 1008)
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, BF16) == 32 * 64 * 3 * 2 + 2 * (2 * 64) * 1008 * 2
     assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 0
 
     def call(x=0x1000, w=0x2000, y=0x3000, B=1, Cin=4, L=16, Cout=4, Kw=3, stride=1, pad=0, dil=1, act=0, dtype=0,
