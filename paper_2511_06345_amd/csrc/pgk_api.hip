@@ -61,13 +61,16 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = fa
     return true;
 }
 
-// A large tile three quarters of which would lie outside the matrix (skinny M or N): the
-// small tile wastes less matrix work and fewer operand loads.  (At one half the two are
-// level: 128 x 65536 x 1024 bf16 took 37 us with the large tile and 39 us with the small one.)
+// A large tile mostly outside the matrix (skinny M or N): the small tile wastes less matrix work
+// and fewer operand loads.  bf16: three quarters empty (between a quarter and a half full the
+// half tiles take over; 128 x 65536 x 1024 took 35 us with the large tile, 28 us with either the
+// small or the half one).  fp32, which has no half tiles: half empty -- 64 x 65536 x 1024 took
+// 146 us with the large tile and 78 us with the small one, 96 x 65536 x 1024 133 and 146 us.
 bool large_tile_mostly_empty(int64_t M, int64_t N, int dtype)
 {
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
-    return 4 * M <= big.bm || 4 * N <= big.bn;
+    const int64_t f = dtype == PGK_DTYPE_BF16 ? 4 : 2;
+    return f * M <= big.bm || f * N <= big.bn;
 }
 
 // Automatic choice (splits == 0): slices of at least kMinStepsPerSlice K steps (shorter ones
@@ -201,29 +204,28 @@ int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
     return -1;
 }
 
-// `units` = batch entries x K splits: workgroups per output tile position.
-// small_tile_forced: -1 = by the grid size, 0 / 1 = the caller (an automatic split plan) decides
+// The tile shape for an output of M x N with `units` workgroups per tile position (batch entries
+// x K splits): the small tile when three quarters of a large tile would be empty, else a half
+// tile when that saves a third of the padding, else the small tile when the large-tile grid would
+// leave a quarter of the CUs idle, else the large tile.
+int auto_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
+{
+    if (large_tile_mostly_empty(M, N, dtype)) return pgk::TILE_SMALL;
+    if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
+    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
+    const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
+    return wgs < 0.75L * kNumCUs ? pgk::TILE_SMALL : pgk::TILE_LARGE;
+}
+
+// kind_forced: -1 = auto_tile_kind, else the caller (an automatic split plan, a convolution plan) decides
 Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
-                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int small_tile_forced = -1,
+                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind_forced = -1,
                  bool b_trans = false)
 {
     const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
-    // the small tile when the large-tile grid would leave a quarter of the CUs idle, or when
-    // half of a large tile would be empty
-    const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
-    const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    int kind;
-    if (small_tile_forced >= 0) {
-        kind = small_tile_forced != 0 ? pgk::TILE_SMALL : pgk::TILE_LARGE;
-    } else if (large_tile_mostly_empty(M, N, dtype)) {
-        kind = pgk::TILE_SMALL;
-    } else if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) {
-        kind = half;
-    } else {
-        kind = wgs < 0.75L * kNumCUs ? pgk::TILE_SMALL : pgk::TILE_LARGE;
-    }
+    const int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, dtype, units, b_trans);
     return Path{true, kind, pgk::mfma_tile_shape(dtype, kind)};
 }
 
@@ -509,7 +511,7 @@ struct ConvPlan {
     // boundaries, so the padded input is written twice, the second copy shifted by one element,
     // and the taps are walked as two groups (even offsets from the first copy, odd from the second)
     bool two_copies;
-    bool small_tile;
+    int kind;            // tile shape (TILE_*), chosen as for a plain GEMM of Cout x Lout
     pgk::TileShape tile;
     size_t w_bytes, x_bytes;   // workspace parts: regrouped weights; padded input or strips
 };
@@ -539,9 +541,8 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
               (int64_t)t.bm * K * es < (1LL << 32) && (int64_t)t.bk * Lp * es + dilation * Kw * es < (1LL << 32);
     if (!pl.fast) return pl;
     // the tile shape the GEMM will use (same rule as for a plain GEMM)
-    const long double wgs = (long double)((Cout + t.bm - 1) / t.bm) * ((pl.Lout + t.bn - 1) / t.bn) * B;
-    pl.small_tile = wgs < 0.75L * kNumCUs;
-    pl.tile = pgk::mfma_tile_shape(dtype, pl.small_tile);
+    pl.kind = auto_tile_kind(Cout, pl.Lout, dtype, B, false);
+    pl.tile = pgk::mfma_tile_shape(dtype, pl.kind);
     pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
     // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
     // halo and the padding no wider than a tile.
@@ -644,7 +645,7 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
             bsrc = xp;
             ldb = pl.Lp;
         }
-        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B, (int)pl.small_tile);
+        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B, pl.kind);
         if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
         a.b_batch_stride = Cin * ldb;
