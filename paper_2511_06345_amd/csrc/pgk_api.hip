@@ -499,6 +499,9 @@ struct ConvPlan {
     // matrix-core path, where the B operand comes from:
     //   strips: the input itself; the tile columns whose reads would leave a row (listed in
     //           edge_tn) read zero-padded strips of edge_w columns instead;
+    //   table:  stride * shifts copies of the input (see launch_conv_phase_copies), rows of Lq
+    //           elements and cin_pad channels; tap k reads copy (k dil mod stride, h) at column
+    //           offset (k dil div stride) - h, with h = 1 where that offset would be odd in bf16;
     //   else:   a zero-padded copy of the whole input with rows of Lp elements (Lp = 0: the
     //           input as it is -- no padding and aligned rows)
     bool strips;
@@ -507,13 +510,12 @@ struct ConvPlan {
     int edge_first_col[3];
     int64_t edge_w;
     int64_t Lp;
-    // bf16 with odd dilation: taps at odd column offsets would put tile bases on 2-byte
-    // boundaries, so the padded input is written twice, the second copy shifted by one element,
-    // and the taps are walked as two groups (even offsets from the first copy, odd from the second)
-    bool two_copies;
+    bool table;
+    int shifts;
+    int64_t Lq, cin_pad;
     int kind;            // tile shape (TILE_*), chosen as for a plain GEMM of Cout x Lout
     pgk::TileShape tile;
-    size_t w_bytes, x_bytes;   // workspace parts: regrouped weights; padded input or strips
+    size_t w_bytes, x_bytes;   // workspace parts: regrouped weights; copies of the input or strips
 };
 
 size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -533,40 +535,67 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     pl.valid = true;
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = 16 / es;
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
-    const int64_t K = Cin * Kw;
-    pl.two_copies = dtype == PGK_DTYPE_BF16 && dilation % 2 != 0 && Kw > 1;
-    const bool needs_copy = pad > 0 || L % epc != 0 || pl.two_copies;
-    const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
-    pl.fast = stride == 1 && Cin % t.bk == 0 && Cout >= 16 && pl.Lout >= 16 && pl.Lout % epc == 0 &&
-              (int64_t)t.bm * K * es < (1LL << 32) && (int64_t)t.bk * Lp * es + dilation * Kw * es < (1LL << 32);
-    if (!pl.fast) return pl;
-    // the tile shape the GEMM will use (same rule as for a plain GEMM)
+    // what every matrix-core route needs: an output the kernels can store in 16-byte chunks
+    if (Cout < 16 || pl.Lout < 16 || pl.Lout % epc != 0) return pl;
     pl.kind = auto_tile_kind(Cout, pl.Lout, dtype, B, false);
     pl.tile = pgk::mfma_tile_shape(dtype, pl.kind);
-    pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
-    // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
-    // halo and the padding no wider than a tile.
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
-    pl.strips = !pl.two_copies && halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 && (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
-    if (pl.strips) {
-        const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
-        pl.edge_w = (int64_t)round_up((size_t)(bn + halo), (size_t)epc);
-        pl.n_edges = 0;
-        if (pad > 0) {
-            const int64_t r0 = pl.Lout > pad ? (pl.Lout - pad) / bn : 0;     // first tile column reading past the end
-            for (int64_t tn = 0; tn < tiles_n; ++tn)
-                if (tn == 0 || tn >= r0) {
-                    pl.edge_tn[pl.n_edges] = (int)tn;
-                    pl.edge_first_col[pl.n_edges] = (int)(tn * bn - pad);
-                    ++pl.n_edges;
-                }
+    const bool shifts_even = dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1;
+
+    if (stride == 1 && Cin % t.bk == 0 && shifts_even) {
+        // the input as it is, or one zero-padded copy of it; taps a constant column step apart
+        const int64_t K = Cin * Kw;
+        const bool needs_copy = pad > 0 || L % epc != 0;
+        const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
+        if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * Lp * es + dilation * Kw * es >= (1LL << 32)) return pl;
+        pl.fast = true;
+        pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
+        // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
+        // halo and the padding no wider than a tile.
+        pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 &&
+                    (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
+        if (pl.strips) {
+            const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
+            pl.edge_w = (int64_t)round_up((size_t)(bn + halo), (size_t)epc);
+            pl.n_edges = 0;
+            if (pad > 0) {
+                const int64_t r0 = pl.Lout > pad ? (pl.Lout - pad) / bn : 0;     // first tile column reading past the end
+                for (int64_t tn = 0; tn < tiles_n; ++tn)
+                    if (tn == 0 || tn >= r0) {
+                        pl.edge_tn[pl.n_edges] = (int)tn;
+                        pl.edge_first_col[pl.n_edges] = (int)(tn * bn - pad);
+                        ++pl.n_edges;
+                    }
+            }
+            pl.x_bytes = round_up((size_t)pl.n_edges * (size_t)B * (size_t)Cin * (size_t)pl.edge_w * (size_t)es, 256);
+            pl.Lp = 0;
+        } else {
+            pl.Lp = needs_copy ? Lp : 0;
+            pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es, 256) : 0;
         }
-        pl.x_bytes = round_up((size_t)pl.n_edges * (size_t)B * (size_t)Cin * (size_t)pl.edge_w * (size_t)es, 256);
-        pl.Lp = 0;
-    } else {
-        pl.Lp = needs_copy ? Lp : 0;
-        pl.x_bytes = needs_copy ? round_up((size_t)B * (size_t)Cin * (size_t)Lp * (size_t)es * (pl.two_copies ? 2 : 1), 256) : 0;
+        return pl;
     }
+
+    // Everything else with enough channels: stride > 1 (one copy per phase), a channel count
+    // that is not a multiple of the K tile (copies and weights padded with zero channels), bf16
+    // taps at odd column offsets (a second copy shifted by one element).  Each tap's place comes
+    // from a table.  Padding the channels more than twofold would cost more than it gains.
+    pl.cin_pad = (int64_t)round_up((size_t)Cin, (size_t)t.bk);
+    if (Kw > pgk::kMaxTableTaps || pl.cin_pad > 2 * Cin) return pl;
+    const int64_t K = pl.cin_pad * Kw;
+    const int64_t q_max = halo / stride;
+    pl.shifts = 1;
+    if (dtype == PGK_DTYPE_BF16)
+        for (int64_t k = 0; k < Kw; ++k)
+            if ((k * dilation / stride) % 2 != 0) pl.shifts = 2;
+    pl.Lq = (int64_t)round_up((size_t)(pl.Lout + q_max + 1), (size_t)epc);
+    if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * pl.Lq * es >= (1LL << 32)) return pl;
+    const long double copies_bytes = (long double)stride * pl.shifts * B * pl.cin_pad * pl.Lq * es;
+    if (copies_bytes >= 4.0e12L || (long double)stride * pl.shifts * B * pl.cin_pad > 4.0e9L) return pl;
+    pl.fast = true;
+    pl.table = true;
+    pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
+    pl.x_bytes = round_up((size_t)copies_bytes, 256);
     return pl;
 }
 
@@ -621,8 +650,24 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
         unsigned char* wr = static_cast<unsigned char*>(workspace);
         unsigned char* xp = wr + pl.w_bytes;
         const void* bsrc = x;
-        int64_t ldb = L;
-        if (pl.strips) {
+        int64_t ldb = L, cin_k = Cin;
+        if (pl.table) {
+            cin_k = pl.cin_pad;
+            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)pl.cin_pad, (int)Kw, dtype, st) != hipSuccess)
+                return PGK_ERR_HIP;
+            if (pgk::launch_conv_phase_copies(x, xp, B, (int)Cin, (int)pl.cin_pad, (int)L, (int)pl.Lq, (int)pad, (int)stride,
+                                              pl.shifts, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+            bsrc = xp;
+            ldb = pl.Lq;
+            a.K = (int)(pl.cin_pad * Kw);
+            a.b_use_tap_table = 1;
+            const int64_t plane = B * pl.cin_pad * pl.Lq;          // elements of one copy
+            for (int64_t k = 0; k < Kw; ++k) {
+                const int64_t o = k * dilation, phase = o % stride, q = o / stride;
+                const int64_t h = (pl.shifts == 2 && q % 2 != 0) ? 1 : 0;
+                a.b_tap_off[k] = ((phase * pl.shifts + h) * plane + (q - h)) * es;
+            }
+        } else if (pl.strips) {
             // strips and regrouped weights in one launch
             if (pgk::launch_conv_prepare(x, xp, B * Cin, (int)L, (int)pl.edge_w, pl.n_edges, pl.edge_first_col, w, wr,
                                          (int)Cout, (int)Cin, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
@@ -636,30 +681,23 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
             }
             a.b_col_shift = -(int)pad;
         } else {
-            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Kw, pl.two_copies ? 1 : 0, dtype, st) != hipSuccess)
+            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)Cin, (int)Kw, dtype, st) != hipSuccess)
                 return PGK_ERR_HIP;
+            if (pl.Lp) {
+                if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, dtype, st) != hipSuccess)
+                    return PGK_ERR_HIP;
+                bsrc = xp;
+                ldb = pl.Lp;
+            }
         }
-        if (!pl.strips && pl.Lp) {
-            if (pgk::launch_conv_pad_input(x, xp, B * Cin, (int)L, (int)pl.Lp, (int)pad, pl.two_copies ? 2 : 1, dtype, st) != hipSuccess)
-                return PGK_ERR_HIP;
-            bsrc = xp;
-            ldb = pl.Lp;
-        }
-        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, Cin * Kw, dtype, B, pl.kind);
+        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, cin_k * Kw, dtype, B, pl.kind);
         if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
-        a.b_batch_stride = Cin * ldb;
+        a.a_batch_stride = 0;
+        a.b_batch_stride = cin_k * ldb;
         a.ldb = (int)ldb;
-        a.b_tiles_per_tap = (int)(Cin / path.tile.bk);
+        a.b_tiles_per_tap = (int)(cin_k / path.tile.bk);
         a.b_tap_step = (int)dilation;
-        if (pl.two_copies) {
-            // slots 0 .. n_even-1 hold the taps 0, 2, 4, ... (column offsets 0, 2 dil, ... in the first
-            // copy), the rest the taps 1, 3, ... (offsets dil - 1, 3 dil - 1, ... in the shifted copy)
-            const int64_t n_even = (Kw + 1) / 2;
-            a.b_tap_step = (int)(2 * dilation);
-            a.b_group_taps = (int)n_even;
-            a.b_group_jump = (B * Cin * ldb + (dilation - 1) - n_even * 2 * dilation) * es;
-        }
         a.k_slice = a.K;
         a.tiles_m = (int)((Cout + path.tile.bm - 1) / path.tile.bm);
         a.tiles_n = (int)((pl.Lout + path.tile.bn - 1) / path.tile.bn);

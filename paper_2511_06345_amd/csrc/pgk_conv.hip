@@ -23,7 +23,7 @@ namespace {
 
 template <typename T>
 __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict__ x, T* __restrict__ xp,
-                                                             long long rows, int L, int Lp, int pad, long long second)
+                                                             long long rows, int L, int Lp, int pad)
 {
     // one workgroup row-slab: blockIdx.y = row (batch entry x channel), blockIdx.x = slab of 1024 outputs
     const long long row = blockIdx.y;
@@ -37,8 +37,6 @@ __global__ __launch_bounds__(256) void conv_pad_input_kernel(const T* __restrict
         if (j < Lp) {
             const int s = j - pad;
             dst[j] = (s >= 0 && s < L) ? src[s] : T(0);
-            // the copy shifted left by one element, `second` elements further on
-            if (second) dst[second + j] = (j + 1 < Lp && s + 1 >= 0 && s + 1 < L) ? src[s + 1] : T(0);
         }
     }
 }
@@ -47,19 +45,47 @@ struct EdgeCols { int first[3]; };
 
 template <typename T>
 __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __restrict__ w, T* __restrict__ wr,
-                                                                  int Cout, int Cin, int Kw, int even_first)
+                                                                  int Cout, int Cin, int Cin_pad, int Kw)
 {
-    const long long total = (long long)Cout * Cin * Kw;
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;     // index into wr: (co, slot, ci)
+    const long long total = (long long)Cout * Cin_pad * Kw;
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;     // index into wr: (co, k, ci)
     if (t >= total) return;
-    const int ci = (int)(t % Cin);
-    const long long r = t / Cin;
-    const int slot = (int)(r % Kw);
+    const int ci = (int)(t % Cin_pad);
+    const long long r = t / Cin_pad;
+    const int k = (int)(r % Kw);
     const long long co = r / Kw;
-    // which tap sits in this slot: in order, or the even taps followed by the odd ones
-    const int n_even = (Kw + 1) / 2;
-    const int k = !even_first ? slot : slot < n_even ? 2 * slot : 2 * (slot - n_even) + 1;
-    wr[t] = w[(co * Cin + ci) * Kw + k];
+    wr[t] = ci < Cin ? w[(co * Cin + ci) * Kw + k] : T(0);
+}
+
+// xc[c][b][ci][j] = x[b][ci][(j + h) * stride + phase - pad] (inside [0, L), ci < Cin; else 0) with
+// c = phase * shifts + h.  One thread per 16-byte chunk of the copies (rows of Lq elements, a
+// multiple of the chunk): element loads, one 16-byte store.
+template <typename T>
+__global__ __launch_bounds__(256) void conv_phase_copies_kernel(const T* __restrict__ x, T* __restrict__ xc, long long B,
+                                                                int Cin, int Cin_pad, int L, int Lq, int pad, int stride,
+                                                                int shifts, long long total_chunks)
+{
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total_chunks) return;
+    const int cpr = Lq / EPC;                                // chunks per row
+    const long long row = t / cpr;                           // (c * B + b) * Cin_pad + ci
+    const int j0 = (int)(t - row * cpr) * EPC;
+    const int ci = (int)(row % Cin_pad);
+    const long long cb = row / Cin_pad;
+    const long long b = cb % B;
+    const int c = (int)(cb / B);
+    const int phase = c / shifts, h = c - phase * shifts;
+    const T* src = x + ((size_t)b * (size_t)Cin + (size_t)(ci < Cin ? ci : 0)) * (size_t)L;
+    T v[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) {
+        const long long s = (long long)(j0 + e + h) * stride + phase - pad;
+        v[e] = (ci < Cin && s >= 0 && s < L) ? src[s] : T(0);
+    }
+    u32x4 out;
+    __builtin_memcpy(&out, v, 16);
+    *(u32x4*)(xc + (size_t)row * (size_t)Lq + j0) = out;
 }
 
 // Both preparations of the in-place path in one launch (each is a few microseconds of work;
@@ -117,10 +143,26 @@ hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int 
     return hipGetLastError();
 }
 
-hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int copies, int dtype, hipStream_t s)
+hipError_t launch_conv_phase_copies(const void* x, void* xc, long long B, int Cin, int Cin_pad, int L, int Lq, int pad,
+                                    int stride, int shifts, int dtype, hipStream_t s)
 {
-    if (rows <= 0 || rows > 65535LL * 65535LL || copies < 1 || copies > 2) return hipErrorInvalidValue;
-    const long long second = copies == 2 ? rows * (long long)Lp : 0;    // elements between the two copies
+    const int epc = dtype == DT_BF16 ? 8 : 4;
+    if (Lq % epc != 0 || B <= 0) return hipErrorInvalidValue;
+    const long long chunks = (long long)stride * shifts * B * Cin_pad * (Lq / epc);
+    const long long blocks = (chunks + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(conv_phase_copies_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const unsigned short*)x, (unsigned short*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks);
+    else
+        hipLaunchKernelGGL(conv_phase_copies_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)x,
+                           (float*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks);
+    return hipGetLastError();
+}
+
+hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s)
+{
+    if (rows <= 0 || rows > 65535LL * 65535LL) return hipErrorInvalidValue;
     // grid.y is limited to 65535: fold the rows when there are more
     const unsigned int slabs = (unsigned int)((Lp + 1023) / 1024);
     for (long long r0 = 0; r0 < rows; r0 += 65535) {
@@ -128,25 +170,25 @@ hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L,
         const dim3 grid(slabs, (unsigned int)n);
         if (dtype == DT_BF16)
             hipLaunchKernelGGL(conv_pad_input_kernel<unsigned short>, grid, dim3(256), 0, s,
-                               (const unsigned short*)x + (size_t)r0 * L, (unsigned short*)xp + (size_t)r0 * Lp, n, L, Lp, pad, second);
+                               (const unsigned short*)x + (size_t)r0 * L, (unsigned short*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
         else
             hipLaunchKernelGGL(conv_pad_input_kernel<float>, grid, dim3(256), 0, s,
-                               (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad, second);
+                               (const float*)x + (size_t)r0 * L, (float*)xp + (size_t)r0 * Lp, n, L, Lp, pad);
     }
     return hipGetLastError();
 }
 
-hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int even_taps_first, int dtype, hipStream_t s)
+hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Cin_pad, int Kw, int dtype, hipStream_t s)
 {
-    const long long total = (long long)Cout * Cin * Kw;
+    const long long total = (long long)Cout * Cin_pad * Kw;
     const long long blocks = (total + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(conv_repack_weights_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw, even_taps_first);
+                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Cin_pad, Kw);
     else
         hipLaunchKernelGGL(conv_repack_weights_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const float*)w, (float*)wr, Cout, Cin, Kw, even_taps_first);
+                           (const float*)w, (float*)wr, Cout, Cin, Cin_pad, Kw);
     return hipGetLastError();
 }
 

@@ -364,7 +364,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // kept as running state: b_step further down, except that after every b_tiles_per_tap
     // tiles (never, for a plain GEMM) the rows start over and the columns move on by
     // b_tap_step elements -- a convolution read as a sum of shifted GEMMs, tap after tap.
-    size_t b_next_off = 0;
+    size_t b_next_off = p.b_use_tap_table ? (size_t)p.b_tap_off[0] : 0;
     int b_next_row_tile = 0, b_taps_done = 0;
     const long long b_tap_jump = (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step;
     auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
@@ -377,8 +377,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             b_next_off += b_step;
             if (++b_next_row_tile == p.b_tiles_per_tap) {
                 b_next_row_tile = 0;
-                b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
-                if (++b_taps_done == p.b_group_taps) b_next_off = (size_t)((long long)b_next_off + p.b_group_jump);
+                ++b_taps_done;
+                // (the last advance comes after the final tile: the index is kept inside the table)
+                if (p.b_use_tap_table) b_next_off = (size_t)p.b_tap_off[b_taps_done < 32 ? b_taps_done : 31];
+                else b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
             }
         }
         (void)kt;

@@ -37,12 +37,12 @@ struct GemmArgs {
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
     // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
     int b_tiles_per_tap, b_tap_step;
-    // ... and after the first b_group_taps taps the B base moves once more by b_group_jump bytes
-    // (never, for INT_MAX taps): the taps of a bf16 convolution with odd dilation are walked as
-    // two groups, those at even column offsets from the padded input and those at odd offsets
-    // from a second copy shifted by one element, so that every tile base stays 4-byte aligned.
-    int b_group_taps;
-    long long b_group_jump;
+    // ... or, with b_use_tap_table, tap t starts at byte offset b_tap_off[t] from the B base: the
+    // taps of a convolution may then read different copies of the input (the phases of a strided
+    // convolution; for bf16 a copy shifted by one element for taps at odd column offsets, so
+    // that every tile base stays 4-byte aligned).  At most kMaxTableTaps taps.
+    int b_use_tap_table;
+    long long b_tap_off[32];
     // Matrix-core kernels, convolution without a padded copy of the input: the columns a tile
     // reads start b_col_shift (= -pad) before its output columns; the (at most three) tile
     // columns whose reads would leave the rows read a small zero-padded strip instead:
@@ -72,8 +72,8 @@ inline void fill_plain_views(GemmArgs& a)
     a.bias_per_row = 0;
     a.b_tiles_per_tap = 0x7fffffff;
     a.b_tap_step = 0;
-    a.b_group_taps = 0x7fffffff;
-    a.b_group_jump = 0;
+    a.b_use_tap_table = 0;
+    for (int t = 0; t < 32; ++t) a.b_tap_off[t] = 0;
     a.b_col_shift = 0;
     for (int e = 0; e < 3; ++e) { a.edge_B[e] = nullptr; a.edge_tn[e] = -1; }
     a.edge_ldb = 0;
@@ -137,14 +137,19 @@ hipError_t launch_reduce_max(const ReducePlan& pl, const void* X, void* out, int
 
 // Convolution helpers (pgk_conv.hip): xp[row][j] = x[row][j - pad] inside [0, L), else 0, for
 // `rows` rows of length L -> Lp; wr[co][k][ci] = w[co][ci][k].
-// `copies` = 2: a second copy follows the first, shifted left by one element (xp1[row][j] = xp[row][j + 1], last column 0)
-hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int copies, int dtype, hipStream_t s);
-// `even_taps_first`: wr holds the taps 0, 2, 4, ... and then 1, 3, 5, ... instead of 0, 1, 2, ...
-hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Kw, int even_taps_first, int dtype, hipStream_t s);
+hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L, int Lp, int pad, int dtype, hipStream_t s);
+// Copies of the input for the table-driven path: copy c = phase * shifts + h (phase < stride,
+// h < shifts) is xc[c][b][ci][j] = x[b][ci][(j + h) * stride + phase - pad] inside [0, L) and for
+// ci < Cin, else 0; ci runs to Cin_pad, j to Lq.
+hipError_t launch_conv_phase_copies(const void* x, void* xc, long long B, int Cin, int Cin_pad, int L, int Lq, int pad,
+                                    int stride, int shifts, int dtype, hipStream_t s);
+// wr[co][k][ci] = w[co][ci][k] for ci < Cin, 0 for Cin <= ci < Cin_pad
+hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Cin_pad, int Kw, int dtype, hipStream_t s);
 // the regrouped weights and, in the same launch, strip e (e < n_edges, may be 0) of
 // S[e][row][j], j < W: x[row][first_col[e] + j] inside [0, L), else 0
 hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int L, int W, int n_edges, const int* first_col,
                                const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s);
+constexpr int kMaxTableTaps = 32;
 
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming

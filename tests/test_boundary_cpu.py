@@ -169,13 +169,19 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1204 * 4
     # no padding and aligned rows: only the weights
     assert binding.conv1d_workspace_bytes(2, 64, 1024, 32, 3, 1, 0, 2, F32) == 32 * 64 * 3 * 4
-    # stride 2, channels not a multiple of the K tile, odd output length: in place, no workspace
-    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 2, 1, 1, F32) == 0
-    assert binding.conv1d_workspace_bytes(2, 48, 1000, 32, 3, 1, 1, 1, F32) == 0
+    # stride 2: one copy of the input per phase (rows of 500 outputs + 1 tap offset + 1, rounded up to 504)
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 2, 1, 1, F32) == 32 * 64 * 3 * 4 + 2 * (2 * 64) * 504 * 4
+    # 48 channels: copy and weights padded to 64 channels (rows of 1000 + 2 + 1, rounded up to 1004)
+    assert binding.conv1d_workspace_bytes(2, 48, 1000, 32, 3, 1, 1, 1, F32) == 32 * 64 * 3 * 4 + (2 * 64) * 1004 * 4
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 2, 2, BF16) > 0
-    # bf16 with odd dilation: weights + two padded copies of the input (rows of 1002, rounded up to 1008)
+    # bf16 with odd dilation: a second copy shifted by one element for the taps at odd offsets (rows of 1008)
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, BF16) == 32 * 64 * 3 * 2 + 2 * (2 * 64) * 1008 * 2
+    # three channels (padding them to a K tile would multiply the work), an output length that is not
+    # a multiple of 16 bytes, fewer than 16 output channels, more than 32 taps at stride 2: in place, no workspace
+    assert binding.conv1d_workspace_bytes(2, 3, 1000, 32, 3, 1, 1, 1, F32) == 0
     assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 8, 3, 1, 1, 1, F32) == 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 33, 2, 16, 1, F32) == 0
 
     def call(x=0x1000, w=0x2000, y=0x3000, B=1, Cin=4, L=16, Cout=4, Kw=3, stride=1, pad=0, dil=1, act=0, dtype=0,
              ws=None, ws_bytes=0):

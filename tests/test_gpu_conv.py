@@ -57,14 +57,21 @@ FAST = {
           (40, 64, 2048, 128, 3, 1, 1, 1), (2, 64, 4096, 256, 3, 1, 0, 2),
           # one tile column that is first and last at once; right edge spread over two tile columns;
           # padding wider than a tile (padded copy of the whole input); halo wider than a tile
-          (2, 32, 60, 32, 5, 1, 2, 1), (2, 32, 1024, 32, 9, 1, 6, 1), (2, 32, 500, 32, 3, 1, 101, 1), (1, 32, 2000, 32, 5, 1, 0, 40)],
+          (2, 32, 60, 32, 5, 1, 2, 1), (2, 32, 1024, 32, 9, 1, 6, 1), (2, 32, 500, 32, 3, 1, 101, 1), (1, 32, 2000, 32, 5, 1, 0, 40),
+          # stride > 1 (one copy of the input per phase), channel counts that are not a multiple of the K tile
+          # (copies and weights padded with zero channels), both, large tiles
+          (2, 64, 1000, 32, 3, 2, 1, 1), (2, 32, 1024, 48, 5, 2, 2, 1), (2, 32, 1200, 32, 4, 3, 2, 2), (2, 48, 1000, 32, 3, 1, 1, 1),
+          (3, 80, 520, 130, 5, 1, 2, 1), (40, 96, 2048, 256, 3, 2, 1, 1), (2, 20, 4096, 64, 7, 4, 3, 1)],
     BF16: [(2, 64, 256, 32, 3, 1, 2, 2), (1, 128, 1024, 48, 5, 1, 4, 2), (3, 64, 520, 130, 1, 1, 0, 1),
            (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8),
            (2, 64, 120, 32, 5, 1, 4, 2), (2, 64, 1030, 32, 3, 1, 3, 2), (2, 64, 1036, 32, 9, 1, 6, 2),
            # odd dilation: taps at odd column offsets come from a second copy shifted by one element
            (2, 64, 256, 32, 3, 1, 1, 1), (1, 128, 1024, 48, 5, 1, 2, 1), (3, 64, 519, 130, 2, 1, 1, 1), (40, 128, 2048, 256, 3, 1, 1, 1),
            (2, 64, 1032, 32, 3, 1, 3, 3), (2, 64, 1024, 32, 9, 1, 4, 1), (2, 64, 2004, 32, 5, 1, 0, 5), (2, 64, 504, 32, 3, 1, 101, 1),
-           (2, 64, 1025, 32, 4, 1, 1, 1), (1, 64, 64, 16, 7, 1, 3, 1)],
+           (2, 64, 1025, 32, 4, 1, 1, 1), (1, 64, 64, 16, 7, 1, 3, 1),
+           # stride > 1, ragged channel counts, both with odd and even tap offsets
+           (2, 64, 1024, 32, 3, 2, 1, 1), (2, 96, 1024, 32, 3, 1, 1, 1), (2, 64, 1200, 32, 4, 3, 2, 2), (40, 160, 2048, 256, 3, 2, 1, 1),
+           (2, 64, 1040, 32, 5, 2, 6, 3), (2, 40, 4096, 64, 7, 4, 3, 1)],
 }
 # everything else: the bounds-checked kernel reading the input in place
 GENERAL = [(1, 1, 9, 1, 3, 1, 0, 1), (2, 3, 17, 4, 3, 1, 1, 1), (2, 5, 50, 7, 5, 2, 2, 1), (1, 2, 130, 70, 4, 3, 5, 2),
