@@ -17,7 +17,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 RESOURCES = os.path.join(HERE, "kernel_resources.json")
 
 SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
-           "pgk_probe.hip", "pgk_conv.hip"]
+           "pgk_probe.hip", "pgk_conv.hip", "pgk_pack.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     # keep the compiler from forming packed fp32 VALU ops

@@ -135,9 +135,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
-                // columns past the end of a ragged N add nothing to the row sum (N is a
-                // multiple of 4, so a run of 4 is all in or all out)
-                const bool in_n = col < n_rem;
+                // columns past the end of a ragged N add nothing to the row sum
                 const f32x4 bv = bvs[g];
                 float y[4];
 #pragma unroll
@@ -146,7 +144,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                         y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
                     } else {
                         y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e] + br);
-                        rs += in_n ? y[e] : 0.0f;
+                        rs += col + e < n_rem ? y[e] : 0.0f;
                     }
                 }
                 unsigned char* dst = base + (((col >> 2) ^ key) * UB);
@@ -201,14 +199,27 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
         v[it] = *(const u32x4*)(base + unit * UB);
     }
     __builtin_amdgcn_sched_barrier(0);
-    const bool col_ok = c * (16 / (OUT_BF16 ? 2 : 4)) < n_rem;
+    // N need not be a multiple of the 16-byte chunk: the row's last chunk may hold fewer
+    // elements, which are then stored one by one (rows start on 4-byte boundaries at least,
+    // which is all a multi-dword store needs)
+    constexpr int EPC = 16 / (OUT_BF16 ? 2 : 4);
+    const int left = n_rem - c * EPC;                  // elements of this chunk that exist
 #pragma unroll
     for (int it = 0; it < ITERS; ++it) {
         const int row = it * ROWS_PER_IT + tid / CPR;
-        if (row < m_rem && col_ok) {
-            u32x4* dst = (u32x4*)(out_tile + (size_t)row * ld_bytes + (size_t)c * 16);
-            if constexpr (STREAM) __builtin_nontemporal_store(v[it], dst);
-            else *dst = v[it];
+        if (row >= m_rem || left <= 0) continue;
+        unsigned char* at = out_tile + (size_t)row * ld_bytes + (size_t)c * 16;
+        if (left >= EPC) {
+            if constexpr (STREAM) __builtin_nontemporal_store(v[it], (u32x4*)at);
+            else *(u32x4*)at = v[it];
+        } else {
+#pragma unroll
+            for (int e = 0; e < EPC - 1; ++e) {
+                if (e >= left) break;
+                const unsigned int word = v[it][OUT_BF16 ? e / 2 : e];
+                if constexpr (OUT_BF16) ((unsigned short*)at)[e] = (unsigned short)(e % 2 ? word >> 16 : word & 0xffffu);
+                else ((unsigned int*)at)[e] = word;
+            }
         }
     }
 }
@@ -326,9 +337,11 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         } else {
             const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
             const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
-            // likewise column chunks past the end of B (N is a multiple of the 16-byte chunk)
+            // likewise column chunks past the end of B.  (When N is not a multiple of the 16-byte
+            // chunk the caller hands over a B whose rows are padded to one, so the row's last,
+            // partly filled chunk can be read whole.)
             constexpr int EPC = 16 / ES;                      // elements per chunk
-            const int cg = (c + 1) * EPC <= n_rem ? c : n_rem / EPC - 1;
+            const int cg = c * EPC < n_rem ? c : (n_rem + EPC - 1) / EPC - 1;
             voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
         }
     }
@@ -711,7 +724,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                     for (int g = 0; g < 4; ++g) {
                         const int n = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;
                         f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        if (wm * Cfg::WM + 32 * i + l32 < m_rem && n < n_rem) *(f32x4*)((float*)w + row_off + n) = o;
+                        if (wm * Cfg::WM + 32 * i + l32 < m_rem) {
+                            if (n + 4 <= n_rem) {
+                                *(f32x4*)((float*)w + row_off + n) = o;
+                            } else {
+#pragma unroll
+                                for (int e = 0; e < 3; ++e)
+                                    if (n + e < n_rem) ((float*)w)[row_off + n + e] = o[e];
+                            }
+                        }
                     }
             }
         }

@@ -130,11 +130,18 @@ def test_tile_table_and_split_rule(lib):
     # only the small-tile grid fills the chip: split from 512 K tiles on
     expect((2048, 2048, 16384, 1), BF16, (128, 128, 64), 1, 256)
     expect((2048, 2048, 65536, 1), BF16, (256, 256, 64), 8, 512)
-    # K or N off the 16-byte grid, or a tiny output: bounds-checked kernel
-    expect((4096, 4096, 4098, 1), F32, (64, 64, 16), 1, 4096, matrix_core=False)
-    expect((4096, 4100, 4096, 1), BF16, (64, 64, 16), 1, 64 * 65, matrix_core=False)
+    # K or N off the 16-byte grid: the plan of the zero-padded copies (bf16 with an odd N: one column wider)
+    expect((4096, 4096, 4098, 1), F32, (128, 128, 32), 1, 1024)
+    expect((4096, 4100, 4096, 1), BF16, (256, 256, 64), 1, 16 * 17)
+    expect((4096, 4101, 4096, 1), BF16, (256, 256, 64), 1, 16 * 17)
     expect((4096, 4100, 4096, 1), F32, (128, 128, 32), 1, 32 * 33)
-    expect((8, 4096, 4096, 1), BF16, (64, 64, 16), 1, 64, matrix_core=False)
+    # a few rows: small tiles, K in slices
+    expect((8, 4096, 4096, 1), BF16, (128, 128, 64), 4, 128)
+    expect((1, 4096, 4096, 1), F32, (64, 64, 32), 8, 512)
+    # an output below 16 x 16, or too little work to copy operands for: bounds-checked kernel
+    expect((12, 12, 100000, 1), BF16, (64, 64, 16), 1, 1, matrix_core=False)
+    expect((2, 300, 5, 1), BF16, (64, 64, 16), 1, 5, matrix_core=False)
+    expect((5, 7, 33, 2), F32, (64, 64, 16), 1, 2, matrix_core=False)
     # ragged everything on the matrix cores
     expect((3000, 5000, 4104, 1), BF16, (256, 256, 64), 1, 12 * 20)
     # invalid sizes

@@ -28,8 +28,8 @@ def pgk():
 
 
 def draw_cases(seed, count):
-    """(dtype, M, N, K, batch) per size class; K and N mostly on the 16-byte grid (matrix-core
-    kernels), sometimes off it (bounds-checked kernel)."""
+    """(dtype, M, N, K, batch) per size class; K and N mostly on the 16-byte grid, sometimes off
+    it (the matrix-core kernels on zero-padded copies, or the bounds-checked kernel when small)."""
     rng = np.random.default_rng(seed)
     cases = []
     for n in range(count):
@@ -38,8 +38,9 @@ def draw_cases(seed, count):
         big = 256 if dtype == BF16 else 128
         kind = ["any", "grid", "large", "tall", "wide", "longk"][n % 6]
         on_grid = lambda v: max(step, int(v) // step * step)
-        if kind == "any":
-            M, N, K, batch = int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 300)), int(rng.integers(1, 4))
+        if kind == "any":      # every other one too small for the operands to be copied: bounds-checked kernel
+            hi = 60 if (n // 6) % 2 else 300
+            M, N, K, batch = int(rng.integers(1, hi)), int(rng.integers(1, hi)), int(rng.integers(1, hi)), int(rng.integers(1, 4))
         elif kind == "grid":
             M, N, K, batch = int(rng.integers(16, 700)), on_grid(rng.integers(16, 700)), on_grid(rng.integers(step, 900)), int(rng.integers(1, 4))
         elif kind == "large":      # enough batch entries for the large-tile grid to reach 192 workgroups
