@@ -67,11 +67,18 @@ typedef enum {
  * when rowsum != NULL, rowsum = C*1 (the matmul operator of Sections 1 / 4.2
  * with the activation and reduction operators fused into its epilogue).
  *
- * M, N, K, batch > 0.  Any shape is accepted.  The matrix-core kernels take every
- * problem with K and N multiples of 16 bytes of elements (4 for float32, 8 for
- * bfloat16), M and N at least 16 and 16-byte aligned pointers; M, N and K need not be
- * tile multiples.  All other shapes go to a bounds-checked kernel.  M, N, K must each be below 2^31 and
- * batch*M*N, batch*M*K, batch*K*N below 2^62 (else PGK_ERR_UNSUPPORTED).
+ * M, N, K, batch > 0.  Any shape is accepted; M, N and K need not be tile multiples.
+ * The matrix-core kernels read operands whose rows are whole 16-byte chunks (K, and for B
+ * as [K][N] also N, a multiple of 4 float32 / 8 bfloat16 elements) in place.  Operands
+ * with other row lengths are first copied into zero-padded buffers of the library (a
+ * second per-(device, stream) pool, sized batch*(M*K' + K'*N') elements with K', N' the
+ * next multiples; allocation, reuse and release as for the scratch buffer below) when the
+ * problem has at least 64^3 multiply-adds.  C, bias and rowsum are always used in place,
+ * whatever N is.  What is left for a slower, bounds-checked kernel: smaller problems off
+ * the chunk grid, outputs below 16 x 16 with K below 1024, and calls whose C or bias (or,
+ * with rows on the chunk grid, A or B) pointer is not 16-byte aligned.
+ * M, N, K must each be below 2^31 and batch*M*N, batch*M*K, batch*K*N below 2^62 (else
+ * PGK_ERR_UNSUPPORTED).
  *
  * The library keeps a device scratch buffer per (device, stream), allocated on first
  * use (hipMalloc; PGK_ERR_HIP if that fails), grown when needed, reused afterwards and
@@ -121,9 +128,9 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
  * the storage of one operand differs).  Every other argument, the layouts of A, bias, C
  * and rowsum, ownership, the scratch buffer, the split rule, the workspace size
  * (pgk_splitk_workspace_bytes does not depend on the layout of B) and the errors are as
- * for pgk_gemm_fused / pgk_gemm_splitk.  The matrix-core kernels take these calls under
- * the same conditions (K and N multiples of 16 bytes of elements, M and N at least 16,
- * 16-byte aligned pointers); they read Bt in place -- no transposed copy is made.
+ * for pgk_gemm_fused / pgk_gemm_splitk.  The matrix-core kernels read Bt in place -- no
+ * transposed copy is made -- when K is a multiple of the 16-byte chunk, whatever N is;
+ * otherwise A and Bt are copied with K padded, as described there.
  */
 int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
                       int64_t M, int64_t N, int64_t K, int64_t batch,

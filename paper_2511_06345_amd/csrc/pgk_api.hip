@@ -52,54 +52,52 @@ int64_t round_up64(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
 // What the matrix-core kernels take as it is: operand rows that are whole 16-byte chunks (K for
 // A and a transposed B; the row length ldb of a plain B, which is N unless the caller has padded
-// it), output rows that start on 4-byte boundaries.  M, N and K need not be tile multiples.  An
-// output below 16 x 16 is left to the bounds-checked kernel, which wastes less.
-bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = false, int64_t ldb = 0, bool out_f32 = false)
+// it).  M, N and K need not be tile multiples, and the output rows may have any length.  An
+// output below 16 x 16 is left to the bounds-checked kernel, which wastes less, unless K is
+// long (then the matrix-core route splits the K range over the chip).
+bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = false, int64_t ldb = 0)
 {
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = chunk_elems(dtype);
     if (!ldb) ldb = b_trans ? K : N;
-    if (K % epc || ldb % epc || (N * (out_f32 ? 4 : es)) % 4) return false;
-    if (M < 16 && N < 16) return false;
+    if (K % epc || ldb % epc) return false;
+    if (M < 16 && N < 16 && K < 1024) return false;
     // per-lane 32-bit byte offsets inside one tile
     if ((int64_t)t.bm * K * es >= (1LL << 32)) return false;
     if ((b_trans ? (int64_t)t.bn * K : (int64_t)t.bk * ldb) * es >= (1LL << 32)) return false;
     return true;
 }
 
-// K or N off the 16-byte grid: the operands are first copied into zero-padded buffers (and a
-// bf16 output with an odd N is computed one column wider, then cropped).  Worth it from about
-// 64^3 multiply-adds on.
-bool needs_packing(int64_t N, int64_t K, int dtype)
+// K off the 16-byte grid, or the rows of a plain B: the operands are first copied into
+// zero-padded buffers.  Worth it from about 64^3 multiply-adds on.
+bool needs_packing(int64_t N, int64_t K, int dtype, bool b_trans)
 {
     const int64_t epc = chunk_elems(dtype);
-    return K % epc != 0 || N % epc != 0;
+    return K % epc != 0 || (!b_trans && N % epc != 0);
 }
 
 // The dimensions the kernels see for a problem that is packed first: K and the row length of B
-// rounded up to whole chunks; N one larger when the output rows would otherwise start off
-// 4-byte boundaries (bf16 written directly, odd N), then `crop` is set.  pack = false: the
-// problem is taken as it is (aligned already, or too small or too large for this to pay).
-struct PackDims { bool pack; int64_t n, k, ldb; bool crop; };
+// rounded up to whole chunks.  pack = false: the problem is taken as it is (aligned already, or
+// too small or too large for this to pay).
+struct PackDims { bool pack; int64_t k, ldb; };
 
-PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans, bool out_f32)
+PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans)
 {
-    const PackDims as_is{false, N, K, 0, false};
-    if (!needs_packing(N, K, dtype)) return as_is;
+    const PackDims as_is{false, K, 0};
+    if (!needs_packing(N, K, dtype, b_trans)) return as_is;
     if ((long double)M * N * K < 262144.0L) return as_is;
-    const int64_t epc = chunk_elems(dtype), es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
-    PackDims d{true, N, round_up64(K, epc), 0, false};
-    if (!out_f32 && (N * es) % 4 != 0) { d.n = N + 1; d.crop = true; }
-    d.ldb = b_trans ? d.k : round_up64(d.n, epc);
-    if (d.k > kMaxDim || d.ldb > kMaxDim || d.n > kMaxDim) return as_is;
-    if (!mfma_shape_ok(M, d.n, d.k, dtype, b_trans, d.ldb, out_f32)) return as_is;
+    const int64_t epc = chunk_elems(dtype);
+    PackDims d{true, round_up64(K, epc), 0};
+    d.ldb = b_trans ? d.k : round_up64(N, epc);
+    if (d.k > kMaxDim || d.ldb > kMaxDim) return as_is;
+    if (!mfma_shape_ok(M, N, d.k, dtype, b_trans, d.ldb)) return as_is;
     return d;
 }
 
 // the plan queries: does this problem end up on the matrix cores, one way or the other
 bool mfma_route(int64_t M, int64_t N, int64_t K, int dtype)
 {
-    return mfma_shape_ok(M, N, K, dtype) || pack_dims(M, N, K, dtype, false, false).pack;
+    return mfma_shape_ok(M, N, K, dtype) || pack_dims(M, N, K, dtype, false).pack;
 }
 
 // A large tile mostly outside the matrix (skinny M or N): the small tile wastes less matrix work
@@ -264,9 +262,9 @@ int auto_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
 // kind_forced: -1 = auto_tile_kind, else the caller (an automatic split plan, a convolution plan) decides
 Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
                  int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind_forced = -1,
-                 bool b_trans = false, int64_t ldb = 0, bool out_f32 = false)
+                 bool b_trans = false, int64_t ldb = 0)
 {
-    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb, out_f32) && aligned16(A) && aligned16(B) && aligned16(C) &&
+    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
     const int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, dtype, units, b_trans);
@@ -288,7 +286,7 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
                      float* workspace, float* part, hipStream_t st, bool b_trans, int64_t ldb = 0)
 {
     const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits, small_tile, b_trans,
-                                  ldb, true);
+                                  ldb);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -357,28 +355,24 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
 
 // Zero-padded copies of the operands of a packed problem (see pack_dims), in the pack pool of the
 // stream: A' [batch][M][d.k] when K is ragged or A misaligned, B' [batch][d.k][d.ldb] (or
-// Bt' [batch][d.n][d.k]) likewise, and for a cropped output a bias of d.n values and the wider C'.
-struct PackedOperands { const void* A; const void* B; const float* bias; void* C; };
+// Bt' [batch][N][d.k]) when K or its rows are ragged or B misaligned.
+struct PackedOperands { const void* A; const void* B; };
 
-int pack_operands(const PackDims& d, const void* A, const void* B, const float* bias, void* C, int64_t M, int64_t N,
-                  int64_t K, int64_t batch, int dtype, bool b_trans, hipStream_t st, PackedOperands* out)
+int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, int64_t N, int64_t K, int64_t batch,
+                  int dtype, bool b_trans, hipStream_t st, PackedOperands* out)
 {
     const size_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
     const bool pack_a = d.k != K || !aligned16(A);
-    // (a transposed B of a cropped output gets a zero row for the extra column)
-    const bool pack_b = d.k != K || (!b_trans && d.ldb != N) || (b_trans && d.crop) || !aligned16(B);
-    const int64_t b_rows = b_trans ? d.n : d.k;
-    const long double total = (long double)batch * M * d.k * es + (long double)batch * b_rows * d.ldb * es +
-                              (long double)batch * M * d.n * es + d.n * 4.0L;
+    const bool pack_b = d.k != K || (!b_trans && d.ldb != N) || !aligned16(B);
+    const int64_t b_rows = b_trans ? N : d.k;
+    const long double total = (long double)batch * M * d.k * es + (long double)batch * b_rows * d.ldb * es;
     if (total >= 4.0e12L) return PGK_ERR_UNSUPPORTED;
     const size_t a_bytes = pack_a ? round_up256((size_t)batch * (size_t)M * (size_t)d.k * es) : 0;
     const size_t b_bytes = pack_b ? round_up256((size_t)batch * (size_t)b_rows * (size_t)d.ldb * es) : 0;
-    const size_t bias_bytes = (d.crop && bias) ? round_up256((size_t)d.n * 4) : 0;
-    const size_t c_bytes = d.crop ? round_up256((size_t)batch * (size_t)M * (size_t)d.n * es) : 0;
     float* buf = nullptr;
-    if (scratch_get(st, a_bytes + b_bytes + bias_bytes + c_bytes + 256, &buf, true) != hipSuccess) return PGK_ERR_HIP;
+    if (scratch_get(st, a_bytes + b_bytes + 256, &buf, true) != hipSuccess) return PGK_ERR_HIP;
     char* p = reinterpret_cast<char*>(buf);
-    *out = PackedOperands{A, B, bias, C};
+    *out = PackedOperands{A, B};
     hipError_t e = hipSuccess;
     if (pack_a) {
         e = pgk::launch_pad_matrix(A, p, batch, (int)M, (int)K, (int)M, (int)d.k, dtype, st);
@@ -386,17 +380,11 @@ int pack_operands(const PackDims& d, const void* A, const void* B, const float* 
         out->A = p; p += a_bytes;
     }
     if (pack_b) {
-        e = b_trans ? pgk::launch_pad_matrix(B, p, batch, (int)N, (int)K, (int)d.n, (int)d.k, dtype, st)
+        e = b_trans ? pgk::launch_pad_matrix(B, p, batch, (int)N, (int)K, (int)N, (int)d.k, dtype, st)
                     : pgk::launch_pad_matrix(B, p, batch, (int)K, (int)N, (int)d.k, (int)d.ldb, dtype, st);
         if (e != hipSuccess) return PGK_ERR_HIP;
-        out->B = p; p += b_bytes;
+        out->B = p;
     }
-    if (bias_bytes) {
-        e = pgk::launch_pad_vector(bias, reinterpret_cast<float*>(p), (int)N, (int)d.n, st);
-        if (e != hipSuccess) return PGK_ERR_HIP;
-        out->bias = reinterpret_cast<float*>(p); p += bias_bytes;
-    }
-    if (d.crop) out->C = p;
     return PGK_OK;
 }
 
@@ -410,15 +398,13 @@ int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, fl
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans, false);
+    const PackDims d = pack_dims(M, N, K, dtype, b_trans);
     if (!d.pack || !aligned16(C) || !aligned16(bias))
         return gemm_fused_core(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, st, b_trans, 0);
     PackedOperands pk{};
-    rc = pack_operands(d, A, B, bias, C, M, N, K, batch, dtype, b_trans, st, &pk);
+    rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
-    rc = gemm_fused_core(pk.A, pk.B, pk.bias, pk.C, rowsum, M, d.n, d.k, batch, act, dtype, st, b_trans, d.ldb);
-    if (rc != PGK_OK || !d.crop) return rc;
-    return pgk::launch_crop_matrix(pk.C, C, batch * M, (int)N, (int)d.n, dtype, st) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+    return gemm_fused_core(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, st, b_trans, d.ldb);
 }
 
 int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
@@ -500,15 +486,15 @@ int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int
     const void* ok = reinterpret_cast<const void*>(uintptr_t{256});   // stands for any 16-byte aligned pointer
     const int rc = validate_common(ok, ok, ok, M, N, K, batch, PGK_ACT_NONE, dtype);
     if (rc != PGK_OK) return rc;
-    const PackDims d = pack_dims(M, N, K, dtype, b_transposed != 0, false);      // as pgk_gemm_fused sees the problem
-    N = d.n; K = d.k;
+    const PackDims d = pack_dims(M, N, K, dtype, b_transposed != 0);      // as pgk_gemm_fused sees the problem
+    K = d.k;
     const FusedPlan fp = plan_fused(ok, ok, nullptr, ok, M, N, K, batch, dtype, b_transposed != 0, d.ldb);
     Path path = fp.path;
     int slices = 1;
     if (fp.split) {
         slices = fp.slices.splits;
         path = choose_path(ok, ok, nullptr, ok, ok, M, N, K, dtype, batch * slices, fp.split_small_tile, b_transposed != 0,
-                           d.ldb, true);
+                           d.ldb);
     }
     const long double wgs = (long double)((M + path.tile.bm - 1) / path.tile.bm) * ((N + path.tile.bn - 1) / path.tile.bn) *
                             batch * slices;
@@ -561,14 +547,13 @@ int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, f
     if (part_bytes && scratch_get(st, part_bytes, &part) != hipSuccess) return PGK_ERR_HIP;
     // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
     const int small_tile = (splits == 0 && mfma_route(M, N, K, dtype)) ? (int)auto_split(M, N, K, batch, dtype).small_tile : -1;
-    // (the partial products are fp32, so an odd N needs no wider output here; the slices are
-    // counted in K steps, which padding K to whole chunks leaves as they are)
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans, true);
+    // (the slices are counted in K steps, which padding K to whole chunks leaves as they are)
+    const PackDims d = pack_dims(M, N, K, dtype, b_trans);
     if (!d.pack)
         return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile,
                                 static_cast<float*>(workspace), part, st, b_trans);
     PackedOperands pk{};
-    rc = pack_operands(d, A, B, bias, C, M, N, K, batch, dtype, b_trans, st, &pk);
+    rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
     return run_split_passes(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, plan, small_tile,
                             static_cast<float*>(workspace), part, st, b_trans, d.ldb);

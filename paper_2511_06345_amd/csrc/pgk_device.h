@@ -19,6 +19,10 @@ typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+// the same 16 bytes at an address that is only aligned to a 2- or 4-byte element (global memory
+// takes multi-dword accesses at any alignment)
+typedef u32x4 u32x4_align2 __attribute__((aligned(2)));
+typedef u32x4 u32x4_align4 __attribute__((aligned(4)));
 
 #define PGK_LDS(p) ((__attribute__((address_space(3))) void*)(p))
 #define PGK_GLB(p) ((const __attribute__((address_space(1))) void*)(p))

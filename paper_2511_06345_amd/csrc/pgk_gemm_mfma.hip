@@ -200,8 +200,9 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
     }
     __builtin_amdgcn_sched_barrier(0);
     // N need not be a multiple of the 16-byte chunk: the row's last chunk may hold fewer
-    // elements, which are then stored one by one (rows start on 4-byte boundaries at least,
-    // which is all a multi-dword store needs)
+    // elements, which are then stored one by one, and rows start on element boundaries only
+    // (the 16-byte stores are declared with that alignment; global memory takes them as they are)
+    using chunk_at_element = typename std::conditional<OUT_BF16, u32x4_align2, u32x4_align4>::type;
     constexpr int EPC = 16 / (OUT_BF16 ? 2 : 4);
     const int left = n_rem - c * EPC;                  // elements of this chunk that exist
 #pragma unroll
@@ -210,8 +211,8 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
         if (row >= m_rem || left <= 0) continue;
         unsigned char* at = out_tile + (size_t)row * ld_bytes + (size_t)c * 16;
         if (left >= EPC) {
-            if constexpr (STREAM) __builtin_nontemporal_store(v[it], (u32x4*)at);
-            else *(u32x4*)at = v[it];
+            if constexpr (STREAM) __builtin_nontemporal_store(v[it], (chunk_at_element*)at);
+            else *(chunk_at_element*)at = v[it];
         } else {
 #pragma unroll
             for (int e = 0; e < EPC - 1; ++e) {
@@ -726,7 +727,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                         f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
                         if (wm * Cfg::WM + 32 * i + l32 < m_rem) {
                             if (n + 4 <= n_rem) {
-                                *(f32x4*)((float*)w + row_off + n) = o;
+                                typedef f32x4 f32x4_at_element __attribute__((aligned(4)));   // rows of any N
+                                *(f32x4_at_element*)((float*)w + row_off + n) = o;
                             } else {
 #pragma unroll
                                 for (int e = 0; e < 3; ++e)

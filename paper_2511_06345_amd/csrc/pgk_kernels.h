@@ -152,12 +152,9 @@ hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int 
 constexpr int kMaxTableTaps = 32;
 
 // Operand packing (pgk_pack.hip): dst[b][r][c] = src[b][r][c] inside the source, else 0 (dst rows of
-// cols_dst elements, a multiple of the 16-byte chunk); dst[i] = src[i] (0 for i >= n or src == nullptr);
-// dst[row][c] = src[row][c], c < cols, from rows of cols_src elements.
+// cols_dst elements, a multiple of the 16-byte chunk).
 hipError_t launch_pad_matrix(const void* src, void* dst, long long batch, int rows_src, int cols_src, int rows_dst,
                              int cols_dst, int dtype, hipStream_t s);
-hipError_t launch_pad_vector(const float* src, float* dst, int n, int n_dst, hipStream_t s);
-hipError_t launch_crop_matrix(const void* src, void* dst, long long rows, int cols, int cols_src, int dtype, hipStream_t s);
 
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming

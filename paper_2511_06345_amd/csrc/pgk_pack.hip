@@ -1,10 +1,11 @@
-// Operand packing for GEMM shapes whose rows are not a whole number of 16-byte chunks
-// (K or N not a multiple of 4 fp32 / 8 bf16 elements).  The matrix-core kernels copy operand
-// tiles in 16-byte pieces, so such operands are first copied into buffers whose rows are padded
-// with zeros to the next chunk (zeros add nothing to the products); an output whose rows would
-// not even start on 4-byte boundaries (bf16, odd N) is computed one column wider and cropped.
-// Streaming copies, a small fraction of the GEMM they make possible.
+// Operand packing for GEMM shapes whose operand rows are not a whole number of 16-byte chunks
+// (K, or the N of a plain B, not a multiple of 4 fp32 / 8 bf16 elements).  The matrix-core
+// kernels copy operand tiles in 16-byte pieces, so such operands are first copied into buffers
+// whose rows are padded with zeros to the next chunk (zeros add nothing to the products).
+// A streaming copy, a small fraction of the GEMM it makes possible.
 #include <hip/hip_runtime.h>
+
+#include <type_traits>
 
 #include "pgk_device.h"
 #include "pgk_kernels.h"
@@ -29,31 +30,20 @@ __global__ __launch_bounds__(256) void pad_matrix_kernel(const T* __restrict__ s
     const long long b = row / rows_dst;
     const int r = (int)(row - b * rows_dst);
     const T* s = src + ((size_t)b * (size_t)rows_src + (size_t)(r < rows_src ? r : 0)) * (size_t)cols_src;
-    T v[EPC];
+    u32x4 out = {0u, 0u, 0u, 0u};
+    if (r < rows_src) {
+        if (c0 + EPC <= cols_src) {
+            // a whole chunk of the source row: one 16-byte load from an element-aligned address
+            using chunk_at_element = typename std::conditional<sizeof(T) == 2, u32x4_align2, u32x4_align4>::type;
+            out = *(const chunk_at_element*)(s + c0);
+        } else {
+            T v[EPC];
 #pragma unroll
-    for (int e = 0; e < EPC; ++e) v[e] = (r < rows_src && c0 + e < cols_src) ? s[c0 + e] : T(0);
-    u32x4 out;
-    __builtin_memcpy(&out, v, 16);
+            for (int e = 0; e < EPC; ++e) v[e] = c0 + e < cols_src ? s[c0 + e] : T(0);
+            __builtin_memcpy(&out, v, 16);
+        }
+    }
     *(u32x4*)(dst + (size_t)row * (size_t)cols_dst + c0) = out;
-}
-
-// dst[i] = i < n ? src[i] : 0 for i < n_dst
-__global__ __launch_bounds__(256) void pad_vector_kernel(const float* __restrict__ src, float* __restrict__ dst, int n, int n_dst)
-{
-    const int i = blockIdx.x * 256 + threadIdx.x;
-    if (i < n_dst) dst[i] = (src && i < n) ? src[i] : 0.0f;
-}
-
-// dst[row][c] = src[row][c] for c < cols (dst rows of cols elements, src rows of cols_src)
-template <typename T>
-__global__ __launch_bounds__(256) void crop_matrix_kernel(const T* __restrict__ src, T* __restrict__ dst, long long rows,
-                                                          int cols, int cols_src)
-{
-    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (t >= rows * cols) return;
-    const long long row = t / cols;
-    const int c = (int)(t - row * cols);
-    dst[t] = src[(size_t)row * (size_t)cols_src + c];
 }
 
 }  // namespace
@@ -72,26 +62,6 @@ hipError_t launch_pad_matrix(const void* src, void* dst, long long batch, int ro
     else
         hipLaunchKernelGGL(pad_matrix_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)src, (float*)dst,
                            batch, rows_src, cols_src, rows_dst, cols_dst, chunks);
-    return hipGetLastError();
-}
-
-hipError_t launch_pad_vector(const float* src, float* dst, int n, int n_dst, hipStream_t s)
-{
-    if (n_dst <= 0) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(pad_vector_kernel, dim3((unsigned int)((n_dst + 255) / 256)), dim3(256), 0, s, src, dst, n, n_dst);
-    return hipGetLastError();
-}
-
-hipError_t launch_crop_matrix(const void* src, void* dst, long long rows, int cols, int cols_src, int dtype, hipStream_t s)
-{
-    const long long blocks = (rows * cols + 255) / 256;
-    if (blocks <= 0 || blocks > 0x7fffffffLL || cols_src < cols) return hipErrorInvalidValue;
-    if (dtype == DT_BF16)
-        hipLaunchKernelGGL(crop_matrix_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)src, (unsigned short*)dst, rows, cols, cols_src);
-    else
-        hipLaunchKernelGGL(crop_matrix_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)src, (float*)dst,
-                           rows, cols, cols_src);
     return hipGetLastError();
 }
 

@@ -138,8 +138,9 @@ def test_tile_table_and_split_rule(lib):
     # a few rows: small tiles, K in slices
     expect((8, 4096, 4096, 1), BF16, (128, 128, 64), 4, 128)
     expect((1, 4096, 4096, 1), F32, (64, 64, 32), 8, 512)
+    expect((12, 12, 100000, 1), BF16, (128, 128, 64), 32, 32)          # a tiny output with a long K as well
     # an output below 16 x 16, or too little work to copy operands for: bounds-checked kernel
-    expect((12, 12, 100000, 1), BF16, (64, 64, 16), 1, 1, matrix_core=False)
+    expect((12, 12, 1000, 1), BF16, (64, 64, 16), 1, 1, matrix_core=False)
     expect((2, 300, 5, 1), BF16, (64, 64, 16), 1, 5, matrix_core=False)
     expect((5, 7, 33, 2), F32, (64, 64, 16), 1, 2, matrix_core=False)
     # ragged everything on the matrix cores

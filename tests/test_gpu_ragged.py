@@ -1,9 +1,9 @@
 """GPU parity for GEMM shapes off the 16-byte grid and for very few rows: K or N not a multiple
-of 4 (fp32) / 8 (bf16) elements -- the library copies the operands into zero-padded buffers and
-runs the matrix-core kernels on those; a bf16 output with an odd N is computed one column wider
-and cropped -- and M below 16.  Every call (fused, split, either layout of B), integer-valued
-inputs exactly, random ones within 1e-4 (fp32) / 2e-2 (bf16), what lies behind the outputs
-untouched.
+of 4 (fp32) / 8 (bf16) elements -- the library copies the operands whose rows are not whole
+16-byte chunks into zero-padded buffers and runs the matrix-core kernels on those, which store
+output rows of any length -- and M below 16.  Every call (fused, split, either layout of B),
+integer-valued inputs exactly, random ones within 1e-4 (fp32) / 2e-2 (bf16), what lies around the
+output untouched.
 """
 import numpy as np
 import pytest
@@ -17,10 +17,11 @@ F32, BF16 = gen.F32, gen.BF16
 CALLS = ["fused", "fused_bt", "splitk", "splitk_bt"]
 
 # (M, N, K, batch): ragged K, ragged even N, odd N, both, few rows, a partial last K tile on top,
-# several tiles each way, a long K that the fused call splits by itself
+# several tiles each way, a long K that the fused call splits by itself, outputs below 16 x 16
+# with a long K
 SHAPES = [(128, 128, 68, 1), (128, 132, 64, 1), (200, 301, 64, 2), (130, 250, 77, 3), (1, 512, 515, 1),
           (8, 1024, 1024, 1), (15, 260, 130, 2), (300, 1030, 129, 1), (640, 515, 70, 1), (64, 101, 4099, 1),
-          (3, 17, 8200, 2), (513, 258, 1026, 1)]
+          (3, 17, 8200, 2), (513, 258, 1026, 1), (12, 12, 20000, 1), (8, 8, 1024, 3), (5, 3, 40002, 2)]
 
 
 @pytest.fixture(scope="module")
