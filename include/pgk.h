@@ -68,15 +68,15 @@ typedef enum {
  * with the activation and reduction operators fused into its epilogue).
  *
  * M, N, K, batch > 0.  Any shape is accepted; M, N and K need not be tile multiples.
- * The matrix-core kernels read operands whose rows are whole 16-byte chunks (K, and for B
- * as [K][N] also N, a multiple of 4 float32 / 8 bfloat16 elements) in place.  Operands
- * with other row lengths are first copied into zero-padded buffers of the library (a
- * second per-(device, stream) pool, sized batch*(M*K' + K'*N') elements with K', N' the
- * next multiples; allocation, reuse and release as for the scratch buffer below) when the
- * problem has at least 64^3 multiply-adds.  C, bias and rowsum are always used in place,
- * whatever N is.  What is left for a slower, bounds-checked kernel: smaller problems off
- * the chunk grid, outputs below 16 x 16 with K below 1024, and calls whose C or bias (or,
- * with rows on the chunk grid, A or B) pointer is not 16-byte aligned.
+ * The matrix-core kernels read operands in place when their rows start on 4-byte boundaries
+ * (float32 always; bfloat16 when K -- and, for B as [K][N], N -- is even).  Otherwise the
+ * operands are first copied into buffers of the library with rows padded with zeros to
+ * whole 16-byte chunks (a second per-(device, stream) pool of up to batch*(M*K' + K'*N')
+ * elements, K' and N' the next multiples of 8; allocation, reuse and release as for the
+ * scratch buffer below) when the problem has at least 64^3 multiply-adds.  C, bias and
+ * rowsum are always used in place, whatever N is.  What is left for a slower,
+ * bounds-checked kernel: smaller problems with such rows, outputs below 16 x 16 with K
+ * below 1024, and calls with a pointer that is not 16-byte aligned.
  * M, N, K must each be below 2^31 and batch*M*N, batch*M*K, batch*K*N below 2^62 (else
  * PGK_ERR_UNSUPPORTED).
  *
@@ -129,8 +129,8 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
  * and rowsum, ownership, the scratch buffer, the split rule, the workspace size
  * (pgk_splitk_workspace_bytes does not depend on the layout of B) and the errors are as
  * for pgk_gemm_fused / pgk_gemm_splitk.  The matrix-core kernels read Bt in place -- no
- * transposed copy is made -- when K is a multiple of the 16-byte chunk, whatever N is;
- * otherwise A and Bt are copied with K padded, as described there.
+ * transposed copy is made -- when its rows start on 4-byte boundaries (float32, or an even
+ * K), whatever N is; otherwise A and Bt are copied with K padded, as described there.
  */
 int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
                       int64_t M, int64_t N, int64_t K, int64_t batch,

@@ -50,17 +50,18 @@ size_t round_up256(size_t v) { return (v + 255) / 256 * 256; }
 int64_t chunk_elems(int dtype) { return dtype == PGK_DTYPE_BF16 ? 8 : 4; }
 int64_t round_up64(int64_t v, int64_t a) { return (v + a - 1) / a * a; }
 
-// What the matrix-core kernels take as it is: operand rows that are whole 16-byte chunks (K for
-// A and a transposed B; the row length ldb of a plain B, which is N unless the caller has padded
-// it).  M, N and K need not be tile multiples, and the output rows may have any length.  An
+// What the matrix-core kernels take as it is: operand rows that start on 4-byte boundaries (K
+// elements for A and a transposed B; the row length ldb of a plain B, which is N unless the
+// caller has padded it).  M, N and K need not be tile multiples, and the output rows may have any
+// length.  An
 // output below 16 x 16 is left to the bounds-checked kernel, which wastes less, unless K is
 // long (then the matrix-core route splits the K range over the chip).
 bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = false, int64_t ldb = 0)
 {
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
-    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = chunk_elems(dtype);
+    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
     if (!ldb) ldb = b_trans ? K : N;
-    if (K % epc || ldb % epc) return false;
+    if ((K * es) % 4 || (ldb * es) % 4) return false;
     if (M < 16 && N < 16 && K < 1024) return false;
     // per-lane 32-bit byte offsets inside one tile
     if ((int64_t)t.bm * K * es >= (1LL << 32)) return false;
@@ -68,16 +69,17 @@ bool mfma_shape_ok(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans = fa
     return true;
 }
 
-// K off the 16-byte grid, or the rows of a plain B: the operands are first copied into
-// zero-padded buffers.  Worth it from about 64^3 multiply-adds on.
+// Operand rows that would start off 4-byte boundaries (bf16: an odd K, or an odd N for a plain
+// B): the operands are first copied into buffers with rows padded with zeros to whole 16-byte
+// chunks.  Worth it from about 64^3 multiply-adds on.
 bool needs_packing(int64_t N, int64_t K, int dtype, bool b_trans)
 {
-    const int64_t epc = chunk_elems(dtype);
-    return K % epc != 0 || (!b_trans && N % epc != 0);
+    const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
+    return (K * es) % 4 != 0 || (!b_trans && (N * es) % 4 != 0);
 }
 
-// The dimensions the kernels see for a problem that is packed first: K and the row length of B
-// rounded up to whole chunks.  pack = false: the problem is taken as it is (aligned already, or
+// The dimensions the kernels see for a problem that is packed first: K and the row length of B,
+// rounded up to whole chunks where they are odd.  pack = false: the problem is taken as it is (aligned already, or
 // too small or too large for this to pay).
 struct PackDims { bool pack; int64_t k, ldb; };
 
@@ -86,9 +88,9 @@ PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans)
     const PackDims as_is{false, K, 0};
     if (!needs_packing(N, K, dtype, b_trans)) return as_is;
     if ((long double)M * N * K < 262144.0L) return as_is;
-    const int64_t epc = chunk_elems(dtype);
-    PackDims d{true, round_up64(K, epc), 0};
-    d.ldb = b_trans ? d.k : round_up64(N, epc);
+    const int64_t epc = chunk_elems(dtype), es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
+    PackDims d{true, (K * es) % 4 ? round_up64(K, epc) : K, 0};
+    d.ldb = b_trans ? d.k : round_up64(N, epc);      // (a plain B is copied in every such case)
     if (d.k > kMaxDim || d.ldb > kMaxDim) return as_is;
     if (!mfma_shape_ok(M, N, d.k, dtype, b_trans, d.ldb)) return as_is;
     return d;
@@ -278,6 +280,12 @@ void set_ldb(GemmArgs& a, int64_t ldb)
     a.b_batch_stride = (long long)(a.b_trans ? a.N : a.K) * ldb;
 }
 
+// call when the views are final: the rows of a plain B that are not whole chunks
+void mark_ragged_rows(GemmArgs& a, int dtype)
+{
+    a.b_tail_bounded = (!a.b_trans && a.ldb % chunk_elems(dtype) != 0) ? 1 : 0;
+}
+
 // The two passes of the split-K path.  `workspace`: batch * plan.splits * M * N floats;
 // `part`: batch * nseg * M floats when rowsum != nullptr and the second pass uses nseg > 1
 // column segments (nseg from splitk_reduce_segments), else unused.
@@ -298,6 +306,7 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
     pgk::fill_plain_views(a);
     if (b_trans) pgk::set_b_transposed(a);
     if (ldb) set_ldb(a, ldb);
+    mark_ragged_rows(a, dtype);
     a.act = PGK_ACT_NONE; a.splits = plan.splits; a.k_slice = plan.k_slice;
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
@@ -431,6 +440,7 @@ int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, fl
     pgk::fill_plain_views(a);
     if (b_trans) pgk::set_b_transposed(a);
     if (ldb) set_ldb(a, ldb);
+    mark_ragged_rows(a, dtype);
     a.act = act; a.splits = 1;
     a.k_slice = (int)(((K + path.tile.bk - 1) / path.tile.bk) * path.tile.bk);
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;

@@ -263,11 +263,14 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const int sp = (int)(z - (unsigned int)b * (unsigned int)p.splits);
     const int k_begin = sp * p.k_slice;
     const int k_end = (k_begin + p.k_slice < p.K) ? (k_begin + p.k_slice) : p.K;
-    // K tiles of this slice; the last one may be partial (K need not be a multiple of BK,
-    // only of the 16-byte chunk): k_last of its BK columns exist
+    // K tiles of this slice; the last one may be partial (K need not be a multiple of BK, nor
+    // of the 16-byte chunk: operand rows only have to start on 4-byte boundaries): k_last of
+    // its BK columns exist
     const int KT = (k_end - k_begin + BK - 1) / BK;
     const int k_last = (k_end - k_begin) - (KT - 1) * BK;
-    const bool k_partial = k_last < BK;
+    // (a last tile that is full is treated the same way when the rows of a plain B are not
+    // whole chunks: the copy of its last row must end where the array ends)
+    const bool k_partial = k_last < BK || p.b_tail_bounded;
 
     const unsigned char* Ag = (const unsigned char*)p.A +
         ((size_t)b * (size_t)p.a_batch_stride + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
@@ -338,9 +341,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         } else {
             const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
             const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
-            // likewise column chunks past the end of B.  (When N is not a multiple of the 16-byte
-            // chunk the caller hands over a B whose rows are padded to one, so the row's last,
-            // partly filled chunk can be read whole.)
+            // likewise column chunks past the end of B.  (When the rows are not whole 16-byte
+            // chunks, the row's last, partly filled chunk is read together with the start of the
+            // next row, which only feeds output columns that do not exist; at the end of the
+            // array the buffer resource cuts it off.)
             constexpr int EPC = 16 / ES;                      // elements per chunk
             const int cg = c * EPC < n_rem ? c : (n_rem + EPC - 1) / EPC - 1;
             voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
@@ -408,25 +412,39 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         for (int t = 0; t < Cfg::B_CPW; ++t) copy_b_op(kt, st, t, k_partial && kt == KT - 1);
     };
     // The columns of a partial last K tile that do not exist: the copy has put whatever
-    // follows the row in memory there (A chunks at or beyond k_last, B rows at or beyond
-    // k_last).  Each lane clears the 16-byte pieces it copied itself; call after the wait
-    // for the copies and before the barrier that publishes the tile.
+    // follows the row in memory there (A elements at or beyond k_last, B rows at or beyond
+    // k_last).  Each lane clears them in the 16-byte pieces it copied itself -- a whole piece,
+    // or the upper elements of the piece that k_last falls into; call after the wait for the
+    // copies and before the barrier that publishes the tile.
+    auto clear_from = [&](unsigned char* piece, int keep) __attribute__((always_inline)) {   // keep: elements that stay
+        constexpr int EPC = 16 / ES;
+        auto* q = (__attribute__((address_space(3))) u32x4*)PGK_LDS(piece);
+        if (keep <= 0) {
+            const u32x4 zero = {0u, 0u, 0u, 0u};
+            *q = zero;
+        } else if (keep < EPC) {
+            u32x4 v = *q;
+            const int keep_bytes = keep * ES;
+#pragma unroll
+            for (int d = 0; d < 4; ++d)
+                v[d] &= keep_bytes >= 4 * d + 4 ? 0xffffffffu : keep_bytes <= 4 * d ? 0u : 0x0000ffffu;
+            *q = v;
+        }
+    };
     auto zero_k_tail = [&](auto sta, auto stb) __attribute__((always_inline)) {
         constexpr int EPC = 16 / ES;
-        const u32x4 zero = {0u, 0u, 0u, 0u};
 #pragma unroll
         for (int t = 0; t < Cfg::A_CPW; ++t) {
             const int r = (wave * Cfg::A_CPW + t) * Cfg::A_RPC + lane / Cfg::A_CPR;
             const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
-            if (c * EPC >= k_last)
-                *(__attribute__((address_space(3))) u32x4*)PGK_LDS(lds_a(sta) + wave * (Cfg::A_CPW * 1024) + t * 1024 + lane * 16) = zero;
+            clear_from(lds_a(sta) + wave * (Cfg::A_CPW * 1024) + t * 1024 + lane * 16, k_last - c * EPC);
         }
 #pragma unroll
         for (int t = 0; t < Cfg::B_CPW; ++t) {
             const int kr = (wave * Cfg::B_CPW + t) * Cfg::B_RPC + lane / Cfg::B_CPR;
             const int cb = (lane % Cfg::B_CPR) ^ swz_a<Cfg::B_CPR>(kr);   // transposed B: kr is a tile column
-            if (Cfg::BT ? cb * EPC >= k_last : kr >= k_last)
-                *(__attribute__((address_space(3))) u32x4*)PGK_LDS(lds_b(stb) + wave * (Cfg::B_CPW * 1024) + t * 1024 + lane * 16) = zero;
+            clear_from(lds_b(stb) + wave * (Cfg::B_CPW * 1024) + t * 1024 + lane * 16,
+                       Cfg::BT ? k_last - cb * EPC : (kr >= k_last ? 0 : EPC));
         }
     };
 

@@ -33,6 +33,7 @@ struct GemmArgs {
     long long a_batch_stride, b_batch_stride;   // elements between batch entries of A and of B
     int ldb;                 // elements between rows of B
     int b_trans;             // 1: B is given transposed, [batch][N][ldb >= K], K contiguous
+    int b_tail_bounded;      // 1: rows of a plain B are not whole 16-byte chunks: the copies of the last K tile stop at the end of B
     int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
     // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
@@ -69,6 +70,7 @@ inline void fill_plain_views(GemmArgs& a)
     a.b_batch_stride = (long long)a.K * a.N;
     a.ldb = a.N;
     a.b_trans = 0;
+    a.b_tail_bounded = 0;
     a.bias_per_row = 0;
     a.b_tiles_per_tap = 0x7fffffff;
     a.b_tap_step = 0;

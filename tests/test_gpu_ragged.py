@@ -118,3 +118,39 @@ def test_vocabulary_sized_output_sampled_rows(pgk, oracle, dtype):
         assert e <= TOL[dtype], f"dtype {dtype} {M}x{N}x{K}: C error {e:.3e}"
         e = rel_err(got_rs[:, sel], ref_rs)
         assert e <= TOL[dtype], f"dtype {dtype} {M}x{N}x{K}: rowsum error {e:.3e}"
+
+
+@pytest.mark.parametrize("dtype", [F32, BF16])
+@pytest.mark.parametrize("call", CALLS)
+@pytest.mark.parametrize("shape", [(130, 250, 78, 2), (64, 130, 4100, 1), (257, 66, 322, 3), (300, 258, 64, 1)])
+def test_rows_read_in_place_ignore_their_surroundings(pgk, oracle, dtype, call, shape):
+    """Rows that start on 4-byte boundaries but are not whole 16-byte chunks are read where they
+    are: the last chunk of a row runs into the next row and, at the end of an operand, into
+    whatever follows it in memory.  With NaNs right before and after A and B the result must
+    still be exact (integer-valued inputs), down to the last row and column."""
+    import torch
+    M, N, K, batch = shape
+    A, B = gen.make_int_inputs(dtype, M, N, K, batch, seed=500 + M)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, None, gen.ACT_NONE)
+    if dtype == BF16:
+        ref_c = gen.bf16_bits_to_f32(gen.f32_to_bf16_bits(ref_c.astype(np.float32))).astype(np.float64)
+    bt = call.endswith("_bt")
+    if bt:
+        B = np.ascontiguousarray(np.swapaxes(B, 1, 2))
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+
+    def inside_nans(arr):
+        t = to_device(arr, dtype)
+        flat = torch.full((t.numel() + 128,), float("nan"), dtype=tdt, device="cuda")
+        flat[64:64 + t.numel()] = t.reshape(-1)
+        return flat[64:64 + t.numel()].view(t.shape)
+
+    dA, dB = inside_nans(A), inside_nans(B)
+    if call.startswith("fused"):
+        C, rs = pgk.gemm_fused(dA, dB, None, gen.ACT_NONE, rowsum=True, b_transposed=bt)
+    else:
+        C, rs = pgk.gemm_splitk(dA, dB, None, gen.ACT_NONE, splits=2, rowsum=True, b_transposed=bt)
+    torch.cuda.synchronize()
+    got_c, got_rs = c_to_numpy(C, dtype), rs.cpu().numpy().astype(np.float64)
+    assert np.array_equal(got_c, ref_c), f"dtype {dtype} {shape} {call}: C"
+    assert np.array_equal(got_rs, ref_rs), f"dtype {dtype} {shape} {call}: rowsum"
