@@ -3,6 +3,7 @@
 // The contract of every entry point is documented in include/pgk.h.
 #include <hip/hip_runtime.h>
 
+#include <cmath>
 #include <map>
 #include <mutex>
 #include <utility>
@@ -248,17 +249,62 @@ int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
     return -1;
 }
 
+// How long a grid of one tile shape takes, in rounds: the chip runs per_cu workgroups per CU
+// side by side, a full round of them takes fixed + per_k * K / 1024 (microseconds on the
+// measured part; only ratios between shapes are used), and a last, partly filled round with j
+// workgroups on its busiest CU takes the share tail[j - 1] of a full one.  Fitted to GEMMs of
+// 2560^2 ... 8192^2 outputs with K = 1024 ... 4096 (e.g. bf16 4096^2 x 4096: 256 large tiles 104 us,
+// 1024 small ones 122 us, 512 half tiles 114 us; fp32: 1024 large 913 us, 4096 small 965 us).
+struct TileCost { int per_cu; double fixed, per_k; double tail[4]; };
+
+TileCost tile_cost(int dtype, int kind)
+{
+    if (dtype == PGK_DTYPE_BF16) {
+        switch (kind) {
+        case pgk::TILE_SMALL: return {2, 2.9, 14.3, {0.47, 1.0, 1.0, 1.0}};
+        case pgk::TILE_TALL: return {1, 5.8, 12.8, {0.65, 1.0, 1.0, 1.0}};
+        case pgk::TILE_WIDE: return {1, 5.7, 13.2, {0.65, 1.0, 1.0, 1.0}};
+        default: return {1, 10.0, 22.5, {0.7, 1.0, 1.0, 1.0}};
+        }
+    }
+    if (kind == pgk::TILE_SMALL) return {4, 1.5, 59.9, {0.3, 0.6, 0.75, 1.0}};
+    return {1, 3.0, 56.2, {1.0, 1.0, 1.0, 1.0}};
+}
+
+double estimated_rounds_time(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind)
+{
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
+    const TileCost c = tile_cost(dtype, kind);
+    const double wgs = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)units;
+    const double slots = (double)kNumCUs * c.per_cu;
+    const double full = std::floor(wgs / slots), rest = wgs - full * slots;
+    const int j = (int)std::ceil(rest / kNumCUs);
+    return (c.fixed + c.per_k * (double)K / 1024.0) * (full + (j > 0 ? c.tail[j - 1] : 0.0));
+}
+
 // The tile shape for an output of M x N with `units` workgroups per tile position (batch entries
 // x K splits): the small tile when three quarters of a large tile would be empty, else a half
 // tile when that saves a third of the padding, else the small tile when the large-tile grid would
-// leave a quarter of the CUs idle, else the large tile.
-int auto_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
+// leave a quarter of the CUs idle, else the large tile -- unless its grid ends in a poorly
+// filled round and the round model above gives another shape at least 6 % less time (K below
+// 1024: the model is not consulted).
+int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans)
 {
     if (large_tile_mostly_empty(M, N, dtype)) return pgk::TILE_SMALL;
     if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    return wgs < 0.75L * kNumCUs ? pgk::TILE_SMALL : pgk::TILE_LARGE;
+    if (wgs < 0.75L * kNumCUs) return pgk::TILE_SMALL;
+    int best = pgk::TILE_LARGE;
+    if (K >= 1024 && wgs > kNumCUs) {      // (the fit does not hold for short K, where the epilogues weigh more)
+        double best_time = 0.94 * estimated_rounds_time(M, N, K, dtype, units, pgk::TILE_LARGE);
+        for (int kind : {pgk::TILE_SMALL, pgk::TILE_TALL, pgk::TILE_WIDE}) {
+            if (!pgk::mfma_has_tile(dtype, kind, b_trans)) continue;
+            const double t = estimated_rounds_time(M, N, K, dtype, units, kind);
+            if (t < best_time) { best_time = t; best = kind; }
+        }
+    }
+    return best;
 }
 
 // kind_forced: -1 = auto_tile_kind, else the caller (an automatic split plan, a convolution plan) decides
@@ -269,7 +315,7 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
     const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
-    const int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, dtype, units, b_trans);
+    const int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
     return Path{true, kind, pgk::mfma_tile_shape(dtype, kind)};
 }
 
@@ -659,7 +705,7 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
     // what every matrix-core route needs: an output the kernels can store in 16-byte chunks
     if (Cout < 16 || pl.Lout < 16 || pl.Lout % epc != 0) return pl;
-    pl.kind = auto_tile_kind(Cout, pl.Lout, dtype, B, false);
+    pl.kind = auto_tile_kind(Cout, pl.Lout, 0, dtype, B, false);
     pl.tile = pgk::mfma_tile_shape(dtype, pl.kind);
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
     const bool shifts_even = dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1;

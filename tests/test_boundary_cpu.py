@@ -116,12 +116,19 @@ def test_tile_table_and_split_rule(lib):
     expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256)
     expect((128, 65536, 1024, 1), BF16, (128, 256, 64), 1, 256)
     expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256, bt=True)
-    expect((65536, 384, 1024, 1), BF16, (256, 256, 64), 1, 512)          # a quarter of padding: large tile stays
+    expect((65536, 384, 512, 1), BF16, (256, 256, 64), 1, 512)           # a quarter of padding: large tile stays
     expect((65536, 128, 1024, 1), F32, (128, 128, 32), 1, 512)
     # three quarters of a large tile empty, or a grid below 192 workgroups: small tile
     expect((64, 65536, 1024, 1), BF16, (128, 128, 64), 1, 512)
     expect((1024, 1024, 1024, 1), BF16, (128, 128, 64), 1, 64)
     expect((2048, 2048, 2048, 1), BF16, (128, 128, 64), 1, 256)
+    # a large-tile grid that ends in a poorly filled round, K from 1024 on: the shape the round model prefers
+    expect((4097, 4096, 4096, 1), BF16, (128, 128, 64), 1, 33 * 32)
+    expect((4608, 4608, 4096, 1), BF16, (256, 128, 64), 1, 18 * 36)
+    expect((4097, 4096, 4096, 1), F32, (64, 64, 32), 1, 65 * 64)
+    expect((3072, 3072, 4096, 1), F32, (64, 64, 32), 1, 48 * 48)
+    expect((5000, 4096, 4096, 1), F32, (128, 128, 32), 1, 40 * 32)
+    expect((4352, 4352, 512, 1), BF16, (256, 256, 64), 1, 17 * 17)
     # few tiles and a long K: slices of at least 16 K tiles, the fewest that give 512 workgroups
     expect((32, 8192, 8192, 1), BF16, (128, 128, 64), 8, 512)
     expect((1024, 1024, 8192, 1), BF16, (128, 128, 64), 8, 512)
@@ -130,11 +137,12 @@ def test_tile_table_and_split_rule(lib):
     # only the small-tile grid fills the chip: split from 512 K tiles on
     expect((2048, 2048, 16384, 1), BF16, (128, 128, 64), 1, 256)
     expect((2048, 2048, 65536, 1), BF16, (256, 256, 64), 8, 512)
-    # K or N off the 16-byte grid: the plan of the zero-padded copies (bf16 with an odd N: one column wider)
+    # K or N off the 16-byte grid: read in place, or the plan of the zero-padded copies (bf16, odd)
     expect((4096, 4096, 4098, 1), F32, (128, 128, 32), 1, 1024)
-    expect((4096, 4100, 4096, 1), BF16, (256, 256, 64), 1, 16 * 17)
-    expect((4096, 4101, 4096, 1), BF16, (256, 256, 64), 1, 16 * 17)
-    expect((4096, 4100, 4096, 1), F32, (128, 128, 32), 1, 32 * 33)
+    expect((4096, 4100, 4096, 1), BF16, (128, 128, 64), 1, 32 * 33)       # (17 tile columns of 256: poorly filled last round)
+    expect((4096, 4101, 4096, 1), BF16, (128, 128, 64), 1, 32 * 33)
+    expect((4096, 4100, 4096, 1), F32, (64, 64, 32), 1, 64 * 65)
+    expect((4096, 4101, 512, 1), BF16, (256, 256, 64), 1, 16 * 17)
     # a few rows: small tiles, K in slices
     expect((8, 4096, 4096, 1), BF16, (128, 128, 64), 4, 128)
     expect((1, 4096, 4096, 1), F32, (64, 64, 32), 8, 512)
