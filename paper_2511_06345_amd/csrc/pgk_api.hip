@@ -79,21 +79,38 @@ bool needs_packing(int64_t N, int64_t K, int dtype, bool b_trans)
     return (K * es) % 4 != 0 || (!b_trans && (N * es) % 4 != 0);
 }
 
+// Outputs with at most 32 columns or rows: the skinny tiles (narrow 128 x 32, flat 32 x 128), on
+// which such a product stays bound by the stream of its large operand instead of by matrix work
+// on padding (bf16 16384 x 16 x 16384: 137 us on 128 x 128 tiles).  The narrow tile exists for a
+// transposed B only; a plain B of so few columns is small and is transposed first (see route_for).
+// -1: not skinny.
+int skinny_tile_kind(int64_t M, int64_t N)
+{
+    if (M <= 32 && N > 32) return pgk::TILE_FLAT;
+    if (N <= 32 && M > 32) return pgk::TILE_NARROW;
+    if (M <= 32 && N <= 32) return pgk::TILE_FLAT;
+    return -1;
+}
+
 // The dimensions the kernels see for a problem that is packed first: K and the row length of B,
 // rounded up to whole chunks where they are odd.  pack = false: the problem is taken as it is (aligned already, or
 // too small or too large for this to pay).
-struct PackDims { bool pack; int64_t k, ldb; };
+// transpose_b: a plain B of at most 32 columns under more than 32 rows of output is copied in
+// transposed form, [N][k], for the narrow tile; the kernels then see a transposed B (b_trans).
+struct PackDims { bool pack; int64_t k, ldb; bool transpose_b; bool b_trans; };
 
 PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans)
 {
-    const PackDims as_is{false, K, 0};
-    if (!needs_packing(N, K, dtype, b_trans)) return as_is;
+    const PackDims as_is{false, K, 0, false, b_trans};
+    const bool transpose_b = !b_trans && skinny_tile_kind(M, N) == pgk::TILE_NARROW;
+    if (!transpose_b && !needs_packing(N, K, dtype, b_trans)) return as_is;
     if ((long double)M * N * K < 262144.0L) return as_is;
     const int64_t epc = chunk_elems(dtype), es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
-    PackDims d{true, (K * es) % 4 ? round_up64(K, epc) : K, 0};
-    d.ldb = b_trans ? d.k : round_up64(N, epc);      // (a plain B is copied in every such case)
+    PackDims d{true, (K * es) % 4 ? round_up64(K, epc) : K, 0, transpose_b, b_trans || transpose_b};
+    // (a plain B is copied in every such case; so is a B that is transposed, with rows of whole chunks)
+    d.ldb = transpose_b ? round_up64(d.k, epc) : d.b_trans ? d.k : round_up64(N, epc);
     if (d.k > kMaxDim || d.ldb > kMaxDim) return as_is;
-    if (!mfma_shape_ok(M, N, d.k, dtype, b_trans, d.ldb)) return as_is;
+    if (!mfma_shape_ok(M, N, d.k, dtype, d.b_trans, d.ldb)) return as_is;
     return d;
 }
 
@@ -117,9 +134,10 @@ bool large_tile_mostly_empty(int64_t M, int64_t N, int dtype)
 
 // Automatic choice (splits == 0): slices of at least kMinStepsPerSlice K steps (shorter ones
 // are all prologue and epilogue), at most kMaxAutoSplits of them, and the smallest count that
-// gives 2 x 256 workgroups.  The tile the count is made with: the large one if it can reach
-// 1.5 x 256 workgroups within those limits and is not mostly empty, else the small one.
-struct AutoPlan { int splits; bool small_tile; };
+// gives 2 x 256 workgroups.  The tile the count is made with: a skinny one for skinny outputs,
+// else the large one if it can reach 1.5 x 256 workgroups within those limits and is not mostly
+// empty, else the small one.
+struct AutoPlan { int splits; int kind; };
 
 AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
 {
@@ -128,15 +146,18 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
     int64_t s_max = ksteps / kMinStepsPerSlice;
     if (s_max < 1) s_max = 1;
     if (s_max > kMaxAutoSplits) s_max = kMaxAutoSplits;
-    auto tiles_of = [&](bool small) {
-        const pgk::TileShape t = pgk::mfma_tile_shape(dtype, small);
+    auto tiles_of = [&](int kind) {
+        const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
         return (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
     };
-    const bool small = large_tile_mostly_empty(M, N, dtype) || tiles_of(false) * s_max < 1.5L * kNumCUs;
-    const long double tiles = tiles_of(small);
+    int kind = skinny_tile_kind(M, N);
+    if (kind < 0)
+        kind = (large_tile_mostly_empty(M, N, dtype) || tiles_of(pgk::TILE_LARGE) * s_max < 1.5L * kNumCUs) ? pgk::TILE_SMALL
+                                                                                                          : pgk::TILE_LARGE;
+    const long double tiles = tiles_of(kind);
     int64_t s = 1;
     while (s < s_max && tiles * s < 2.0L * kNumCUs) ++s;
-    return {(int)s, small};
+    return {(int)s, kind};
 }
 
 SplitPlan plan_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
@@ -290,6 +311,8 @@ double estimated_rounds_time(int64_t M, int64_t N, int64_t K, int dtype, int64_t
 // 1024: the model is not consulted).
 int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans)
 {
+    // (K = 0: a convolution, which keeps to the shapes its operand views were written for)
+    if (const int skinny = skinny_tile_kind(M, N); K > 0 && skinny >= 0 && pgk::mfma_has_tile(dtype, skinny, b_trans)) return skinny;
     if (large_tile_mostly_empty(M, N, dtype)) return pgk::TILE_SMALL;
     if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
@@ -315,7 +338,8 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
     const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(C) &&
                     aligned16(bias) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
-    const int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
+    int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
+    if (!pgk::mfma_has_tile(dtype, kind, b_trans)) kind = pgk::TILE_SMALL;      // (the narrow tile with a plain B)
     return Path{true, kind, pgk::mfma_tile_shape(dtype, kind)};
 }
 
@@ -401,7 +425,7 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
     const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
     if (fp.path.mfma && (few_tiles || long_k)) {
         fp.slices = plan_splits(M, N, K, batch, dtype, 0);
-        fp.split_small_tile = (int)auto_split(M, N, K, batch, dtype).small_tile;
+        fp.split_small_tile = auto_split(M, N, K, batch, dtype).kind;
         const long double ws_bytes = (long double)batch * fp.slices.splits * M * N * sizeof(float);
         fp.split = fp.slices.splits > 1 && ws_bytes <= (long double)kAutoSplitMaxWorkspace;
     }
@@ -410,7 +434,8 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
 
 // Zero-padded copies of the operands of a packed problem (see pack_dims), in the pack pool of the
 // stream: A' [batch][M][d.k] when K is ragged or A misaligned, B' [batch][d.k][d.ldb] (or
-// Bt' [batch][N][d.k]) when K or its rows are ragged or B misaligned.
+// Bt' [batch][N][d.k]) when K or its rows are ragged or B misaligned, or when a narrow plain B is
+// to be transposed (d.transpose_b; `b_trans` is the layout of the B given).
 struct PackedOperands { const void* A; const void* B; };
 
 int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, int64_t N, int64_t K, int64_t batch,
@@ -418,8 +443,8 @@ int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, in
 {
     const size_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
     const bool pack_a = d.k != K || !aligned16(A);
-    const bool pack_b = d.k != K || (!b_trans && d.ldb != N) || !aligned16(B);
-    const int64_t b_rows = b_trans ? N : d.k;
+    const bool pack_b = d.transpose_b || d.k != K || (!b_trans && d.ldb != N) || !aligned16(B);
+    const int64_t b_rows = d.b_trans ? N : d.k;
     const long double total = (long double)batch * M * d.k * es + (long double)batch * b_rows * d.ldb * es;
     if (total >= 4.0e12L) return PGK_ERR_UNSUPPORTED;
     const size_t a_bytes = pack_a ? round_up256((size_t)batch * (size_t)M * (size_t)d.k * es) : 0;
@@ -435,8 +460,9 @@ int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, in
         out->A = p; p += a_bytes;
     }
     if (pack_b) {
-        e = b_trans ? pgk::launch_pad_matrix(B, p, batch, (int)N, (int)K, (int)N, (int)d.k, dtype, st)
-                    : pgk::launch_pad_matrix(B, p, batch, (int)K, (int)N, (int)d.k, (int)d.ldb, dtype, st);
+        e = d.transpose_b ? pgk::launch_transpose_pad(B, p, batch, (int)K, (int)N, (int)d.ldb, dtype, st)
+            : b_trans     ? pgk::launch_pad_matrix(B, p, batch, (int)N, (int)K, (int)N, (int)d.k, dtype, st)
+                          : pgk::launch_pad_matrix(B, p, batch, (int)K, (int)N, (int)d.k, (int)d.ldb, dtype, st);
         if (e != hipSuccess) return PGK_ERR_HIP;
         out->B = p;
     }
@@ -459,7 +485,7 @@ int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, fl
     PackedOperands pk{};
     rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
-    return gemm_fused_core(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, st, b_trans, d.ldb);
+    return gemm_fused_core(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, st, d.b_trans, d.ldb);
 }
 
 int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
@@ -544,13 +570,12 @@ int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int
     if (rc != PGK_OK) return rc;
     const PackDims d = pack_dims(M, N, K, dtype, b_transposed != 0);      // as pgk_gemm_fused sees the problem
     K = d.k;
-    const FusedPlan fp = plan_fused(ok, ok, nullptr, ok, M, N, K, batch, dtype, b_transposed != 0, d.ldb);
+    const FusedPlan fp = plan_fused(ok, ok, nullptr, ok, M, N, K, batch, dtype, d.b_trans, d.ldb);
     Path path = fp.path;
     int slices = 1;
     if (fp.split) {
         slices = fp.slices.splits;
-        path = choose_path(ok, ok, nullptr, ok, ok, M, N, K, dtype, batch * slices, fp.split_small_tile, b_transposed != 0,
-                           d.ldb);
+        path = choose_path(ok, ok, nullptr, ok, ok, M, N, K, dtype, batch * slices, fp.split_small_tile, d.b_trans, d.ldb);
     }
     const long double wgs = (long double)((M + path.tile.bm - 1) / path.tile.bm) * ((N + path.tile.bn - 1) / path.tile.bn) *
                             batch * slices;
@@ -602,7 +627,7 @@ int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, f
     const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
     if (part_bytes && scratch_get(st, part_bytes, &part) != hipSuccess) return PGK_ERR_HIP;
     // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
-    const int small_tile = (splits == 0 && mfma_route(M, N, K, dtype)) ? (int)auto_split(M, N, K, batch, dtype).small_tile : -1;
+    const int small_tile = (splits == 0 && mfma_route(M, N, K, dtype)) ? auto_split(M, N, K, batch, dtype).kind : -1;
     // (the slices are counted in K steps, which padding K to whole chunks leaves as they are)
     const PackDims d = pack_dims(M, N, K, dtype, b_trans);
     if (!d.pack)
@@ -612,7 +637,7 @@ int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, f
     rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
     return run_split_passes(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, plan, small_tile,
-                            static_cast<float*>(workspace), part, st, b_trans, d.ldb);
+                            static_cast<float*>(workspace), part, st, d.b_trans, d.ldb);
 }
 
 }  // namespace

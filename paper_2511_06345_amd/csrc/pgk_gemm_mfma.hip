@@ -58,6 +58,10 @@ struct MfmaCfgBase {
     static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
     static constexpr int A_RPC = 1024 / RA, B_RPC = 1024 / RB;  // rows per 1 KiB
     static constexpr int LDS_BYTES = A_STAGES * A_BYTES + 2 * B_BYTES;
+    // the epilogue stages the output tile in the operand buffers, in pieces the size of the
+    // larger kind (the B stages first when the B tile is the larger one: skinny-M tiles)
+    static constexpr bool STAGE_IN_B = B_BYTES > A_BYTES;
+    static constexpr int PIECE_BYTES = STAGE_IN_B ? B_BYTES : A_BYTES;
     static_assert(A_STAGES == 2 || A_STAGES == 3, "A ring depth");
     static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
     static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
@@ -106,7 +110,7 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     constexpr int UB = OUT_BF16 ? 8 : 16;                 // bytes per unit
     constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
     constexpr int UNITS = ROW_BYTES / UB;                 // units per row
-    constexpr int ROWS_PER_OBJ = Cfg::A_BYTES / ROW_BYTES;   // output rows one operand buffer holds
+    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     const int half = lane >> 5;
     const int row_in = lane & 31;
     // per accumulator block row: where its output row is staged, its row bias, its row sum
@@ -180,7 +184,7 @@ __device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t l
     constexpr int CPR = ROW_BYTES / 16;                   // 16-byte chunks per row
     constexpr int UB = OUT_BF16 ? 8 : 16;
     constexpr int UNITS = ROW_BYTES / UB;
-    constexpr int ROWS_PER_OBJ = Cfg::A_BYTES / ROW_BYTES;   // output rows one operand buffer holds
+    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     constexpr int ROWS_PER_IT = Cfg::NT / CPR;
     constexpr int ITERS = Cfg::BM / ROWS_PER_IT;
     static_assert(ROWS_PER_OBJ % ROWS_PER_IT == 0, "an iteration stays inside one buffer");
@@ -709,19 +713,22 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 
     // ---- epilogue: activation into LDS (the operand buffers are free now), then
     // whole-row stores.  The row-sum exchange has a small buffer of its own.
-    // the output tile is staged in pieces of A_BYTES, whole 32-row blocks each, in the two A
-    // stages and, when it needs more than two pieces, the two B stages
-    constexpr int OUT_PIECES = BM * BN * (BF16 ? 2 : 4) / Cfg::A_BYTES;
-    static_assert(OUT_PIECES * Cfg::A_BYTES == BM * BN * (BF16 ? 2 : 4) && OUT_PIECES <= 4 &&
-                  (OUT_PIECES <= 2 || Cfg::B_BYTES >= Cfg::A_BYTES) &&
-                  (Cfg::A_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
+    // the output tile is staged in pieces of PIECE_BYTES, whole 32-row blocks each, in the two
+    // stages of the larger operand and, when it needs more than two pieces, two of the other
+    constexpr int OUT_BYTES = BM * BN * (BF16 ? 2 : 4);
+    constexpr int OUT_PIECES = (OUT_BYTES + Cfg::PIECE_BYTES - 1) / Cfg::PIECE_BYTES;
+    static_assert(OUT_PIECES <= 4 && (OUT_PIECES <= 2 || Cfg::B_BYTES == Cfg::A_BYTES) &&
+                  (Cfg::PIECE_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
                   "the operand buffers hold the output tile, whole 32-row blocks each");
+    // (split-K pass 1 of an fp32 kernel stages the same number of bytes; bf16 kernels store
+    // their fp32 partial products directly)
     // row-sum exchange buffer: the third A stage when there is one, else a small array
     // (followed by the tile's biases, BIAS_N floats)
     __shared__ __attribute__((aligned(16))) float rs_own[SA > 2 ? 4 : Cfg::WGN * BM + 2 * BIAS_N];
     float* rs_buf = SA > 2 ? (float*)lds_a2 : rs_own;
     static_assert((Cfg::WGN * BM + 2 * BIAS_N) * 4 <= Cfg::A_BYTES, "row-sum and bias buffers fit an A stage");
-    unsigned char* const obj[4] = {lds_a0, lds_a1, lds_b0, lds_b1};
+    unsigned char* const obj[4] = {Cfg::STAGE_IN_B ? lds_b0 : lds_a0, Cfg::STAGE_IN_B ? lds_b1 : lds_a1,
+                                   Cfg::STAGE_IN_B ? lds_a0 : lds_b0, Cfg::STAGE_IN_B ? lds_a1 : lds_b1};
     __syncthreads();   // every wave is done with the operand tiles
     if (out_mode == 1) {
         // split-K pass 1: raw fp32 partial products to the workspace slice
@@ -855,16 +862,35 @@ using CfgBF16SmallT = MfmaCfgBt<true, 128, 128, 64, 2, 2, 3, 2>;
 using CfgF32SmallT = MfmaCfgBt<false, 64, 64, 32, 2, 2, 2, 2>;
 using CfgBF16TallT = MfmaCfgBt<true, 256, 128, 64, 4, 2, 3, 2>;
 using CfgBF16WideT = MfmaCfgBt<true, 128, 256, 64, 2, 4, 3, 2>;
+// Skinny tiles, four waves of 32x32, for outputs with at most 32 columns or rows, where the
+// tiles above would spend most of their matrix work and LDS traffic on padding and turn a
+// memory-bound product into a compute-bound one:
+//   narrow 128x32 (B transposed only: a plain B tile would have rows of 64 bytes; the host
+//          transposes such a B, which is small), flat 32x128 (either layout of B).
+// Two-deep rings, 40 KiB of LDS (fp32 and bf16 alike): these run at the latency of the operand
+// stream, and the third A stage bought nothing (bf16 16384 x 16 x 16384: 145 us with it, 137 without).
+using CfgBF16NarrowT = MfmaCfgBt<true, 128, 32, 64, 4, 1, 2, 2>;
+using CfgF32NarrowT = MfmaCfgBt<false, 128, 32, 32, 4, 1, 2, 2>;
+using CfgBF16Flat = MfmaCfg<true, 32, 128, 64, 1, 4, 2, 2>;
+using CfgF32Flat = MfmaCfg<false, 32, 128, 32, 1, 4, 2, 2>;
+using CfgBF16FlatT = MfmaCfgBt<true, 32, 128, 64, 1, 4, 2, 2>;
+using CfgF32FlatT = MfmaCfgBt<false, 32, 128, 32, 1, 4, 2, 2>;
 
 bool mfma_has_tile(int dtype, int kind, bool b_trans)
 {
-    if (kind == TILE_LARGE || kind == TILE_SMALL) return true;
-    (void)b_trans;   // both layouts of B have every bf16 shape
-    return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16;
+    if (kind == TILE_LARGE || kind == TILE_SMALL || kind == TILE_FLAT) return true;
+    if (kind == TILE_NARROW) return b_trans;
+    return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16;   // (either layout of B)
 }
 
 TileShape mfma_tile_shape(int dtype, int kind)
 {
+    if (kind == TILE_NARROW)
+        return dtype == DT_BF16 ? TileShape{CfgBF16NarrowT::BM, CfgBF16NarrowT::BN, CfgBF16NarrowT::BK}
+                                : TileShape{CfgF32NarrowT::BM, CfgF32NarrowT::BN, CfgF32NarrowT::BK};
+    if (kind == TILE_FLAT)
+        return dtype == DT_BF16 ? TileShape{CfgBF16Flat::BM, CfgBF16Flat::BN, CfgBF16Flat::BK}
+                                : TileShape{CfgF32Flat::BM, CfgF32Flat::BN, CfgF32Flat::BK};
     if (dtype == DT_BF16) {
         if (kind == TILE_TALL) return TileShape{CfgBF16Tall::BM, CfgBF16Tall::BN, CfgBF16Tall::BK};
         if (kind == TILE_WIDE) return TileShape{CfgBF16Wide::BM, CfgBF16Wide::BN, CfgBF16Wide::BK};
@@ -890,6 +916,11 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
     const bool small = kind == TILE_SMALL;
     // the operand views of the convolution path assume B as [K][N]
     if (a.b_trans && (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0])) return hipErrorInvalidValue;
+    if (kind == TILE_NARROW) return dtype == DT_BF16 ? launch_cfg<CfgBF16NarrowT>(a, out_mode, s) : launch_cfg<CfgF32NarrowT>(a, out_mode, s);
+    if (kind == TILE_FLAT) {
+        if (dtype == DT_BF16) return a.b_trans ? launch_cfg<CfgBF16FlatT>(a, out_mode, s) : launch_cfg<CfgBF16Flat>(a, out_mode, s);
+        return a.b_trans ? launch_cfg<CfgF32FlatT>(a, out_mode, s) : launch_cfg<CfgF32Flat>(a, out_mode, s);
+    }
     if (kind == TILE_TALL) return a.b_trans ? launch_cfg<CfgBF16TallT>(a, out_mode, s) : launch_cfg<CfgBF16Tall>(a, out_mode, s);
     if (kind == TILE_WIDE) return a.b_trans ? launch_cfg<CfgBF16WideT>(a, out_mode, s) : launch_cfg<CfgBF16Wide>(a, out_mode, s);
     if (a.b_trans) {

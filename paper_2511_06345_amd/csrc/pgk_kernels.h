@@ -93,9 +93,10 @@ inline void set_b_transposed(GemmArgs& a)
 // Tile geometry of the matrix-core kernels: a large and a small tile per element type (same
 // K tile), the small one for grids that would not fill the chip; for bf16 also the two halves
 // of the large tile (tall = half as wide, wide = half as high) for outputs whose last tile
-// column / row would be at most half full.  A kind the type does not have gives the large tile.
+// column / row would be at most half full; and two skinny tiles per type, narrow (32 columns; B
+// transposed only) and flat (32 rows).  A kind the type does not have gives the large tile.
 struct TileShape { int bm, bn, bk; };
-enum { TILE_LARGE = 0, TILE_SMALL = 1, TILE_TALL = 2, TILE_WIDE = 3 };
+enum { TILE_LARGE = 0, TILE_SMALL = 1, TILE_TALL = 2, TILE_WIDE = 3, TILE_NARROW = 4, TILE_FLAT = 5 };
 TileShape mfma_tile_shape(int dtype, int kind);
 bool mfma_has_tile(int dtype, int kind, bool b_trans);
 TileShape guarded_tile_shape();
@@ -157,6 +158,8 @@ constexpr int kMaxTableTaps = 32;
 // cols_dst elements, a multiple of the 16-byte chunk).
 hipError_t launch_pad_matrix(const void* src, void* dst, long long batch, int rows_src, int cols_src, int rows_dst,
                              int cols_dst, int dtype, hipStream_t s);
+// dst[b][n][k] = src[b][k][n] for k < K, 0 up to Kd (a multiple of the chunk): a narrow B transposed
+hipError_t launch_transpose_pad(const void* src, void* dst, long long batch, int K, int N, int Kd, int dtype, hipStream_t s);
 
 // Measurement aids (pgk_probe.hip): a matrix-instruction-only loop (workgroups of 256
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming

@@ -46,7 +46,48 @@ __global__ __launch_bounds__(256) void pad_matrix_kernel(const T* __restrict__ s
     *(u32x4*)(dst + (size_t)row * (size_t)cols_dst + c0) = out;
 }
 
+// dst[b][n][k] = src[b][k][n] for k < K, 0 for K <= k < Kd (a B of few columns turned into its
+// transposed form with rows of Kd elements, a multiple of the chunk); one thread per 16-byte
+// chunk of dst.  The source is small (N is at most a tile's 32 columns), so its strided reads
+// stay in the caches.
+template <typename T>
+__global__ __launch_bounds__(256) void transpose_pad_kernel(const T* __restrict__ src, T* __restrict__ dst, int K, int N,
+                                                            int Kd, long long total_chunks)
+{
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    if (t >= total_chunks) return;
+    const int cpr = Kd / EPC;
+    const long long row = t / cpr;                     // b * N + n
+    const int k0 = (int)(t - row * cpr) * EPC;
+    const long long b = row / N;
+    const int n = (int)(row - b * N);
+    const T* s = src + (size_t)b * (size_t)K * (size_t)N + n;
+    T v[EPC];
+#pragma unroll
+    for (int e = 0; e < EPC; ++e) v[e] = k0 + e < K ? s[(size_t)(k0 + e) * (size_t)N] : T(0);
+    u32x4 out;
+    __builtin_memcpy(&out, v, 16);
+    *(u32x4*)(dst + (size_t)row * (size_t)Kd + k0) = out;
+}
+
 }  // namespace
+
+hipError_t launch_transpose_pad(const void* src, void* dst, long long batch, int K, int N, int Kd, int dtype, hipStream_t s)
+{
+    const int epc = dtype == DT_BF16 ? 8 : 4;
+    if (Kd % epc != 0 || batch <= 0 || Kd < K || N <= 0) return hipErrorInvalidValue;
+    const long long chunks = batch * N * (long long)(Kd / epc);
+    const long long blocks = (chunks + 255) / 256;
+    if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
+    if (dtype == DT_BF16)
+        hipLaunchKernelGGL(transpose_pad_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
+                           (const unsigned short*)src, (unsigned short*)dst, K, N, Kd, chunks);
+    else
+        hipLaunchKernelGGL(transpose_pad_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)src,
+                           (float*)dst, K, N, Kd, chunks);
+    return hipGetLastError();
+}
 
 hipError_t launch_pad_matrix(const void* src, void* dst, long long batch, int rows_src, int cols_src, int rows_dst,
                              int cols_dst, int dtype, hipStream_t s)

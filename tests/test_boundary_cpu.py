@@ -130,7 +130,8 @@ def test_tile_table_and_split_rule(lib):
     expect((5000, 4096, 4096, 1), F32, (128, 128, 32), 1, 40 * 32)
     expect((4352, 4352, 512, 1), BF16, (256, 256, 64), 1, 17 * 17)
     # few tiles and a long K: slices of at least 16 K tiles, the fewest that give 512 workgroups
-    expect((32, 8192, 8192, 1), BF16, (128, 128, 64), 8, 512)
+    expect((32, 8192, 8192, 1), BF16, (32, 128, 64), 8, 512)
+    expect((48, 8192, 8192, 1), BF16, (128, 128, 64), 8, 512)
     expect((1024, 1024, 8192, 1), BF16, (128, 128, 64), 8, 512)
     expect((256, 256, 65536, 1), BF16, (128, 128, 64), 32, 128)
     expect((256, 256, 1024, 1), BF16, (128, 128, 64), 1, 4)                 # 16 K tiles: not worth a second pass
@@ -143,10 +144,13 @@ def test_tile_table_and_split_rule(lib):
     expect((4096, 4101, 4096, 1), BF16, (128, 128, 64), 1, 32 * 33)
     expect((4096, 4100, 4096, 1), F32, (64, 64, 32), 1, 64 * 65)
     expect((4096, 4101, 512, 1), BF16, (256, 256, 64), 1, 16 * 17)
-    # a few rows: small tiles, K in slices
-    expect((8, 4096, 4096, 1), BF16, (128, 128, 64), 4, 128)
-    expect((1, 4096, 4096, 1), F32, (64, 64, 32), 8, 512)
-    expect((12, 12, 100000, 1), BF16, (128, 128, 64), 32, 32)          # a tiny output with a long K as well
+    # at most 32 rows or columns: the skinny tiles (flat 32 x 128, narrow 128 x 32), K in slices
+    expect((8, 4096, 4096, 1), BF16, (32, 128, 64), 4, 128)
+    expect((1, 4096, 4096, 1), F32, (32, 128, 32), 8, 256)
+    expect((16384, 16, 16384, 1), BF16, (128, 32, 64), 4, 512)         # (a plain B of 16 columns is transposed first)
+    expect((16384, 16, 16384, 1), F32, (128, 32, 32), 4, 512, bt=True)
+    expect((100000, 8, 8, 1), F32, (128, 32, 32), 1, 782)
+    expect((12, 12, 100000, 1), BF16, (32, 128, 64), 32, 32)           # a tiny output with a long K as well
     # an output below 16 x 16, or too little work to copy operands for: bounds-checked kernel
     expect((12, 12, 1000, 1), BF16, (64, 64, 16), 1, 1, matrix_core=False)
     expect((2, 300, 5, 1), BF16, (64, 64, 16), 1, 5, matrix_core=False)

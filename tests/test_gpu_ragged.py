@@ -18,10 +18,13 @@ CALLS = ["fused", "fused_bt", "splitk", "splitk_bt"]
 
 # (M, N, K, batch): ragged K, ragged even N, odd N, both, few rows, a partial last K tile on top,
 # several tiles each way, a long K that the fused call splits by itself, outputs below 16 x 16
-# with a long K
+# with a long K, outputs of at most 32 columns or rows (the skinny tiles; a plain B of few columns
+# is transposed first)
 SHAPES = [(128, 128, 68, 1), (128, 132, 64, 1), (200, 301, 64, 2), (130, 250, 77, 3), (1, 512, 515, 1),
           (8, 1024, 1024, 1), (15, 260, 130, 2), (300, 1030, 129, 1), (640, 515, 70, 1), (64, 101, 4099, 1),
-          (3, 17, 8200, 2), (513, 258, 1026, 1), (12, 12, 20000, 1), (8, 8, 1024, 3), (5, 3, 40002, 2)]
+          (3, 17, 8200, 2), (513, 258, 1026, 1), (12, 12, 20000, 1), (8, 8, 1024, 3), (5, 3, 40002, 2),
+          (300, 16, 1000, 2), (1000, 1, 515, 1), (257, 32, 4100, 1), (4096, 8, 64, 1), (100, 31, 333, 3), (32, 300, 520, 2),
+          (2000, 24, 8192, 1), (20, 2000, 8192, 1)]
 
 
 @pytest.fixture(scope="module")
@@ -95,6 +98,11 @@ def test_ragged_shapes_run_on_the_matrix_cores(pgk):
             assert p["matrix_core"], (dtype, M, N, K, p)
         for M, N, K in [(4096, 4096, 4100), (4096, 4100, 4096), (4096, 50257, 1024), (512, 30522, 768), (1, 4096, 4096), (8, 4096, 4096)]:
             assert pgk.gemm_plan(M, N, K, 1, dtype)["matrix_core"], (dtype, M, N, K)
+        # the skinny tiles: flat for few rows, narrow for few columns (either layout of B)
+        bk = 64 if dtype == BF16 else 32
+        for bt in (False, True):
+            assert pgk.gemm_plan(20, 2000, 8192, 1, dtype, b_transposed=bt)["tile"] == (32, 128, bk)
+            assert pgk.gemm_plan(2000, 24, 8192, 1, dtype, b_transposed=bt)["tile"] == (128, 32, bk)
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
