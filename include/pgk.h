@@ -213,19 +213,19 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx,
  * within the index ranges of pgk_gemm_fused (else PGK_ERR_INVALID_ARG / PGK_ERR_UNSUPPORTED).
  *
  * The convolution runs on the matrix cores as a sum over the taps of GEMMs on shifted views of
- * the input (no unfolded copy of the input is made) when Cout and Lout are at least 16, Lout is
- * a multiple of 16 bytes of elements and the pointers are 16-byte aligned, in one of two ways.
+ * the input (no unfolded copy of the input is made) when Cout and Lout are at least 16 and the
+ * pointers are 16-byte aligned, in one of two ways.
  * Stride 1, Cin a multiple of the K tile (32 float32 / 64 bfloat16) and, for bfloat16, an even
  * dilation (or Kw = 1): the views are taken of the input itself -- only the tile columns at the
- * ends of the rows read small zero-padded strips -- or of one zero-padded copy of it.  Otherwise
+ * ends of the rows read small zero-padded strips -- or (also whenever Lout is not a multiple of
+ * 16 bytes of elements) of one zero-padded copy of it.  Otherwise
  * -- stride > 1, any Cin of at least half a K tile's multiple (Cin >= its round-up / 2), odd
  * dilation in bfloat16 -- with Kw <= 32: the views are taken of copies of the input, one per
  * phase of the stride (and a second one shifted by one element for bfloat16 taps at odd
  * offsets), channels padded with zeros to a multiple of the K tile.  Both need `workspace`
  * (device memory, 256-byte aligned, contents destroyed) of pgk_conv1d_workspace_bytes(...)
  * bytes for the regrouped weights and the strips or copies.  Too small or NULL gives
- * PGK_ERR_WORKSPACE.  Every other case (a few input channels, odd output lengths, tiny
- * outputs) is computed by a bounds-checked kernel that reads the input in place and needs no
+ * PGK_ERR_WORKSPACE.  Every other case (a few input channels, tiny outputs) is computed by a bounds-checked kernel that reads the input in place and needs no
  * workspace (the query then returns 0).
  */
 int pgk_conv1d(const void* x, const void* w, const float* bias, void* y,

@@ -3,6 +3,7 @@
 // The contract of every entry point is documented in include/pgk.h.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cmath>
 #include <map>
 #include <mutex>
@@ -728,8 +729,11 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     pl.valid = true;
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = 16 / es;
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
-    // what every matrix-core route needs: an output the kernels can store in 16-byte chunks
-    if (Cout < 16 || pl.Lout < 16 || pl.Lout % epc != 0) return pl;
+    // tiny outputs stay with the bounds-checked kernel.  The output length may be anything (the
+    // kernels store a row's last, partly filled chunk element by element), but the B copies then
+    // reach up to Lr - 1 = the last column of that chunk, which the copies of the input must hold.
+    if (Cout < 16 || pl.Lout < 16) return pl;
+    const int64_t Lr = (int64_t)round_up((size_t)pl.Lout, (size_t)epc);
     pl.kind = auto_tile_kind(Cout, pl.Lout, 0, dtype, B, false);
     pl.tile = pgk::mfma_tile_shape(dtype, pl.kind);
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
@@ -738,14 +742,14 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     if (stride == 1 && Cin % t.bk == 0 && shifts_even) {
         // the input as it is, or one zero-padded copy of it; taps a constant column step apart
         const int64_t K = Cin * Kw;
-        const bool needs_copy = pad > 0 || L % epc != 0;
-        const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)(L + 2 * pad), (size_t)epc) : L;
+        const bool needs_copy = pad > 0 || L % epc != 0 || pl.Lout % epc != 0;
+        const int64_t Lp = needs_copy ? (int64_t)round_up((size_t)std::max(L + 2 * pad, Lr + halo), (size_t)epc) : L;
         if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * Lp * es + dilation * Kw * es >= (1LL << 32)) return pl;
         pl.fast = true;
         pl.w_bytes = round_up((size_t)(Cout * K * es), 256);
         // Reading the input in place needs every tile base 4-byte aligned (rows and shifts), the
         // halo and the padding no wider than a tile.
-        pl.strips = halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 &&
+        pl.strips = pl.Lout % epc == 0 && halo <= bn && pad <= bn && (L * es) % 4 == 0 && (pad * es) % 4 == 0 &&
                     (long double)B * Cin * 3 * ((bn + halo) / 256 + 2) < 2.0e9L;
         if (pl.strips) {
             const int64_t tiles_n = (pl.Lout + bn - 1) / bn;
@@ -781,7 +785,7 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     if (dtype == PGK_DTYPE_BF16)
         for (int64_t k = 0; k < Kw; ++k)
             if ((k * dilation / stride) % 2 != 0) pl.shifts = 2;
-    pl.Lq = (int64_t)round_up((size_t)(pl.Lout + q_max + 1), (size_t)epc);
+    pl.Lq = (int64_t)round_up((size_t)(Lr + q_max + 1), (size_t)epc);
     if ((int64_t)t.bm * K * es >= (1LL << 32) || (int64_t)t.bk * pl.Lq * es >= (1LL << 32)) return pl;
     const long double copies_bytes = (long double)stride * pl.shifts * B * pl.cin_pad * pl.Lq * es;
     if (copies_bytes >= 4.0e12L || (long double)stride * pl.shifts * B * pl.cin_pad > 4.0e9L) return pl;
@@ -883,7 +887,7 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
                 ldb = pl.Lp;
             }
         }
-        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, cin_k * Kw, dtype, B, pl.kind);
+        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, cin_k * Kw, dtype, B, pl.kind, false, ldb);
         if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
         a.a_batch_stride = 0;

@@ -196,10 +196,12 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 2, 2, BF16) > 0
     # bf16 with odd dilation: a second copy shifted by one element for the taps at odd offsets (rows of 1008)
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, BF16) == 32 * 64 * 3 * 2 + 2 * (2 * 64) * 1008 * 2
-    # three channels (padding them to a K tile would multiply the work), an output length that is not
-    # a multiple of 16 bytes, fewer than 16 output channels, more than 32 taps at stride 2: in place, no workspace
+    # an output length that is not a multiple of 16 bytes (1001): a padded copy whose rows hold the
+    # last chunk's columns and the halo (1004 + 2, rounded up to 1008)
+    assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 32 * 64 * 3 * 4 + 2 * 64 * 1008 * 4
+    # three channels (padding them to a K tile would multiply the work), fewer than 16 output
+    # channels, more than 32 taps at stride 2: in place, no workspace
     assert binding.conv1d_workspace_bytes(2, 3, 1000, 32, 3, 1, 1, 1, F32) == 0
-    assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 0
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 8, 3, 1, 1, 1, F32) == 0
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 33, 2, 16, 1, F32) == 0
 

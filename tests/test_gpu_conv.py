@@ -48,9 +48,9 @@ def int_case(dtype, B, Cin, L, Cout, Kw, seed):
     return x, w
 
 
-# (B, Cin, L, Cout, Kw, stride, pad, dilation).  FAST: stride 1, channels a multiple of the K
-# tile, output length a multiple of 16 bytes -> matrix-core path (shifted views, several
-# taps, padded copy or not, small and large tiles, ragged Cout and Lout tiles).
+# (B, Cin, L, Cout, Kw, stride, pad, dilation).  FAST: enough channels, at least 16 output
+# channels and outputs -> matrix-core path (shifted views, several taps, padded copy or not,
+# small and large tiles, ragged Cout and Lout tiles, any output length).
 FAST = {
     F32: [(2, 32, 256, 32, 3, 1, 1, 1), (1, 64, 1024, 48, 5, 1, 2, 1), (3, 32, 520, 130, 3, 1, 1, 1),
           (2, 96, 300, 64, 1, 1, 0, 1), (2, 32, 1028, 20, 4, 1, 3, 2), (1, 32, 1024, 64, 7, 1, 9, 3),
@@ -61,7 +61,10 @@ FAST = {
           # stride > 1 (one copy of the input per phase), channel counts that are not a multiple of the K tile
           # (copies and weights padded with zero channels), both, large tiles
           (2, 64, 1000, 32, 3, 2, 1, 1), (2, 32, 1024, 48, 5, 2, 2, 1), (2, 32, 1200, 32, 4, 3, 2, 2), (2, 48, 1000, 32, 3, 1, 1, 1),
-          (3, 80, 520, 130, 5, 1, 2, 1), (40, 96, 2048, 256, 3, 2, 1, 1), (2, 20, 4096, 64, 7, 4, 3, 1)],
+          (3, 80, 520, 130, 5, 1, 2, 1), (40, 96, 2048, 256, 3, 2, 1, 1), (2, 20, 4096, 64, 7, 4, 3, 1),
+          # output lengths that are not a multiple of the 16-byte chunk, on every route
+          (2, 32, 1001, 32, 3, 1, 0, 1), (2, 32, 1001, 40, 3, 1, 1, 1), (2, 64, 1000, 32, 3, 2, 0, 1), (2, 48, 777, 32, 5, 1, 2, 1),
+          (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 32, 1024, 32, 3, 1, 0, 1)],
     BF16: [(2, 64, 256, 32, 3, 1, 2, 2), (1, 128, 1024, 48, 5, 1, 4, 2), (3, 64, 520, 130, 1, 1, 0, 1),
            (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8),
            (2, 64, 120, 32, 5, 1, 4, 2), (2, 64, 1030, 32, 3, 1, 3, 2), (2, 64, 1036, 32, 9, 1, 6, 2),
@@ -71,11 +74,14 @@ FAST = {
            (2, 64, 1025, 32, 4, 1, 1, 1), (1, 64, 64, 16, 7, 1, 3, 1),
            # stride > 1, ragged channel counts, both with odd and even tap offsets
            (2, 64, 1024, 32, 3, 2, 1, 1), (2, 96, 1024, 32, 3, 1, 1, 1), (2, 64, 1200, 32, 4, 3, 2, 2), (40, 160, 2048, 256, 3, 2, 1, 1),
-           (2, 64, 1040, 32, 5, 2, 6, 3), (2, 40, 4096, 64, 7, 4, 3, 1)],
+           (2, 64, 1040, 32, 5, 2, 6, 3), (2, 40, 4096, 64, 7, 4, 3, 1),
+           # output lengths that are odd, or even and not a multiple of the chunk, on every route
+           (2, 64, 1001, 32, 3, 1, 0, 2), (2, 64, 1001, 32, 3, 1, 1, 1), (2, 64, 1000, 32, 3, 2, 0, 1), (2, 64, 1030, 32, 3, 1, 0, 2),
+           (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 64, 1024, 32, 3, 1, 0, 2)],
 }
 # everything else: the bounds-checked kernel reading the input in place
 GENERAL = [(1, 1, 9, 1, 3, 1, 0, 1), (2, 3, 17, 4, 3, 1, 1, 1), (2, 5, 50, 7, 5, 2, 2, 1), (1, 2, 130, 70, 4, 3, 5, 2),
-           (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (1, 7, 300, 5, 9, 1, 0, 3), (2, 64, 256, 8, 3, 1, 1, 1)]
+           (1, 7, 300, 5, 9, 1, 0, 3), (2, 64, 256, 8, 3, 1, 1, 1), (2, 8, 101, 33, 3, 1, 1, 1)]
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
