@@ -225,8 +225,9 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx,
  * offsets), channels padded with zeros to a multiple of the K tile.  Both need `workspace`
  * (device memory, 256-byte aligned, contents destroyed) of pgk_conv1d_workspace_bytes(...)
  * bytes for the regrouped weights and the strips or copies.  Too small or NULL gives
- * PGK_ERR_WORKSPACE.  Every other case (a few input channels, tiny outputs) is computed by a bounds-checked kernel that reads the input in place and needs no
- * workspace (the query then returns 0).
+ * PGK_ERR_WORKSPACE.  Every other case (a few input channels, tiny outputs) is computed by
+ * a bounds-checked kernel that reads the input in place and needs no workspace (the query
+ * then returns 0).
  */
 int pgk_conv1d(const void* x, const void* w, const float* bias, void* y,
                int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw,
