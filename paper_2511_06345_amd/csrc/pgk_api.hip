@@ -729,12 +729,13 @@ ConvPlan plan_conv1d(int64_t B, int64_t Cin, int64_t L, int64_t Cout, int64_t Kw
     pl.valid = true;
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4, epc = 16 / es;
     const pgk::TileShape t = pgk::mfma_tile_shape(dtype, false);
-    // tiny outputs stay with the bounds-checked kernel.  The output length may be anything (the
-    // kernels store a row's last, partly filled chunk element by element), but the B copies then
-    // reach up to Lr - 1 = the last column of that chunk, which the copies of the input must hold.
-    if (Cout < 16 || pl.Lout < 16) return pl;
+    // very short outputs stay with the bounds-checked kernel.  The output length may be anything
+    // (the kernels store a row's last, partly filled chunk element by element), but the B copies
+    // then reach up to Lr - 1 = the last column of that chunk, which the copies of the input must hold.
+    if (pl.Lout < 16) return pl;
     const int64_t Lr = (int64_t)round_up((size_t)pl.Lout, (size_t)epc);
-    pl.kind = auto_tile_kind(Cout, pl.Lout, 0, dtype, B, false);
+    // (up to 32 output channels: the flat tile, as for a GEMM with that many rows)
+    pl.kind = Cout <= 32 ? pgk::TILE_FLAT : auto_tile_kind(Cout, pl.Lout, 0, dtype, B, false);
     pl.tile = pgk::mfma_tile_shape(dtype, pl.kind);
     const int64_t bn = pl.tile.bn, halo = (Kw - 1) * dilation;
     const bool shifts_even = dtype == PGK_DTYPE_F32 || dilation % 2 == 0 || Kw == 1;

@@ -182,11 +182,13 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     assert binding.conv1d_out_len(5, 3, 1, 0, 3) == 0 and binding.conv1d_out_len(0, 3) == 0
     # matrix-core path: regrouped weights + zero-padded strips for the first and the last tile
     # column (64-column tiles on this small grid, halo 2, rounded up to 16 bytes: 68 columns)
-    need = binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, F32)
-    assert need == 32 * 64 * 3 * 4 + 2 * (2 * 64) * 68 * 4
+    need = binding.conv1d_workspace_bytes(2, 64, 1000, 64, 3, 1, 1, 1, F32)
+    assert need == 64 * 64 * 3 * 4 + 2 * (2 * 64) * 68 * 4
+    # (32 output channels: the flat tile, 128 columns wide)
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 1, 1, F32) == 32 * 64 * 3 * 4 + 2 * (2 * 64) * 132 * 4
     # padding wider than a tile: a padded copy of the whole input instead (rows of 1000 + 2 * 101, rounded up)
-    need = binding.conv1d_workspace_bytes(2, 64, 1000, 32, 3, 1, 101, 1, F32)
-    assert need == 32 * 64 * 3 * 4 + 2 * 64 * 1204 * 4
+    need = binding.conv1d_workspace_bytes(2, 64, 1000, 64, 3, 1, 101, 1, F32)
+    assert need == 64 * 64 * 3 * 4 + 2 * 64 * 1204 * 4
     # no padding and aligned rows: only the weights
     assert binding.conv1d_workspace_bytes(2, 64, 1024, 32, 3, 1, 0, 2, F32) == 32 * 64 * 3 * 4
     # stride 2: one copy of the input per phase (rows of 500 outputs + 1 tap offset + 1, rounded up to 504)
@@ -199,10 +201,11 @@ def test_conv1d_host_arithmetic_and_validation(lib):
     # an output length that is not a multiple of 16 bytes (1001): a padded copy whose rows hold the
     # last chunk's columns and the halo (1004 + 2, rounded up to 1008)
     assert binding.conv1d_workspace_bytes(2, 64, 1001, 32, 3, 1, 1, 1, F32) == 32 * 64 * 3 * 4 + 2 * 64 * 1008 * 4
-    # three channels (padding them to a K tile would multiply the work), fewer than 16 output
-    # channels, more than 32 taps at stride 2: in place, no workspace
+    # three channels (padding them to a K tile would multiply the work), fewer than 16 outputs
+    # per row, more than 32 taps at stride 2: in place, no workspace
     assert binding.conv1d_workspace_bytes(2, 3, 1000, 32, 3, 1, 1, 1, F32) == 0
-    assert binding.conv1d_workspace_bytes(2, 64, 1000, 8, 3, 1, 1, 1, F32) == 0
+    assert binding.conv1d_workspace_bytes(2, 64, 1000, 8, 3, 1, 1, 1, F32) > 0     # (8 output channels: the flat tile)
+    assert binding.conv1d_workspace_bytes(2, 64, 15, 32, 3, 1, 1, 1, F32) == 0      # 15 outputs per row
     assert binding.conv1d_workspace_bytes(2, 64, 1000, 32, 33, 2, 16, 1, F32) == 0
 
     def call(x=0x1000, w=0x2000, y=0x3000, B=1, Cin=4, L=16, Cout=4, Kw=3, stride=1, pad=0, dil=1, act=0, dtype=0,

@@ -64,7 +64,9 @@ FAST = {
           (3, 80, 520, 130, 5, 1, 2, 1), (40, 96, 2048, 256, 3, 2, 1, 1), (2, 20, 4096, 64, 7, 4, 3, 1),
           # output lengths that are not a multiple of the 16-byte chunk, on every route
           (2, 32, 1001, 32, 3, 1, 0, 1), (2, 32, 1001, 40, 3, 1, 1, 1), (2, 64, 1000, 32, 3, 2, 0, 1), (2, 48, 777, 32, 5, 1, 2, 1),
-          (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 32, 1024, 32, 3, 1, 0, 1)],
+          (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 32, 1024, 32, 3, 1, 0, 1),
+          # few output channels: the flat tile, on every route
+          (2, 64, 256, 8, 3, 1, 1, 1), (3, 64, 1000, 1, 3, 1, 1, 1), (2, 32, 1001, 5, 5, 2, 2, 1), (2, 64, 4096, 20, 3, 1, 0, 2), (2, 48, 600, 3, 3, 1, 50, 1)],
     BF16: [(2, 64, 256, 32, 3, 1, 2, 2), (1, 128, 1024, 48, 5, 1, 4, 2), (3, 64, 520, 130, 1, 1, 0, 1),
            (2, 64, 1032, 24, 3, 1, 4, 4), (40, 128, 2048, 256, 3, 1, 2, 2), (2, 64, 4104, 256, 2, 1, 0, 8),
            (2, 64, 120, 32, 5, 1, 4, 2), (2, 64, 1030, 32, 3, 1, 3, 2), (2, 64, 1036, 32, 9, 1, 6, 2),
@@ -77,11 +79,12 @@ FAST = {
            (2, 64, 1040, 32, 5, 2, 6, 3), (2, 40, 4096, 64, 7, 4, 3, 1),
            # output lengths that are odd, or even and not a multiple of the chunk, on every route
            (2, 64, 1001, 32, 3, 1, 0, 2), (2, 64, 1001, 32, 3, 1, 1, 1), (2, 64, 1000, 32, 3, 2, 0, 1), (2, 64, 1030, 32, 3, 1, 0, 2),
-           (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 64, 1024, 32, 3, 1, 0, 2)],
+           (3, 32, 101, 33, 3, 1, 1, 1), (2, 64, 257, 16, 3, 2, 1, 1), (2, 64, 1024, 32, 3, 1, 0, 2),
+           (2, 64, 256, 8, 3, 1, 2, 2), (3, 64, 1000, 1, 3, 1, 1, 1), (2, 64, 1001, 5, 5, 2, 2, 1), (2, 64, 4096, 20, 3, 1, 0, 2), (2, 96, 600, 3, 3, 1, 50, 1)],
 }
 # everything else: the bounds-checked kernel reading the input in place
 GENERAL = [(1, 1, 9, 1, 3, 1, 0, 1), (2, 3, 17, 4, 3, 1, 1, 1), (2, 5, 50, 7, 5, 2, 2, 1), (1, 2, 130, 70, 4, 3, 5, 2),
-           (1, 7, 300, 5, 9, 1, 0, 3), (2, 64, 256, 8, 3, 1, 1, 1), (2, 8, 101, 33, 3, 1, 1, 1)]
+           (1, 7, 300, 5, 9, 1, 0, 3), (2, 64, 15, 8, 3, 1, 1, 1), (2, 8, 101, 33, 3, 1, 1, 1)]
 
 
 @pytest.mark.parametrize("dtype", [F32, BF16])
