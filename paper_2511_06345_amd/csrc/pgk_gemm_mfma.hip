@@ -275,6 +275,16 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // (a last tile that is full is treated the same way when the rows of a plain B are not
     // whole chunks: the copy of its last row must end where the array ends)
     const bool k_partial = k_last < BK || p.b_tail_bounded;
+    // Memory-bound skinny products: every workgroup walks its K tiles from a different starting
+    // tile (and wraps around).  With row strides that are large powers of two, workgroups that
+    // all start at tile 0 and move in step keep asking the same few memory channels
+    // (bf16 16384 x 16 x 16384, rows 32 KiB apart: 4.0 TB/s; with rows of 32896 bytes 5.4 TB/s).
+    // Only with whole K tiles (the peeled partial tile has to come last) and plain GEMM views.
+    const int k_rot = (p.k_rotate && !k_partial) ? (int)((unsigned int)(tm + tn) % (unsigned int)KT) : 0;
+    auto k_tile_at = [&](int kt) __attribute__((always_inline)) -> int {      // the K tile processed in step kt
+        const int kk = kt + k_rot;
+        return kk >= KT ? kk - KT : kk;
+    };
 
     const unsigned char* Ag = (const unsigned char*)p.A +
         ((size_t)b * (size_t)p.a_batch_stride + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
@@ -377,7 +387,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     };
     auto copy_a_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
-        const unsigned char* base = Ag + (size_t)kt * a_step;
+        const unsigned char* base = Ag + (size_t)k_tile_at(kt) * a_step;
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, A_end, bounded), 0x00020000),
             PGK_LDS(la + t * 1024), 16, voff_a[t], 0, 0, 0);
@@ -391,7 +401,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const long long b_tap_jump = (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step;
     auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
         unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
-        const unsigned char* base = Bg + b_next_off;
+        const unsigned char* base = Bg + (p.k_rotate ? (size_t)k_tile_at(kt) * b_step : b_next_off);
         __builtin_amdgcn_raw_ptr_buffer_load_lds(
             __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, B_end, bounded), 0x00020000),
             PGK_LDS(lb + t * 1024), 16, voff_b[t], 0, 0, 0);
@@ -405,7 +415,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                 else b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
             }
         }
-        (void)kt;
     };
     auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
 #pragma unroll

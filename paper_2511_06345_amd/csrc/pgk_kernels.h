@@ -33,6 +33,7 @@ struct GemmArgs {
     long long a_batch_stride, b_batch_stride;   // elements between batch entries of A and of B
     int ldb;                 // elements between rows of B
     int b_trans;             // 1: B is given transposed, [batch][N][ldb >= K], K contiguous
+    int k_rotate;            // 1: each workgroup starts its K loop at a tile of its own (plain GEMM views, whole K tiles only)
     int b_tail_bounded;      // 1: rows of a plain B are not whole 16-byte chunks: the copies of the last K tile stop at the end of B
     int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
@@ -71,6 +72,7 @@ inline void fill_plain_views(GemmArgs& a)
     a.ldb = a.N;
     a.b_trans = 0;
     a.b_tail_bounded = 0;
+    a.k_rotate = 0;
     a.bias_per_row = 0;
     a.b_tiles_per_tap = 0x7fffffff;
     a.b_tap_step = 0;
