@@ -156,8 +156,10 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
         kind = (large_tile_mostly_empty(M, N, dtype) || tiles_of(pgk::TILE_LARGE) * s_max < 1.5L * kNumCUs) ? pgk::TILE_SMALL
                                                                                                           : pgk::TILE_LARGE;
     const long double tiles = tiles_of(kind);
+    // (enough slices for two workgroups per CU; four of the fp32 small tile, which is how many fit)
+    const long double target = (dtype == PGK_DTYPE_F32 && kind == pgk::TILE_SMALL ? 4.0L : 2.0L) * kNumCUs;
     int64_t s = 1;
-    while (s < s_max && tiles * s < 2.0L * kNumCUs) ++s;
+    while (s < s_max && tiles * s < target) ++s;
     return {(int)s, kind};
 }
 
@@ -357,17 +359,20 @@ void mark_ragged_rows(GemmArgs& a, int dtype)
     a.b_tail_bounded = (!a.b_trans && a.ldb % chunk_elems(dtype) != 0) ? 1 : 0;
 }
 
-// The skinny tiles stream one large operand with nothing shared between workgroups.  Where that
-// operand has K along its rows (A under the narrow tile, a transposed B under the flat one) the K
-// loops start at different tiles, so that power-of-two row strides do not send every workgroup to
-// the same memory channels at once.  (The other shapes share operand panels through L2 between
-// workgroups that walk K together.)  Whole K tiles only: a partial tile has to come last.
-void mark_k_rotation(GemmArgs& a, int kind, const pgk::TileShape& t)
+// One tile column (or, with a transposed B, one tile row): the workgroups stream disjoint rows of
+// the large operand, K along the rows, and share only the small one.  Their K loops then start
+// at different tiles, so that power-of-two row strides do not send every workgroup to the same
+// memory channels at once.  Not when the operand they share is too large to stay in L2 (walking
+// K in step, they fetch each of its tiles once), not with several tile columns and rows (they
+// share panels of both operands), and not for a tile row over a plain B, which reads whole rows
+// of B side by side with its neighbours -- the pattern the memory likes best (16 x 16384 x 16384
+// fp32: 183 us, rotated 214 us).  Whole K tiles only: a partial tile has to come last.
+void mark_k_rotation(GemmArgs& a, int dtype, const pgk::TileShape& t)
 {
-    // (a flat tile over a plain B reads whole rows of B side by side with its neighbours, which is
-    // the pattern the memory likes best: left alone; 16 x 16384 x 16384 fp32 183 us, rotated 214 us)
-    const bool streams_k_rows = kind == pgk::TILE_NARROW || (kind == pgk::TILE_FLAT && a.b_trans);
-    a.k_rotate = (streams_k_rows && a.K % t.bk == 0 && a.k_slice % t.bk == 0 && !a.b_tail_bounded) ? 1 : 0;
+    const long double es = dtype == PGK_DTYPE_BF16 ? 2 : 4, small = 2.0e6L;
+    const bool streams_a = a.tiles_n == 1 && a.tiles_m > 1 && (long double)a.K * a.N * es <= small;
+    const bool streams_bt = a.tiles_m == 1 && a.tiles_n > 1 && a.b_trans && (long double)a.K * a.M * es <= small;
+    a.k_rotate = ((streams_a || streams_bt) && a.K % t.bk == 0 && a.k_slice % t.bk == 0 && !a.b_tail_bounded) ? 1 : 0;
 }
 
 // The two passes of the split-K path.  `workspace`: batch * plan.splits * M * N floats;
@@ -395,7 +400,7 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
 
-    if (path.mfma) mark_k_rotation(a, path.kind, path.tile);
+    if (path.mfma) mark_k_rotation(a, dtype, path.tile);
     hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.kind, 1, st) : pgk::launch_gemm_guarded(a, dtype, 1, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     const int nseg = pgk::splitk_reduce_segments((int)M, (int)N, (int)batch);
@@ -438,7 +443,13 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
     const long double big_tiles = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * batch;
     const bool few_tiles = (long double)tiles_m * tiles_n * batch < (3 * kNumCUs) / 4;
     const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
-    if (fp.path.mfma && (few_tiles || long_k)) {
+    // (The fp32 small tile fits a CU four times; a grid that fills less than three quarters of
+    // those places leaves each CU with one wave per SIMD and nothing to hide its waits behind.
+    // From 128 K tiles on the split pays: 16384 x 64 x 8192 275 -> 173 us, 1024 x 1024 x 4096 81 -> 72 us;
+    // at 64 K tiles it is even, at 32 it loses.)
+    const bool under_filled = dtype == PGK_DTYPE_F32 && fp.path.kind == pgk::TILE_SMALL &&
+                              (long double)tiles_m * tiles_n * batch < 3 * kNumCUs && (K + big.bk - 1) / big.bk >= 128;
+    if (fp.path.mfma && (few_tiles || long_k || under_filled)) {
         fp.slices = plan_splits(M, N, K, batch, dtype, 0);
         fp.split_small_tile = auto_split(M, N, K, batch, dtype).kind;
         const long double ws_bytes = (long double)batch * fp.slices.splits * M * N * sizeof(float);
@@ -552,7 +563,7 @@ int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, fl
             }
         }
     }
-    if (path.mfma) mark_k_rotation(a, path.kind, path.tile);
+    if (path.mfma) mark_k_rotation(a, dtype, path.tile);
     hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.kind, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
     if (part) {
