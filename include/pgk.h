@@ -74,11 +74,12 @@ typedef enum {
  * whole 16-byte chunks (a second per-(device, stream) pool of up to batch*(M*K' + K'*N')
  * elements, K' and N' the next multiples of 8; allocation, reuse and release as for the
  * scratch buffer below) when the problem has at least 64^3 multiply-adds.  C, bias and
- * rowsum are always used in place, whatever N is.  A B given as [K][N] with at most 32
- * columns (under an output of more than 32 rows) is likewise copied first, in transposed
- * form, so that the product can run on the 128 x 32 tile.  What is left for a slower,
- * bounds-checked kernel: smaller problems with such rows, outputs below 16 x 16 with K
- * below 1024, and calls with a pointer that is not 16-byte aligned.
+ * rowsum are always used in place, whatever N is and wherever they start (element
+ * alignment).  A B given as [K][N] with at most 32 columns (under an output of more than
+ * 32 rows) is likewise copied first, in transposed form, so that the product can run on
+ * the 128 x 32 tile, and so is an A or B that does not start on a 16-byte boundary.  What
+ * is left for a slower, bounds-checked kernel: problems below 64^3 multiply-adds that
+ * would need such a copy, and outputs below 16 x 16 with K below 1024.
  * M, N, K must each be below 2^31 and batch*M*N, batch*M*K, batch*K*N below 2^62 (else
  * PGK_ERR_UNSUPPORTED).
  *

@@ -100,14 +100,16 @@ int skinny_tile_kind(int64_t M, int64_t N)
 // transposed form, [N][k], for the narrow tile; the kernels then see a transposed B (b_trans).
 struct PackDims { bool pack; int64_t k, ldb; bool transpose_b; bool b_trans; };
 
-PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans)
+// misaligned: A or B does not start on a 16-byte boundary; the copies do (pack_operands copies
+// whichever operand needs it), and their rows are whole chunks.
+PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans, bool misaligned = false)
 {
     const PackDims as_is{false, K, 0, false, b_trans};
     const bool transpose_b = !b_trans && skinny_tile_kind(M, N) == pgk::TILE_NARROW;
-    if (!transpose_b && !needs_packing(N, K, dtype, b_trans)) return as_is;
+    if (!transpose_b && !misaligned && !needs_packing(N, K, dtype, b_trans)) return as_is;
     if ((long double)M * N * K < 262144.0L) return as_is;
     const int64_t epc = chunk_elems(dtype), es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
-    PackDims d{true, (K * es) % 4 ? round_up64(K, epc) : K, 0, transpose_b, b_trans || transpose_b};
+    PackDims d{true, ((K * es) % 4 || misaligned) ? round_up64(K, epc) : K, 0, transpose_b, b_trans || transpose_b};
     // (a plain B is copied in every such case; so is a B that is transposed, with rows of whole chunks)
     d.ldb = transpose_b ? round_up64(d.k, epc) : d.b_trans ? d.k : round_up64(N, epc);
     if (d.k > kMaxDim || d.ldb > kMaxDim) return as_is;
@@ -338,8 +340,10 @@ Path choose_path(const void* A, const void* B, const void* bias, const void* C, 
                  int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind_forced = -1,
                  bool b_trans = false, int64_t ldb = 0)
 {
-    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(C) &&
-                    aligned16(bias) && aligned16(ws);
+    // (C, the biases and the row sums only need the alignment of their elements: a row of C may
+    // start anywhere, so its 16-byte stores are element-aligned ones in any case)
+    (void)bias; (void)C;
+    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(ws);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
     int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
     if (!pgk::mfma_has_tile(dtype, kind, b_trans)) kind = pgk::TILE_SMALL;      // (the narrow tile with a plain B)
@@ -505,9 +509,8 @@ int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, fl
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans);
-    if (!d.pack || !aligned16(C) || !aligned16(bias))
-        return gemm_fused_core(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, st, b_trans, 0);
+    const PackDims d = pack_dims(M, N, K, dtype, b_trans, !aligned16(A) || !aligned16(B));
+    if (!d.pack) return gemm_fused_core(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, st, b_trans, 0);
     PackedOperands pk{};
     rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
@@ -656,7 +659,7 @@ int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, f
     // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
     const int small_tile = (splits == 0 && mfma_route(M, N, K, dtype)) ? auto_split(M, N, K, batch, dtype).kind : -1;
     // (the slices are counted in K steps, which padding K to whole chunks leaves as they are)
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans);
+    const PackDims d = pack_dims(M, N, K, dtype, b_trans, !aligned16(A) || !aligned16(B));
     if (!d.pack)
         return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile,
                                 static_cast<float*>(workspace), part, st, b_trans);

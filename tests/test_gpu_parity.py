@@ -217,8 +217,9 @@ def test_skinny_splitk_is_exact_on_integers(pgk, oracle, dtype):
 @pytest.mark.parametrize("dtype", [F32, BF16])
 @pytest.mark.parametrize("which", ["A", "B", "C", "bias", "workspace"])
 def test_pointers_off_the_16_byte_grid(pgk, oracle, dtype, which):
-    """A tile-friendly shape with one pointer a single element past a 16-byte boundary: the
-    matrix-core kernels cannot take it, the bounds-checked kernel must, with the same result."""
+    """A tile-friendly shape with one pointer a single element past a 16-byte boundary: a
+    misaligned operand is copied first, C and the bias are used where they are (their rows may
+    start on any element), all with the same result; a misaligned workspace is refused."""
     import torch
     M, N, K, batch = 128, 256, 192, 2
     A, B, bias = random_case(dtype, M, N, K, batch, seed=41)
