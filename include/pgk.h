@@ -214,8 +214,9 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx,
  * within the index ranges of pgk_gemm_fused (else PGK_ERR_INVALID_ARG / PGK_ERR_UNSUPPORTED).
  *
  * The convolution runs on the matrix cores as a sum over the taps of GEMMs on shifted views of
- * the input (no unfolded copy of the input is made) when Lout is at least 16 and the pointers
- * are 16-byte aligned, in one of two ways.
+ * the input (no unfolded copy of the input is made) when Lout is at least 16, in one of two
+ * ways (where the kernels read x itself, x must start on a 16-byte boundary; w, bias and y may
+ * start on any element).
  * Stride 1, Cin a multiple of the K tile (32 float32 / 64 bfloat16) and, for bfloat16, an even
  * dilation (or Kw = 1): the views are taken of the input itself -- only the tile columns at the
  * ends of the rows read small zero-padded strips -- or (also whenever Lout is not a multiple of

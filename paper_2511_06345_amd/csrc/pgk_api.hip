@@ -861,7 +861,10 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int64_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
     if ((long double)B * Cout * pl.Lout >= 4.6e18L || (long double)B * Cin * L >= 4.6e18L) return PGK_ERR_UNSUPPORTED;
-    if (pl.fast && !(aligned16(x) && aligned16(w) && aligned16(y) && aligned16(bias))) pl.fast = false;
+    // The weights are always regrouped into the workspace, y and the bias may start on any element;
+    // only an input that the kernels read in place has to start on a 16-byte boundary.
+    const bool reads_x_in_place = pl.strips || (!pl.table && pl.Lp == 0);
+    if (pl.fast && reads_x_in_place && !aligned16(x)) pl.fast = false;
 
     GemmArgs a{};
     a.bias = bias; a.C = y; a.ws = nullptr; a.rs_part = nullptr;

@@ -138,8 +138,14 @@ def test_both_paths_agree_and_are_deterministic(pgk):
     flat = torch.cat([torch.zeros(1, device="cuda"), dx.reshape(-1)])
     off = flat[1:].view(B, Cin, L)
     b = pgk.conv1d(off, dw, None, NONE, 1, 1, 1)
+    # weights and output one element past a 16-byte boundary: still the matrix-core path (the
+    # weights are regrouped into the workspace, output rows may start on any element)
+    woff = torch.cat([torch.zeros(1, device="cuda"), dw.reshape(-1)])[1:].view(Cout, Cin, Kw)
+    yflat = torch.full((a.numel() + 2,), 7.0, device="cuda")
+    c = pgk.conv1d(dx, woff, None, NONE, 1, 1, 1, out=yflat[1:-1].view(a.shape))
     torch.cuda.synchronize()
-    assert torch.equal(a, a2) and torch.equal(a, b)
+    assert torch.equal(a, a2) and torch.equal(a, b) and torch.equal(a, c)
+    assert float(yflat[0]) == 7.0 and float(yflat[-1]) == 7.0
 
 
 @pytest.mark.parametrize("name", sorted(gen.CONV_WORKLOADS))
