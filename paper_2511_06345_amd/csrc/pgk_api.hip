@@ -158,8 +158,13 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
         kind = (large_tile_mostly_empty(M, N, dtype) || tiles_of(pgk::TILE_LARGE) * s_max < 1.5L * kNumCUs) ? pgk::TILE_SMALL
                                                                                                           : pgk::TILE_LARGE;
     const long double tiles = tiles_of(kind);
-    // (enough slices for two workgroups per CU; four of the fp32 small tile, which is how many fit)
-    const long double target = (dtype == PGK_DTYPE_F32 && kind == pgk::TILE_SMALL ? 4.0L : 2.0L) * kNumCUs;
+    // (enough slices for two workgroups per CU; four of the fp32 small tile and one of the bf16
+    // large tile, which is how many of those fit a CU: a second round of half-length slices does
+    // the same matrix work and doubles the partial products -- bf16 1024 x 2048 x 16384 took 100 us
+    // in 16 slices and 78 us in 8)
+    const long double target = (dtype == PGK_DTYPE_F32 && kind == pgk::TILE_SMALL   ? 4.0L
+                                : dtype == PGK_DTYPE_BF16 && kind == pgk::TILE_LARGE ? 1.0L
+                                                                                      : 2.0L) * kNumCUs;
     int64_t s = 1;
     while (s < s_max && tiles * s < target) ++s;
     return {(int)s, kind};
