@@ -135,6 +135,39 @@ bool large_tile_mostly_empty(int64_t M, int64_t N, int dtype)
     return f * M <= big.bm || f * N <= big.bn;
 }
 
+// How long a grid of one tile shape takes, in rounds: the chip runs per_cu workgroups per CU
+// side by side, a full round of them takes fixed + per_k * K / 1024 (microseconds on the
+// measured part; only ratios between shapes are used), and a last, partly filled round with j
+// workgroups on its busiest CU takes the share tail[j - 1] of a full one.  Fitted to GEMMs of
+// 2560^2 ... 8192^2 outputs with K = 1024 ... 4096 (e.g. bf16 4096^2 x 4096: 256 large tiles 104 us,
+// 1024 small ones 122 us, 512 half tiles 114 us; fp32: 1024 large 913 us, 4096 small 965 us).
+struct TileCost { int per_cu; double fixed, per_k; double tail[4]; };
+
+TileCost tile_cost(int dtype, int kind)
+{
+    if (dtype == PGK_DTYPE_BF16) {
+        switch (kind) {
+        case pgk::TILE_SMALL: return {2, 2.9, 14.3, {0.47, 1.0, 1.0, 1.0}};
+        case pgk::TILE_TALL: return {1, 5.8, 12.8, {0.65, 1.0, 1.0, 1.0}};
+        case pgk::TILE_WIDE: return {1, 5.7, 13.2, {0.65, 1.0, 1.0, 1.0}};
+        default: return {1, 10.0, 22.5, {0.7, 1.0, 1.0, 1.0}};
+        }
+    }
+    if (kind == pgk::TILE_SMALL) return {4, 1.5, 59.9, {0.3, 0.6, 0.75, 1.0}};
+    return {1, 3.0, 56.2, {1.0, 1.0, 1.0, 1.0}};
+}
+
+double estimated_rounds_time(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind)
+{
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
+    const TileCost c = tile_cost(dtype, kind);
+    const double wgs = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)units;
+    const double slots = (double)kNumCUs * c.per_cu;
+    const double full = std::floor(wgs / slots), rest = wgs - full * slots;
+    const int j = (int)std::ceil(rest / kNumCUs);
+    return (c.fixed + c.per_k * (double)K / 1024.0) * (full + (j > 0 ? c.tail[j - 1] : 0.0));
+}
+
 // Automatic choice (splits == 0): slices of at least kMinStepsPerSlice K steps (shorter ones
 // are all prologue and epilogue), at most kMaxAutoSplits of them, and the smallest count that
 // gives 2 x 256 workgroups.  The tile the count is made with: a skinny one for skinny outputs,
@@ -165,8 +198,34 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
     const long double target = (dtype == PGK_DTYPE_F32 && kind == pgk::TILE_SMALL   ? 4.0L
                                 : dtype == PGK_DTYPE_BF16 && kind == pgk::TILE_LARGE ? 1.0L
                                                                                       : 2.0L) * kNumCUs;
-    int64_t s = 1;
-    while (s < s_max && tiles * s < target) ++s;
+    auto slices_for = [&](long double n_tiles, long double goal) {
+        int64_t n = 1;
+        while (n < s_max && n_tiles * n < goal) ++n;
+        return n;
+    };
+    int64_t s = slices_for(tiles, target);
+    // Large against small tile once more, now with their slice counts, by the round model (plus
+    // what the partial products cost: written and read once, at about 4 TB/s, and a launch): the
+    // rule above takes the large tile whenever it can fill the chip, also when its grid then ends
+    // in a poorly filled round or needs many more slices (fp32 1536 x 1536 x 8192: 144 large tiles
+    // x 4 slices = 2.25 rounds, 357 us; 576 small tiles x 2 slices 313 us).  Slices of 1024 K
+    // values and more only: that is what the model was fitted to.
+    if (kind == pgk::TILE_LARGE || kind == pgk::TILE_SMALL) {
+        auto estimate = [&](int knd, int64_t n) {
+            const double second_pass = 2.0 * (double)n * (double)M * (double)N * (double)batch * 4.0 / 4.0e6 + 5.0;
+            return estimated_rounds_time(M, N, (K + n - 1) / n, dtype, batch * n, knd) + (n > 1 ? second_pass : 0.0);
+        };
+        const int other = kind == pgk::TILE_LARGE ? pgk::TILE_SMALL : pgk::TILE_LARGE;
+        const long double other_target = (dtype == PGK_DTYPE_F32 && other == pgk::TILE_SMALL   ? 4.0L
+                                          : dtype == PGK_DTYPE_BF16 && other == pgk::TILE_LARGE ? 1.0L
+                                                                                                 : 2.0L) * kNumCUs;
+        const int64_t s_other = slices_for(tiles_of(other), other_target);
+        const bool other_allowed = other == pgk::TILE_SMALL || !large_tile_mostly_empty(M, N, dtype);
+        if (other_allowed && K / s >= 1024 && K / s_other >= 1024 && estimate(other, s_other) < 0.94 * estimate(kind, s)) {
+            kind = other;
+            s = s_other;
+        }
+    }
     return {(int)s, kind};
 }
 
@@ -278,39 +337,6 @@ int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
         if (3 * area <= 2 * area_large && (long double)tm * tn * units >= 0.75L * kNumCUs) return kind;
     }
     return -1;
-}
-
-// How long a grid of one tile shape takes, in rounds: the chip runs per_cu workgroups per CU
-// side by side, a full round of them takes fixed + per_k * K / 1024 (microseconds on the
-// measured part; only ratios between shapes are used), and a last, partly filled round with j
-// workgroups on its busiest CU takes the share tail[j - 1] of a full one.  Fitted to GEMMs of
-// 2560^2 ... 8192^2 outputs with K = 1024 ... 4096 (e.g. bf16 4096^2 x 4096: 256 large tiles 104 us,
-// 1024 small ones 122 us, 512 half tiles 114 us; fp32: 1024 large 913 us, 4096 small 965 us).
-struct TileCost { int per_cu; double fixed, per_k; double tail[4]; };
-
-TileCost tile_cost(int dtype, int kind)
-{
-    if (dtype == PGK_DTYPE_BF16) {
-        switch (kind) {
-        case pgk::TILE_SMALL: return {2, 2.9, 14.3, {0.47, 1.0, 1.0, 1.0}};
-        case pgk::TILE_TALL: return {1, 5.8, 12.8, {0.65, 1.0, 1.0, 1.0}};
-        case pgk::TILE_WIDE: return {1, 5.7, 13.2, {0.65, 1.0, 1.0, 1.0}};
-        default: return {1, 10.0, 22.5, {0.7, 1.0, 1.0, 1.0}};
-        }
-    }
-    if (kind == pgk::TILE_SMALL) return {4, 1.5, 59.9, {0.3, 0.6, 0.75, 1.0}};
-    return {1, 3.0, 56.2, {1.0, 1.0, 1.0, 1.0}};
-}
-
-double estimated_rounds_time(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind)
-{
-    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
-    const TileCost c = tile_cost(dtype, kind);
-    const double wgs = (double)((M + t.bm - 1) / t.bm) * (double)((N + t.bn - 1) / t.bn) * (double)units;
-    const double slots = (double)kNumCUs * c.per_cu;
-    const double full = std::floor(wgs / slots), rest = wgs - full * slots;
-    const int j = (int)std::ceil(rest / kNumCUs);
-    return (c.fixed + c.per_k * (double)K / 1024.0) * (full + (j > 0 ? c.tail[j - 1] : 0.0));
 }
 
 // The tile shape for an output of M x N with `units` workgroups per tile position (batch entries
