@@ -117,10 +117,12 @@ PackDims pack_dims(int64_t M, int64_t N, int64_t K, int dtype, bool b_trans, boo
     return d;
 }
 
-// the plan queries: does this problem end up on the matrix cores, one way or the other
+// the plan queries, which do not know the layout of B: does this problem end up on the matrix
+// cores, one way or the other, with either layout
 bool mfma_route(int64_t M, int64_t N, int64_t K, int dtype)
 {
-    return mfma_shape_ok(M, N, K, dtype) || pack_dims(M, N, K, dtype, false).pack;
+    return mfma_shape_ok(M, N, K, dtype) || pack_dims(M, N, K, dtype, false).pack ||
+           mfma_shape_ok(M, N, K, dtype, true) || pack_dims(M, N, K, dtype, true).pack;
 }
 
 // A large tile mostly outside the matrix (skinny M or N): the small tile wastes less matrix work

@@ -1,6 +1,8 @@
 """The C-ABI library without a GPU: it loads, exports every declared symbol, and
 rejects bad arguments on the host before any device work (no compute calls here)."""
 import ctypes
+
+import numpy as np
 import os
 import re
 
@@ -244,3 +246,36 @@ def test_python_binding_validates_before_calling(lib):
 
 def test_release_scratch_without_any(lib):
     binding.release_scratch()
+
+
+def test_plan_is_consistent_on_random_shapes(lib):
+    """pgk_gemm_plan on seeded random shapes of every size class: the tile is one of the table's,
+    the workgroup count is tiles x batch x slices, slices stay within their limits and keep at
+    least 16 K tiles each, and only small problems are left to the bounds-checked kernel."""
+    rng = np.random.default_rng(7)
+    tiles = {gen.BF16: {(256, 256, 64), (128, 128, 64), (256, 128, 64), (128, 256, 64), (128, 32, 64), (32, 128, 64)},
+             gen.F32: {(128, 128, 32), (64, 64, 32), (128, 32, 32), (32, 128, 32)}}
+    for n in range(3000):
+        dtype = gen.BF16 if rng.integers(2) else gen.F32
+        hi = [40, 300, 3000, 40000][n % 4]
+        M, N, K = (int(rng.integers(1, hi)) for _ in range(3))
+        if n % 7 == 0:
+            K = int(rng.integers(1, 400000))
+        batch = int(rng.integers(1, 5)) if n % 3 == 0 else 1
+        bt = bool(rng.integers(2))
+        p = binding.gemm_plan(M, N, K, batch, dtype, b_transposed=bt)
+        what = (dtype, M, N, K, batch, bt, p)
+        bm, bn, bk = p["tile"]
+        assert p["workgroups"] == -(-M // bm) * -(-N // bn) * batch * p["slices"], what
+        assert 1 <= p["slices"] <= 32, what
+        if p["matrix_core"]:
+            assert p["tile"] in tiles[dtype], what
+            if p["slices"] > 1:
+                assert -(-K // bk) // p["slices"] >= 16, what
+            if bm == 32:
+                assert M <= 32, what
+            if bn == 32:
+                assert N <= 32 and M > 32, what
+        else:
+            assert p["tile"] == (64, 64, 16) and p["slices"] == 1, what
+            assert M * N * K < 262144 or (M < 16 and N < 16 and K < 1024), what
