@@ -109,7 +109,8 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
  * splits >= 1, or 0 to let the library choose (pgk_splitk_auto_splits): the smallest
  * number of slices that fills the chip with the tile shape chosen with it (256 workgroups
  * of the large bfloat16 tile, 1024 of the small float32 tile, else 512), with slices of
- * at least 16 K tiles and at most 32 slices.  The
+ * at least 16 K tiles (32 for bfloat16 outputs of 96 and more 128 x 128 tiles) and at most
+ * 32 slices.  The
  * K range is cut into slices of L = kstep * ceil(ceil(K / kstep) / splits)
  * elements (kstep = the kernel's K tile: 32 for float32, 64 for bfloat16);
  * slice s covers [s*L, min(K, (s+1)*L)); trailing empty slices are dropped.

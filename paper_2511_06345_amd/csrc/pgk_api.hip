@@ -20,7 +20,12 @@ using pgk::GemmArgs;
 constexpr int64_t kMaxDim = 0x7fffffffLL;
 constexpr int kNumCUs = 256;          // MI355X
 constexpr int64_t kFusedCombineMaxWorkgroups = 64;
-constexpr int kMinStepsPerSlice = 16;
+// Shortest slice of an automatic split, in K tiles: below that the second pass and launch cost
+// more than the shorter loop saves.  16; for bf16, whose K tile takes half as long as an fp32
+// one, 32 once the small-tile grid has 96 workgroups (with slices of 16: 1024 x 2048 x 2048 27 us
+// in two slices, 20 us in one, 1536 x 1536 x 4096 45 us in four, 41 us in two; but 768 x 768 x 3072,
+// 36 tiles, 22 us in three and 32 us in one; fp32 512 x 512 x 1024 18 us in two, 22 us in one).
+int min_steps_per_slice(int dtype, long double small_tiles) { return dtype == PGK_DTYPE_BF16 && small_tiles >= 96 ? 32 : 16; }
 constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // scratch pgk_gemm_fused may take for an automatic split
 constexpr int kMaxAutoSplits = 32;
 constexpr int64_t kLongKSteps = 512;
@@ -170,7 +175,7 @@ double estimated_rounds_time(int64_t M, int64_t N, int64_t K, int dtype, int64_t
     return (c.fixed + c.per_k * (double)K / 1024.0) * (full + (j > 0 ? c.tail[j - 1] : 0.0));
 }
 
-// Automatic choice (splits == 0): slices of at least kMinStepsPerSlice K steps (shorter ones
+// Automatic choice (splits == 0): slices of at least min_steps_per_slice K steps (shorter ones
 // are all prologue and epilogue), at most kMaxAutoSplits of them, and the smallest count that
 // gives 2 x 256 workgroups.  The tile the count is made with: a skinny one for skinny outputs,
 // else the large one if it can reach 1.5 x 256 workgroups within those limits and is not mostly
@@ -181,13 +186,15 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
 {
     const int ks = kstep_of(dtype);
     const int64_t ksteps = (K + ks - 1) / ks;
-    int64_t s_max = ksteps / kMinStepsPerSlice;
-    if (s_max < 1) s_max = 1;
-    if (s_max > kMaxAutoSplits) s_max = kMaxAutoSplits;
     auto tiles_of = [&](int kind) {
         const pgk::TileShape t = pgk::mfma_tile_shape(dtype, kind);
         return (long double)((M + t.bm - 1) / t.bm) * ((N + t.bn - 1) / t.bn) * batch;
     };
+    // (outputs of at most 64 rows or columns are bound by the stream of their large operand, which
+    // more workgroups pull harder on: 16 K tiles per slice for them in any case)
+    int64_t s_max = ksteps / ((M <= 64 || N <= 64) ? 16 : min_steps_per_slice(dtype, tiles_of(pgk::TILE_SMALL)));
+    if (s_max < 1) s_max = 1;
+    if (s_max > kMaxAutoSplits) s_max = kMaxAutoSplits;
     int kind = skinny_tile_kind(M, N);
     if (kind < 0)
         kind = (large_tile_mostly_empty(M, N, dtype) || tiles_of(pgk::TILE_LARGE) * s_max < 1.5L * kNumCUs) ? pgk::TILE_SMALL
