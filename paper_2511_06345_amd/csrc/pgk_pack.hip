@@ -17,9 +17,8 @@ namespace {
 // dst[b][r][c] = src[b][r][c] for r < rows_src, c < cols_src, else 0; dst rows of cols_dst
 // elements (a multiple of the chunk); one thread per 16-byte chunk of dst
 template <typename T>
-__global__ __launch_bounds__(256) void pad_matrix_kernel(const T* __restrict__ src, T* __restrict__ dst, long long batch,
-                                                         int rows_src, int cols_src, int rows_dst, int cols_dst,
-                                                         long long total_chunks)
+__global__ __launch_bounds__(256) void pad_matrix_kernel(const T* __restrict__ src, T* __restrict__ dst, int rows_src,
+                                                         int cols_src, int rows_dst, int cols_dst, long long total_chunks)
 {
     constexpr int EPC = 16 / (int)sizeof(T);
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
@@ -99,10 +98,10 @@ hipError_t launch_pad_matrix(const void* src, void* dst, long long batch, int ro
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(pad_matrix_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)src, (unsigned short*)dst, batch, rows_src, cols_src, rows_dst, cols_dst, chunks);
+                           (const unsigned short*)src, (unsigned short*)dst, rows_src, cols_src, rows_dst, cols_dst, chunks);
     else
         hipLaunchKernelGGL(pad_matrix_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)src, (float*)dst,
-                           batch, rows_src, cols_src, rows_dst, cols_dst, chunks);
+                           rows_src, cols_src, rows_dst, cols_dst, chunks);
     return hipGetLastError();
 }
 
