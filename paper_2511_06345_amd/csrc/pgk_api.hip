@@ -209,7 +209,7 @@ AutoPlan auto_split(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
                                                                                       : 2.0L) * kNumCUs;
     auto slices_for = [&](long double n_tiles, long double goal) {
         int64_t n = 1;
-        while (n < s_max && n_tiles * n < goal) ++n;
+        while (n < s_max && n_tiles * n < 0.95L * goal) ++n;      // (250 tiles: two slices, not three)
         return n;
     };
     int64_t s = slices_for(tiles, target);
@@ -485,7 +485,10 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
     // pass costs more than it gains -- 2048 x 2048 x 16384 bf16: 130 us against 152 us.)
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double big_tiles = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * batch;
-    const bool few_tiles = (long double)tiles_m * tiles_n * batch < (3 * kNumCUs) / 4;
+    // (skinny tiles run at the speed of their operand stream, which takes two workgroups per CU
+    // to keep busy: 16 x 32000 x 4096 fp32, 250 flat tiles, 122 us in one piece and 94 us in two slices)
+    const bool skinny = fp.path.kind == pgk::TILE_NARROW || fp.path.kind == pgk::TILE_FLAT;
+    const bool few_tiles = (long double)tiles_m * tiles_n * batch < (skinny ? (3 * kNumCUs) / 2 : (3 * kNumCUs) / 4);
     const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
     // (The fp32 small tile fits a CU four times; a grid that fills less than three quarters of
     // those places leaves each CU with one wave per SIMD and nothing to hide its waits behind.
