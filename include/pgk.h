@@ -87,9 +87,10 @@ typedef enum {
  * use (hipMalloc; PGK_ERR_HIP if that fails), grown when needed, reused afterwards and
  * released by pgk_release_scratch().  It holds the per-tile partial row sums when rowsum
  * is requested and N spans several tile columns, and -- for problems with few output
- * tiles and a long K (fewer than 192 tiles of the shape in use and K of at least 32 K
- * tiles, or fewer than 192 large tiles and K of at least 512 K tiles; skinny or small
- * outputs) -- the partial products of an automatic K split, computed exactly as by
+ * tiles and a long K (a grid that would leave most of the chip idle -- fewer than 192
+ * tiles of the shape in use, 384 for the skinny tiles -- and K long enough for at least
+ * two slices; or fewer than 192 large tiles and K of at least 512 K tiles; pgk_gemm_plan
+ * tells) -- the partial products of an automatic K split, computed exactly as by
  * pgk_gemm_splitk with splits = 0 (at most 256 MiB; larger cases are not split).  Which
  * route a problem takes depends on its shape only, so results stay bit-reproducible.
  */
