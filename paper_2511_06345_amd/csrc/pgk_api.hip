@@ -351,7 +351,7 @@ int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
 // The tile shape for an output of M x N with `units` workgroups per tile position (batch entries
 // x K splits): the small tile when three quarters of a large tile would be empty, else a half
 // tile when that saves a third of the padding, else the small tile when the large-tile grid would
-// leave a quarter of the CUs idle, else the large tile -- unless its grid ends in a poorly
+// leave a quarter of the CUs idle or K is at most two bf16 K tiles, else the large tile -- unless its grid ends in a poorly
 // filled round and the round model above gives another shape at least 6 % less time (K below
 // 1024: the model is not consulted).
 int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans)
@@ -360,6 +360,10 @@ int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bo
     if (const int skinny = skinny_tile_kind(M, N); K > 0 && skinny >= 0 && pgk::mfma_has_tile(dtype, skinny, b_trans)) return skinny;
     if (large_tile_mostly_empty(M, N, dtype)) return pgk::TILE_SMALL;
     if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
+    // One or two bf16 K tiles: there is no main loop for the large tile to be good at, and two small
+    // workgroups per CU overlap one's copies and stores with the other's (8192 x 8192 x 64 46 -> 39 us,
+    // 96 x [1024 x 1024 x 64] 58 -> 52 us; 16384 x 16384 x 64 loses 6 %).
+    if (dtype == PGK_DTYPE_BF16 && K > 0 && K <= 128) return pgk::TILE_SMALL;
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
     if (wgs < 0.75L * kNumCUs) return pgk::TILE_SMALL;
@@ -406,16 +410,21 @@ void mark_ragged_rows(GemmArgs& a, int dtype)
 // One tile column (or, with a transposed B, one tile row): the workgroups stream disjoint rows of
 // the large operand, K along the rows, and share only the small one.  Their K loops then start
 // at different tiles, so that power-of-two row strides do not send every workgroup to the same
-// memory channels at once.  Not when the operand they share is too large to stay in L2 (walking
-// K in step, they fetch each of its tiles once), not with several tile columns and rows (they
+// memory channels at once.  With several batch entries the starting tile goes by entry: the
+// workgroups of one entry share its small operand and walk K together (rotated against each
+// other they fetched it several times: 32 x [2048 x 128 x 2048] bf16 47 -> 53 us).  Not when a single
+// entry's shared operand is too large to stay in L2 (walking K in step, they fetch each of its
+// tiles once), not with several tile columns and rows (they
 // share panels of both operands), and not for a tile row over a plain B, which reads whole rows
 // of B side by side with its neighbours -- the pattern the memory likes best (16 x 16384 x 16384
 // fp32: 183 us, rotated 214 us).  Whole K tiles only: a partial tile has to come last.
 void mark_k_rotation(GemmArgs& a, int dtype, const pgk::TileShape& t)
 {
     const long double es = dtype == PGK_DTYPE_BF16 ? 2 : 4, small = 2.0e6L;
-    const bool streams_a = a.tiles_n == 1 && a.tiles_m > 1 && (long double)a.K * a.N * es <= small;
-    const bool streams_bt = a.tiles_m == 1 && a.tiles_n > 1 && a.b_trans && (long double)a.K * a.M * es <= small;
+    // (with several batch entries the rotation goes by entry and the tiles of one entry stay in
+    // step, so the size of what they share does not matter)
+    const bool streams_a = a.tiles_n == 1 && a.tiles_m > 1 && (a.batch > 1 || (long double)a.K * a.N * es <= small);
+    const bool streams_bt = a.tiles_m == 1 && a.tiles_n > 1 && a.b_trans && (a.batch > 1 || (long double)a.K * a.M * es <= small);
     a.k_rotate = ((streams_a || streams_bt) && a.K % t.bk == 0 && a.k_slice % t.bk == 0 && !a.b_tail_bounded) ? 1 : 0;
 }
 

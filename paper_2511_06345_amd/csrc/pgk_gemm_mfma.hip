@@ -280,7 +280,9 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // all start at tile 0 and move in step keep asking the same few memory channels
     // (bf16 16384 x 16 x 16384, rows 32 KiB apart: 4.0 TB/s; with rows of 32896 bytes 5.4 TB/s).
     // Only with whole K tiles (the peeled partial tile has to come last) and plain GEMM views.
-    const int k_rot = (p.k_rotate && !k_partial) ? (int)((unsigned int)(tm + tn) % (unsigned int)KT) : 0;
+    // (The workgroups of one batch entry share its small operand through L2 and stay in step;
+    // the batch entries start apart.  A single entry: every tile on its own.)
+    const int k_rot = (p.k_rotate && !k_partial) ? (int)((unsigned int)(p.batch > 1 ? b : tm + tn) % (unsigned int)KT) : 0;
     auto k_tile_at = [&](int kt) __attribute__((always_inline)) -> int {      // the K tile processed in step kt
         const int kk = kt + k_rot;
         return kk >= KT ? kk - KT : kk;
