@@ -33,10 +33,10 @@ PEAK_HBM_GBS = 8000.0
 # L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
 # (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
 # profiles/.  Valid only for the kernel configuration named here; None otherwise.
-TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745804713),
-                 "c4": ("MfmaCfg<true,256,256,64,4,2,3,2>", 235884709),
-                 "c2": ("MfmaCfg<false,128,128,32,2,2,2,1>", 868709353)}
-REDUCE_TRAFFIC_BYTES = {"r1": 1076477596, "r3": 1083079480, "r4": 1073865487}   # both kernels of a call
+TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745761432),
+                 "c4": ("MfmaCfg<true,256,256,64,4,2,3,2>", 235868169),
+                 "c2": ("MfmaCfg<false,128,128,32,2,2,2,1>", 868724653)}
+REDUCE_TRAFFIC_BYTES = {"r1": 1076477276, "r3": 1083079531, "r4": 1073865295}   # both kernels of a call
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
