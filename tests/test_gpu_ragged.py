@@ -24,7 +24,9 @@ SHAPES = [(128, 128, 68, 1), (128, 132, 64, 1), (200, 301, 64, 2), (130, 250, 77
           (8, 1024, 1024, 1), (15, 260, 130, 2), (300, 1030, 129, 1), (640, 515, 70, 1), (64, 101, 4099, 1),
           (3, 17, 8200, 2), (513, 258, 1026, 1), (12, 12, 20000, 1), (8, 8, 1024, 3), (5, 3, 40002, 2),
           (300, 16, 1000, 2), (1000, 1, 515, 1), (257, 32, 4100, 1), (4096, 8, 64, 1), (100, 31, 333, 3), (32, 300, 520, 2),
-          (2000, 24, 8192, 1), (20, 2000, 8192, 1)]
+          (2000, 24, 8192, 1), (20, 2000, 8192, 1),
+          # one tile column or row, whole K tiles: K loops that start at a tile of their own (per tile, per batch entry)
+          (512, 64, 1024, 3), (700, 128, 2048, 2), (40, 900, 1024, 3), (1100, 100, 512, 1), (2000, 32, 4096, 2)]
 
 
 @pytest.fixture(scope="module")
