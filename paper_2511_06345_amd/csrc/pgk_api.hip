@@ -362,8 +362,9 @@ int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bo
     if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
     // One or two bf16 K tiles: there is no main loop for the large tile to be good at, and two small
     // workgroups per CU overlap one's copies and stores with the other's (8192 x 8192 x 64 46 -> 39 us,
-    // 96 x [1024 x 1024 x 64] 58 -> 52 us; 16384 x 16384 x 64 loses 6 %).
-    if (dtype == PGK_DTYPE_BF16 && K > 0 && K <= 128) return pgk::TILE_SMALL;
+    // 96 x [1024 x 1024 x 64] 58 -> 52 us).  Not with output rows of 32 KiB and more, where the 256-byte
+    // pieces of a small tile's rows lie too far apart for the memory (16384 x 16384 x 128: 158 against 171 us).
+    if (dtype == PGK_DTYPE_BF16 && K > 0 && K <= 128 && N < 16384) return pgk::TILE_SMALL;
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
     if (wgs < 0.75L * kNumCUs) return pgk::TILE_SMALL;
