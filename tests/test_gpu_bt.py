@@ -65,7 +65,7 @@ def bf16_round(ref):
 
 # bounds-checked kernel (tiny / odd sizes); matrix-core kernels on the small tiles (exact
 # multiples, ragged M and N, partial last K tile) and, with many batch entries, on the large ones
-GUARDED = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (2, 300, 5, 1)]
+GUARDED = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (2, 300, 5, 1), (15, 15, 1000, 2), (9, 14, 513, 3), (33, 31, 255, 1)]
 SMALL_TILE = {F32: [(128, 128, 32, 1), (128, 384, 160, 2), (100, 36, 64, 2), (129, 132, 96, 1), (17, 500, 128, 1),
                     (250, 16, 64, 3), (128, 128, 36, 1), (100, 36, 4, 2), (70, 200, 524, 1)],
               BF16: [(256, 256, 64, 1), (512, 256, 320, 2), (100, 40, 64, 2), (257, 264, 128, 1), (17, 1000, 192, 1),

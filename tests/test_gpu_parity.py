@@ -62,9 +62,11 @@ def check(got_c, got_rs, ref_c, ref_rs, dtype, what):
         assert e <= TOL[dtype], f"{what}: rowsum error {e:.3e}"
 
 
-# shapes: tiny and ragged (bounds-checked kernel), exact tile multiples with several
-# K-tile counts (matrix-core kernels), and mixes with a ragged tail in each dimension
-GUARDED_SHAPES = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (64, 64, 16, 1), (2, 300, 5, 1)]
+# shapes: tiny and ragged (outputs below 16 x 16 and problems too small to copy operands for run on
+# the bounds-checked kernel, the others on the matrix cores in place or from padded copies), exact
+# tile multiples with several K-tile counts, and mixes with a ragged tail in each dimension
+GUARDED_SHAPES = [(1, 1, 1, 1), (5, 7, 33, 2), (65, 63, 17, 1), (130, 70, 100, 3), (64, 64, 16, 1), (2, 300, 5, 1),
+                  (15, 15, 1000, 2), (9, 14, 513, 3), (1, 15, 1023, 1), (33, 31, 255, 1), (60, 61, 63, 1)]
 # K a whole number of K tiles, M and N ragged: matrix-core kernels with edge tiles
 F32_EDGE_SHAPES = [(100, 36, 64, 2), (129, 132, 96, 1), (300, 260, 32, 1), (17, 500, 128, 1), (250, 16, 64, 3)]
 BF16_EDGE_SHAPES = [(100, 40, 64, 2), (257, 264, 128, 1), (300, 520, 64, 1), (17, 1000, 192, 1), (700, 16, 64, 2)]
