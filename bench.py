@@ -91,9 +91,12 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
     fn = pgk.gemm_splitk if w.call == "splitk" else pgk.gemm_fused
     bufs = []
     for i in range(max(1, sets)):
+        # the workspace is the caller's: one per buffer set, allocated before timing
         kw = {}
-        if w.call == "splitk":
-            need = pgk.splitk_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, 0)
+        flags = pgk.WS_ROWSUM if w.rowsum else 0
+        need = (pgk.gemm_splitk_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, 0, flags) if w.call == "splitk"
+                else pgk.gemm_fused_workspace_bytes(w.M, w.N, w.K, w.batch, w.dtype, flags))
+        if need:
             kw["workspace"] = torch.empty(need, dtype=torch.uint8, device="cuda")
         bufs.append(dict(
             A=dA if i == 0 else dA.clone(), B=dB if i == 0 else dB.clone(),
@@ -147,9 +150,13 @@ def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, s
     vals = torch.empty(shape, dtype=dX.dtype, device="cuda")
     idx = torch.empty(shape, dtype=torch.int32, device="cuda")
     copies = [dX] + [dX.clone() for _ in range(max(1, sets) - 1)]
+    outer = int(np.prod(w.shape[:w.dim], dtype=np.int64))
+    inner = int(np.prod(w.shape[w.dim + 1:], dtype=np.int64))
+    need = pgk.reduce_max_workspace_bytes(outer, w.shape[w.dim], inner, w.dtype)
+    ws = torch.empty(need, dtype=torch.uint8, device="cuda") if need else None
 
     def step(i):
-        pgk.reduce_max(copies[i % len(copies)], w.dim, want_idx=True, out=vals, idx_out=idx)
+        pgk.reduce_max(copies[i % len(copies)], w.dim, want_idx=True, out=vals, idx_out=idx, workspace=ws)
 
     for i in range(warmup):
         step(i)

@@ -23,14 +23,31 @@
  *     C      [batch][M][N]   same element type as A (bf16: round-to-nearest-even)
  *     rowsum [batch][M]      float32; NULL = row reduction not computed
  *
- * Ownership.  The caller owns every buffer.  Outputs are fully overwritten
- * (no accumulate-into-C).  Calls enqueue work on `stream` and return without
- * synchronising it.  Results are deterministic: no value is accumulated with an
- * atomic, every reduction has a fixed order, so equal inputs give bit-equal outputs.
+ * Ownership.  The caller owns every buffer, the workspace included: the library
+ * allocates and frees no device memory, keeps no state between calls, and records
+ * nothing but kernel launches on `stream` (no memset, no copy node), so every call
+ * may be captured into a HIP graph, a first call included.  Outputs are fully
+ * overwritten (no accumulate-into-C).  Calls enqueue work on `stream` and return
+ * without synchronising it.  Results are deterministic: no value is accumulated
+ * with an atomic, every reduction has a fixed order, so equal inputs give bit-equal
+ * outputs.
  *
- * Errors.  Every entry point returns a pgk_status_t as int.  Arguments are
- * validated on the host before any device work is enqueued, so an error return
- * means nothing was launched.
+ * Workspace.  Calls that need device memory beyond their inputs and outputs (partial
+ * row sums of several tile columns, partial products of a K split, zero-padded copies
+ * of operands the matrix-core kernels cannot read in place, segment results of a
+ * reduction) take it from `workspace`: device memory of at least the number of bytes
+ * the matching *_workspace_bytes query returns, starting on a 16-byte boundary, owned
+ * by the caller, contents destroyed by the call, free for reuse once the work the call
+ * enqueued has run.  A query that returns 0 means workspace may be NULL.  Too small,
+ * misaligned or NULL where bytes are needed gives PGK_ERR_WORKSPACE.  Two calls that
+ * may run at the same time (different streams) need different workspaces.
+ *
+ * Errors.  Every entry point returns a pgk_status_t as int.  Arguments, sizes and
+ * the workspace are validated on the host before any device work is enqueued:
+ * PGK_ERR_INVALID_ARG, PGK_ERR_UNSUPPORTED and PGK_ERR_WORKSPACE mean that nothing
+ * was launched.  PGK_ERR_HIP means the runtime refused a launch; launches of the
+ * same call that came before it stay enqueued, and the contents of the outputs and
+ * of the workspace are then undefined.
  */
 #ifndef PGK_H
 #define PGK_H
@@ -58,9 +75,16 @@ typedef enum {
     PGK_OK = 0,
     PGK_ERR_INVALID_ARG = -1, /* NULL A/B/C, non-positive size, unknown act/dtype, bad splits */
     PGK_ERR_UNSUPPORTED = -2, /* size beyond what the kernels index (see each call) */
-    PGK_ERR_WORKSPACE = -3,   /* workspace missing or smaller than pgk_splitk_workspace_bytes */
-    PGK_ERR_HIP = -4          /* the HIP runtime refused a launch or an allocation */
+    PGK_ERR_WORKSPACE = -3,   /* workspace missing, misaligned or smaller than the matching query says */
+    PGK_ERR_HIP = -4          /* the HIP runtime refused a launch */
 } pgk_status_t;
+
+/* What the workspace queries need to know beyond the sizes (bitwise or). */
+typedef enum {
+    PGK_WS_ROWSUM = 1,       /* the call is made with rowsum != NULL */
+    PGK_WS_B_TRANSPOSED = 2, /* the _bt form of the call (second factor as [batch][N][K]) */
+    PGK_WS_UNALIGNED = 4     /* A or B does not start on a 16-byte boundary */
+} pgk_ws_flags_t;
 
 /*
  * pgk_gemm_fused -- one launch sequence computing C = act(A*B + bias) and,
@@ -69,34 +93,41 @@ typedef enum {
  *
  * M, N, K, batch > 0.  Any shape is accepted; M, N and K need not be tile multiples.
  * The matrix-core kernels read operands in place when their rows start on 4-byte boundaries
- * (float32 always; bfloat16 when K -- and, for B as [K][N], N -- is even).  Otherwise the
- * operands are first copied into buffers of the library with rows padded with zeros to
- * whole 16-byte chunks (a second per-(device, stream) pool of up to batch*(M*K' + K'*N')
- * elements, K' and N' the next multiples of 8; allocation, reuse and release as for the
- * scratch buffer below) when the problem has at least 64^3 multiply-adds.  C, bias and
- * rowsum are always used in place, whatever N is and wherever they start (element
- * alignment).  A B given as [K][N] with at most 32 columns (under an output of more than
- * 32 rows) is likewise copied first, in transposed form, so that the product can run on
- * the 128 x 32 tile, and so is an A or B that does not start on a 16-byte boundary.  What
- * is left for a slower, bounds-checked kernel: problems below 64^3 multiply-adds that
- * would need such a copy, and outputs below 16 x 16 with K below 1024.
+ * (float32 always; bfloat16 when K -- and, for B as [K][N], N -- is even).  Otherwise, when
+ * the problem has at least 64^3 multiply-adds, the operands are first copied into the
+ * workspace with rows padded with zeros to whole 16-byte chunks (up to batch*(M*K' + K'*N')
+ * elements, K' and N' the next multiples of 8).  C, bias and rowsum are always used in place,
+ * whatever N is and wherever they start (element alignment).  A B given as [K][N] with at
+ * most 32 columns (under an output of more than 32 rows) is likewise copied first, in
+ * transposed form, so that the product can run on the 128 x 32 tile, and so is an A or B
+ * that does not start on a 16-byte boundary.  What is left for a slower, bounds-checked
+ * kernel: problems below 64^3 multiply-adds that would need such a copy, and outputs below
+ * 16 x 16 with K below 1024.
  * M, N, K must each be below 2^31 and batch*M*N, batch*M*K, batch*K*N below 2^62 (else
  * PGK_ERR_UNSUPPORTED).
  *
- * The library keeps a device scratch buffer per (device, stream), allocated on first
- * use (hipMalloc; PGK_ERR_HIP if that fails), grown when needed, reused afterwards and
- * released by pgk_release_scratch().  It holds the per-tile partial row sums when rowsum
- * is requested and N spans several tile columns, and -- for problems with few output
- * tiles and a long K (a grid that would leave most of the chip idle -- fewer than 192
- * tiles of the shape in use, 384 for the skinny tiles -- and K long enough for at least
- * two slices; or fewer than 192 large tiles and K of at least 512 K tiles; pgk_gemm_plan
- * tells) -- the partial products of an automatic K split, computed exactly as by
- * pgk_gemm_splitk with splits = 0 (at most 256 MiB; larger cases are not split).  Which
- * route a problem takes depends on its shape only, so results stay bit-reproducible.
+ * workspace: pgk_gemm_fused_workspace_bytes(M, N, K, batch, dtype, flags) bytes (see
+ * "Workspace" above); NULL / 0 when that is 0, as it is for problems that fill the chip,
+ * have aligned operands and either no row sums or a single tile column.  Besides the operand
+ * copies it holds the per-tile-column partial row sums when rowsum is requested and N spans
+ * several tile columns (they are added in tile-column order by a second small kernel), and --
+ * for problems with few output tiles and a long K (a grid that would leave most of the chip
+ * idle -- fewer than 192 tiles of the shape in use, 384 for the skinny tiles -- and K long
+ * enough for at least two slices; or fewer than 192 large tiles and K of at least 512 K
+ * tiles; pgk_gemm_plan tells) -- the partial products of an automatic K split, computed
+ * exactly as by pgk_gemm_splitk with splits = 0 (at most 256 MiB; larger cases are not
+ * split).  Which route a problem takes depends on its shape and on the alignment of A and B
+ * only, so results stay bit-reproducible.
  */
 int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
                    int64_t M, int64_t N, int64_t K, int64_t batch,
-                   int act, int dtype, void* stream);
+                   int act, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace pgk_gemm_fused (or, with PGK_WS_B_TRANSPOSED, pgk_gemm_fused_bt) needs
+ * for this problem; `flags` is a bitwise or of pgk_ws_flags_t saying how the call will be
+ * made.  Pure host arithmetic; 0 also for invalid arguments (the call then reports them). */
+size_t pgk_gemm_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int flags);
 
 /*
  * pgk_gemm_splitk -- the same operator for small M,N and large K, computed in
@@ -117,9 +148,11 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
  * slice s covers [s*L, min(K, (s+1)*L)); trailing empty slices are dropped.
  * splits > K is PGK_ERR_INVALID_ARG.
  *
- * workspace: device buffer of at least pgk_splitk_workspace_bytes(...) bytes,
- * 16-byte aligned, owned by the caller, contents destroyed.  Too small or NULL
- * gives PGK_ERR_WORKSPACE.
+ * workspace: device buffer of at least pgk_splitk_workspace_bytes(...) bytes (or the exact
+ * pgk_gemm_splitk_workspace_bytes(..., flags)), 16-byte aligned, owned by the caller,
+ * contents destroyed: the partial products first, then the per-segment partial row sums
+ * of a skinny output's second pass and the operand copies described under pgk_gemm_fused,
+ * where the problem has them.  Too small or NULL gives PGK_ERR_WORKSPACE.
  */
 int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, float* rowsum,
                     int64_t M, int64_t N, int64_t K, int64_t batch,
@@ -132,15 +165,16 @@ int pgk_gemm_splitk(const void* A, const void* B, const float* bias, void* C, fl
  * [out_features][in_features] is stored), so that C = act(A * Bt^T + bias).  This is the
  * "pre-transposed B" form of the matmul operator (Sections 1 / 4.2; same definition, only
  * the storage of one operand differs).  Every other argument, the layouts of A, bias, C
- * and rowsum, ownership, the scratch buffer, the split rule, the workspace size
- * (pgk_splitk_workspace_bytes does not depend on the layout of B) and the errors are as
- * for pgk_gemm_fused / pgk_gemm_splitk.  The matrix-core kernels read Bt in place -- no
+ * and rowsum, ownership, the workspace, the split rule and the errors are as for
+ * pgk_gemm_fused / pgk_gemm_splitk (workspace queries: flag PGK_WS_B_TRANSPOSED;
+ * pgk_splitk_workspace_bytes covers both layouts).  The matrix-core kernels read Bt in place -- no
  * transposed copy is made -- when its rows start on 4-byte boundaries (float32, or an even
  * K), whatever N is; otherwise A and Bt are copied with K padded, as described there.
  */
 int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
                       int64_t M, int64_t N, int64_t K, int64_t batch,
-                      int act, int dtype, void* stream);
+                      int act, int dtype,
+                      void* workspace, size_t workspace_bytes, void* stream);
 int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
                        int64_t M, int64_t N, int64_t K, int64_t batch,
                        int act, int dtype, int splits,
@@ -161,10 +195,17 @@ int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C
  */
 int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_transposed, int32_t* out);
 
-/* Bytes of workspace pgk_gemm_splitk needs for this problem (splits = 0: the
- * automatic choice).  Pure host arithmetic; returns 0 for invalid arguments. */
+/* Bytes of workspace that are enough for pgk_gemm_splitk and pgk_gemm_splitk_bt on this
+ * problem (splits = 0: the automatic choice), with or without row sums, when A and B start
+ * on 16-byte boundaries.  Pure host arithmetic; returns 0 for invalid arguments. */
 size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch,
                                   int dtype, int splits);
+
+/* The exact need of one way of making the call (`flags`: bitwise or of pgk_ws_flags_t),
+ * operands off the 16-byte grid included.  Never more than pgk_splitk_workspace_bytes
+ * unless PGK_WS_UNALIGNED is set.  0 for invalid arguments. */
+size_t pgk_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch,
+                                       int dtype, int splits, int flags);
 
 /* The number of splits pgk_gemm_splitk uses for splits = 0, or the effective
  * number (after dropping empty slices) for splits >= 1.  0 for invalid
@@ -193,12 +234,18 @@ int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch,
  * PGK_ERR_UNSUPPORTED.  Any shape and alignment is accepted (16-byte loads are used when
  * X is 16-byte aligned and the contiguous extent is a multiple of 16 bytes).  When there
  * are few outputs and a long reduced dimension the range is reduced in segments and a
- * second small kernel combines them; the segment results live in the same per
- * (device, stream) scratch buffer as the row-sum partials (hipMalloc on first use).
+ * second small kernel combines them; the segment results (value, position) live in
+ * `workspace`: pgk_reduce_max_workspace_bytes(...) bytes of device memory on a 4-byte
+ * boundary, NULL / 0 when that is 0 (see "Workspace" at the top).
  * The result does not depend on how the work was split and is bit-reproducible.
  */
 int pgk_reduce_max(const void* X, void* out, int32_t* idx,
-                   int64_t outer, int64_t red, int64_t inner, int dtype, void* stream);
+                   int64_t outer, int64_t red, int64_t inner, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream);
+
+/* Bytes of workspace pgk_reduce_max needs for this shape (enough wherever X starts).  Pure
+ * host arithmetic; 0 also for invalid arguments. */
+size_t pgk_reduce_max_workspace_bytes(int64_t outer, int64_t red, int64_t inner, int dtype);
 
 /*
  * pgk_conv1d -- one-dimensional convolution with fused bias and activation (the paper's second
@@ -263,10 +310,6 @@ int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, i
  */
 int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream);
 int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
-
-/* Frees the row-sum scratch buffers of the current process (synchronises the
- * devices that own them).  Optional; safe to call when none exist. */
-int pgk_release_scratch(void);
 
 /* Human-readable name of a status code; never NULL.  Host pointer, static storage. */
 const char* pgk_status_string(int status);

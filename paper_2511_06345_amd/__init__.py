@@ -6,7 +6,8 @@ binding is loaded lazily on first use of ``gemm_fused`` / ``gemm_splitk`` / ``re
 from . import inputs  # noqa: F401
 
 _LAZY = {"gemm_fused", "gemm_splitk", "gemm_fused_bt", "gemm_splitk_bt", "reduce_max", "conv1d", "splitk_workspace_bytes", "splitk_auto_splits",
-         "status_string", "version", "load_library", "release_scratch", "PgkError"}
+         "gemm_fused_workspace_bytes", "gemm_splitk_workspace_bytes", "reduce_max_workspace_bytes",
+         "status_string", "version", "load_library", "PgkError"}
 
 
 def __getattr__(name):

@@ -19,10 +19,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
 EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_splitk_bt", "pgk_gemm_plan",
-           "pgk_splitk_workspace_bytes",
-           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_conv1d", "pgk_conv1d_workspace_bytes",
-           "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
-           "pgk_release_scratch", "pgk_status_string", "pgk_version")
+           "pgk_gemm_fused_workspace_bytes", "pgk_gemm_splitk_workspace_bytes", "pgk_splitk_workspace_bytes",
+           "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_reduce_max_workspace_bytes", "pgk_conv1d",
+           "pgk_conv1d_workspace_bytes", "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
+           "pgk_status_string", "pgk_version")
+
+# pgk_ws_flags_t
+WS_ROWSUM, WS_B_TRANSPOSED, WS_UNALIGNED = 1, 2, 4
 
 _lib = None
 
@@ -45,7 +48,7 @@ def load_library() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.pgk_gemm_fused.restype = ci
-    lib.pgk_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp]
+    lib.pgk_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, ctypes.c_size_t, vp]
     lib.pgk_gemm_splitk.restype = ci
     lib.pgk_gemm_splitk.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp,
                                     ctypes.c_size_t, vp]
@@ -57,10 +60,16 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_gemm_plan.argtypes = [i64, i64, i64, i64, ci, ci, ctypes.POINTER(ctypes.c_int32)]
     lib.pgk_splitk_workspace_bytes.restype = ctypes.c_size_t
     lib.pgk_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
+    lib.pgk_gemm_splitk_workspace_bytes.restype = ctypes.c_size_t
+    lib.pgk_gemm_splitk_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci, ci]
+    lib.pgk_gemm_fused_workspace_bytes.restype = ctypes.c_size_t
+    lib.pgk_gemm_fused_workspace_bytes.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_splitk_auto_splits.restype = ci
     lib.pgk_splitk_auto_splits.argtypes = [i64, i64, i64, i64, ci, ci]
     lib.pgk_reduce_max.restype = ci
-    lib.pgk_reduce_max.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp]
+    lib.pgk_reduce_max.argtypes = [vp, vp, vp, i64, i64, i64, ci, vp, ctypes.c_size_t, vp]
+    lib.pgk_reduce_max_workspace_bytes.restype = ctypes.c_size_t
+    lib.pgk_reduce_max_workspace_bytes.argtypes = [i64, i64, i64, ci]
     lib.pgk_conv1d.restype = ci
     lib.pgk_conv1d.argtypes = [vp, vp, vp, vp] + [i64] * 8 + [ci, ci, vp, ctypes.c_size_t, vp]
     lib.pgk_conv1d_workspace_bytes.restype = ctypes.c_size_t
@@ -71,8 +80,6 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.pgk_probe_stream_read.restype = ci
     lib.pgk_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
-    lib.pgk_release_scratch.restype = ci
-    lib.pgk_release_scratch.argtypes = []
     lib.pgk_status_string.restype = ctypes.c_char_p
     lib.pgk_status_string.argtypes = [ci]
     lib.pgk_version.restype = ci
@@ -90,7 +97,20 @@ def version() -> int:
 
 
 def splitk_workspace_bytes(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0) -> int:
+    """Enough for either layout of B, with or without row sums, aligned operands."""
     return int(load_library().pgk_splitk_workspace_bytes(M, N, K, batch, dtype, splits))
+
+
+def gemm_splitk_workspace_bytes(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0, flags: int = 0) -> int:
+    return int(load_library().pgk_gemm_splitk_workspace_bytes(M, N, K, batch, dtype, splits, flags))
+
+
+def gemm_fused_workspace_bytes(M: int, N: int, K: int, batch: int, dtype: int, flags: int = 0) -> int:
+    return int(load_library().pgk_gemm_fused_workspace_bytes(M, N, K, batch, dtype, flags))
+
+
+def reduce_max_workspace_bytes(outer: int, red: int, inner: int, dtype: int) -> int:
+    return int(load_library().pgk_reduce_max_workspace_bytes(outer, red, inner, dtype))
 
 
 def splitk_auto_splits(M: int, N: int, K: int, batch: int, dtype: int, splits: int = 0) -> int:
@@ -106,12 +126,6 @@ def gemm_plan(M: int, N: int, K: int, batch: int, dtype: int, b_transposed: bool
     return {"matrix_core": bool(out[0]), "tile": (out[1], out[2], out[3]), "slices": out[4], "workgroups": out[5]}
 
 
-def release_scratch() -> None:
-    rc = load_library().pgk_release_scratch()
-    if rc != 0:
-        raise PgkError(rc, "pgk_release_scratch")
-
-
 def _shape(A: torch.Tensor, B: torch.Tensor, b_transposed: bool = False) -> Tuple[int, int, int, int, int]:
     if A.dim() == 2:
         A = A.unsqueeze(0)
@@ -122,6 +136,8 @@ def _shape(A: torch.Tensor, B: torch.Tensor, b_transposed: bool = False) -> Tupl
         raise ValueError("expected A [batch, M, K] and B [batch, K, N] (transposed: [batch, N, K])")
     if not (A.is_cuda and B.is_cuda and A.is_contiguous() and B.is_contiguous()):
         raise ValueError("A and B must be contiguous device tensors")
+    if A.device != B.device:
+        raise ValueError("A and B must live on the same device")
     if A.dtype == torch.float32 and B.dtype == torch.float32:
         dtype = F32
     elif A.dtype == torch.bfloat16 and B.dtype == torch.bfloat16:
@@ -132,12 +148,65 @@ def _shape(A: torch.Tensor, B: torch.Tensor, b_transposed: bool = False) -> Tupl
     return int(batch), int(M), int(B.shape[ndim]), int(K), dtype
 
 
-def _check_bias(bias: Optional[torch.Tensor], N: int) -> int:
+def _check_bias(bias: Optional[torch.Tensor], N: int, device=None) -> int:
     if bias is None:
         return 0
     if not (bias.is_cuda and bias.dtype == torch.float32 and bias.is_contiguous() and bias.numel() == N):
         raise ValueError("bias must be a contiguous float32 device tensor of N elements")
+    if device is not None and bias.device != device:
+        raise ValueError("bias must live on the device of the operands")
     return bias.data_ptr()
+
+
+def _check_out(t: torch.Tensor, what: str, shape, dtype, device) -> torch.Tensor:
+    """A caller-supplied output: the kernels write `shape` elements of `dtype` from its data
+    pointer on, so anything else (a view with strides, another dtype or device, fewer
+    elements) must be refused here."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or t.device != device:
+        raise ValueError(f"{what} must be a tensor on {device}")
+    if t.dtype != dtype:
+        raise TypeError(f"{what} must have dtype {dtype}, not {t.dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what} must be contiguous")
+    if tuple(t.shape) != tuple(shape) and not (t.numel() == _numel(shape) and t.dim() <= len(shape)):
+        raise ValueError(f"{what} must have shape {tuple(shape)}, not {tuple(t.shape)}")
+    return t
+
+
+def _numel(shape) -> int:
+    n = 1
+    for d in shape:
+        n *= int(d)
+    return n
+
+
+def _check_workspace(ws: Optional[torch.Tensor], need: int, device) -> Tuple[Optional[int], int]:
+    """(pointer or None, bytes) of a caller-supplied workspace after validation."""
+    if ws is None:
+        if need:
+            raise ValueError(f"this call needs a workspace of {need} bytes")
+        return None, 0
+    if not (isinstance(ws, torch.Tensor) and ws.is_cuda and ws.device == device and ws.dtype == torch.uint8
+            and ws.is_contiguous()):
+        raise ValueError(f"workspace must be a contiguous uint8 tensor on {device}")
+    return ws.data_ptr(), ws.numel()
+
+
+class _on_stream:
+    """Temporaries the binding allocates itself (outputs, workspaces) must belong, in torch's
+    caching allocator, to the stream the kernels run on: allocated under that stream, a block
+    freed on return is not handed out again before the queued kernels are done."""
+
+    def __init__(self, stream):
+        self.ctx = torch.cuda.stream(stream) if stream is not None else None
+
+    def __enter__(self):
+        if self.ctx is not None:
+            self.ctx.__enter__()
+
+    def __exit__(self, *exc):
+        if self.ctx is not None:
+            self.ctx.__exit__(*exc)
 
 
 def _stream_ptr(stream) -> int:
@@ -145,27 +214,44 @@ def _stream_ptr(stream) -> int:
     return int(s.cuda_stream)
 
 
+def _ws_flags(A, B, rowsum: bool, b_transposed: bool) -> int:
+    flags = (WS_ROWSUM if rowsum else 0) | (WS_B_TRANSPOSED if b_transposed else 0)
+    if A.data_ptr() % 16 or B.data_ptr() % 16:
+        flags |= WS_UNALIGNED
+    return flags
+
+
 def gemm_fused(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
                rowsum: bool = True, out: Optional[torch.Tensor] = None,
-               rowsum_out: Optional[torch.Tensor] = None, stream=None, b_transposed: bool = False):
+               rowsum_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
+               stream=None, b_transposed: bool = False):
     """C = act(A @ B + bias) and (optionally) rowsum = C.sum(-1) in fp32 via pgk_gemm_fused.
 
     Returns (C, rowsum) with C [batch, M, N] in the dtype of A and rowsum
     [batch, M] float32 (None when ``rowsum`` is False).  Asynchronous on the
     current (or given) torch stream.  ``b_transposed``: B is [batch, N, K] and the call is
-    pgk_gemm_fused_bt.
+    pgk_gemm_fused_bt.  ``workspace``: a uint8 device tensor of at least
+    ``gemm_fused_workspace_bytes(...)`` bytes; allocated here (torch device memory) when None
+    and the problem needs one.
     """
     lib = load_library()
     batch, M, N, K, dtype = _shape(A, B, b_transposed)
     entry = lib.pgk_gemm_fused_bt if b_transposed else lib.pgk_gemm_fused
-    C = out if out is not None else torch.empty((batch, M, N), dtype=A.dtype, device=A.device)
-    rs = None
-    if rowsum:
-        rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
-                                                                   device=A.device)
-    rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
-               rs.data_ptr() if rs is not None else None,
-               M, N, K, batch, int(act), dtype, _stream_ptr(stream) or None)
+    dev = A.device
+    need = gemm_fused_workspace_bytes(M, N, K, batch, dtype, _ws_flags(A, B, rowsum, b_transposed))
+    with _on_stream(stream):
+        if workspace is None and need:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+        ws_ptr, ws_bytes = _check_workspace(workspace, need, dev)
+        C = (_check_out(out, "out", (batch, M, N), A.dtype, dev) if out is not None
+             else torch.empty((batch, M, N), dtype=A.dtype, device=dev))
+        rs = None
+        if rowsum:
+            rs = (_check_out(rowsum_out, "rowsum_out", (batch, M), torch.float32, dev) if rowsum_out is not None
+                  else torch.empty((batch, M), dtype=torch.float32, device=dev))
+        rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N, dev) or None, C.data_ptr(),
+                   rs.data_ptr() if rs is not None else None,
+                   M, N, K, batch, int(act), dtype, ws_ptr, ws_bytes, _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_gemm_fused_bt" if b_transposed else "pgk_gemm_fused")
     return C, rs
@@ -181,24 +267,26 @@ def gemm_splitk(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], 
                 rowsum_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None,
                 stream=None, b_transposed: bool = False):
     """Two-pass split-K variant (pgk_gemm_splitk; pgk_gemm_splitk_bt when ``b_transposed``).
-    ``workspace`` is a uint8 device tensor of at least ``splitk_workspace_bytes(...)`` bytes;
-    allocated here when None."""
+    ``workspace`` is a uint8 device tensor of at least ``gemm_splitk_workspace_bytes(...)`` bytes
+    (``splitk_workspace_bytes(...)`` is enough for aligned operands); allocated here when None."""
     lib = load_library()
     batch, M, N, K, dtype = _shape(A, B, b_transposed)
     entry = lib.pgk_gemm_splitk_bt if b_transposed else lib.pgk_gemm_splitk
-    need = splitk_workspace_bytes(M, N, K, batch, dtype, splits)
-    if workspace is None:
-        workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=A.device)
-    C = out if out is not None else torch.empty((batch, M, N), dtype=A.dtype, device=A.device)
-    rs = None
-    if rowsum:
-        rs = rowsum_out if rowsum_out is not None else torch.empty((batch, M), dtype=torch.float32,
-                                                                   device=A.device)
-    rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N) or None, C.data_ptr(),
-               rs.data_ptr() if rs is not None else None,
-               M, N, K, batch, int(act), dtype, int(splits),
-               workspace.data_ptr(), workspace.numel() * workspace.element_size(),
-               _stream_ptr(stream) or None)
+    dev = A.device
+    need = gemm_splitk_workspace_bytes(M, N, K, batch, dtype, splits, _ws_flags(A, B, rowsum, b_transposed))
+    with _on_stream(stream):
+        if workspace is None:
+            workspace = torch.empty((max(need, 16),), dtype=torch.uint8, device=dev)
+        ws_ptr, ws_bytes = _check_workspace(workspace, need, dev)
+        C = (_check_out(out, "out", (batch, M, N), A.dtype, dev) if out is not None
+             else torch.empty((batch, M, N), dtype=A.dtype, device=dev))
+        rs = None
+        if rowsum:
+            rs = (_check_out(rowsum_out, "rowsum_out", (batch, M), torch.float32, dev) if rowsum_out is not None
+                  else torch.empty((batch, M), dtype=torch.float32, device=dev))
+        rc = entry(A.data_ptr(), B.data_ptr(), _check_bias(bias, N, dev) or None, C.data_ptr(),
+                   rs.data_ptr() if rs is not None else None,
+                   M, N, K, batch, int(act), dtype, int(splits), ws_ptr, ws_bytes, _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_gemm_splitk_bt" if b_transposed else "pgk_gemm_splitk")
     return C, rs
@@ -210,10 +298,11 @@ def gemm_splitk_bt(A: torch.Tensor, Bt: torch.Tensor, bias: Optional[torch.Tenso
 
 
 def reduce_max(X: torch.Tensor, dim: int, want_idx: bool = True, out: Optional[torch.Tensor] = None,
-               idx_out: Optional[torch.Tensor] = None, stream=None):
+               idx_out: Optional[torch.Tensor] = None, workspace: Optional[torch.Tensor] = None, stream=None):
     """Maximum of X over dimension ``dim`` and the first position attaining it
     (pgk_reduce_max).  X: contiguous float32 or bfloat16 device tensor.  Returns
-    (values in the dtype of X with ``dim`` removed, int32 positions or None)."""
+    (values in the dtype of X with ``dim`` removed, int32 positions or None).  ``workspace``: uint8
+    device tensor of at least ``reduce_max_workspace_bytes(...)`` bytes, allocated here when None."""
     lib = load_library()
     if not (X.is_cuda and X.is_contiguous()):
         raise ValueError("X must be a contiguous device tensor")
@@ -231,12 +320,19 @@ def reduce_max(X: torch.Tensor, dim: int, want_idx: bool = True, out: Optional[t
         inner *= int(d)
     red = int(X.shape[dim])
     shape = tuple(X.shape[:dim]) + tuple(X.shape[dim + 1:])
-    vals = out if out is not None else torch.empty(shape, dtype=X.dtype, device=X.device)
-    idx = None
-    if want_idx:
-        idx = idx_out if idx_out is not None else torch.empty(shape, dtype=torch.int32, device=X.device)
-    rc = lib.pgk_reduce_max(X.data_ptr(), vals.data_ptr(), idx.data_ptr() if idx is not None else None,
-                            outer, red, inner, dtype, _stream_ptr(stream) or None)
+    dev = X.device
+    need = reduce_max_workspace_bytes(outer, red, inner, dtype)
+    with _on_stream(stream):
+        if workspace is None and need:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+        ws_ptr, ws_bytes = _check_workspace(workspace, need, dev)
+        vals = _check_out(out, "out", shape, X.dtype, dev) if out is not None else torch.empty(shape, dtype=X.dtype, device=dev)
+        idx = None
+        if want_idx:
+            idx = (_check_out(idx_out, "idx_out", shape, torch.int32, dev) if idx_out is not None
+                   else torch.empty(shape, dtype=torch.int32, device=dev))
+        rc = lib.pgk_reduce_max(X.data_ptr(), vals.data_ptr(), idx.data_ptr() if idx is not None else None,
+                                outer, red, inner, dtype, ws_ptr, ws_bytes, _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_reduce_max")
     return vals, idx
@@ -279,8 +375,8 @@ def conv1d(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], act: 
     lib = load_library()
     if x.dim() != 3 or w.dim() != 3 or x.shape[1] != w.shape[1]:
         raise ValueError("expected x [B, Cin, L] and w [Cout, Cin, Kw]")
-    if not (x.is_cuda and w.is_cuda and x.is_contiguous() and w.is_contiguous()):
-        raise ValueError("x and w must be contiguous device tensors")
+    if not (x.is_cuda and w.is_cuda and x.is_contiguous() and w.is_contiguous() and x.device == w.device):
+        raise ValueError("x and w must be contiguous tensors on one device")
     if x.dtype == torch.float32 and w.dtype == torch.float32:
         dtype = F32
     elif x.dtype == torch.bfloat16 and w.dtype == torch.bfloat16:
@@ -292,14 +388,17 @@ def conv1d(x: torch.Tensor, w: torch.Tensor, bias: Optional[torch.Tensor], act: 
     Lout = conv1d_out_len(L, Kw, stride, pad, dilation)
     if Lout <= 0:
         raise ValueError("the convolution has no output for these sizes")
+    dev = x.device
     need = conv1d_workspace_bytes(B, Cin, L, Cout, Kw, stride, pad, dilation, dtype)
-    if workspace is None and need:
-        workspace = torch.empty((need,), dtype=torch.uint8, device=x.device)
-    y = out if out is not None else torch.empty((B, Cout, Lout), dtype=x.dtype, device=x.device)
-    rc = lib.pgk_conv1d(x.data_ptr(), w.data_ptr(), _check_bias(bias, Cout) or None, y.data_ptr(),
-                        B, Cin, L, Cout, Kw, stride, pad, dilation, int(act), dtype,
-                        workspace.data_ptr() if workspace is not None else None,
-                        workspace.numel() if workspace is not None else 0, _stream_ptr(stream) or None)
+    with _on_stream(stream):
+        if workspace is None and need:
+            workspace = torch.empty((need,), dtype=torch.uint8, device=dev)
+        ws_ptr, ws_bytes = _check_workspace(workspace, need, dev)
+        y = (_check_out(out, "out", (B, Cout, Lout), x.dtype, dev) if out is not None
+             else torch.empty((B, Cout, Lout), dtype=x.dtype, device=dev))
+        rc = lib.pgk_conv1d(x.data_ptr(), w.data_ptr(), _check_bias(bias, Cout, dev) or None, y.data_ptr(),
+                            B, Cin, L, Cout, Kw, stride, pad, dilation, int(act), dtype,
+                            ws_ptr, ws_bytes, _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_conv1d")
     return y

@@ -16,7 +16,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 # build time next to the library; the profile harness reads it
 RESOURCES = os.path.join(HERE, "kernel_resources.json")
 
-SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
+SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_mfma_conv.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
            "pgk_probe.hip", "pgk_conv.hip", "pgk_pack.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
@@ -76,7 +76,7 @@ def _compile(src: str):
 def build_library(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link libpgk.so.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as ex:
+    with ThreadPoolExecutor(max_workers=6) as ex:
         compiled = list(ex.map(_compile, SOURCES))
     objs = [c[0] for c in compiled]
     resources = {}

@@ -1,14 +1,11 @@
 // C-ABI layer of libpgk: argument validation (host only, before any HIP call),
-// choice of kernel path and launch geometry, and the row-sum scratch pool.
+// choice of kernel path and launch geometry, and the layout of the caller's workspace.
+// The library allocates no device memory and keeps no state between calls.
 // The contract of every entry point is documented in include/pgk.h.
 #include <hip/hip_runtime.h>
 
 #include <algorithm>
 #include <cmath>
-#include <map>
-#include <mutex>
-#include <utility>
-#include <vector>
 
 #include "../../include/pgk.h"
 #include "pgk_kernels.h"
@@ -19,14 +16,13 @@ using pgk::GemmArgs;
 
 constexpr int64_t kMaxDim = 0x7fffffffLL;
 constexpr int kNumCUs = 256;          // MI355X
-constexpr int64_t kFusedCombineMaxWorkgroups = 64;
 // Shortest slice of an automatic split, in K tiles: below that the second pass and launch cost
 // more than the shorter loop saves.  16; for bf16, whose K tile takes half as long as an fp32
 // one, 32 once the small-tile grid has 96 workgroups (with slices of 16: 1024 x 2048 x 2048 27 us
 // in two slices, 20 us in one, 1536 x 1536 x 4096 45 us in four, 41 us in two; but 768 x 768 x 3072,
 // 36 tiles, 22 us in three and 32 us in one; fp32 512 x 512 x 1024 18 us in two, 22 us in one).
 int min_steps_per_slice(int dtype, long double small_tiles) { return dtype == PGK_DTYPE_BF16 && small_tiles >= 96 ? 32 : 16; }
-constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // scratch pgk_gemm_fused may take for an automatic split
+constexpr size_t kAutoSplitMaxWorkspace = (size_t)256 << 20;   // workspace pgk_gemm_fused may ask for an automatic split
 constexpr int kMaxAutoSplits = 32;
 constexpr int64_t kLongKSteps = 512;
 
@@ -268,65 +264,6 @@ int group_m_for(int tiles_m, int tiles_n)
     return g;
 }
 
-// ---- row-sum scratch: one grow-only buffer per (device, stream)
-struct Scratch { void* ptr = nullptr; size_t bytes = 0; };
-std::mutex g_mu;
-std::map<std::pair<int, hipStream_t>, Scratch> g_scratch;
-std::vector<void*> g_retired;
-
-// a second pool of the same kind for packed operands, which live while the first is in use
-std::map<std::pair<int, hipStream_t>, Scratch> g_pack;
-
-hipError_t scratch_get(hipStream_t stream, size_t bytes, float** out, bool pack_pool = false)
-{
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    std::lock_guard<std::mutex> lk(g_mu);
-    Scratch& s = pack_pool ? g_pack[{dev, stream}] : g_scratch[{dev, stream}];
-    if (s.bytes < bytes) {
-        size_t want = bytes < (1u << 20) ? (1u << 20) : bytes;
-        if (want < 2 * s.bytes) want = 2 * s.bytes;
-        void* p = nullptr;
-        e = hipMalloc(&p, want);
-        if (e != hipSuccess) return e;
-        // kernels already queued on the stream may still use the old buffer
-        if (s.ptr) g_retired.push_back(s.ptr);
-        s.ptr = p;
-        s.bytes = want;
-    }
-    *out = static_cast<float*>(s.ptr);
-    return hipSuccess;
-}
-
-// ---- tile-row counters of the fused row-sum combine: one grow-only array per (device, stream),
-// zero when handed out (cleared on the stream when allocated; every kernel leaves it zero)
-std::map<std::pair<int, hipStream_t>, Scratch> g_counters;
-
-hipError_t counters_get(hipStream_t stream, size_t count, unsigned int** out)
-{
-    int dev = 0;
-    hipError_t e = hipGetDevice(&dev);
-    if (e != hipSuccess) return e;
-    std::lock_guard<std::mutex> lk(g_mu);
-    Scratch& s = g_counters[{dev, stream}];
-    const size_t bytes = count * sizeof(unsigned int);
-    if (s.bytes < bytes) {
-        size_t want = bytes < (1u << 16) ? (1u << 16) : bytes;
-        if (want < 2 * s.bytes) want = 2 * s.bytes;
-        void* p = nullptr;
-        e = hipMalloc(&p, want);
-        if (e != hipSuccess) return e;
-        e = hipMemsetAsync(p, 0, want, stream);
-        if (e != hipSuccess) { (void)hipFree(p); return e; }
-        if (s.ptr) g_retired.push_back(s.ptr);
-        s.ptr = p;
-        s.bytes = want;
-    }
-    *out = static_cast<unsigned int*>(s.ptr);
-    return hipSuccess;
-}
-
 struct Path { bool mfma; int kind; pgk::TileShape tile; };
 
 // Half of a large tile (tall: half as wide; wide: half as high) when that takes away at least
@@ -380,15 +317,14 @@ int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bo
     return best;
 }
 
-// kind_forced: -1 = auto_tile_kind, else the caller (an automatic split plan, a convolution plan) decides
-Path choose_path(const void* A, const void* B, const void* bias, const void* C, const void* ws,
-                 int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind_forced = -1,
+// kind_forced: -1 = auto_tile_kind, else the caller (an automatic split plan, a convolution plan) decides.
+// `aligned`: A, B and the split-K partial products start on 16-byte boundaries (C, the biases and
+// the row sums only need the alignment of their elements: a row of C may start anywhere, so its
+// 16-byte stores are element-aligned ones in any case).
+Path choose_path(bool aligned, int64_t M, int64_t N, int64_t K, int dtype, int64_t units, int kind_forced = -1,
                  bool b_trans = false, int64_t ldb = 0)
 {
-    // (C, the biases and the row sums only need the alignment of their elements: a row of C may
-    // start anywhere, so its 16-byte stores are element-aligned ones in any case)
-    (void)bias; (void)C;
-    const bool ok = mfma_shape_ok(M, N, K, dtype, b_trans, ldb) && aligned16(A) && aligned16(B) && aligned16(ws);
+    const bool ok = aligned && mfma_shape_ok(M, N, K, dtype, b_trans, ldb);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
     int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
     if (!pgk::mfma_has_tile(dtype, kind, b_trans)) kind = pgk::TILE_SMALL;      // (the narrow tile with a plain B)
@@ -431,13 +367,13 @@ void mark_k_rotation(GemmArgs& a, int dtype, const pgk::TileShape& t)
 
 // The two passes of the split-K path.  `workspace`: batch * plan.splits * M * N floats;
 // `part`: batch * nseg * M floats when rowsum != nullptr and the second pass uses nseg > 1
-// column segments (nseg from splitk_reduce_segments), else unused.
+// column segments (nseg from splitk_reduce_segments), else unused.  A, B and the workspace
+// start on 16-byte boundaries.
 int run_split_passes(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
                      int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, int small_tile,
-                     float* workspace, float* part, hipStream_t st, bool b_trans, int64_t ldb = 0)
+                     float* workspace, float* part, hipStream_t st, bool aligned, bool b_trans, int64_t ldb = 0)
 {
-    const Path path = choose_path(A, B, nullptr, workspace, workspace, M, N, K, dtype, batch * plan.splits, small_tile, b_trans,
-                                  ldb);
+    const Path path = choose_path(aligned, M, N, K, dtype, batch * plan.splits, small_tile, b_trans, ldb);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;
@@ -480,16 +416,15 @@ struct FusedPlan {
     int split_small_tile;
 };
 
-FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void* C, int64_t M, int64_t N, int64_t K,
-                     int64_t batch, int dtype, bool b_trans, int64_t ldb = 0)
+FusedPlan plan_fused(bool aligned, int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, bool b_trans, int64_t ldb = 0)
 {
     FusedPlan fp{};
-    fp.path = choose_path(A, B, bias, C, nullptr, M, N, K, dtype, batch, -1, b_trans, ldb);
+    fp.path = choose_path(aligned, M, N, K, dtype, batch, -1, b_trans, ldb);
     const int64_t tiles_m = (M + fp.path.tile.bm - 1) / fp.path.tile.bm;
     const int64_t tiles_n = (N + fp.path.tile.bn - 1) / fp.path.tile.bn;
     // Few output tiles and a long K (skinny or small outputs): one workgroup per tile would
     // leave most of the chip idle, so the K range is split as in pgk_gemm_splitk, with the
-    // partial products in the library's scratch buffer.  The choice depends on the shape only.
+    // partial products in the caller's workspace.  The choice depends on the shape only.
     // (Also when only the small-tile grid fills the chip and K is very long: 256 x 256 x 65536 x 16
     // fp32 took 1536 us on 256 small tiles and 1083 us split; below 512 K tiles the split's extra
     // pass costs more than it gains -- 2048 x 2048 x 16384 bf16: 130 us against 152 us.)
@@ -515,34 +450,112 @@ FusedPlan plan_fused(const void* A, const void* B, const float* bias, const void
     return fp;
 }
 
-// Zero-padded copies of the operands of a packed problem (see pack_dims), in the pack pool of the
-// stream: A' [batch][M][d.k] when K is ragged or A misaligned, B' [batch][d.k][d.ldb] (or
-// Bt' [batch][N][d.k]) when K or its rows are ragged or B misaligned, or when a narrow plain B is
-// to be transposed (d.transpose_b; `b_trans` is the layout of the B given).
-struct PackedOperands { const void* A; const void* B; };
+// ---- The caller's workspace.  Everything a call needs beyond its inputs and outputs is cut from
+// it, each piece starting on a multiple of 256 bytes from its (16-byte aligned) base:
+//   products  split-K partial products [batch][slices][M][N] fp32 (first, at offset 0)
+//   rs_part   row-sum partials, per tile column (single pass) or per column segment (second pass)
+//   pack_a/b  zero-padded (or transposed) copies of operands the kernels cannot read in place
+// The sizes depend on the shape, the layout of B, whether row sums are wanted and whether A / B
+// start on 16-byte boundaries -- the same function answers the workspace queries and lays the
+// workspace out inside the calls.
+struct WsNeeds {
+    bool ok;                 // sizes are representable
+    PackDims d;
+    bool pack_a, pack_b;
+    FusedPlan fp;            // fused call only
+    size_t products, rs_part, a_bytes, b_bytes;
+    size_t off_rs_part, off_a, off_b, total;
+};
 
-int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, int64_t N, int64_t K, int64_t batch,
-                  int dtype, bool b_trans, hipStream_t st, PackedOperands* out)
+void lay_out(WsNeeds& w)
+{
+    size_t at = round_up256(w.products);
+    w.off_rs_part = at; at += round_up256(w.rs_part);
+    w.off_a = at; at += round_up256(w.a_bytes);
+    w.off_b = at; at += round_up256(w.b_bytes);
+    w.total = at;
+}
+
+// the operand copies of a packed problem (see pack_dims); a_mis / b_mis: that operand does not
+// start on a 16-byte boundary
+bool pack_needs(WsNeeds& w, int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, bool b_trans, bool a_mis, bool b_mis)
 {
     const size_t es = dtype == PGK_DTYPE_BF16 ? 2 : 4;
-    const bool pack_a = d.k != K || !aligned16(A);
-    const bool pack_b = d.transpose_b || d.k != K || (!b_trans && d.ldb != N) || !aligned16(B);
-    const int64_t b_rows = d.b_trans ? N : d.k;
-    const long double total = (long double)batch * M * d.k * es + (long double)batch * b_rows * d.ldb * es;
-    if (total >= 4.0e12L) return PGK_ERR_UNSUPPORTED;
-    const size_t a_bytes = pack_a ? round_up256((size_t)batch * (size_t)M * (size_t)d.k * es) : 0;
-    const size_t b_bytes = pack_b ? round_up256((size_t)batch * (size_t)b_rows * (size_t)d.ldb * es) : 0;
-    float* buf = nullptr;
-    if (scratch_get(st, a_bytes + b_bytes + 256, &buf, true) != hipSuccess) return PGK_ERR_HIP;
-    char* p = reinterpret_cast<char*>(buf);
+    w.d = pack_dims(M, N, K, dtype, b_trans, a_mis || b_mis);
+    w.pack_a = w.pack_b = false;
+    w.a_bytes = w.b_bytes = 0;
+    if (!w.d.pack) return true;
+    w.pack_a = w.d.k != K || a_mis;
+    w.pack_b = w.d.transpose_b || w.d.k != K || (!b_trans && w.d.ldb != N) || b_mis;
+    const int64_t b_rows = w.d.b_trans ? N : w.d.k;
+    const long double total = (long double)batch * M * w.d.k * es + (long double)batch * b_rows * w.d.ldb * es;
+    if (total >= 4.0e12L) return false;
+    if (w.pack_a) w.a_bytes = (size_t)batch * (size_t)M * (size_t)w.d.k * es;
+    if (w.pack_b) w.b_bytes = (size_t)batch * (size_t)b_rows * (size_t)w.d.ldb * es;
+    return true;
+}
+
+WsNeeds fused_needs(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, bool b_trans, bool want_rowsum, bool a_mis,
+                    bool b_mis)
+{
+    WsNeeds w{};
+    w.ok = pack_needs(w, M, N, K, batch, dtype, b_trans, a_mis, b_mis);
+    if (!w.ok) return w;
+    // the problem as the kernels see it
+    const bool packed = w.d.pack;
+    const int64_t Kc = packed ? w.d.k : K;
+    w.fp = plan_fused(packed || !(a_mis || b_mis), M, N, Kc, batch, dtype, packed ? w.d.b_trans : b_trans, packed ? w.d.ldb : 0);
+    if (w.fp.split) {
+        w.products = (size_t)batch * (size_t)w.fp.slices.splits * (size_t)M * (size_t)N * sizeof(float);
+        w.rs_part = split_part_bytes(M, N, batch, want_rowsum);
+    } else {
+        const int64_t tiles_n = (N + w.fp.path.tile.bn - 1) / w.fp.path.tile.bn;
+        if ((long double)batch * tiles_n * M * 4.0L >= 1.8e19L) { w.ok = false; return w; }
+        w.rs_part = (want_rowsum && tiles_n > 1) ? (size_t)batch * (size_t)tiles_n * (size_t)M * sizeof(float) : 0;
+    }
+    lay_out(w);
+    return w;
+}
+
+WsNeeds splitk_needs(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int effective_splits, bool b_trans,
+                     bool want_rowsum, bool a_mis, bool b_mis)
+{
+    WsNeeds w{};
+    w.ok = pack_needs(w, M, N, K, batch, dtype, b_trans, a_mis, b_mis);
+    if (!w.ok) return w;
+    if ((long double)batch * effective_splits * M * N * sizeof(float) >= 1.8e19L) { w.ok = false; return w; }
+    w.products = (size_t)batch * (size_t)effective_splits * (size_t)M * (size_t)N * sizeof(float);
+    w.rs_part = split_part_bytes(M, N, batch, want_rowsum);
+    lay_out(w);
+    return w;
+}
+
+bool sizes_valid(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype)
+{
+    const void* ok = reinterpret_cast<const void*>(uintptr_t{256});
+    return validate_common(ok, ok, ok, M, N, K, batch, PGK_ACT_NONE, dtype) == PGK_OK;
+}
+
+// Zero-padded copies of the operands of a packed problem (see pack_dims) into the workspace
+// pieces w.off_a / w.off_b: A' [batch][M][d.k] when K is ragged or A misaligned, B' [batch][d.k][d.ldb]
+// (or Bt' [batch][N][d.k]) when K or its rows are ragged or B misaligned, or when a narrow plain
+// B is to be transposed (d.transpose_b; `b_trans` is the layout of the B given).
+struct PackedOperands { const void* A; const void* B; };
+
+int pack_operands(const WsNeeds& w, unsigned char* base, const void* A, const void* B, int64_t M, int64_t N, int64_t K,
+                  int64_t batch, int dtype, bool b_trans, hipStream_t st, PackedOperands* out)
+{
+    const PackDims& d = w.d;
     *out = PackedOperands{A, B};
     hipError_t e = hipSuccess;
-    if (pack_a) {
+    if (w.pack_a) {
+        unsigned char* p = base + w.off_a;
         e = pgk::launch_pad_matrix(A, p, batch, (int)M, (int)K, (int)M, (int)d.k, dtype, st);
         if (e != hipSuccess) return PGK_ERR_HIP;
-        out->A = p; p += a_bytes;
+        out->A = p;
     }
-    if (pack_b) {
+    if (w.pack_b) {
+        unsigned char* p = base + w.off_b;
         e = d.transpose_b ? pgk::launch_transpose_pad(B, p, batch, (int)K, (int)N, (int)d.ldb, dtype, st)
             : b_trans     ? pgk::launch_pad_matrix(B, p, batch, (int)N, (int)K, (int)N, (int)d.k, dtype, st)
                           : pgk::launch_pad_matrix(B, p, batch, (int)K, (int)N, (int)d.k, (int)d.ldb, dtype, st);
@@ -552,44 +565,50 @@ int pack_operands(const PackDims& d, const void* A, const void* B, int64_t M, in
     return PGK_OK;
 }
 
-int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
-                    int64_t K, int64_t batch, int act, int dtype, hipStream_t st, bool b_trans, int64_t ldb);
+int check_workspace(const WsNeeds& w, const void* workspace, size_t workspace_bytes)
+{
+    if (!w.ok) return PGK_ERR_UNSUPPORTED;
+    if (w.total == 0) return PGK_OK;
+    if (!workspace || workspace_bytes < w.total || !aligned16(workspace)) return PGK_ERR_WORKSPACE;
+    return PGK_OK;
+}
 
 // pgk_gemm_fused and pgk_gemm_fused_bt (b_trans: B given as [batch][N][K])
 int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, float* rowsum,
-                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream, bool b_trans)
+                    int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype,
+                    void* workspace, size_t workspace_bytes, void* stream, bool b_trans)
 {
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans, !aligned16(A) || !aligned16(B));
-    if (!d.pack) return gemm_fused_core(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, st, b_trans, 0);
-    PackedOperands pk{};
-    rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
+    const bool a_mis = !aligned16(A), b_mis = !aligned16(B);
+    const WsNeeds w = fused_needs(M, N, K, batch, dtype, b_trans, rowsum != nullptr, a_mis, b_mis);
+    rc = check_workspace(w, workspace, workspace_bytes);
     if (rc != PGK_OK) return rc;
-    return gemm_fused_core(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, st, d.b_trans, d.ldb);
-}
-
-int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, float* rowsum, int64_t M, int64_t N,
-                    int64_t K, int64_t batch, int act, int dtype, hipStream_t st, bool b_trans, int64_t ldb)
-{
-    const FusedPlan fp = plan_fused(A, B, bias, C, M, N, K, batch, dtype, b_trans, ldb);
+    const FusedPlan& fp = w.fp;
     const Path& path = fp.path;
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch > 2.0e9L) return PGK_ERR_UNSUPPORTED;
-
-    if (fp.split) {
-        const size_t ws_bytes = (size_t)batch * (size_t)fp.slices.splits * (size_t)M * (size_t)N * sizeof(float);
-        const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
-        float* buf = nullptr;
-        if (scratch_get(st, ws_bytes + part_bytes, &buf) != hipSuccess) return PGK_ERR_HIP;
-        return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, fp.slices, fp.split_small_tile, buf,
-                                buf + ws_bytes / sizeof(float), st, b_trans, ldb);
+    // ---- everything below enqueues work
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    PackedOperands pk{A, B};
+    int64_t ldb = 0;
+    bool aligned = !(a_mis || b_mis);
+    if (w.d.pack) {
+        rc = pack_operands(w, base, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
+        if (rc != PGK_OK) return rc;
+        K = w.d.k; b_trans = w.d.b_trans; ldb = w.d.ldb;
+        aligned = true;
     }
+    float* part = w.rs_part ? reinterpret_cast<float*>(base + w.off_rs_part) : nullptr;
+
+    if (fp.split)
+        return run_split_passes(pk.A, pk.B, bias, C, rowsum, M, N, K, batch, act, dtype, fp.slices, fp.split_small_tile,
+                                reinterpret_cast<float*>(base), part, st, aligned, b_trans, ldb);
 
     GemmArgs a{};
-    a.A = A; a.B = B; a.bias = bias; a.C = C; a.ws = nullptr;
+    a.A = pk.A; a.B = pk.B; a.bias = bias; a.C = C; a.ws = nullptr;
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = (int)batch;
     pgk::fill_plain_views(a);
     if (b_trans) pgk::set_b_transposed(a);
@@ -599,30 +618,13 @@ int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, fl
     a.k_slice = (int)(((K + path.tile.bk - 1) / path.tile.bk) * path.tile.bk);
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
-
-    float* part = nullptr;
-    if (rowsum) {
-        if (tiles_n == 1) {
-            a.rs_part = rowsum;
-        } else {
-            const size_t bytes = (size_t)batch * (size_t)tiles_n * (size_t)M * sizeof(float);
-            if (scratch_get(st, bytes, &part) != hipSuccess) return PGK_ERR_HIP;
-            a.rs_part = part;
-            // Small grids (latency-bound): the matrix-core kernel adds the partials itself, in the
-            // last workgroup of a tile row, and the second launch is saved.  Its device-scope
-            // fences write the whole L2 back, which on a large grid costs far more than the
-            // 4 us combine kernel (measured on the 16384 x 1024 x 4096 workload: 182 us against 139 us).
-            if (path.mfma && tiles_m * tiles_n * batch <= kFusedCombineMaxWorkgroups) {
-                if (counters_get(st, (size_t)batch * (size_t)tiles_m, &a.rs_counter) != hipSuccess) return PGK_ERR_HIP;
-                a.rowsum = rowsum;
-                part = nullptr;
-            }
-        }
-    }
+    // one tile column: the kernel's row sums are final; several: per-tile-column partials, added
+    // in tile-column order by a second small kernel
+    if (rowsum) a.rs_part = tiles_n == 1 ? rowsum : part;
     if (path.mfma) mark_k_rotation(a, dtype, path.tile);
     hipError_t e = path.mfma ? pgk::launch_gemm_mfma(a, dtype, path.kind, 0, st) : pgk::launch_gemm_guarded(a, dtype, 0, st);
     if (e != hipSuccess) return PGK_ERR_HIP;
-    if (part) {
+    if (rowsum && tiles_n > 1) {
         e = pgk::launch_rowsum_combine(part, rowsum, (int)M, (int)batch, (int)tiles_n, st);
         if (e != hipSuccess) return PGK_ERR_HIP;
     }
@@ -634,15 +636,25 @@ int gemm_fused_core(const void* A, const void* B, const float* bias, void* C, fl
 extern "C" {
 
 int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, float* rowsum,
-                   int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+                   int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype,
+                   void* workspace, size_t workspace_bytes, void* stream)
 {
-    return gemm_fused_impl(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, stream, false);
+    return gemm_fused_impl(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, workspace, workspace_bytes, stream, false);
 }
 
 int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C, float* rowsum,
-                      int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+                      int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype,
+                      void* workspace, size_t workspace_bytes, void* stream)
 {
-    return gemm_fused_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, stream, true);
+    return gemm_fused_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, workspace, workspace_bytes, stream, true);
+}
+
+size_t pgk_gemm_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int flags)
+{
+    if (!sizes_valid(M, N, K, batch, dtype) || (flags & ~(PGK_WS_ROWSUM | PGK_WS_B_TRANSPOSED | PGK_WS_UNALIGNED))) return 0;
+    const bool mis = (flags & PGK_WS_UNALIGNED) != 0;
+    const WsNeeds w = fused_needs(M, N, K, batch, dtype, (flags & PGK_WS_B_TRANSPOSED) != 0, (flags & PGK_WS_ROWSUM) != 0, mis, mis);
+    return w.ok ? w.total : 0;
 }
 
 int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int b_transposed, int32_t* out)
@@ -653,12 +665,12 @@ int pgk_gemm_plan(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int
     if (rc != PGK_OK) return rc;
     const PackDims d = pack_dims(M, N, K, dtype, b_transposed != 0);      // as pgk_gemm_fused sees the problem
     K = d.k;
-    const FusedPlan fp = plan_fused(ok, ok, nullptr, ok, M, N, K, batch, dtype, d.b_trans, d.ldb);
+    const FusedPlan fp = plan_fused(true, M, N, K, batch, dtype, d.b_trans, d.ldb);
     Path path = fp.path;
     int slices = 1;
     if (fp.split) {
         slices = fp.slices.splits;
-        path = choose_path(ok, ok, nullptr, ok, ok, M, N, K, dtype, batch * slices, fp.split_small_tile, d.b_trans, d.ldb);
+        path = choose_path(true, M, N, K, dtype, batch * slices, fp.split_small_tile, d.b_trans, d.ldb);
     }
     const long double wgs = (long double)((M + path.tile.bm - 1) / path.tile.bm) * ((N + path.tile.bn - 1) / path.tile.bn) *
                             batch * slices;
@@ -679,13 +691,22 @@ int pgk_splitk_auto_splits(int64_t M, int64_t N, int64_t K, int64_t batch, int d
     return plan_splits(M, N, K, batch, dtype, splits).splits;
 }
 
-size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
+size_t pgk_gemm_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits, int flags)
 {
+    if (!sizes_valid(M, N, K, batch, dtype) || (flags & ~(PGK_WS_ROWSUM | PGK_WS_B_TRANSPOSED | PGK_WS_UNALIGNED))) return 0;
     const int s = pgk_splitk_auto_splits(M, N, K, batch, dtype, splits);
     if (s <= 0) return 0;
-    const long double bytes = (long double)batch * s * M * N * sizeof(float);
-    if (bytes >= 1.8e19L) return 0;
-    return (size_t)batch * (size_t)s * (size_t)M * (size_t)N * sizeof(float);
+    const bool mis = (flags & PGK_WS_UNALIGNED) != 0;
+    const WsNeeds w = splitk_needs(M, N, K, batch, dtype, s, (flags & PGK_WS_B_TRANSPOSED) != 0, (flags & PGK_WS_ROWSUM) != 0, mis, mis);
+    return w.ok ? w.total : 0;
+}
+
+size_t pgk_splitk_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int splits)
+{
+    // enough for either layout of B, with or without row sums, operands on 16-byte boundaries
+    const size_t plain = pgk_gemm_splitk_workspace_bytes(M, N, K, batch, dtype, splits, PGK_WS_ROWSUM);
+    const size_t bt = pgk_gemm_splitk_workspace_bytes(M, N, K, batch, dtype, splits, PGK_WS_ROWSUM | PGK_WS_B_TRANSPOSED);
+    return plain > bt ? plain : bt;
 }
 
 }  // extern "C"
@@ -699,28 +720,27 @@ int gemm_splitk_impl(const void* A, const void* B, const float* bias, void* C, f
     int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
     if (rc != PGK_OK) return rc;
     if (splits < 0 || splits > K) return PGK_ERR_INVALID_ARG;
-    const size_t need = pgk_splitk_workspace_bytes(M, N, K, batch, dtype, splits);
-    if (need == 0) return PGK_ERR_UNSUPPORTED;
-    if (!workspace || workspace_bytes < need) return PGK_ERR_WORKSPACE;
-    if (!aligned16(workspace)) return PGK_ERR_WORKSPACE;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-
     const SplitPlan plan = plan_splits(M, N, K, batch, dtype, splits);
-    float* part = nullptr;
-    const size_t part_bytes = split_part_bytes(M, N, batch, rowsum != nullptr);
-    if (part_bytes && scratch_get(st, part_bytes, &part) != hipSuccess) return PGK_ERR_HIP;
+    const bool a_mis = !aligned16(A), b_mis = !aligned16(B);
+    const WsNeeds w = splitk_needs(M, N, K, batch, dtype, plan.splits, b_trans, rowsum != nullptr, a_mis, b_mis);
+    if (!w.ok) return PGK_ERR_UNSUPPORTED;
+    rc = check_workspace(w, workspace, workspace_bytes);
+    if (rc != PGK_OK) return rc;
+    // ---- everything below enqueues work
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    unsigned char* base = static_cast<unsigned char*>(workspace);
+    float* part = w.rs_part ? reinterpret_cast<float*>(base + w.off_rs_part) : nullptr;
     // an automatic plan comes with its tile; explicit splits get the tile their grid suggests
     const int small_tile = (splits == 0 && mfma_route(M, N, K, dtype)) ? auto_split(M, N, K, batch, dtype).kind : -1;
     // (the slices are counted in K steps, which padding K to whole chunks leaves as they are)
-    const PackDims d = pack_dims(M, N, K, dtype, b_trans, !aligned16(A) || !aligned16(B));
-    if (!d.pack)
+    if (!w.d.pack)
         return run_split_passes(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, plan, small_tile,
-                                static_cast<float*>(workspace), part, st, b_trans);
+                                reinterpret_cast<float*>(base), part, st, !(a_mis || b_mis), b_trans);
     PackedOperands pk{};
-    rc = pack_operands(d, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
+    rc = pack_operands(w, base, A, B, M, N, K, batch, dtype, b_trans, st, &pk);
     if (rc != PGK_OK) return rc;
-    return run_split_passes(pk.A, pk.B, bias, C, rowsum, M, N, d.k, batch, act, dtype, plan, small_tile,
-                            static_cast<float*>(workspace), part, st, d.b_trans, d.ldb);
+    return run_split_passes(pk.A, pk.B, bias, C, rowsum, M, N, w.d.k, batch, act, dtype, plan, small_tile,
+                            reinterpret_cast<float*>(base), part, st, true, w.d.b_trans, w.d.ldb);
 }
 
 }  // namespace
@@ -743,8 +763,20 @@ int pgk_gemm_splitk_bt(const void* A, const void* Bt, const float* bias, void* C
                             stream, true);
 }
 
+size_t pgk_reduce_max_workspace_bytes(int64_t outer, int64_t red, int64_t inner, int dtype)
+{
+    if (outer <= 0 || red <= 0 || inner <= 0 || (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16)) return 0;
+    if (red > (1LL << 31) - 1024) return 0;
+    if ((long double)outer * (long double)inner >= 4.6e18L ||
+        (long double)outer * (long double)inner * (long double)red >= 4.6e18L) return 0;
+    // (the plan depends on whether X starts on a 16-byte boundary: enough for either case)
+    const size_t a = pgk::plan_reduce_max(outer, red, inner, dtype, true).partial_elems;
+    const size_t b = pgk::plan_reduce_max(outer, red, inner, dtype, false).partial_elems;
+    return (a > b ? a : b) * 8;
+}
+
 int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_t red, int64_t inner,
-                   int dtype, void* stream)
+                   int dtype, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!X || !out || outer <= 0 || red <= 0 || inner <= 0) return PGK_ERR_INVALID_ARG;
     if (dtype != PGK_DTYPE_F32 && dtype != PGK_DTYPE_BF16) return PGK_ERR_INVALID_ARG;
@@ -757,7 +789,10 @@ int pgk_reduce_max(const void* X, void* out, int32_t* idx, int64_t outer, int64_
     float* pv = nullptr;
     int* pi = nullptr;
     if (pl.partial_elems) {
-        if (scratch_get(st, pl.partial_elems * 8, &pv) != hipSuccess) return PGK_ERR_HIP;
+        // segment results (value, position) of the first pass
+        if (!workspace || workspace_bytes < pl.partial_elems * 8 || (reinterpret_cast<uintptr_t>(workspace) & 3u))
+            return PGK_ERR_WORKSPACE;
+        pv = static_cast<float*>(workspace);
         pi = reinterpret_cast<int*>(pv + pl.partial_elems);
     }
     const hipError_t e = pgk::launch_reduce_max(pl, X, out, idx, pv, pi, outer, red, inner, dtype, st);
@@ -973,7 +1008,7 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
                 ldb = pl.Lp;
             }
         }
-        const Path path = choose_path(wr, bsrc, bias, y, nullptr, Cout, pl.Lout, cin_k * Kw, dtype, B, pl.kind, false, ldb);
+        const Path path = choose_path(aligned16(wr) && aligned16(bsrc), Cout, pl.Lout, cin_k * Kw, dtype, B, pl.kind, false, ldb);
         if (!path.mfma) return PGK_ERR_UNSUPPORTED;   // the plan has checked what the kernel needs
         a.A = wr; a.B = bsrc;
         a.a_batch_stride = 0;
@@ -1022,25 +1057,6 @@ int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stre
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
-int pgk_release_scratch(void)
-{
-    std::lock_guard<std::mutex> lk(g_mu);
-    int rc = PGK_OK;
-    for (auto& kv : g_scratch)
-        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
-    for (auto& kv : g_counters)
-        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
-    g_counters.clear();
-    for (auto& kv : g_pack)
-        if (kv.second.ptr && hipFree(kv.second.ptr) != hipSuccess) rc = PGK_ERR_HIP;
-    g_pack.clear();
-    for (void* p : g_retired)
-        if (hipFree(p) != hipSuccess) rc = PGK_ERR_HIP;
-    g_scratch.clear();
-    g_retired.clear();
-    return rc;
-}
-
 const char* pgk_status_string(int status)
 {
     switch (status) {
@@ -1053,6 +1069,6 @@ const char* pgk_status_string(int status)
     }
 }
 
-int pgk_version(void) { return 100; }
+int pgk_version(void) { return 200; }
 
 }  // extern "C"

@@ -1,891 +1,8 @@
-// Matrix-core GEMM main loop with the fused epilogue, for gfx950 (MI355X).
-//
-// The operator is the textbook one the paper's matmul / activation / reduction
-// categories refer to (PRAGMA Sections 1 and 4.2): C = act(A*B + bias) with an
-// optional row sum.  Everything about how it is computed below is this
-// library's own design for CDNA4:
-//
-//  * One workgroup owns a BM x BN tile of C.  A and B tiles of BK along K are
-//    copied global -> LDS with 128-bit direct-to-LDS loads into a two-stage
-//    ring, so the copy of tile kt+1 overlaps the matrix-core work on tile kt.
-//  * LDS rows are stored in 16-byte chunks whose position is XOR-swizzled with
-//    the row index; the direct-to-LDS write is always one contiguous 1 KiB per
-//    wave instruction, so the swizzle is applied by choosing which global chunk
-//    each lane fetches.
-//  * MFMA operand roles are swapped (the B-matrix columns feed the "A" operand
-//    and the A-matrix rows the "B" operand), so the accumulator tile a lane holds
-//    is one row of C with runs of 4 consecutive columns.  Row sums are then
-//    mostly in-lane adds, bias loads and C stores are 4 elements wide.
-//  * bf16: v_mfma_f32_32x32x16_bf16.  A rows are K-contiguous in LDS
-//    (ds_read_b128); B is N-contiguous, so its operand is gathered with the
-//    transposing ds_read_b64_tr_b16.
-//  * fp32: v_mfma_f32_32x32x2_f32.
-//  * Workgroup ids are remapped so that each XCD (own L2) works on a compact
-//    group of tiles.
-#include <hip/hip_runtime.h>
-
-#include <type_traits>
-
-#include "pgk_device.h"
-#include "pgk_kernels.h"
+// Matrix-core GEMM kernels, plain operand views: instances, tile table and launcher.
+// The kernel template is in pgk_gemm_mfma_kernel.h.
+#include "pgk_gemm_mfma_kernel.h"
 
 namespace pgk {
-
-template <bool BT_, bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
-struct MfmaCfgBase {
-    static constexpr bool BF16 = BF16_;
-    // B given transposed, [N][K] with K contiguous (a linear layer's weight as stored): its
-    // tile then sits in LDS like the A tile, [BN][BK], and is fetched like it
-    static constexpr bool BT = BT_;
-    static constexpr int BM = BM_, BN = BN_, BK = BK_, WGM = WGM_, WGN = WGN_;
-    // LDS ring depth of the A tiles (2 or 3); the B tiles always have 2 stages.  With 3,
-    // the copy of an A tile is issued a whole K tile earlier than it is needed, so only
-    // the B half of the traffic has to land within one tile's worth of MFMAs.
-    static constexpr int A_STAGES = A_STAGES_;
-    // waves the register allocation must leave room for on one SIMD
-    static constexpr int WAVES_PER_SIMD = WAVES_PER_SIMD_;
-    static constexpr int ES = BF16_ ? 2 : 4;       // element bytes
-    static constexpr int NW = WGM * WGN;           // waves per workgroup
-    static constexpr int NT = NW * 64;             // threads per workgroup
-    static constexpr int WM = BM / WGM;            // rows per wave
-    static constexpr int WN = BN / WGN;            // cols per wave
-    static constexpr int TM = WM / 32, TN = WN / 32;
-    static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
-    static constexpr int RB = BT ? BK * ES : BN * ES;   // LDS row bytes of the B tile
-    static constexpr int A_BYTES = BM * RA, B_BYTES = BN * BK * ES;
-    static constexpr int A_CPW = A_BYTES / 1024 / NW;  // 1 KiB copy instructions per wave
-    static constexpr int B_CPW = B_BYTES / 1024 / NW;
-    static constexpr int A_CPR = RA / 16, B_CPR = RB / 16;  // 16 B chunks per row
-    static constexpr int A_RPC = 1024 / RA, B_RPC = 1024 / RB;  // rows per 1 KiB
-    static constexpr int LDS_BYTES = A_STAGES * A_BYTES + 2 * B_BYTES;
-    // the epilogue stages the output tile in the operand buffers, in pieces the size of the
-    // larger kind (the B stages first when the B tile is the larger one: skinny-M tiles)
-    static constexpr bool STAGE_IN_B = B_BYTES > A_BYTES;
-    static constexpr int PIECE_BYTES = STAGE_IN_B ? B_BYTES : A_BYTES;
-    static_assert(A_STAGES == 2 || A_STAGES == 3, "A ring depth");
-    static_assert(LDS_BYTES <= 160 * 1024, "LDS of one CU");
-    static_assert(RA == 128 || RA == 64, "A-tile swizzle assumes 128- or 64-byte rows");
-    static_assert(BT || RB % 256 == 0, "B-tile swizzle assumes rows of a multiple of 256 bytes");
-    static_assert(A_BYTES % (1024 * NW) == 0 && B_BYTES % (1024 * NW) == 0, "tile / wave split");
-    static_assert(BM <= NT, "row-sum combine uses one thread per tile row");
-};
-// <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>: B as [K][N] ...
-template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
-struct MfmaCfg : MfmaCfgBase<false, BF16_, BM_, BN_, BK_, WGM_, WGN_, A_STAGES_, WAVES_PER_SIMD_> {};
-// ... and B given transposed, [N][K]
-template <bool BF16_, int BM_, int BN_, int BK_, int WGM_, int WGN_, int A_STAGES_, int WAVES_PER_SIMD_>
-struct MfmaCfgBt : MfmaCfgBase<true, BF16_, BM_, BN_, BK_, WGM_, WGN_, A_STAGES_, WAVES_PER_SIMD_> {};
-
-// A tile: rows of CPR chunks; 16 consecutive rows read the same logical chunk
-// at once, so the 16 chunk slots of a 256-byte bank period must all differ.
-template <int CPR>
-__device__ __forceinline__ int swz_a(int row) { return (row / (16 / CPR)) % CPR; }
-template <bool BF16>
-__device__ __forceinline__ int swz_b(int krow)
-{
-    // bf16: the transposing read of a 16-lane group touches 4 consecutive k rows;
-    // fp32: the two half-waves read rows 4 apart.
-    return BF16 ? 4 * (krow & 3) : 8 * ((krow >> 2) & 1);
-}
-
-// Epilogue, part 1: bias + activation on the accumulators, row-sum contribution, and
-// the output tile written to LDS in the output element type.  A lane's accumulators
-// are rows of C in runs of 4 consecutive columns (8 bytes as bf16, 16 bytes as fp32);
-// such a run is one "unit".  The tile is spread over (up to) four operand buffers of
-// the main loop, whole rows of BN elements each; inside a row the unit index is
-// XORed with twice the row index, so that the 32 rows a wave writes at once fall in
-// different banks, and so that the pair of units forming a 16-byte chunk stays
-// adjacent for part 2.
-// `bias` / `bias_row`: this tile's column or row biases, already in LDS (see the kernel).
-// PLAIN: no row bias and no row sum (the caller guarantees bias_row == rs_lds == nullptr), so
-// the per-element work is one add, the activation and the rounding -- the large GEMMs' case.
-// HAS_BIAS false: `bias` is not read (the split-K partial products).
-template <int ACT, bool OUT_BF16, bool PLAIN, typename Cfg, bool HAS_BIAS = true>
-__device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
-                                                const float* bias_row,
-                                                int n_rem, int wm, int wn, int lane,
-                                                unsigned char* const (&obj)[4], float* rs_lds)
-{
-    constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int UB = OUT_BF16 ? 8 : 16;                 // bytes per unit
-    constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
-    constexpr int UNITS = ROW_BYTES / UB;                 // units per row
-    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
-    const int half = lane >> 5;
-    const int row_in = lane & 31;
-    // per accumulator block row: where its output row is staged, its row bias, its row sum
-    // Block by block (32 rows x 32 columns of the wave's part): the lane's sixteen column
-    // biases of the block are fetched together, one LDS round trip per block instead of one
-    // per group of four outputs.  `bias` always points at staged values, zero when the call has
-    // no column bias.
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        float rs = 0.0f;
-        const int row = wm * Cfg::WM + 32 * i + row_in;   // row inside the tile
-        const int o = (wm * Cfg::WM + 32 * i) / ROWS_PER_OBJ;
-        unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
-                              (row % ROWS_PER_OBJ) * ROW_BYTES;
-        const int key = (2 * row) % UNITS;
-        // bias added to rows instead of columns: staged in LDS, zero past the edge
-        const float br = (!PLAIN && bias_row) ? bias_row[row] : 0.0f;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            f32x4 bvs[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                if constexpr (HAS_BIAS) bvs[g] = *(const f32x4*)(bias + wn * Cfg::WN + 32 * j + 8 * g + 4 * half);
-                else bvs[g] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
-                // columns past the end of a ragged N add nothing to the row sum
-                const f32x4 bv = bvs[g];
-                float y[4];
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    if constexpr (PLAIN) {
-                        y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
-                    } else {
-                        y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e] + br);
-                        rs += col + e < n_rem ? y[e] : 0.0f;
-                    }
-                }
-                unsigned char* dst = base + (((col >> 2) ^ key) * UB);
-                if constexpr (OUT_BF16) {
-                    u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-                    *(u32x2*)dst = pk;
-                } else {
-                    f32x4 v = {y[0], y[1], y[2], y[3]};
-                    *(f32x4*)dst = v;
-                }
-            }
-            // keeps the next block's bias fetches below this block's work: hoisting all of
-            // them to the top would cost 64 registers
-            asm volatile("" ::: "memory");
-        }
-        if (!PLAIN && rs_lds) {
-            rs += __shfl_xor(rs, 32);
-            if (half == 0) rs_lds[wn * Cfg::BM + row] = rs;
-        }
-    }
-}
-
-// Epilogue, part 2: the staged tile goes to global memory as whole rows: a wave
-// instruction stores 64 x 16 bytes = complete 128-byte lines of consecutive rows.
-// STREAM: the output is not read again soon (C, as opposed to split-K partial products):
-// non-temporal stores, which leave the operand panels in L2 alone (measured with rotating
-// buffers: 8192 x 8192 x 1024 bf16 176 -> 166 us, x 8192 809 -> 803 us, conv1d 524 -> 509 us).
-template <bool OUT_BF16, typename Cfg, bool STREAM>
-__device__ __forceinline__ void epilogue_store(unsigned char* out_tile, size_t ld_bytes, int tid,
-                                               int m_rem, int n_rem, unsigned char* const (&obj)[4])
-{
-    constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
-    constexpr int CPR = ROW_BYTES / 16;                   // 16-byte chunks per row
-    constexpr int UB = OUT_BF16 ? 8 : 16;
-    constexpr int UNITS = ROW_BYTES / UB;
-    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
-    constexpr int ROWS_PER_IT = Cfg::NT / CPR;
-    constexpr int ITERS = Cfg::BM / ROWS_PER_IT;
-    static_assert(ROWS_PER_OBJ % ROWS_PER_IT == 0, "an iteration stays inside one buffer");
-    const int c = tid % CPR;
-    // all of the thread's chunks are read from LDS first (one round trip), then stored; the
-    // scheduling barrier keeps the compiler from sinking each read into its store's branch
-    u32x4 v[ITERS];
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int row = it * ROWS_PER_IT + tid / CPR;
-        const int o = (it * ROWS_PER_IT) / ROWS_PER_OBJ;  // compile-time after unrolling
-        const unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
-                                    (row % ROWS_PER_OBJ) * ROW_BYTES;
-        const int key = (2 * row) % UNITS;
-        const int unit = OUT_BF16 ? ((2 * c) ^ key) : (c ^ key);
-        v[it] = *(const u32x4*)(base + unit * UB);
-    }
-    __builtin_amdgcn_sched_barrier(0);
-    // N need not be a multiple of the 16-byte chunk: the row's last chunk may hold fewer
-    // elements, which are then stored one by one, and rows start on element boundaries only
-    // (the 16-byte stores are declared with that alignment; global memory takes them as they are)
-    using chunk_at_element = typename std::conditional<OUT_BF16, u32x4_align2, u32x4_align4>::type;
-    constexpr int EPC = 16 / (OUT_BF16 ? 2 : 4);
-    const int left = n_rem - c * EPC;                  // elements of this chunk that exist
-#pragma unroll
-    for (int it = 0; it < ITERS; ++it) {
-        const int row = it * ROWS_PER_IT + tid / CPR;
-        if (row >= m_rem || left <= 0) continue;
-        unsigned char* at = out_tile + (size_t)row * ld_bytes + (size_t)c * 16;
-        if (left >= EPC) {
-            if constexpr (STREAM) __builtin_nontemporal_store(v[it], (chunk_at_element*)at);
-            else *(chunk_at_element*)at = v[it];
-        } else {
-#pragma unroll
-            for (int e = 0; e < EPC - 1; ++e) {
-                if (e >= left) break;
-                const unsigned int word = v[it][OUT_BF16 ? e / 2 : e];
-                if constexpr (OUT_BF16) ((unsigned short*)at)[e] = (unsigned short)(e % 2 ? word >> 16 : word & 0xffffu);
-                else ((unsigned int*)at)[e] = word;
-            }
-        }
-    }
-}
-
-template <int V>
-struct IC { static constexpr int value = V; };
-
-template <typename Cfg>
-__global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel(const GemmArgs p, const int out_mode)
-{
-#if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub (and has no buffer-resource type)
-    constexpr bool BF16 = Cfg::BF16;
-    constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ES = Cfg::ES;
-    constexpr int TM = Cfg::TM, TN = Cfg::TN, RA = Cfg::RA, RB = Cfg::RB;
-    constexpr int NS = BF16 ? BK / 16 : BK / 8;   // operand-fetch steps per K tile
-    static_assert(NS % 2 == 0, "fragment double buffer assumes an even step count");
-
-    // Separate LDS objects per stage and operand (not one array indexed by stage): the
-    // compiler can then tell that a direct-to-LDS copy into one stage does not alias
-    // the operand reads of another stage, and does not make those reads wait for it.
-    constexpr int SA = Cfg::A_STAGES;
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a0[Cfg::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a1[Cfg::A_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_a2[SA > 2 ? Cfg::A_BYTES : 16];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_b0[Cfg::B_BYTES];
-    __shared__ __attribute__((aligned(1024))) unsigned char lds_b1[Cfg::B_BYTES];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
-
-    // ---- which tile, batch entry and K slice this workgroup owns
-    const unsigned int tiles = (unsigned int)p.tiles_m * (unsigned int)p.tiles_n;
-    const unsigned int logical = xcd_remap(blockIdx.x, gridDim.x);
-    const unsigned int z = logical / tiles;
-    int tm, tn;
-    tile_coords(logical - z * tiles, p.tiles_m, p.tiles_n, p.group_m, tm, tn);
-    const int b = (int)(z / (unsigned int)p.splits);
-    const int sp = (int)(z - (unsigned int)b * (unsigned int)p.splits);
-    const int k_begin = sp * p.k_slice;
-    const int k_end = (k_begin + p.k_slice < p.K) ? (k_begin + p.k_slice) : p.K;
-    // K tiles of this slice; the last one may be partial (K need not be a multiple of BK, nor
-    // of the 16-byte chunk: operand rows only have to start on 4-byte boundaries): k_last of
-    // its BK columns exist
-    const int KT = (k_end - k_begin + BK - 1) / BK;
-    const int k_last = (k_end - k_begin) - (KT - 1) * BK;
-    // (a last tile that is full is treated the same way when the rows of a plain B are not
-    // whole chunks: the copy of its last row must end where the array ends)
-    const bool k_partial = k_last < BK || p.b_tail_bounded;
-    // Memory-bound skinny products: every workgroup walks its K tiles from a different starting
-    // tile (and wraps around).  With row strides that are large powers of two, workgroups that
-    // all start at tile 0 and move in step keep asking the same few memory channels
-    // (bf16 16384 x 16 x 16384, rows 32 KiB apart: 4.0 TB/s; with rows of 32896 bytes 5.4 TB/s).
-    // Only with whole K tiles (the peeled partial tile has to come last) and plain GEMM views.
-    // (The workgroups of one batch entry share its small operand through L2 and stay in step;
-    // the batch entries start apart.  A single entry: every tile on its own.)
-    const int k_rot = (p.k_rotate && !k_partial) ? (int)((unsigned int)(p.batch > 1 ? b : tm + tn) % (unsigned int)KT) : 0;
-    auto k_tile_at = [&](int kt) __attribute__((always_inline)) -> int {      // the K tile processed in step kt
-        const int kk = kt + k_rot;
-        return kk >= KT ? kk - KT : kk;
-    };
-
-    const unsigned char* Ag = (const unsigned char*)p.A +
-        ((size_t)b * (size_t)p.a_batch_stride + (size_t)tm * BM * p.K + (size_t)k_begin) * ES;
-    // where this tile column's B operand lives: the B array itself, its columns shifted by
-    // b_col_shift (0 for a GEMM), or, for an edge tile column of a convolution, a strip
-    const unsigned char* b_src = (const unsigned char*)p.B;
-    int ldb = p.ldb;
-    long long b_batch_stride = p.b_batch_stride;
-    long long b_col0 = (long long)tn * BN + p.b_col_shift;
-#pragma unroll
-    for (int e = 0; e < 3; ++e) {
-        if (p.edge_B[e] && p.edge_tn[e] == tn) {
-            b_src = (const unsigned char*)p.edge_B[e];
-            ldb = p.edge_ldb;
-            b_batch_stride = p.edge_batch_stride;
-            b_col0 = 0;
-        }
-    }
-    // (transposed B: rows are tile columns, K runs along them)
-    const unsigned char* Bg = b_src +
-        (Cfg::BT ? ((long long)b * b_batch_stride + b_col0 * ldb + (long long)k_begin) * ES
-                 : ((long long)b * b_batch_stride + (long long)k_begin * ldb + b_col0) * ES);
-    const size_t a_step = (size_t)BK * ES;             // bytes per K tile along an A row
-    const size_t b_step = Cfg::BT ? (size_t)BK * ES : (size_t)BK * ldb * ES;   // bytes per K tile of B
-    // one past the last byte of A and of B: copies of a partial K tile run past the end of a
-    // row (into the next row, harmless) and, for the last row, past the end of the array,
-    // where the buffer resource's size check makes them read nothing
-    const unsigned char* const A_end = (const unsigned char*)p.A +
-        ((size_t)(p.batch - 1) * (size_t)p.a_batch_stride + (size_t)p.M * p.K) * ES;
-    const unsigned char* const B_end = (const unsigned char*)p.B +
-        ((size_t)(p.batch - 1) * (size_t)p.b_batch_stride + (size_t)(Cfg::BT ? p.N : p.K) * p.ldb) * ES;
-
-    // rows / columns of this tile that exist (smaller than the tile on a ragged edge)
-    const int m_rem = (p.M - tm * BM) < BM ? (p.M - tm * BM) : BM;
-    const int n_rem = (p.N - tn * BN) < BN ? (p.N - tn * BN) : BN;
-
-    // this tile's biases (one per column, or one per row), one value per thread, fetched now
-    // and handed out through LDS in the epilogue
-    constexpr int BIAS_N = BM > BN ? BM : BN;
-    static_assert(BIAS_N <= Cfg::NT, "one thread per bias value");
-    float bias_pre = 0.0f;
-    if (p.bias && out_mode == 0) {
-        if (p.bias_per_row) { if (tid < m_rem) bias_pre = p.bias[(size_t)tm * BM + tid]; }
-        else if (tid < n_rem) bias_pre = p.bias[(size_t)tn * BN + tid];
-    }
-
-    // ---- per-lane byte offsets of the global chunks this lane copies
-    unsigned int voff_a[Cfg::A_CPW], voff_b[Cfg::B_CPW];
-#pragma unroll
-    for (int t = 0; t < Cfg::A_CPW; ++t) {
-        const int ch = wave * Cfg::A_CPW + t;
-        const int r = ch * Cfg::A_RPC + lane / Cfg::A_CPR;
-        const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
-        // rows past the end of A (last tile row of a ragged M) re-read the last valid row:
-        // they only feed output rows that are never stored
-        const int rg = r < m_rem ? r : m_rem - 1;
-        voff_a[t] = (unsigned int)rg * (unsigned int)p.K * ES + (unsigned int)c * 16u;
-    }
-#pragma unroll
-    for (int t = 0; t < Cfg::B_CPW; ++t) {
-        const int ch = wave * Cfg::B_CPW + t;
-        if constexpr (Cfg::BT) {
-            // rows of the transposed B are tile columns: same scheme as for A
-            const int r = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
-            const int c = (lane % Cfg::B_CPR) ^ swz_a<Cfg::B_CPR>(r);
-            const int rg = r < n_rem ? r : n_rem - 1;
-            voff_b[t] = (unsigned int)rg * (unsigned int)ldb * ES + (unsigned int)c * 16u;
-        } else {
-            const int kr = ch * Cfg::B_RPC + lane / Cfg::B_CPR;
-            const int c = (lane % Cfg::B_CPR) ^ swz_b<BF16>(kr);
-            // likewise column chunks past the end of B.  (When the rows are not whole 16-byte
-            // chunks, the row's last, partly filled chunk is read together with the start of the
-            // next row, which only feeds output columns that do not exist; at the end of the
-            // array the buffer resource cuts it off.)
-            constexpr int EPC = 16 / ES;                      // elements per chunk
-            const int cg = c * EPC < n_rem ? c : (n_rem + EPC - 1) / EPC - 1;
-            voff_b[t] = (unsigned int)kr * (unsigned int)ldb * ES + (unsigned int)cg * 16u;
-        }
-    }
-
-    auto lds_a = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
-        constexpr int v = decltype(st)::value;
-        if constexpr (v == 0) return lds_a0; else if constexpr (v == 1) return lds_a1; else return lds_a2;
-    };
-    auto lds_b = [&](auto st) __attribute__((always_inline)) -> unsigned char* {
-        if constexpr (decltype(st)::value == 0) return lds_b0; else return lds_b1;
-    };
-
-    // global -> LDS copies of K tile kt: the A part into A stage `st`, the B part into
-    // B stage `st`; instruction t of this wave's share (one contiguous 1 KiB of LDS each).
-    // Buffer addressing: a scalar resource whose base is this K tile of the workgroup's
-    // A (or B) panel, plus the lane's constant 32-bit byte offset -- no vector ALU work
-    // per copy.  The resource covers 4 GiB from its base; lane offsets stay below that
-    // (checked on the host).
-    // `bounded`: the resource ends where the array ends instead of 4 GiB after its base
-    // (partial last K tile only; out-of-range lanes then fetch nothing).
-    auto records = [](const unsigned char* base, const unsigned char* end, bool bounded) __attribute__((always_inline)) -> int {
-        const size_t left = (size_t)(end - base);
-        return (bounded && left < 0xffffffffull) ? (int)(unsigned int)left : (int)0xffffffffu;
-    };
-    auto copy_a_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
-        unsigned char* la = lds_a(st) + wave * (Cfg::A_CPW * 1024);
-        const unsigned char* base = Ag + (size_t)k_tile_at(kt) * a_step;
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, A_end, bounded), 0x00020000),
-            PGK_LDS(la + t * 1024), 16, voff_a[t], 0, 0, 0);
-    };
-    // B tiles are copied in K order, one after the other, so where the next one starts is
-    // kept as running state: b_step further down, except that after every b_tiles_per_tap
-    // tiles (never, for a plain GEMM) the rows start over and the columns move on by
-    // b_tap_step elements -- a convolution read as a sum of shifted GEMMs, tap after tap.
-    size_t b_next_off = p.b_use_tap_table ? (size_t)p.b_tap_off[0] : 0;
-    int b_next_row_tile = 0, b_taps_done = 0;
-    const long long b_tap_jump = (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step;
-    auto copy_b_op = [&](int kt, auto st, int t, bool bounded) __attribute__((always_inline)) {
-        unsigned char* lb = lds_b(st) + wave * (Cfg::B_CPW * 1024);
-        const unsigned char* base = Bg + (p.k_rotate ? (size_t)k_tile_at(kt) * b_step : b_next_off);
-        __builtin_amdgcn_raw_ptr_buffer_load_lds(
-            __builtin_amdgcn_make_buffer_rsrc((void*)base, 0, records(base, B_end, bounded), 0x00020000),
-            PGK_LDS(lb + t * 1024), 16, voff_b[t], 0, 0, 0);
-        if (t == Cfg::B_CPW - 1) {        // the tile's last piece: move on to the next tile
-            b_next_off += b_step;
-            if (++b_next_row_tile == p.b_tiles_per_tap) {
-                b_next_row_tile = 0;
-                ++b_taps_done;
-                // (the last advance comes after the final tile: the index is kept inside the table)
-                if (p.b_use_tap_table) b_next_off = (size_t)p.b_tap_off[b_taps_done < 32 ? b_taps_done : 31];
-                else b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
-            }
-        }
-    };
-    auto copy_a = [&](int kt, auto st) __attribute__((always_inline)) {
-#pragma unroll
-        for (int t = 0; t < Cfg::A_CPW; ++t) copy_a_op(kt, st, t, k_partial && kt == KT - 1);
-    };
-    auto copy_b = [&](int kt, auto st) __attribute__((always_inline)) {
-#pragma unroll
-        for (int t = 0; t < Cfg::B_CPW; ++t) copy_b_op(kt, st, t, k_partial && kt == KT - 1);
-    };
-    // The columns of a partial last K tile that do not exist: the copy has put whatever
-    // follows the row in memory there (A elements at or beyond k_last, B rows at or beyond
-    // k_last).  Each lane clears them in the 16-byte pieces it copied itself -- a whole piece,
-    // or the upper elements of the piece that k_last falls into; call after the wait for the
-    // copies and before the barrier that publishes the tile.
-    auto clear_from = [&](unsigned char* piece, int keep) __attribute__((always_inline)) {   // keep: elements that stay
-        constexpr int EPC = 16 / ES;
-        auto* q = (__attribute__((address_space(3))) u32x4*)PGK_LDS(piece);
-        if (keep <= 0) {
-            const u32x4 zero = {0u, 0u, 0u, 0u};
-            *q = zero;
-        } else if (keep < EPC) {
-            u32x4 v = *q;
-            const int keep_bytes = keep * ES;
-#pragma unroll
-            for (int d = 0; d < 4; ++d)
-                v[d] &= keep_bytes >= 4 * d + 4 ? 0xffffffffu : keep_bytes <= 4 * d ? 0u : 0x0000ffffu;
-            *q = v;
-        }
-    };
-    auto zero_k_tail = [&](auto sta, auto stb) __attribute__((always_inline)) {
-        constexpr int EPC = 16 / ES;
-#pragma unroll
-        for (int t = 0; t < Cfg::A_CPW; ++t) {
-            const int r = (wave * Cfg::A_CPW + t) * Cfg::A_RPC + lane / Cfg::A_CPR;
-            const int c = (lane % Cfg::A_CPR) ^ swz_a<Cfg::A_CPR>(r);
-            clear_from(lds_a(sta) + wave * (Cfg::A_CPW * 1024) + t * 1024 + lane * 16, k_last - c * EPC);
-        }
-#pragma unroll
-        for (int t = 0; t < Cfg::B_CPW; ++t) {
-            const int kr = (wave * Cfg::B_CPW + t) * Cfg::B_RPC + lane / Cfg::B_CPR;
-            const int cb = (lane % Cfg::B_CPR) ^ swz_a<Cfg::B_CPR>(kr);   // transposed B: kr is a tile column
-            clear_from(lds_b(stb) + wave * (Cfg::B_CPW * 1024) + t * 1024 + lane * 16,
-                       Cfg::BT ? k_last - cb * EPC : (kr >= k_last ? 0 : EPC));
-        }
-    };
-
-    // ---- per-lane LDS read offsets
-    const int half = lane >> 5;     // which K half of the MFMA operand this lane feeds
-    const int l32 = lane & 31;
-    // A rows (MFMA "B" operand): row = wave row base + 32 i + l32, logical chunk 2 s + half
-    const int a_row_off = (wm * Cfg::WM + l32) * RA;
-    int a_koff[NS];                 // per step: row offset + swizzled chunk offset (bytes)
-#pragma unroll
-    for (int s = 0; s < NS; ++s) a_koff[s] = a_row_off + (((2 * s + half) ^ swz_a<Cfg::A_CPR>(l32)) * 16);
-    // B columns (MFMA "A" operand)
-    int b_off[Cfg::BT ? NS : TN];
-    if constexpr (Cfg::BT) {
-        // transposed B: column n of B is row n of the LDS tile; per step like a_koff
-#pragma unroll
-        for (int s = 0; s < NS; ++s)
-            b_off[s] = (wn * Cfg::WN + l32) * RB + (((2 * s + half) ^ swz_a<Cfg::B_CPR>(l32)) * 16);
-    } else if constexpr (BF16) {
-        const int grp = lane >> 4, pl = lane & 15;
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = wn * Cfg::WN + 32 * j + 16 * (grp & 1) + 4 * (pl & 3);
-            const int krow = 8 * (grp >> 1) + (pl >> 2);
-            const int c = (n >> 3) ^ swz_b<true>(krow);
-            b_off[j] = krow * RB + c * 16 + (n & 7) * 2;
-        }
-    } else {
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = wn * Cfg::WN + 32 * j + l32;
-            const int krow = 4 * half;
-            const int c = (n >> 2) ^ swz_b<false>(krow);
-            b_off[j] = krow * RB + c * 16 + (n & 3) * 4;
-        }
-    }
-
-    // Operand fragments for one step.  bf16: one step = one MFMA K (16); the B
-    // operand arrives as two transposing 64-bit reads.  fp32: one step = 8 K values =
-    // four MFMAs per tile pair.
-    // Transposed B: its fragments look like A's (one 128-bit read per 32 columns and step).
-    struct FragBF16 { bf16x8 a[TM]; s16x4 blo[TN], bhi[TN]; };
-    struct FragF32 { f32x4 a[TM]; float b[4][TN]; };
-    struct FragBF16T { bf16x8 a[TM]; bf16x8 bt[TN]; };
-    struct FragF32T { f32x4 a[TM]; f32x4 bt[TN]; };
-    using Frag = typename std::conditional<Cfg::BT, typename std::conditional<BF16, FragBF16T, FragF32T>::type,
-                                           typename std::conditional<BF16, FragBF16, FragF32>::type>::type;
-
-    // LDS fetches of one step, numbered in the order the MFMAs need them (the MFMAs
-    // run over the A fragments in the outer loop): A fragment 0, every B fragment,
-    // then the remaining A fragments.
-    constexpr int N_DS = Cfg::BT ? TM + TN : BF16 ? TM + 2 * TN : TM + 4 * TN;
-    auto fetch_op = [&](auto sta, auto stb, int s, Frag& f, int q) __attribute__((always_inline)) {
-        const unsigned char* as = lds_a(sta);
-        const unsigned char* bs = lds_b(stb);
-        constexpr int NB = Cfg::BT ? TN : BF16 ? 2 * TN : 4 * TN;
-        if (q == 0 || q > NB) {
-            const int i = q == 0 ? 0 : q - NB;
-            if constexpr (BF16)
-                f.a[i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
-            else
-                f.a[i] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
-        } else if constexpr (Cfg::BT) {
-            const int j = q - 1;
-            if constexpr (BF16)
-                f.bt[j] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
-            else
-                f.bt[j] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
-        } else if constexpr (BF16) {
-            const int j = (q - 1) / 2, h = (q - 1) % 2;
-            const unsigned char* src = bs + b_off[j] + (16 * s + 4 * h) * RB;
-            s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)PGK_LDS(src));
-            if (h == 0) f.blo[j] = v; else f.bhi[j] = v;
-        } else {
-            const int t = (q - 1) / TN, j = (q - 1) % TN;
-            f.b[t][j] = *(const __attribute__((address_space(3))) float*)PGK_LDS(bs + b_off[j] + (8 * s + t) * RB);
-        }
-    };
-    auto read_frags = [&](auto sta, auto stb, int s, Frag& f) __attribute__((always_inline)) {
-#pragma unroll
-        for (int q = 0; q < N_DS; ++q) fetch_op(sta, stb, s, f, q);
-    };
-
-    f32x16 acc[TM][TN];
-#pragma unroll
-    for (int i = 0; i < TM; ++i)
-#pragma unroll
-        for (int j = 0; j < TN; ++j)
-#pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
-
-    // MFMA number m of a step (A fragments in the outer loop)
-    constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
-    auto mfma_op = [&](const Frag& f, int m) __attribute__((always_inline)) {
-        if constexpr (Cfg::BT && BF16) {
-            const int i = m / TN, j = m % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.bt[j], f.a[i], acc[i][j], 0, 0, 0);
-        } else if constexpr (Cfg::BT) {
-            const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.bt[j][t], f.a[i][t], acc[i][j], 0, 0, 0);
-        } else if constexpr (BF16) {
-            const int i = m / TN, j = m % TN;
-            const s16x8 both = __builtin_shufflevector(f.blo[j], f.bhi[j], 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), f.a[i], acc[i][j], 0, 0, 0);
-        } else {
-            const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[t][j], f.a[i][t], acc[i][j], 0, 0, 0);
-        }
-    };
-
-    // Wait until at most `allowed` of this wave's direct-to-LDS copy instructions are
-    // still in flight (they complete in order), and for its own LDS reads; then meet
-    // the other waves.  After the barrier the tile that has just landed is visible to
-    // everybody, and everybody has fetched its last operands from the stages that are
-    // overwritten next.  The sched_barriers keep the compiler from moving MFMAs or
-    // fetches across.
-    auto wait_copies_and_sync = [&](auto allowed) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(%0) lgkmcnt(0)\n\ts_barrier" ::"n"(decltype(allowed)::value) : "memory");
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // the same for a partial last K tile landing in stages sta / stb: all copies awaited,
-    // missing columns cleared, then the barrier
-    auto wait_clear_and_sync = [&](auto sta, auto stb) __attribute__((always_inline)) {
-        __builtin_amdgcn_sched_barrier(0);
-        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-        zero_k_tail(sta, stb);
-        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-        __builtin_amdgcn_sched_barrier(0);
-    };
-    // With a three-deep A ring the A copy issued in this tile's first step is for the
-    // tile after next and may still be in flight when the next tile is awaited.
-    constexpr int STEADY_IN_FLIGHT = (SA - 2) * Cfg::A_CPW;
-
-    Frag frag[2];
-
-    // One K tile: A operands from A stage kt % SA, B operands from B stage kt % 2.
-    //   * Operands of step s+1 are fetched while the MFMAs of step s issue.
-    //   * Before the MFMAs of the last step, when a next tile exists: wait for its
-    //     copies, meet the other waves, fetch its first operands, and issue the first
-    //     half of the copy of tile kt+2 into a stage of this tile, which nobody reads
-    //     any more.  The second half follows in the first step of the next tile.
-    //   * A rows are 128-byte pieces 2*K bytes apart and take longer to arrive than the
-    //     512-byte B rows, so the A half goes first.  Two-deep A ring: A(kt+2) after the
-    //     barrier, B(kt+1) in the first step.  Three-deep A ring: A(kt+2) already in
-    //     this tile's first step (its stage was last read by tile kt-1), B(kt+2) after
-    //     the barrier; the A copy then has a whole extra tile to land.
-    //   * Copy instructions are spaced evenly between the MFMAs of their step: a burst
-    //     would fill the texture-address path (about 16 cycles per 1 KiB instruction
-    //     for the whole CU) and stall the in-order waves.
-    // `steady`: every tile up to kt+SA-1 and kt+2 exists, so the in-flight count at the
-    // wait is the steady-state one; otherwise the wait is for all copies.
-    // The instruction order of a step is written out and pinned (a scheduling barrier
-    // after every MFMA slot): MFMA m, then the operand fetches and copy instructions
-    // that belong to slot m, spread evenly over the slots.  The compiler allocates
-    // registers and places the lgkmcnt waits; it does not reorder.
-    // The fetches go into the first three quarters of the slots, so that the last of
-    // them has the remaining MFMAs to come back before the next step needs it.
-    // has_a / has_b: tile kt+2 exists (its A / B copy is issued here).
-    constexpr int DS_SLOTS = N_MFMA - N_MFMA / 4;
-    auto ds_first = [](int m) { return m >= DS_SLOTS ? N_DS : (m * N_DS) / DS_SLOTS; };
-    auto tile_body = [&](int kt, auto sta, auto stb, auto steady_tag, bool has_next, bool has_a, bool has_b) __attribute__((always_inline)) {
-        constexpr int STA = decltype(sta)::value, STB = decltype(stb)::value;
-        constexpr bool STEADY = decltype(steady_tag)::value != 0;
-        using NextA = IC<(STA + 1) % SA>;
-        using NextB = IC<(STB + 1) % 2>;
-#pragma unroll
-        for (int s = 0; s < NS; ++s) {
-            const bool last = s + 1 == NS;
-            // which copy (if any) is issued during this step
-            const bool early = s == 0 && (SA == 3 ? has_a : has_next);    // A(kt+2) or B(kt+1)
-            const bool late = last && has_next && (SA == 3 ? has_b : has_a);  // B(kt+2) or A(kt+2)
-            const int n_copy = early ? (SA == 3 ? Cfg::A_CPW : Cfg::B_CPW)
-                             : late ? (SA == 3 ? Cfg::B_CPW : Cfg::A_CPW) : 0;
-            const bool fetch = !last || has_next;
-            if (last && has_next) {
-                if constexpr (STEADY) {
-                    wait_copies_and_sync(IC<STEADY_IN_FLIGHT>{});
-                } else {
-                    if (k_partial && kt + 2 == KT) wait_clear_and_sync(NextA{}, NextB{});
-                    else wait_copies_and_sync(IC<0>{});
-                }
-            }
-#pragma unroll
-            for (int m = 0; m < N_MFMA; ++m) {
-                mfma_op(frag[s & 1], m);
-                if (fetch) {
-#pragma unroll
-                    for (int q = ds_first(m); q < ds_first(m + 1); ++q) {
-                        if (!last) fetch_op(sta, stb, s + 1, frag[(s + 1) & 1], q);
-                        else fetch_op(NextA{}, NextB{}, 0, frag[0], q);
-                    }
-                }
-#pragma unroll
-                for (int t = 0; t < (Cfg::A_CPW > Cfg::B_CPW ? Cfg::A_CPW : Cfg::B_CPW); ++t) {
-                    if (t < (m * n_copy) / N_MFMA || t >= ((m + 1) * n_copy) / N_MFMA) continue;
-                    // steady tiles never copy the last K tile when that one is partial
-                    const bool b1 = !STEADY && k_partial && kt + 2 == KT, b2 = !STEADY && k_partial && kt + 3 == KT;
-                    if constexpr (SA == 3) {
-                        if (early) copy_a_op(kt + 2, IC<(STA + 2) % 3>{}, t, b2);
-                        else copy_b_op(kt + 2, stb, t, b2);
-                    } else {
-                        if (early) copy_b_op(kt + 1, NextB{}, t, b1);
-                        else copy_a_op(kt + 2, sta, t, b2);
-                    }
-                }
-                __builtin_amdgcn_sched_barrier(0);
-            }
-        }
-    };
-
-    // prologue: tile 0 in full; what a tile body expects to find in flight follows
-    copy_a(0, IC<0>{});
-    copy_b(0, IC<0>{});
-    if constexpr (SA == 3) {
-        if (KT > 1) {
-            copy_a(1, IC<1>{});
-            wait_copies_and_sync(IC<Cfg::A_CPW>{});
-            copy_b(1, IC<1>{});
-        } else if (k_partial) {
-            wait_clear_and_sync(IC<0>{}, IC<0>{});
-        } else {
-            wait_copies_and_sync(IC<0>{});
-        }
-    } else {
-        if (k_partial && KT == 1) wait_clear_and_sync(IC<0>{}, IC<0>{});
-        else wait_copies_and_sync(IC<0>{});
-        if (KT > 1) copy_a(1, IC<1>{});
-    }
-    read_frags(IC<0>{}, IC<0>{}, 0, frag[0]);
-
-    int kt = 0;
-    constexpr int UNROLL = SA == 3 ? 6 : 2;      // lcm of the two ring depths
-    constexpr int LOOKAHEAD = 2;
-    // steady state: every copy issued in the trip exists, no conditionals in the body
-    const int KT_full = KT - (k_partial ? 1 : 0);   // the steady loop leaves a partial tile to the tail
-    for (; kt + UNROLL - 1 + LOOKAHEAD < KT_full; kt += UNROLL) {
-        tile_body(kt, IC<0>{}, IC<0>{}, IC<1>{}, true, true, true);
-        tile_body(kt + 1, IC<1 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
-        if constexpr (SA == 3) {
-            tile_body(kt + 2, IC<2 % SA>{}, IC<0>{}, IC<1>{}, true, true, true);
-            tile_body(kt + 3, IC<3 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
-            tile_body(kt + 4, IC<4 % SA>{}, IC<0>{}, IC<1>{}, true, true, true);
-            tile_body(kt + 5, IC<5 % SA>{}, IC<1>{}, IC<1>{}, true, true, true);
-        }
-    }
-    // tail: the remaining tiles (at most UNROLL + LOOKAHEAD), with run-time
-    // existence checks and a wait for all copies at each barrier
-    auto tail_tile = [&](int t, auto sta, auto stb) __attribute__((always_inline)) {
-        if (t < KT) tile_body(t, sta, stb, IC<0>{}, t + 1 < KT, t + 2 < KT, t + 2 < KT);
-    };
-    tail_tile(kt, IC<0>{}, IC<0>{});
-    tail_tile(kt + 1, IC<1 % SA>{}, IC<1>{});
-    tail_tile(kt + 2, IC<2 % SA>{}, IC<0>{});
-    tail_tile(kt + 3, IC<3 % SA>{}, IC<1>{});
-    if constexpr (SA == 3) {
-        tail_tile(kt + 4, IC<4 % SA>{}, IC<0>{});
-        tail_tile(kt + 5, IC<5 % SA>{}, IC<1>{});
-        tail_tile(kt + 6, IC<6 % SA>{}, IC<0>{});
-        tail_tile(kt + 7, IC<7 % SA>{}, IC<1>{});
-    }
-
-    // ---- epilogue: activation into LDS (the operand buffers are free now), then
-    // whole-row stores.  The row-sum exchange has a small buffer of its own.
-    // the output tile is staged in pieces of PIECE_BYTES, whole 32-row blocks each, in the two
-    // stages of the larger operand and, when it needs more than two pieces, two of the other
-    constexpr int OUT_BYTES = BM * BN * (BF16 ? 2 : 4);
-    constexpr int OUT_PIECES = (OUT_BYTES + Cfg::PIECE_BYTES - 1) / Cfg::PIECE_BYTES;
-    static_assert(OUT_PIECES <= 4 && (OUT_PIECES <= 2 || Cfg::B_BYTES == Cfg::A_BYTES) &&
-                  (Cfg::PIECE_BYTES / (BN * (BF16 ? 2 : 4))) % 32 == 0,
-                  "the operand buffers hold the output tile, whole 32-row blocks each");
-    // (split-K pass 1 of an fp32 kernel stages the same number of bytes; bf16 kernels store
-    // their fp32 partial products directly)
-    // row-sum exchange buffer: the third A stage when there is one, else a small array
-    // (followed by the tile's biases, BIAS_N floats)
-    __shared__ __attribute__((aligned(16))) float rs_own[SA > 2 ? 4 : Cfg::WGN * BM + 2 * BIAS_N];
-    float* rs_buf = SA > 2 ? (float*)lds_a2 : rs_own;
-    static_assert((Cfg::WGN * BM + 2 * BIAS_N) * 4 <= Cfg::A_BYTES, "row-sum and bias buffers fit an A stage");
-    unsigned char* const obj[4] = {Cfg::STAGE_IN_B ? lds_b0 : lds_a0, Cfg::STAGE_IN_B ? lds_b1 : lds_a1,
-                                   Cfg::STAGE_IN_B ? lds_a0 : lds_b0, Cfg::STAGE_IN_B ? lds_a1 : lds_b1};
-    __syncthreads();   // every wave is done with the operand tiles
-    if (out_mode == 1) {
-        // split-K pass 1: raw fp32 partial products to the workspace slice
-        // (BF16 kernels stage half of the columns at a time: the fp32 tile is twice
-        // the size of the operand buffers)
-        unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
-                                            (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
-        if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, false, true, Cfg, false>(acc, nullptr, nullptr, n_rem, wm, wn, lane, obj, nullptr);
-            __syncthreads();
-            epilogue_store<false, Cfg, false>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
-        } else {
-#pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const size_t row_off = (size_t)(wm * Cfg::WM + 32 * i + l32) * (size_t)p.N;
-#pragma unroll
-                for (int j = 0; j < TN; ++j)
-#pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;
-                        f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        if (wm * Cfg::WM + 32 * i + l32 < m_rem) {
-                            if (n + 4 <= n_rem) {
-                                typedef f32x4 f32x4_at_element __attribute__((aligned(4)));   // rows of any N
-                                *(f32x4_at_element*)((float*)w + row_off + n) = o;
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 3; ++e)
-                                    if (n + e < n_rem) ((float*)w)[row_off + n + e] = o[e];
-                            }
-                        }
-                    }
-            }
-        }
-        return;
-    }
-
-    float* rs_lds = p.rs_part ? rs_buf : nullptr;
-    // the tile's biases, fetched at kernel start, go through LDS to the lanes that need them
-    // (sixteen dependent global loads per lane at this point cost 12 000 cycles per tile)
-    float* const bias_lds = rs_buf + Cfg::WGN * BM;
-    // (row biases go to a second array; the column array then holds zeros, and so it does
-    // when the call has no bias)
-    float* const bias_lds_row = bias_lds + BIAS_N;
-    if (tid < BIAS_N) {
-        bias_lds[tid] = p.bias_per_row ? 0.0f : bias_pre;
-        if (p.bias_per_row) bias_lds_row[tid] = bias_pre;
-    }
-    __syncthreads();
-    const float* const bias_col = bias_lds;
-    const float* const bias_row = (p.bias && p.bias_per_row) ? bias_lds_row : nullptr;
-    if (!bias_row && !rs_lds) {
-        switch (p.act) {
-        case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
-        case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
-        case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
-        default: epilogue_to_lds<ACT_NONE, BF16, true, Cfg>(acc, bias_col, nullptr, n_rem, wm, wn, lane, obj, nullptr); break;
-        }
-    } else {
-        switch (p.act) {
-        case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
-        case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
-        case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
-        default: epilogue_to_lds<ACT_NONE, BF16, false, Cfg>(acc, bias_col, bias_row, n_rem, wm, wn, lane, obj, rs_lds); break;
-        }
-    }
-    __syncthreads();
-    unsigned char* c_tile = (unsigned char*)p.C +
-        ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
-    epilogue_store<BF16, Cfg, true>(c_tile, (size_t)p.N * ES, tid, m_rem, n_rem, obj);
-    if (p.rs_part && tid < m_rem) {
-        // partial row sums of the waves that share a row, added in wave-column order
-        float s = rs_buf[tid];
-#pragma unroll
-        for (int w = 1; w < Cfg::WGN; ++w) s += rs_buf[w * BM + tid];
-        p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
-    }
-    // Several tile columns: the workgroup that finishes a tile row last adds the row's
-    // partials, always in tile-column order, so the sum does not depend on which one that is.
-    // Each workgroup publishes its partials (device-scope fence), then counts itself in; the
-    // one that sees the count complete reads all of them (fence again: other XCDs' partials
-    // come through memory, not through this XCD's L2) and puts the counter back to zero for
-    // the next call on the stream.
-    if (p.rs_counter) {
-        // the flag lives in the first word of an operand buffer: after the barrier nobody reads
-        // the staged output tile any more (LDS has no room for another object)
-        int* const is_last = (int*)lds_a0;
-        __threadfence();
-        __syncthreads();
-        if (tid == 0) {
-            const unsigned int seen = atomicAdd(p.rs_counter + (size_t)b * p.tiles_m + tm, 1u);
-            *is_last = seen + 1u == (unsigned int)p.tiles_n;
-        }
-        __syncthreads();
-        if (*is_last) {
-            __threadfence();
-            if (tid < m_rem) {
-                const size_t row = (size_t)tm * BM + tid;
-                const volatile float* part = p.rs_part + (size_t)b * p.tiles_n * (size_t)p.M + row;
-                float s = part[0];
-                for (int t = 1; t < p.tiles_n; ++t) s += part[(size_t)t * p.M];
-                p.rowsum[(size_t)b * p.M + row] = s;
-            }
-            if (tid == 0) p.rs_counter[(size_t)b * p.tiles_m + tm] = 0u;
-        }
-    }
-#endif
-}
-
-// Shipping configurations: <bf16, BM, BN, BK, wave rows, wave cols, A ring depth, waves/SIMD>.
-// Large tiles for problems that fill the chip with them:
-//   bf16 256x256x64, eight waves of 64x128 (two per SIMD, so one wave's operand fetches
-//        and barrier waits overlap the other's MFMAs), A ring 3 + B ring 2 = 160 KiB LDS;
-//   fp32 128x128x32, four waves of 64x64, 64 KiB of LDS, two workgroups per CU.
-// Small tiles (a quarter of the area) for problems whose large-tile grid would leave
-// most of the 256 CUs idle:
-//   bf16 128x128x64, four waves of 64x64, 80 KiB of LDS, two workgroups per CU;
-//   fp32 64x64x32, four waves of 32x32, 32 KiB of LDS.
-using CfgBF16 = MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>;
-using CfgF32 = MfmaCfg<false, 128, 128, 32, 2, 2, 2, 1>;
-using CfgBF16Small = MfmaCfg<true, 128, 128, 64, 2, 2, 3, 2>;
-using CfgF32Small = MfmaCfg<false, 64, 64, 32, 2, 2, 2, 2>;
-// Halves of the large bf16 tile, eight waves of 64x64, for outputs whose last tile column (tall,
-// 256x128) or last tile row (wide, 128x256) would be at most half full with the large tile:
-using CfgBF16Tall = MfmaCfg<true, 256, 128, 64, 4, 2, 3, 2>;
-using CfgBF16Wide = MfmaCfg<true, 128, 256, 64, 2, 4, 3, 2>;
-// the same four for B given transposed ([N][K])
-using CfgBF16T = MfmaCfgBt<true, 256, 256, 64, 4, 2, 3, 2>;
-using CfgF32T = MfmaCfgBt<false, 128, 128, 32, 2, 2, 2, 1>;
-using CfgBF16SmallT = MfmaCfgBt<true, 128, 128, 64, 2, 2, 3, 2>;
-using CfgF32SmallT = MfmaCfgBt<false, 64, 64, 32, 2, 2, 2, 2>;
-using CfgBF16TallT = MfmaCfgBt<true, 256, 128, 64, 4, 2, 3, 2>;
-using CfgBF16WideT = MfmaCfgBt<true, 128, 256, 64, 2, 4, 3, 2>;
-// Skinny tiles, four waves of 32x32, for outputs with at most 32 columns or rows, where the
-// tiles above would spend most of their matrix work and LDS traffic on padding and turn a
-// memory-bound product into a compute-bound one:
-//   narrow 128x32 (B transposed only: a plain B tile would have rows of 64 bytes; the host
-//          transposes such a B, which is small), flat 32x128 (either layout of B).
-// Two-deep rings, 40 KiB of LDS (fp32 and bf16 alike): these run at the latency of the operand
-// stream, and the third A stage bought nothing (bf16 16384 x 16 x 16384: 145 us with it, 137 without).
-using CfgBF16NarrowT = MfmaCfgBt<true, 128, 32, 64, 4, 1, 2, 2>;
-using CfgF32NarrowT = MfmaCfgBt<false, 128, 32, 32, 4, 1, 2, 2>;
-using CfgBF16Flat = MfmaCfg<true, 32, 128, 64, 1, 4, 2, 2>;
-using CfgF32Flat = MfmaCfg<false, 32, 128, 32, 1, 4, 2, 2>;
-using CfgBF16FlatT = MfmaCfgBt<true, 32, 128, 64, 1, 4, 2, 2>;
-using CfgF32FlatT = MfmaCfgBt<false, 32, 128, 32, 1, 4, 2, 2>;
 
 bool mfma_has_tile(int dtype, int kind, bool b_trans)
 {
@@ -912,34 +29,26 @@ TileShape mfma_tile_shape(int dtype, int kind)
                               : TileShape{CfgF32::BM, CfgF32::BN, CfgF32::BK};
 }
 
-template <typename Cfg>
-static hipError_t launch_cfg(const GemmArgs& a, int out_mode, hipStream_t s)
-{
-    const long long wgs = (long long)a.tiles_m * a.tiles_n * a.batch * a.splits;
-    if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(gemm_mfma_kernel<Cfg>, dim3((unsigned int)wgs), dim3(Cfg::NT), 0, s, a, out_mode);
-    return hipGetLastError();
-}
-
 hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s)
 {
     if (!mfma_has_tile(dtype, kind, a.b_trans != 0)) return hipErrorInvalidValue;
+    // a convolution's operand views (one bias per row marks them) have instances of their own
+    if (a.bias_per_row) return launch_gemm_mfma_conv(a, dtype, kind, out_mode, s);
+    if (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0] || a.b_use_tap_table) return hipErrorInvalidValue;
     const bool small = kind == TILE_SMALL;
-    // the operand views of the convolution path assume B as [K][N]
-    if (a.b_trans && (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0])) return hipErrorInvalidValue;
-    if (kind == TILE_NARROW) return dtype == DT_BF16 ? launch_cfg<CfgBF16NarrowT>(a, out_mode, s) : launch_cfg<CfgF32NarrowT>(a, out_mode, s);
+    if (kind == TILE_NARROW) return dtype == DT_BF16 ? launch_cfg<CfgBF16NarrowT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32NarrowT, VIEW_GEMM>(a, out_mode, s);
     if (kind == TILE_FLAT) {
-        if (dtype == DT_BF16) return a.b_trans ? launch_cfg<CfgBF16FlatT>(a, out_mode, s) : launch_cfg<CfgBF16Flat>(a, out_mode, s);
-        return a.b_trans ? launch_cfg<CfgF32FlatT>(a, out_mode, s) : launch_cfg<CfgF32Flat>(a, out_mode, s);
+        if (dtype == DT_BF16) return a.b_trans ? launch_cfg<CfgBF16FlatT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgBF16Flat, VIEW_GEMM>(a, out_mode, s);
+        return a.b_trans ? launch_cfg<CfgF32FlatT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32Flat, VIEW_GEMM>(a, out_mode, s);
     }
-    if (kind == TILE_TALL) return a.b_trans ? launch_cfg<CfgBF16TallT>(a, out_mode, s) : launch_cfg<CfgBF16Tall>(a, out_mode, s);
-    if (kind == TILE_WIDE) return a.b_trans ? launch_cfg<CfgBF16WideT>(a, out_mode, s) : launch_cfg<CfgBF16Wide>(a, out_mode, s);
+    if (kind == TILE_TALL) return a.b_trans ? launch_cfg<CfgBF16TallT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgBF16Tall, VIEW_GEMM>(a, out_mode, s);
+    if (kind == TILE_WIDE) return a.b_trans ? launch_cfg<CfgBF16WideT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgBF16Wide, VIEW_GEMM>(a, out_mode, s);
     if (a.b_trans) {
-        if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16SmallT>(a, out_mode, s) : launch_cfg<CfgBF16T>(a, out_mode, s);
-        return small ? launch_cfg<CfgF32SmallT>(a, out_mode, s) : launch_cfg<CfgF32T>(a, out_mode, s);
+        if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16SmallT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgBF16T, VIEW_GEMM>(a, out_mode, s);
+        return small ? launch_cfg<CfgF32SmallT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32T, VIEW_GEMM>(a, out_mode, s);
     }
-    if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16Small>(a, out_mode, s) : launch_cfg<CfgBF16>(a, out_mode, s);
-    return small ? launch_cfg<CfgF32Small>(a, out_mode, s) : launch_cfg<CfgF32>(a, out_mode, s);
+    if (dtype == DT_BF16) return small ? launch_cfg<CfgBF16Small, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgBF16, VIEW_GEMM>(a, out_mode, s);
+    return small ? launch_cfg<CfgF32Small, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32, VIEW_GEMM>(a, out_mode, s);
 }
 
 }  // namespace pgk

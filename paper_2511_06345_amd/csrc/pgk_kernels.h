@@ -22,9 +22,6 @@ struct GemmArgs {
     void* C;            // [batch][M][N]
     float* rs_part;     // row-sum partials [batch][tiles_n][M], or final [batch][M]
                         // when tiles_n == 1; nullptr = no row-sum
-    float* rowsum;      // final row sums [batch][M], written by the last workgroup of a tile row
-                        // when rs_counter != nullptr (matrix-core kernels, tiles_n > 1)
-    unsigned int* rs_counter;  // [batch][tiles_m], zero before the launch and again after it
     float* ws;          // split-K partial products [batch][splits][M][N]
     int M, N, K, batch;
     // Operand views.  Plain GEMM: a_batch_stride = M*K, b_batch_stride = K*N, ldb = N,
@@ -35,7 +32,8 @@ struct GemmArgs {
     int b_trans;             // 1: B is given transposed, [batch][N][ldb >= K], K contiguous
     int k_rotate;            // 1: each workgroup starts its K loop at a tile of its own (plain GEMM views, whole K tiles only)
     int b_tail_bounded;      // 1: rows of a plain B are not whole 16-byte chunks: the copies of the last K tile stop at the end of B
-    int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows
+    int bias_per_row;        // 0: bias[N] added to columns; 1: bias[M] added to rows (a convolution's views: the
+                             // matrix-core kernels then run their convolution instances)
     // Matrix-core kernels, convolution as a sum of shifted GEMMs: K tile kt reads B rows
     // (kt % b_tiles_per_tap) * bk ... at column offset (kt / b_tiles_per_tap) * b_tap_step.
     int b_tiles_per_tap, b_tap_step;
@@ -108,6 +106,10 @@ TileShape guarded_tile_shape();
 // M, N and K need not be tile multiples: edge tiles re-read valid rows / columns and
 // store only what exists; the missing columns of a partial last K tile are cleared in LDS.
 hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s);
+// The instances for a convolution's operand views (bias_per_row = 1, A shared by the batch
+// entries, B tiles walking tap after tap, edge strips; B as [K][N], out_mode 0); reached through
+// launch_gemm_mfma.
+hipError_t launch_gemm_mfma_conv(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.
 hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);

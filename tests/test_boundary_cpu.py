@@ -33,7 +33,7 @@ def test_exports_match_header(lib):
 
 
 def test_version_and_status_strings(lib):
-    assert binding.version() == 100
+    assert binding.version() == 200
     seen = set()
     for code in (OK, INVALID, UNSUPPORTED, WORKSPACE, HIP, 12345):
         s = binding.status_string(code)
@@ -42,8 +42,10 @@ def test_version_and_status_strings(lib):
     assert binding.status_string(OK) == "PGK_OK"
 
 
-def _fused(lib, A=0x1000, B=0x2000, bias=None, C=0x3000, rs=None, M=4, N=4, K=4, batch=1, act=0, dtype=0):
-    return lib.pgk_gemm_fused(A, B, bias, C, rs, M, N, K, batch, act, dtype, None)
+def _fused(lib, A=0x1000, B=0x2000, bias=None, C=0x3000, rs=None, M=4, N=4, K=4, batch=1, act=0, dtype=0, ws=None,
+           ws_bytes=0, bt=False):
+    fn = lib.pgk_gemm_fused_bt if bt else lib.pgk_gemm_fused
+    return fn(A, B, bias, C, rs, M, N, K, batch, act, dtype, ws, ws_bytes, None)
 
 
 def test_fused_rejects_bad_arguments_on_the_host(lib):
@@ -55,6 +57,50 @@ def test_fused_rejects_bad_arguments_on_the_host(lib):
         assert _fused(lib, **bad) == INVALID, bad
     assert _fused(lib, M=1 << 31) == UNSUPPORTED
     assert _fused(lib, M=(1 << 31) - 1, N=(1 << 31) - 1, K=8, batch=2) == UNSUPPORTED
+
+
+def test_fused_workspace_is_the_callers(lib):
+    """The library owns no device memory: whatever a call needs beyond inputs and outputs comes
+    from the workspace argument, the query says how much, and a call without it is refused on
+    the host (nothing is launched; the pointers here are never dereferenced)."""
+    F32, BF16 = gen.F32, gen.BF16
+    q = binding.gemm_fused_workspace_bytes
+    RS, BT, UN = binding.WS_ROWSUM, binding.WS_B_TRANSPOSED, binding.WS_UNALIGNED
+    # the large workloads without row sums: nothing
+    assert q(8192, 8192, 8192, 1, BF16) == 0 and q(4096, 4096, 4096, 1, F32) == 0
+    assert q(8192, 8192, 8192, 1, BF16, BT) == 0
+    # row sums over four tile columns of 256: one fp32 partial per row and tile column
+    assert q(16384, 1024, 4096, 1, BF16, RS) == 4 * 16384 * 4
+    assert q(16384, 1024, 4096, 1, BF16) == 0
+    # the small fp32 workload: four tile columns of 64
+    assert q(256, 256, 256, 1, F32, RS) == 4 * 256 * 4
+    # one tile column: the kernel's row sums are final
+    assert q(65536, 128, 1024, 1, BF16, RS) == 0
+    # few tiles and a long K: the partial products of the automatic split (8 slices here)
+    assert binding.gemm_plan(1024, 1024, 8192, 1, BF16)["slices"] == 8
+    assert q(1024, 1024, 8192, 1, BF16) == 8 * 1024 * 1024 * 4
+    assert q(256, 256, 65536, 16, F32, RS) == binding.splitk_workspace_bytes(256, 256, 65536, 16, F32, 0)
+    # bf16 rows off the 4-byte grid: zero-padded copies of both operands (K 515 -> 520, N 251 -> 256)
+    r256 = lambda n: -(-n // 256) * 256          # every piece starts on a multiple of 256 bytes
+    assert q(130, 251, 515, 1, BF16) == r256(130 * 520 * 2) + r256(520 * 256 * 2)
+    assert q(130, 251, 515, 1, BF16, BT) == r256(130 * 520 * 2) + r256(251 * 520 * 2)
+    # misaligned operands of a tile-friendly problem: copies of both, rows as they are
+    assert q(128, 256, 192, 2, F32, UN) == 2 * 128 * 192 * 4 + 2 * 192 * 256 * 4
+    assert q(128, 256, 192, 2, F32) == 0
+    # too small to be worth a copy: the bounds-checked kernel, row-sum partials per 64-column tile
+    assert q(5, 7, 33, 2, BF16, RS | UN) == 0
+    assert q(33, 130, 17, 1, BF16, RS) == r256(3 * 33 * 4)
+    # invalid queries
+    assert q(0, 4, 4, 1, F32) == 0 and q(4, 4, 4, 1, 7) == 0 and q(4, 4, 4, 1, F32, 8) == 0
+    # the calls check what they are given
+    need = q(16384, 1024, 4096, 1, BF16, RS)
+    big = dict(M=16384, N=1024, K=4096, dtype=BF16)
+    assert _fused(lib, rs=0x5000, **big) == WORKSPACE
+    assert _fused(lib, rs=0x5000, ws=0x10000, ws_bytes=need - 1, **big) == WORKSPACE
+    assert _fused(lib, rs=0x5000, ws=0x10004, ws_bytes=need + 16, **big) == WORKSPACE      # misaligned
+    assert _fused(lib, A=0x1002, M=128, N=256, K=192, dtype=BF16) == WORKSPACE            # a misaligned operand is copied
+    assert _fused(lib, M=1024, N=1024, K=8192, dtype=BF16) == WORKSPACE                    # automatic split
+    assert _fused(lib, M=1024, N=1024, K=8192, dtype=BF16, bt=True) == WORKSPACE
 
 
 def _splitk(lib, ws=0x4000, ws_bytes=1 << 30, splits=0, **kw):
@@ -74,6 +120,20 @@ def test_splitk_rejects_bad_arguments_on_the_host(lib):
     assert _splitk(lib, ws=0x4004) == WORKSPACE                # misaligned
     need = binding.splitk_workspace_bytes(4, 4, 64, 1, gen.F32, 2)
     assert _splitk(lib, splits=2, ws_bytes=need - 1) == WORKSPACE
+    # the exact query never asks for more than the covering one (aligned operands) ...
+    for shape, dt in (((4, 4, 64, 1), gen.F32), ((20, 2056, 512, 1), gen.BF16), ((130, 251, 515, 2), gen.BF16),
+                      ((16384, 16, 4096, 1), gen.BF16), ((256, 256, 65536, 16), gen.F32)):
+        cover = binding.splitk_workspace_bytes(*shape, dt, 0)
+        for flags in range(4):
+            assert 0 < binding.gemm_splitk_workspace_bytes(*shape, dt, 0, flags) <= cover, (shape, flags)
+    # ... a skinny output's second pass keeps per-segment row sums after the partial products
+    s = binding.splitk_auto_splits(20, 2056, 512, 1, gen.BF16, 0)
+    assert binding.gemm_splitk_workspace_bytes(20, 2056, 512, 1, gen.BF16, 0, 0) == -(-s * 20 * 2056 * 4 // 256) * 256
+    assert binding.gemm_splitk_workspace_bytes(20, 2056, 512, 1, gen.BF16, 0, binding.WS_ROWSUM) > \
+        binding.gemm_splitk_workspace_bytes(20, 2056, 512, 1, gen.BF16, 0, 0)
+    # ... and misaligned operands are copied into it
+    assert binding.gemm_splitk_workspace_bytes(128, 128, 1024, 1, gen.F32, 2, binding.WS_UNALIGNED) == \
+        2 * 128 * 128 * 4 + 2 * 128 * 1024 * 4
 
 
 def test_split_plan_arithmetic(lib):
@@ -168,14 +228,23 @@ def test_tile_table_and_split_rule(lib):
 
 
 def test_reduce_max_rejects_bad_arguments_on_the_host(lib):
-    def call(X=0x1000, out=0x2000, idx=None, outer=2, red=3, inner=4, dtype=0):
-        return lib.pgk_reduce_max(X, out, idx, outer, red, inner, dtype, None)
+    def call(X=0x1000, out=0x2000, idx=None, outer=2, red=3, inner=4, dtype=0, ws=None, ws_bytes=0):
+        return lib.pgk_reduce_max(X, out, idx, outer, red, inner, dtype, ws, ws_bytes, None)
     assert call(X=None) == INVALID
     assert call(out=None) == INVALID
     for bad in ({"outer": 0}, {"red": 0}, {"inner": -3}, {"dtype": 2}):
         assert call(**bad) == INVALID, bad
     assert call(red=1 << 31) == UNSUPPORTED
     assert call(outer=1 << 40, inner=1 << 40) == UNSUPPORTED
+    # few outputs, a long reduced range: two passes, the segment results in the caller's workspace
+    q = binding.reduce_max_workspace_bytes
+    assert q(100000, 8, 1, gen.F32) == 0 and q(2, 3, 4, gen.F32) == 0 and q(64, 4096, 1024, gen.F32) > 0
+    need = q(16, 1 << 24, 1, gen.F32)
+    assert need > 0 and need % 8 == 0
+    assert call(outer=16, red=1 << 24, inner=1) == WORKSPACE
+    assert call(outer=16, red=1 << 24, inner=1, ws=0x8000, ws_bytes=need - 8) == WORKSPACE
+    assert call(outer=16, red=1 << 24, inner=1, ws=0x8002, ws_bytes=need) == WORKSPACE
+    assert q(0, 3, 4, gen.F32) == 0 and q(2, 3, 4, 5) == 0
 
 
 def test_conv1d_host_arithmetic_and_validation(lib):
@@ -244,8 +313,55 @@ def test_python_binding_validates_before_calling(lib):
         binding.reduce_max(torch.zeros(2, 3), 0)
 
 
-def test_release_scratch_without_any(lib):
-    binding.release_scratch()
+def test_python_binding_validates_outputs_and_workspace(lib):
+    """Caller-supplied outputs and workspaces are checked before their pointers reach the C ABI:
+    device, dtype, contiguity, element count.  (Host tensors stand in here: the device check is
+    the first to fire, the others are exercised on the checker itself.)"""
+    import torch
+    dev = torch.device("cpu")
+    ok = torch.zeros(2, 3, 4)
+
+    class Fake:      # what _check_out looks at, with a switchable is_cuda
+        def __init__(self, t, is_cuda=True, device=dev):
+            self.t, self.is_cuda, self.device = t, is_cuda, device
+            self.dtype, self.shape = t.dtype, t.shape
+        def is_contiguous(self): return self.t.is_contiguous()
+        def numel(self): return self.t.numel()
+        def dim(self): return self.t.dim()
+        def data_ptr(self): return self.t.data_ptr()
+
+    chk = binding._check_out
+    orig = torch.Tensor
+    try:
+        binding.torch.Tensor = Fake            # isinstance check of the helper
+        assert chk(Fake(ok), "out", (2, 3, 4), torch.float32, dev).t is ok
+        assert chk(Fake(ok.view(6, 4)), "out", (2, 3, 4), torch.float32, dev) is not None     # same elements, flattened
+        with pytest.raises(ValueError):
+            chk(Fake(ok, is_cuda=False), "out", (2, 3, 4), torch.float32, dev)
+        with pytest.raises(ValueError):
+            chk(Fake(ok, device=torch.device("meta")), "out", (2, 3, 4), torch.float32, dev)
+        with pytest.raises(TypeError):
+            chk(Fake(ok.double()), "out", (2, 3, 4), torch.float32, dev)
+        with pytest.raises(ValueError):
+            chk(Fake(ok.transpose(1, 2)), "out", (2, 4, 3), torch.float32, dev)            # strided view
+        with pytest.raises(ValueError):
+            chk(Fake(ok[:, :2]), "out", (2, 2, 4), torch.float32, dev)                       # not contiguous
+        with pytest.raises(ValueError):
+            chk(Fake(torch.zeros(2, 3, 3)), "out", (2, 3, 4), torch.float32, dev)            # too small
+        with pytest.raises(ValueError):
+            chk(Fake(torch.zeros(4, 3, 4)), "out", (2, 3, 4), torch.float32, dev)            # too large is refused too
+        wchk = binding._check_workspace
+        assert wchk(None, 0, dev) == (None, 0)
+        with pytest.raises(ValueError):
+            wchk(None, 16, dev)
+        with pytest.raises(ValueError):
+            wchk(Fake(torch.zeros(64)), 16, dev)                                              # not uint8
+        with pytest.raises(ValueError):
+            wchk(Fake(torch.zeros(64, dtype=torch.uint8), is_cuda=False), 16, dev)
+        ptr, n = wchk(Fake(torch.zeros(64, dtype=torch.uint8)), 16, dev)
+        assert n == 64
+    finally:
+        binding.torch.Tensor = orig
 
 
 def test_plan_is_consistent_on_random_shapes(lib):
