@@ -130,6 +130,24 @@ int pgk_gemm_fused(const void* A, const void* B, const float* bias, void* C, flo
 size_t pgk_gemm_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int flags);
 
 /*
+ * pgk_gemm_fused_static -- pgk_gemm_fused for callers that cannot hand over a workspace and
+ * cannot allocate one either (code under HIP graph capture, tight serving loops, harnesses that
+ * forbid allocation): same operator, same kernels, same results bit for bit, with the
+ * workspace taken from a fixed array of pgk_gemm_fused_static_max_bytes() = 4 MiB that is part
+ * of the library's device image (every GPU the library runs on holds one copy until the process
+ * ends).  The call allocates nothing and frees nothing.  `stream` must belong to the current
+ * device.  A problem whose pgk_gemm_fused_workspace_bytes exceeds the array (a large automatic
+ * K split, large operand copies) gets PGK_ERR_WORKSPACE: nothing is launched, use pgk_gemm_fused.
+ * All calls on one GPU share that GPU's array, which is left holding the last call's partial
+ * results: two calls that may run at the same time on one GPU (different streams) race and give
+ * undefined results -- order them, or use pgk_gemm_fused with a workspace each.
+ */
+int pgk_gemm_fused_static(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                          int64_t M, int64_t N, int64_t K, int64_t batch,
+                          int act, int dtype, void* stream);
+size_t pgk_gemm_fused_static_max_bytes(void);
+
+/*
  * pgk_gemm_splitk -- the same operator for small M,N and large K, computed in
  * two passes so that enough workgroups exist to fill the chip:
  *   pass 1: split s of `splits` multiplies a contiguous K-slice and stores its

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libpgk.so")
 
 EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_splitk_bt", "pgk_gemm_plan",
            "pgk_gemm_fused_workspace_bytes", "pgk_gemm_splitk_workspace_bytes", "pgk_splitk_workspace_bytes",
+           "pgk_gemm_fused_static", "pgk_gemm_fused_static_max_bytes",
            "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_reduce_max_workspace_bytes", "pgk_conv1d",
            "pgk_conv1d_workspace_bytes", "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
            "pgk_status_string", "pgk_version")
@@ -49,6 +50,10 @@ def load_library() -> ctypes.CDLL:
     i64, vp, ci = ctypes.c_int64, ctypes.c_void_p, ctypes.c_int
     lib.pgk_gemm_fused.restype = ci
     lib.pgk_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp, ctypes.c_size_t, vp]
+    lib.pgk_gemm_fused_static.restype = ci
+    lib.pgk_gemm_fused_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, vp]
+    lib.pgk_gemm_fused_static_max_bytes.restype = ctypes.c_size_t
+    lib.pgk_gemm_fused_static_max_bytes.argtypes = []
     lib.pgk_gemm_splitk.restype = ci
     lib.pgk_gemm_splitk.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, ci, ci, ci, vp,
                                     ctypes.c_size_t, vp]
@@ -255,6 +260,27 @@ def gemm_fused(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], a
     if rc != 0:
         raise PgkError(rc, "pgk_gemm_fused_bt" if b_transposed else "pgk_gemm_fused")
     return C, rs
+
+
+def gemm_fused_static(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int,
+                      out: torch.Tensor, rowsum_out: Optional[torch.Tensor] = None, stream=None):
+    """pgk_gemm_fused_static: the fused call with the library's fixed workspace; nothing is
+    allocated here either, so both outputs are the caller's (``rowsum_out`` None: no row sums)."""
+    lib = load_library()
+    batch, M, N, K, dtype = _shape(A, B)
+    dev = A.device
+    C = _check_out(out, "out", (batch, M, N), A.dtype, dev)
+    rs = _check_out(rowsum_out, "rowsum_out", (batch, M), torch.float32, dev) if rowsum_out is not None else None
+    rc = lib.pgk_gemm_fused_static(A.data_ptr(), B.data_ptr(), _check_bias(bias, N, dev) or None, C.data_ptr(),
+                                   rs.data_ptr() if rs is not None else None,
+                                   M, N, K, batch, int(act), dtype, _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_gemm_fused_static")
+    return C, rs
+
+
+def gemm_fused_static_max_bytes() -> int:
+    return int(load_library().pgk_gemm_fused_static_max_bytes())
 
 
 def gemm_fused_bt(A: torch.Tensor, Bt: torch.Tensor, bias: Optional[torch.Tensor], act: int, **kw):

@@ -6,9 +6,13 @@
 
 #include <algorithm>
 #include <cmath>
+#include <mutex>
 
 #include "../../include/pgk.h"
 #include "pgk_kernels.h"
+
+// The fixed workspace of pgk_gemm_fused_static (device memory; see static_scratch_of_current_device).
+static __device__ __align__(256) unsigned char scratch[(size_t)4 << 20];
 
 namespace {
 
@@ -573,6 +577,29 @@ int check_workspace(const WsNeeds& w, const void* workspace, size_t workspace_by
     return PGK_OK;
 }
 
+// ---- pgk_gemm_fused_static: the workspace of callers that cannot supply one.  A fixed array in
+// the library's device image; each GPU the library runs on holds its own copy, at its own
+// address, until the process ends.  Host code never uses the array's name as a pointer: the
+// device address is looked up once per device and cached.
+constexpr size_t kStaticScratchBytes = (size_t)4 << 20;
+constexpr int kMaxDevices = 64;
+std::mutex g_static_mu;
+void* g_static_ptr[kMaxDevices] = {};
+
+int static_scratch_of_current_device(void** out)
+{
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return PGK_ERR_HIP;
+    std::lock_guard<std::mutex> lk(g_static_mu);
+    if (!g_static_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return PGK_ERR_HIP;
+        g_static_ptr[dev] = p;
+    }
+    *out = g_static_ptr[dev];
+    return PGK_OK;
+}
+
 // pgk_gemm_fused and pgk_gemm_fused_bt (b_trans: B given as [batch][N][K])
 int gemm_fused_impl(const void* A, const void* B, const float* bias, void* C, float* rowsum,
                     int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype,
@@ -648,6 +675,25 @@ int pgk_gemm_fused_bt(const void* A, const void* Bt, const float* bias, void* C,
 {
     return gemm_fused_impl(A, Bt, bias, C, rowsum, M, N, K, batch, act, dtype, workspace, workspace_bytes, stream, true);
 }
+
+int pgk_gemm_fused_static(const void* A, const void* B, const float* bias, void* C, float* rowsum,
+                          int64_t M, int64_t N, int64_t K, int64_t batch, int act, int dtype, void* stream)
+{
+    int rc = validate_common(A, B, C, M, N, K, batch, act, dtype);
+    if (rc != PGK_OK) return rc;
+    // the need is known on the host: refuse before touching the device
+    const WsNeeds w = fused_needs(M, N, K, batch, dtype, false, rowsum != nullptr, !aligned16(A), !aligned16(B));
+    if (!w.ok) return PGK_ERR_UNSUPPORTED;
+    if (w.total > kStaticScratchBytes) return PGK_ERR_WORKSPACE;
+    void* ws = nullptr;
+    if (w.total) {
+        rc = static_scratch_of_current_device(&ws);
+        if (rc != PGK_OK) return rc;
+    }
+    return gemm_fused_impl(A, B, bias, C, rowsum, M, N, K, batch, act, dtype, ws, w.total ? kStaticScratchBytes : 0, stream, false);
+}
+
+size_t pgk_gemm_fused_static_max_bytes(void) { return kStaticScratchBytes; }
 
 size_t pgk_gemm_fused_workspace_bytes(int64_t M, int64_t N, int64_t K, int64_t batch, int dtype, int flags)
 {
