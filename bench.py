@@ -30,13 +30,9 @@ import numpy as np  # noqa: E402
 # MI355X published peaks
 PEAK_TFLOPS = {"bf16": 2500.0, "f32": 157.3}
 PEAK_HBM_GBS = 8000.0
-# L2 <-> memory bytes per launch of the dominant kernel from two rocprofv3 --pmc runs
-# (FETCH_SIZE, WRITE_SIZE, each scaled by the same counter on a plain 1 GiB copy); see
-# profiles/.  Valid only for the kernel configuration named here; None otherwise.
-TRAFFIC_BYTES = {"c3": ("MfmaCfg<true,256,256,64,4,2,3,2>", 1745761432),
-                 "c4": ("MfmaCfg<true,256,256,64,4,2,3,2>", 235868169),
-                 "c2": ("MfmaCfg<false,128,128,32,2,2,2,1>", 868724653)}
-REDUCE_TRAFFIC_BYTES = {"r1": 1076477276, "r3": 1083079531, "r4": 1073865295}   # both kernels of a call
+# roofline.traffic (L2 <-> memory bytes per launch of the dominant kernel, from rocprofv3 FETCH_SIZE /
+# WRITE_SIZE runs scaled by a plain copy) is read from the traffic-record lines of the summaries under
+# profiles/; a record counts only if it was taken with the kernel sources as they are now.
 
 DESCR = {
     "c1": "c1: fp32 GEMM 256x256x256, bias + ReLU + rowsum",
@@ -86,7 +82,10 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
     w = gen.WORKLOADS[name]
     t0 = time.time()
     host, (dA, dB, dbias) = device_inputs(w, gen, torch)
-    log(f"[{name}] inputs generated and copied in {time.time() - t0:.1f} s")
+    # reproducibility: checksums of the exact input bits
+    checksums = {"A": f"{gen.fnv1a64(host[0]):016x}", "B": f"{gen.fnv1a64(host[1]):016x}",
+                 "bias": f"{gen.fnv1a64(host[2]):016x}" if host[2] is not None else None}
+    log(f"[{name}] inputs generated, checksummed and copied in {time.time() - t0:.1f} s")
     out_dt = torch.bfloat16 if w.dtype == gen.BF16 else torch.float32
     fn = pgk.gemm_splitk if w.call == "splitk" else pgk.gemm_fused
     bufs = []
@@ -131,10 +130,127 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
         "call_ms_min": float(per.min()),
         "algorithmic_gbs": w.algorithmic_bytes / (float(per.mean()) * 1e-3) / 1e9,
         "buffer_sets": len(bufs),
+        "input_checksums_fnv1a64": checksums,
     }
     if keep_host:
         res["_host"] = host
     return res
+
+
+def gemm_kernel_name(w, pgk, gen):
+    """The instance of the matrix-core kernel the fused / split call runs for this workload, as the
+    profiler prints it (from pgk_gemm_plan: tile shape; the wave layout follows from the tile)."""
+    plan = pgk.gemm_plan(w.M, w.N, w.K, w.batch, w.dtype)
+    bm, bn, bk = plan["tile"]
+    if not plan["matrix_core"]:
+        return "pgk::gemm_guarded_kernel", plan
+    bf = w.dtype == gen.BF16
+    layout = {(256, 256): "4, 2, 3, 2", (128, 128): "2, 2, 3, 2" if bf else "2, 2, 2, 1", (64, 64): "2, 2, 2, 2",
+              (256, 128): "4, 2, 3, 2", (128, 256): "2, 4, 3, 2", (32, 128): "1, 4, 2, 2", (128, 32): "4, 1, 2, 2"}[(bm, bn)]
+    return f"MfmaCfg<{'true' if bf else 'false'}, {bm}, {bn}, {bk}, {layout}>, 0, false>", plan
+
+
+def gemm_roofline(name, w, res, pgk, gen):
+    """Roofline block of one GEMM workload: the matrix pipe binds all five (their HBM times are 3-40 %
+    of their matrix times), so `frac` is against the published matrix peak of the type; the HBM
+    fraction of the algorithmic bytes is reported beside it."""
+    from paper_2511_06345_amd import profile
+    dtype_key = "bf16" if w.dtype == gen.BF16 else "f32"
+    achieved = w.flops / (res["call_ms_avg"] * 1e-3) / 1e12
+    kernel, plan = gemm_kernel_name(w, pgk, gen)
+    return {
+        "bound": "mfma",
+        "kernel": "pgk::gemm_mfma_kernel<" + kernel if kernel.startswith("MfmaCfg") else kernel,
+        "plan": plan,
+        "achieved": achieved,
+        "peak": PEAK_TFLOPS[dtype_key],
+        "unit": "TFLOP/s",
+        "frac": achieved / PEAK_TFLOPS[dtype_key],
+        "launch_ms_avg": res["call_ms_avg"],
+        "launch_ms_median": res["call_ms_median"],
+        "launch_ms_min": res["call_ms_min"],
+        "traffic": profile.stored_traffic(name, kernel),
+        "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE and WRITE_SIZE, each scaled by the same counter on a plain "
+                        "1 GiB copy; null: no summary under profiles/ was taken with the kernel sources as they are now)",
+        "hbm_achieved_gbs_algorithmic": res["algorithmic_gbs"],
+        "hbm_frac_algorithmic": res["algorithmic_gbs"] / PEAK_HBM_GBS,
+    }
+
+
+def phase_budget(name, pgk, gen, torch, launches=6):
+    """Where the time of the large bf16 kernel goes on workload `name` (c3 or c4): a few launches of
+    the timed instance (pgk_probe_gemm_phases), stamps of the last one reduced to medians over the
+    workgroups of each round.  Also gives the shader clock under the kernel: cycles per 100 MHz tick."""
+    w = gen.WORKLOADS[name]
+    if w.dtype != gen.BF16 or w.batch != 1:
+        raise SystemExit("--phases: the timed instance is the large bf16 kernel (workloads c3, c4)")
+    _, (dA, dB, dbias) = device_inputs(w, gen, torch)
+    C = torch.empty((1, w.M, w.N), dtype=torch.bfloat16, device="cuda")
+    tiles_n = -(-w.N // 256)
+    part = torch.empty((tiles_n, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None
+    wgs = -(-w.M // 256) * tiles_n
+    stamps = torch.zeros((wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for i in range(launches):
+        if i == launches - 1:
+            ev0.record()
+        pgk.probe_gemm_phases(dA, dB, dbias, w.act, C, stamps, rowsum_partials=part)
+    ev1.record()
+    torch.cuda.synchronize()
+    st = stamps.cpu().numpy().astype(np.float64)
+    cyc, tick = st[:, 0:12:2], st[:, 1:12:2]                      # [workgroup][stamp]
+    t0 = tick[:, 0].min()
+    us = (tick - t0) / 100.0                                      # 100 MHz ticks -> microseconds since the first entry
+    cus = 256
+    rounds = max(1, -(-wgs // cus))
+    order = np.argsort(us[:, 0], kind="stable")                   # by entry time: round r = r-th group of 256
+    names = ["entry -> first K tile landed", "main loop", "bias/activation(/row sums) -> tile staged in LDS",
+             "stores issued", "stores acknowledged"]
+    per_round = []
+    for r in range(rounds):
+        sel = order[r * cus:(r + 1) * cus]
+        d_us = np.diff(us[sel], axis=1)
+        d_cyc = np.diff(cyc[sel], axis=1)
+        per_round.append({
+            "workgroups": int(sel.size),
+            "entry_us_median": float(np.median(us[sel, 0])),
+            "exit_us_median": float(np.median(us[sel, 5])),
+            "phases": [{"phase": names[k], "us_median": float(np.median(d_us[:, k])), "us_max": float(d_us[:, k].max()),
+                        "cycles_median": float(np.median(d_cyc[:, k]))} for k in range(5)],
+        })
+    span_ticks = tick[:, 5].max() - t0
+    total_cyc = (cyc[:, 5] - cyc[:, 0]).sum()
+    total_tick = (tick[:, 5] - tick[:, 0]).sum()
+    kt = -(-w.K // 64)
+    loop_cyc = float(np.median(cyc[:, 2] - cyc[:, 1]))
+    xcd = st[:, 13].astype(np.int64) & 0xF
+    return {
+        "workload": DESCR[name], "workgroups": int(wgs), "rounds": rounds, "k_tiles": kt,
+        "kernel_span_us": float(span_ticks / 100.0),
+        "launch_us_event": float(ev0.elapsed_time(ev1) * 1e3),
+        "shader_clock_ghz_under_kernel": float(total_cyc / total_tick * 0.1),
+        "main_loop_cycles_per_k_tile": loop_cyc / max(1, kt - 1),
+        "mfma_issue_cycles_per_k_tile": 2048,
+        "xcd_of_workgroup_matches_id_mod_8": bool(np.all(xcd == (np.arange(wgs) % 8))),
+        "rounds_detail": per_round,
+        "how": "thread-0 stamps of s_memtime / s_memrealtime inside a measurement instance of the kernel "
+               "(pgk_probe_gemm_phases); medians over the workgroups of a round",
+    }
+
+
+def gpu_clocks():
+    """Clock readings of the board right after the timed region, as the system tool reports them
+    (best effort: None when the tool is missing or prints something else)."""
+    import shutil
+    import subprocess
+    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
+    try:
+        out = subprocess.run([tool, "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
+        data = json.loads(out.stdout)
+        card = next(iter(data.values()))
+        return {k: v for k, v in card.items() if "clock" in k.lower()}
+    except Exception as exc:      # noqa: BLE001
+        return {"unavailable": str(exc)[:120]}
 
 
 def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
@@ -308,8 +424,9 @@ def reduce_main(args, name, pgk, gen, torch):
             "unit": "GB/s",
             "frac": head["algorithmic_gbs"] / PEAK_HBM_GBS,
             "launch_ms_avg": head["call_ms_avg"],
-            "traffic": REDUCE_TRAFFIC_BYTES.get(name),
-            "traffic_unit": "bytes per call (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
+            "traffic": __import__("paper_2511_06345_amd.profile", fromlist=["x"]).stored_traffic(name, "pgk::reduce_max"),
+            "traffic_unit": "bytes per launch of the first (streaming) kernel (rocprofv3 FETCH_SIZE and WRITE_SIZE, scaled by "
+                            "a plain 1 GiB copy); null: no summary taken with the kernel sources as they are now",
         },
     }
     if not args.no_cpu_baseline:
@@ -396,7 +513,12 @@ def main():
                     help="c1..c5: fused GEMM workloads (c3 is the headline); r1..r4: max-reduction workloads; "
                          "v1..v3: conv1d workloads")
     ap.add_argument("--others", action="store_true",
-                    help="also time the other GEMM workloads and the reduction workloads (reported under 'others')")
+                    help="also time the reduction and convolution workloads (the other four GEMM workloads are "
+                         "always timed and reported under 'others')")
+    ap.add_argument("--headline-only", action="store_true", help="time the named workload only")
+    ap.add_argument("--phases", action="store_true",
+                    help="print the phase budget of the large bf16 kernel on the workload (c3 or c4) as one JSON line "
+                         "and exit (timed instance of the kernel; see pgk_probe_gemm_phases)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-ceilings", action="store_true",
                     help="skip the probe kernels that measure what the chip sustains (profiling runs)")
@@ -451,24 +573,16 @@ def main():
         conv_main(args, name, pgk, gen, torch)
         return
     w = gen.WORKLOADS[name]
+    if args.phases:
+        print(json.dumps({"phase_budget": phase_budget(name, pgk, gen, torch)}), flush=True)
+        return
     head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
+    clocks = gpu_clocks()
     host = head.pop("_host")
 
     dtype_key = "bf16" if w.dtype == gen.BF16 else "f32"
-    peak = PEAK_TFLOPS[dtype_key]
-    achieved = w.flops / (head["call_ms_avg"] * 1e-3) / 1e12
-    roofline = {
-        "bound": "mfma",
-        "kernel": "pgk::gemm_mfma_kernel (matrix-core main loop + fused epilogue)",
-        "achieved": achieved,
-        "peak": peak,
-        "unit": "TFLOP/s",
-        "frac": achieved / peak,
-        "launch_ms_avg": head["call_ms_avg"],
-        "traffic": TRAFFIC_BYTES[name][1] if name in TRAFFIC_BYTES else None,
-        "traffic_unit": "bytes per launch (rocprofv3 FETCH_SIZE x2.0 + WRITE_SIZE x1.0)",
-        "hbm_frac_algorithmic": head["algorithmic_gbs"] / PEAK_HBM_GBS,
-    }
+    roofline = gemm_roofline(name, w, head, pgk, gen)
+    achieved = roofline["achieved"]
 
     out = {
         "metric": "fused GEMM+epilogue TFLOP/s on 1 MI355X",
@@ -485,8 +599,11 @@ def main():
         "data": "synthetic (seeded SplitMix64 generator, resident in HBM before timing; calls rotate through "
                 f"{head['buffer_sets']} copies of the buffers)",
         "config": {"workload": DESCR[name], "M": w.M, "N": w.N, "K": w.K, "batch": w.batch,
-                   "call": w.call, "flops_per_step": w.flops, "algorithmic_bytes_per_step": w.algorithmic_bytes},
+                   "call": w.call, "flops_per_step": w.flops, "algorithmic_bytes_per_step": w.algorithmic_bytes,
+                   "input_checksums_fnv1a64": head["input_checksums_fnv1a64"]},
         "roofline": roofline,
+        "call_ms": {"avg": head["call_ms_avg"], "median": head["call_ms_median"], "min": head["call_ms_min"]},
+        "gpu_clocks_after_timed_region": clocks,
     }
     if not args.no_ceilings:
         out["measured_ceilings"] = measured_ceilings(pgk, gen, torch)
@@ -497,18 +614,31 @@ def main():
         log("[cpu_baseline] timing the oracle on a bounded sample ...")
         out["cpu_baseline"] = cpu_baseline(w, host, gen)
     del host
-    if args.others:
-        others = {}
+    if w.dtype == gen.BF16 and w.batch == 1 and not args.no_ceilings:
+        # the shader clock the kernel itself sees (cycle counter against the 100 MHz counter)
+        try:
+            pb = phase_budget(name, pgk, gen, torch, launches=3)
+            out["shader_clock_ghz_under_kernel"] = pb["shader_clock_ghz_under_kernel"]
+            out["main_loop_cycles_per_k_tile"] = pb["main_loop_cycles_per_k_tile"]
+        except Exception as exc:      # noqa: BLE001  (a measurement aid must not take the bench line down)
+            out["shader_clock_ghz_under_kernel"] = None
+            log(f"[phases] skipped: {exc}")
+        torch.cuda.empty_cache()
+    others = {}
+    if not args.headline_only:
+        # the other four GEMM workloads, each with its own roofline block
         for other in sorted(DESCR):
             if other == name:
                 continue
             r = run_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
             ow = gen.WORKLOADS[other]
-            pk = PEAK_TFLOPS["bf16" if ow.dtype == gen.BF16 else "f32"]
-            r["mfma_frac"] = ow.flops / (r["call_ms_avg"] * 1e-3) / 1e12 / pk
-            r["hbm_frac_algorithmic"] = r["algorithmic_gbs"] / PEAK_HBM_GBS
+            r["roofline"] = gemm_roofline(other, ow, r, pgk, gen)
+            r["config"] = {"M": ow.M, "N": ow.N, "K": ow.K, "batch": ow.batch, "call": ow.call,
+                           "flops_per_step": ow.flops, "algorithmic_bytes_per_step": ow.algorithmic_bytes}
             others[other] = r
             torch.cuda.empty_cache()
+        out["others"] = others
+    if args.others:
         for other in sorted(REDUCE_DESCR):
             others[other] = run_reduce_workload(other, args.steps, args.warmup, pgk, gen, torch, sets=args.buffer_sets)
             torch.cuda.empty_cache()

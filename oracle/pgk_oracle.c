@@ -167,7 +167,6 @@ int oracle_gemm_fused(const void *A, const void *B, const float *bias,
     return failed ? -1 : 0;
 }
 
-/* Number of threads the parallel region above will use. */
 /*
  * Maximum over the middle dimension of X viewed as [outer][red][inner]
  * (row-major, contiguous), which covers a reduction over any one dimension of a

@@ -1096,6 +1096,33 @@ int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, doubl
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
+int pgk_probe_gemm_phases(const void* A, const void* B, const float* bias, void* C, float* rowsum_partials,
+                          int64_t M, int64_t N, int64_t K, int act, uint64_t* stamps, size_t stamps_bytes,
+                          int32_t* workgroups_out, void* stream)
+{
+    int rc = validate_common(A, B, C, M, N, K, 1, act, PGK_DTYPE_BF16);
+    if (rc != PGK_OK) return rc;
+    if (!stamps || (reinterpret_cast<uintptr_t>(stamps) & 7u)) return PGK_ERR_INVALID_ARG;
+    const pgk::TileShape t = pgk::mfma_tile_shape(PGK_DTYPE_BF16, pgk::TILE_LARGE);
+    if (!aligned16(A) || !aligned16(B) || !mfma_shape_ok(M, N, K, PGK_DTYPE_BF16) || needs_packing(N, K, PGK_DTYPE_BF16, false))
+        return PGK_ERR_UNSUPPORTED;
+    const int64_t tiles_m = (M + t.bm - 1) / t.bm, tiles_n = (N + t.bn - 1) / t.bn;
+    if ((long double)tiles_m * tiles_n > 1.0e6L) return PGK_ERR_UNSUPPORTED;
+    if (workgroups_out) *workgroups_out = (int32_t)(tiles_m * tiles_n);
+    if (stamps_bytes < (size_t)(tiles_m * tiles_n) * pgk::kStampWords * sizeof(uint64_t)) return PGK_ERR_WORKSPACE;
+    GemmArgs a{};
+    a.A = A; a.B = B; a.bias = bias; a.C = C; a.rs_part = rowsum_partials;
+    a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = 1;
+    pgk::fill_plain_views(a);
+    mark_ragged_rows(a, PGK_DTYPE_BF16);
+    a.act = act; a.splits = 1;
+    a.k_slice = (int)(((K + t.bk - 1) / t.bk) * t.bk);
+    a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
+    a.group_m = group_m_for(a.tiles_m, a.tiles_n);
+    a.stamps = reinterpret_cast<unsigned long long*>(stamps);
+    return pgk::launch_gemm_mfma_timed(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
 int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream)
 {
     if (!src || !sink || bytes == 0 || bytes % 16 || !aligned16(src)) return PGK_ERR_INVALID_ARG;

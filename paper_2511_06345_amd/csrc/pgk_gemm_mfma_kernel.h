@@ -253,7 +253,11 @@ struct IC { static constexpr int value = V; };
 // the convolution's address state.
 enum { VIEW_GEMM = 0, VIEW_CONV = 1 };
 
-template <typename Cfg, int VIEW>
+// TIMED: a measurement instance (see pgk_probe_gemm_phases): wave 0 of every workgroup writes
+// the shader-clock cycle counter and the constant 100 MHz counter at six points of the kernel to
+// p.stamps[workgroup][kStampWords], and waits for its stores to be acknowledged before the last
+// stamp.  The shipping instances (TIMED false) contain none of it.
+template <typename Cfg, int VIEW, bool TIMED = false>
 __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel(const GemmArgs p, const int out_mode)
 {
 #if defined(__HIP_DEVICE_COMPILE__)   // the host pass only needs the launch stub (and has no buffer-resource type)
@@ -277,6 +281,30 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / Cfg::WGN, wn = wave % Cfg::WGN;
+    // phase stamp k of this workgroup: (cycles, 100 MHz ticks)
+    auto stamp = [&](int k) __attribute__((always_inline)) {
+        if constexpr (TIMED) {
+            __builtin_amdgcn_sched_barrier(0);
+            const unsigned long long cyc = __builtin_readcyclecounter();
+            const unsigned long long tick = __builtin_amdgcn_s_memrealtime();
+            // (all lanes of wave 0 store the same two words: a wave-uniform branch, so that the
+            // code after it is not seen as reached under a divergent condition)
+            if (wave == 0) {
+                unsigned long long* at = p.stamps + (size_t)blockIdx.x * kStampWords + 2 * k;
+                at[0] = cyc;
+                at[1] = tick;
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    };
+    stamp(0);
+    if constexpr (TIMED) {
+        // where the workgroup runs: hardware id register (CU, shader engine) and XCD number
+        if (wave == 0) {
+            p.stamps[(size_t)blockIdx.x * kStampWords + 12] = (unsigned long long)__builtin_amdgcn_s_getreg(63492);   // HW_ID, 32 bits
+            p.stamps[(size_t)blockIdx.x * kStampWords + 13] = (unsigned long long)__builtin_amdgcn_s_getreg(63508);   // XCC_ID, 32 bits
+        }
+    }
 
     // ---- which tile, batch entry and K slice this workgroup owns
     const unsigned int tiles = (unsigned int)p.tiles_m * (unsigned int)p.tiles_n;
@@ -727,6 +755,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         if (KT > 1) copy_a(1, IC<1>{});
     }
     read_frags(IC<0>{}, IC<0>{}, 0, frag[0]);
+    stamp(1);      // the first K tile has landed
 
     int kt = 0;
     constexpr int UNROLL = SA == 3 ? 6 : 2;      // lcm of the two ring depths
@@ -778,6 +807,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     unsigned char* const obj[4] = {Cfg::STAGE_IN_B ? lds_b0 : lds_a0, Cfg::STAGE_IN_B ? lds_b1 : lds_a1,
                                    Cfg::STAGE_IN_B ? lds_a0 : lds_b0, Cfg::STAGE_IN_B ? lds_a1 : lds_b1};
     __syncthreads();   // every wave is done with the operand tiles
+    stamp(2);          // end of the main loop
     if (out_mode == 1) {
         // split-K pass 1: raw fp32 partial products to the workspace slice
         // (BF16 kernels stage half of the columns at a time: the fp32 tile is twice
@@ -849,6 +879,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         else run_epilogue(IC<EPI_ROWSUM_MASKED>{});
     }
     __syncthreads();
+    stamp(3);          // bias, activation and row sums done, output tile staged
     unsigned char* c_tile = (unsigned char*)p.C +
         ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
     epilogue_store<BF16, Cfg, true>(c_tile, (size_t)p.N * ES, tid, m_rem, n_rem, obj);
@@ -858,6 +889,12 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
 #pragma unroll
         for (int w = 1; w < Cfg::WGN; ++w) s += rs_buf[w * BM + tid];
         p.rs_part[((size_t)b * p.tiles_n + tn) * (size_t)p.M + (size_t)tm * BM + tid] = s;
+    }
+    stamp(4);          // stores issued
+    if constexpr (TIMED) {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        stamp(5);      // every wave's stores acknowledged
     }
 #endif
 }
@@ -900,12 +937,13 @@ using CfgF32Flat = MfmaCfg<false, 32, 128, 32, 1, 4, 2, 2>;
 using CfgBF16FlatT = MfmaCfgBt<true, 32, 128, 64, 1, 4, 2, 2>;
 using CfgF32FlatT = MfmaCfgBt<false, 32, 128, 32, 1, 4, 2, 2>;
 
-template <typename Cfg, int VIEW>
+template <typename Cfg, int VIEW, bool TIMED = false>
 static hipError_t launch_cfg(const GemmArgs& a, int out_mode, hipStream_t s)
 {
     const long long wgs = (long long)a.tiles_m * a.tiles_n * a.batch * a.splits;
     if (wgs <= 0 || wgs > 0x7fffffffLL) return hipErrorInvalidValue;
-    hipLaunchKernelGGL((gemm_mfma_kernel<Cfg, VIEW>), dim3((unsigned int)wgs), dim3(Cfg::NT), 0, s, a, out_mode);
+    if (TIMED != (a.stamps != nullptr)) return hipErrorInvalidValue;
+    hipLaunchKernelGGL((gemm_mfma_kernel<Cfg, VIEW, TIMED>), dim3((unsigned int)wgs), dim3(Cfg::NT), 0, s, a, out_mode);
     return hipGetLastError();
 }
 

@@ -61,7 +61,14 @@ struct GemmArgs {
     int k_slice;        // K elements per split (multiple of the K tile)
     int tiles_m, tiles_n;
     int group_m;        // tile rows per scheduling group
+    // measurement instance only (launch_gemm_mfma_timed): kStampWords 64-bit words per workgroup
+    unsigned long long* stamps;
 };
+
+// Words per workgroup the timed instance writes: six (cycle counter, 100 MHz counter) pairs --
+// kernel entry, first K tile landed, end of the main loop, output tile staged, stores issued,
+// stores acknowledged -- then the hardware id register and the XCD number, two words unused.
+constexpr int kStampWords = 16;
 
 inline void fill_plain_views(GemmArgs& a)
 {
@@ -110,6 +117,9 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
 // entries, B tiles walking tap after tap, edge strips; B as [K][N], out_mode 0); reached through
 // launch_gemm_mfma.
 hipError_t launch_gemm_mfma_conv(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s);
+
+// The large bf16 tile, plain operand views, out_mode 0, with phase stamps (a.stamps set).
+hipError_t launch_gemm_mfma_timed(const GemmArgs& a, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.
 hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);

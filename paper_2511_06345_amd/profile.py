@@ -328,6 +328,7 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
     step_us = sum(k["time_us"] * k["calls"] for k in kernels) / max(1, steps)
     return {
         "workload": workload,
+        "sources": kernel_source_hash(),
         "when": datetime.datetime.now().isoformat(timespec="seconds"),
         "step_time_us": step_us,
         "kernels": kernels,
@@ -335,6 +336,49 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
         "bench": {k: bench_line[k] for k in ("metric", "value", "unit", "ms_per_step", "dtype")} if bench_line else None,
         "runs": ["trace"] + [g[0] for g in groups] + (["cal_fetch", "cal_write"] if calibrate else []),
     }
+
+
+def kernel_source_hash() -> str:
+    """A short hash of the kernel sources as they stand (csrc/*.hip, *.h): counter values taken from
+    one version of the kernels say nothing about another, so every stored traffic figure carries it."""
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")) + glob.glob(os.path.join(HERE, "csrc", "*.h"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
+
+
+_TRAFFIC_RE = re.compile(r"^traffic-record: workload=(\S+) sources=(\S+) bytes=(\d+) kernel=(.+)$")
+
+
+def traffic_record_line(workload: str, sources: str, nbytes: float, kernel: str) -> str:
+    return f"traffic-record: workload={workload} sources={sources} bytes={int(round(nbytes))} kernel={kernel}"
+
+
+def read_traffic_records(profiles_dir: str) -> List[dict]:
+    """Every traffic-record line of the summaries under `profiles_dir` (written by to_markdown)."""
+    out = []
+    for path in sorted(glob.glob(os.path.join(profiles_dir, "*.md"))):
+        with open(path) as f:
+            for line in f:
+                m = _TRAFFIC_RE.match(line.strip().strip("`"))
+                if m:
+                    out.append({"workload": m.group(1), "sources": m.group(2), "bytes": int(m.group(3)),
+                                "kernel": m.group(4).strip(), "file": os.path.basename(path)})
+    return out
+
+
+def stored_traffic(workload: str, kernel_substring: str, profiles_dir: Optional[str] = None) -> Optional[int]:
+    """L2 <-> fabric bytes per launch of the kernel whose name contains `kernel_substring` on `workload`,
+    from a summary taken with the kernel sources as they are now; None when there is none (then the
+    figure would describe other code)."""
+    now = kernel_source_hash()
+    for rec in read_traffic_records(profiles_dir or os.path.join(ROOT, "profiles")):
+        if rec["workload"] == workload and rec["sources"] == now and _squash(kernel_substring) in _squash(rec["kernel"]):
+            return rec["bytes"]
+    return None
 
 
 def to_markdown(prof: dict, command: str) -> str:
@@ -368,6 +412,10 @@ def to_markdown(prof: dict, command: str) -> str:
         for name, v in sorted(k.get("extra_counters", {}).items()):
             out.append(f"| {name} | {v:.6g} |")
         out.append("")
+        if "gb_per_s" in m:
+            # one line a program can read back (bench.py: roofline.traffic), tied to the kernel sources
+            out += ["`" + traffic_record_line(w, prof.get("sources", kernel_source_hash()),
+                                              m["read_bytes"] + m["written_bytes"], k["kernel"]) + "`", ""]
     return "\n".join(out)
 
 

@@ -147,8 +147,26 @@ def test_built_library_comes_with_its_resource_table():
     if not os.path.exists(profile.RESOURCES):
         build.build_library()
     table = profile.load_resources()
-    # (the instance for plain GEMM operands: second template argument 0)
-    big = profile.match_resources(MFMA.replace("> >(", ">, 0>("), table)
+    # (the shipping instance for plain GEMM operands: view 0, not the timed one)
+    big = profile.match_resources(MFMA.replace("> >(", ">, 0, false>("), table)
     assert big is not None and big["scratch_bytes_per_lane"] == 0 and big["vgpr_spills"] == 0
     assert big["sgpr_spills"] <= 16
     assert big["lds_bytes_per_workgroup"] == 160 * 1024 and big["vgprs"] + big["agprs"] <= 256
+
+
+def test_traffic_records_round_trip(tmp_path):
+    """What the harness writes into a summary, bench.py reads back -- but only for the kernel
+    sources the counters were taken with."""
+    now = profile.kernel_source_hash()
+    assert len(now) == 16 and now == profile.kernel_source_hash()
+    kern = "void pgk::gemm_mfma_kernel<pgk::MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>, 0, false>(pgk::GemmArgs, int)"
+    text = "\n".join(["# a summary", "`" + profile.traffic_record_line("c3", now, 1745802240.4, kern) + "`",
+                      "`" + profile.traffic_record_line("c4", "0123456789abcdef", 235868169, kern) + "`", ""])
+    (tmp_path / "x_metric_set.md").write_text(text)
+    recs = profile.read_traffic_records(str(tmp_path))
+    assert [r["workload"] for r in recs] == ["c3", "c4"] and recs[0]["bytes"] == 1745802240 and recs[0]["kernel"] == kern
+    assert profile.stored_traffic("c3", "MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>, 0, false>", str(tmp_path)) == 1745802240
+    assert profile.stored_traffic("c3", "MfmaCfg<true,256,256,64,4,2,3,2>,0,false>", str(tmp_path)) == 1745802240   # white space
+    assert profile.stored_traffic("c4", "MfmaCfg<true, 256, 256, 64, 4, 2, 3, 2>, 0, false>", str(tmp_path)) is None  # other sources
+    assert profile.stored_traffic("c3", "MfmaCfg<false, 128, 128", str(tmp_path)) is None
+    assert profile.stored_traffic("c2", "MfmaCfg", str(tmp_path)) is None

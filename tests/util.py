@@ -45,3 +45,23 @@ def sample_rows(M: int, tile: int, n_random: int, seed: int) -> np.ndarray:
     rng = np.random.default_rng(seed)
     rows.update(rng.integers(0, M, n_random).tolist())
     return np.array(sorted(rows), dtype=np.int64)
+
+
+def strict_rel_err(got: np.ndarray, ref: np.ndarray) -> float:
+    """Unjudged companion of rel_err: plain max |g - r| / |r| over the entries with |r| >= RMS(r)."""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    rms = float(np.sqrt(np.mean(ref * ref)))
+    big = np.abs(ref) >= rms
+    if not big.any():
+        return 0.0
+    return float(np.max(np.abs(got[big] - ref[big]) / np.abs(ref[big])))
+
+
+def abs_inputs(A: np.ndarray, B: np.ndarray, bias, dtype: int):
+    """|A|, |B|, |bias| in the storage format of the inputs (bf16 bit patterns: sign bit cleared)."""
+    if dtype == gen.BF16:
+        a, b = A & np.uint16(0x7FFF), B & np.uint16(0x7FFF)
+    else:
+        a, b = np.abs(A), np.abs(B)
+    return a, b, (np.abs(bias) if bias is not None else None)
