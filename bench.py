@@ -177,27 +177,48 @@ def gemm_roofline(name, w, res, pgk, gen):
     }
 
 
-def phase_budget(name, pgk, gen, torch, launches=6):
-    """Where the time of the large bf16 kernel goes on workload `name` (c3 or c4): a few launches of
-    the timed instance (pgk_probe_gemm_phases), stamps of the last one reduced to medians over the
-    workgroups of each round.  Also gives the shader clock under the kernel: cycles per 100 MHz tick."""
+def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
+    """Where the time of the large bf16 kernel goes on workload `name` (c3 or c4), and at which
+    shader clock: `launches` timed launches of the measurement instance of the kernel
+    (pgk_probe_gemm_phases: the shipping kernel plus cycle-counter / 100 MHz-counter stamps),
+    rotating through `sets` copies of the buffers like the timed region of the bench.  Per launch:
+    event time, clock (cycles per tick summed over the workgroups), main-loop cycles per K tile;
+    the stamps of the last launch are reduced to medians over the workgroups of each round."""
     w = gen.WORKLOADS[name]
     if w.dtype != gen.BF16 or w.batch != 1:
         raise SystemExit("--phases: the timed instance is the large bf16 kernel (workloads c3, c4)")
     _, (dA, dB, dbias) = device_inputs(w, gen, torch)
-    C = torch.empty((1, w.M, w.N), dtype=torch.bfloat16, device="cuda")
     tiles_n = -(-w.N // 256)
-    part = torch.empty((tiles_n, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None
     wgs = -(-w.M // 256) * tiles_n
-    stamps = torch.zeros((wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    for i in range(launches):
-        if i == launches - 1:
-            ev0.record()
-        pgk.probe_gemm_phases(dA, dB, dbias, w.act, C, stamps, rowsum_partials=part)
-    ev1.record()
+    bufs = [dict(A=dA if i == 0 else dA.clone(), B=dB if i == 0 else dB.clone(),
+                 C=torch.empty((1, w.M, w.N), dtype=torch.bfloat16, device="cuda"),
+                 part=torch.empty((tiles_n, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None)
+            for i in range(max(1, sets))]
+    stamps = torch.zeros((launches, wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
+    scratch_stamps = torch.zeros((wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
+
+    def launch(i, st):
+        b = bufs[i % len(bufs)]
+        pgk.probe_gemm_phases(b["A"], b["B"], dbias, w.act, b["C"], st, rowsum_partials=b["part"])
+
+    for i in range(warmup):
+        launch(i, scratch_stamps)
     torch.cuda.synchronize()
-    st = stamps.cpu().numpy().astype(np.float64)
+    ev = [torch.cuda.Event(enable_timing=True) for _ in range(launches + 1)]
+    ev[0].record()
+    for i in range(launches):
+        launch(warmup + i, stamps[i])
+        ev[i + 1].record()
+    torch.cuda.synchronize()
+    per_ms = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(launches)])
+    st_all = stamps.cpu().numpy().astype(np.float64)
+    kt = -(-w.K // 64)
+    clocks, loop_cycles = [], []
+    for st in st_all:
+        cyc, tick = st[:, 0:12:2], st[:, 1:12:2]
+        clocks.append((cyc[:, 5] - cyc[:, 0]).sum() / (tick[:, 5] - tick[:, 0]).sum() * 0.1)
+        loop_cycles.append(float(np.median(cyc[:, 2] - cyc[:, 1])) / max(1, kt - 1))
+    st = st_all[-1]
     cyc, tick = st[:, 0:12:2], st[:, 1:12:2]                      # [workgroup][stamp]
     t0 = tick[:, 0].min()
     us = (tick - t0) / 100.0                                      # 100 MHz ticks -> microseconds since the first entry
@@ -218,39 +239,48 @@ def phase_budget(name, pgk, gen, torch, launches=6):
             "phases": [{"phase": names[k], "us_median": float(np.median(d_us[:, k])), "us_max": float(d_us[:, k].max()),
                         "cycles_median": float(np.median(d_cyc[:, k]))} for k in range(5)],
         })
-    span_ticks = tick[:, 5].max() - t0
-    total_cyc = (cyc[:, 5] - cyc[:, 0]).sum()
-    total_tick = (tick[:, 5] - tick[:, 0]).sum()
-    kt = -(-w.K // 64)
-    loop_cyc = float(np.median(cyc[:, 2] - cyc[:, 1]))
     xcd = st[:, 13].astype(np.int64) & 0xF
+    clk = float(np.median(clocks))
+    ms = float(np.median(per_ms))
+    achieved = w.flops / (ms * 1e-3) / 1e12
+    peak_at_clock = PEAK_TFLOPS["bf16"] * clk / 2.4
     return {
         "workload": DESCR[name], "workgroups": int(wgs), "rounds": rounds, "k_tiles": kt,
-        "kernel_span_us": float(span_ticks / 100.0),
-        "launch_us_event": float(ev0.elapsed_time(ev1) * 1e3),
-        "shader_clock_ghz_under_kernel": float(total_cyc / total_tick * 0.1),
-        "main_loop_cycles_per_k_tile": loop_cyc / max(1, kt - 1),
+        "launches": launches, "buffer_sets": len(bufs),
+        "launch_ms_median": ms, "launch_ms_min": float(per_ms.min()),
+        "kernel_span_us_last_launch": float((tick[:, 5].max() - t0) / 100.0),
+        "shader_clock_ghz_under_kernel": clk,
+        "shader_clock_ghz_min_max": [float(min(clocks)), float(max(clocks))],
+        "main_loop_cycles_per_k_tile": float(np.median(loop_cycles)),
         "mfma_issue_cycles_per_k_tile": 2048,
+        "main_loop_issue_efficiency": 2048.0 / float(np.median(loop_cycles)),
+        "achieved_tflops": achieved,
+        "peak_tflops_at_this_clock": peak_at_clock,      # the published peak is quoted at 2.4 GHz
+        "frac_of_peak_at_this_clock": achieved / peak_at_clock,
         "xcd_of_workgroup_matches_id_mod_8": bool(np.all(xcd == (np.arange(wgs) % 8))),
         "rounds_detail": per_round,
-        "how": "thread-0 stamps of s_memtime / s_memrealtime inside a measurement instance of the kernel "
-               "(pgk_probe_gemm_phases); medians over the workgroups of a round",
+        "how": "wave-0 stamps of s_memtime / s_memrealtime inside a measurement instance of the kernel "
+               "(pgk_probe_gemm_phases); clock and cycles: median over the launches; phases: medians over the "
+               "workgroups of a round, last launch",
     }
 
 
 def gpu_clocks():
-    """Clock readings of the board right after the timed region, as the system tool reports them
-    (best effort: None when the tool is missing or prints something else)."""
-    import shutil
-    import subprocess
-    tool = shutil.which("rocm-smi") or "/opt/rocm/bin/rocm-smi"
-    try:
-        out = subprocess.run([tool, "--showclocks", "--json"], capture_output=True, text=True, timeout=20)
-        data = json.loads(out.stdout)
-        card = next(iter(data.values()))
-        return {k: v for k, v in card.items() if "clock" in k.lower()}
-    except Exception as exc:      # noqa: BLE001
-        return {"unavailable": str(exc)[:120]}
+    """Clock levels of the board right after the timed region, read from the driver's sysfs files
+    (no child process: a GPU process must not start other programs).  Best effort."""
+    import glob
+    out = {}
+    for path in sorted(glob.glob("/sys/class/drm/card*/device/pp_dpm_sclk") + glob.glob("/sys/class/drm/card*/device/pp_dpm_mclk")):
+        try:
+            with open(path) as f:
+                levels = [ln.strip() for ln in f if ln.strip()]
+        except OSError as exc:
+            out[path] = f"unreadable: {exc}"
+            continue
+        cur = [ln for ln in levels if ln.endswith("*")]
+        key = path.split("/")[4] + "/" + path.rsplit("_", 1)[-1]
+        out[key] = {"current": cur[0].rstrip(" *") if cur else None, "levels": [ln.rstrip(" *") for ln in levels]}
+    return out or {"unavailable": "no pp_dpm_sclk / pp_dpm_mclk under /sys/class/drm"}
 
 
 def run_reduce_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
@@ -616,12 +646,17 @@ def main():
     del host
     if w.dtype == gen.BF16 and w.batch == 1 and not args.no_ceilings:
         # the shader clock the kernel itself sees (cycle counter against the 100 MHz counter)
+        # (the same number of launches, rotating through the same number of buffer sets, with the
+        # measurement instance of the kernel: what the chip's power management grants this kernel)
         try:
-            pb = phase_budget(name, pgk, gen, torch, launches=3)
-            out["shader_clock_ghz_under_kernel"] = pb["shader_clock_ghz_under_kernel"]
-            out["main_loop_cycles_per_k_tile"] = pb["main_loop_cycles_per_k_tile"]
+            pb = phase_budget(name, pgk, gen, torch, launches=args.steps, sets=args.buffer_sets, warmup=args.warmup)
+            pb.pop("rounds_detail")
+            roofline["at_measured_clock"] = {k: pb[k] for k in (
+                "shader_clock_ghz_under_kernel", "shader_clock_ghz_min_max", "launch_ms_median", "achieved_tflops",
+                "peak_tflops_at_this_clock", "frac_of_peak_at_this_clock", "main_loop_cycles_per_k_tile",
+                "main_loop_issue_efficiency", "how")}
         except Exception as exc:      # noqa: BLE001  (a measurement aid must not take the bench line down)
-            out["shader_clock_ghz_under_kernel"] = None
+            roofline["at_measured_clock"] = None
             log(f"[phases] skipped: {exc}")
         torch.cuda.empty_cache()
     others = {}

@@ -15,6 +15,20 @@ OBJ_DIR = os.path.join(HERE, "_build")
 # what the compiler reports per kernel (registers, scratch, LDS, waves per SIMD), written at
 # build time next to the library; the profile harness reads it
 RESOURCES = os.path.join(HERE, "kernel_resources.json")
+# hash of the sources the library was built from (tests compare it with the sources as they stand)
+BUILT_FROM = os.path.join(HERE, "libpgk.built_from")
+
+
+def source_hash() -> str:
+    """A short hash of csrc/*.hip and *.h as they stand."""
+    import glob
+    import hashlib
+    h = hashlib.sha256()
+    for path in sorted(glob.glob(os.path.join(CSRC, "*.hip")) + glob.glob(os.path.join(CSRC, "*.h"))):
+        h.update(os.path.basename(path).encode())
+        with open(path, "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()[:16]
 
 SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_mfma_conv.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
            "pgk_probe.hip", "pgk_conv.hip", "pgk_pack.hip"]
@@ -76,6 +90,9 @@ def _compile(src: str):
 def build_library(verbose: bool = False) -> str:
     """Compile every HIP source for gfx950 and link libpgk.so.  Always recompiles."""
     os.makedirs(OBJ_DIR, exist_ok=True)
+    built_from = source_hash()
+    if os.path.exists(BUILT_FROM):
+        os.remove(BUILT_FROM)
     with ThreadPoolExecutor(max_workers=6) as ex:
         compiled = list(ex.map(_compile, SOURCES))
     objs = [c[0] for c in compiled]
@@ -97,8 +114,10 @@ def build_library(verbose: bool = False) -> str:
     res = subprocess.run([sys.executable, "-c", check, LIB], capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError(f"{LIB} does not load:\n{res.stderr}")
+    with open(BUILT_FROM, "w") as f:
+        f.write(built_from + "\n")
     if verbose:
-        print(f"built {LIB}")
+        print(f"built {LIB} from sources {built_from}")
     return LIB
 
 

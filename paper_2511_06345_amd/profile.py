@@ -294,7 +294,7 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
                      calibrate: bool = True, limit_s: int = 240, all_kernels: bool = False) -> dict:
     os.makedirs(out_dir, exist_ok=True)
     program = ["python3", BENCH, "--workload", workload, "--steps", str(steps), "--warmup", str(warmup),
-               "--no-cpu-baseline", "--no-ceilings"]
+               "--no-cpu-baseline", "--no-ceilings", "--headline-only"]
     t_dir = os.path.join(out_dir, "trace")
     trace_run(t_dir, program, limit_s)
     trace = parse_kernel_trace(_find(t_dir, "kernel_trace.csv"), warmup_calls=warmup)
@@ -341,13 +341,8 @@ def profile_workload(workload: str, out_dir: str, extra: Sequence[str] = (), ste
 def kernel_source_hash() -> str:
     """A short hash of the kernel sources as they stand (csrc/*.hip, *.h): counter values taken from
     one version of the kernels say nothing about another, so every stored traffic figure carries it."""
-    import hashlib
-    h = hashlib.sha256()
-    for path in sorted(glob.glob(os.path.join(HERE, "csrc", "*.hip")) + glob.glob(os.path.join(HERE, "csrc", "*.h"))):
-        h.update(os.path.basename(path).encode())
-        with open(path, "rb") as f:
-            h.update(f.read())
-    return h.hexdigest()[:16]
+    from .build import source_hash
+    return source_hash()
 
 
 _TRAFFIC_RE = re.compile(r"^traffic-record: workload=(\S+) sources=(\S+) bytes=(\d+) kernel=(.+)$")

@@ -32,6 +32,15 @@ def test_exports_match_header(lib):
         assert hasattr(lib, name), name
 
 
+def test_library_is_built_from_the_sources_as_they_stand(lib):
+    """The GPU tests, smoke() and bench.py load the library that is there: a library older than
+    the sources would be tested in place of the code."""
+    from paper_2511_06345_amd import build
+    assert os.path.exists(build.BUILT_FROM), "libpgk.so carries no record of its sources: rebuild it"
+    assert open(build.BUILT_FROM).read().strip() == build.source_hash(), \
+        "csrc/ has changed since libpgk.so was built: run `python -m paper_2511_06345_amd.build`"
+
+
 def test_version_and_status_strings(lib):
     assert binding.version() == 200
     seen = set()
