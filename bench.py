@@ -454,7 +454,7 @@ def reduce_main(args, name, pgk, gen, torch):
             "unit": "GB/s",
             "frac": head["algorithmic_gbs"] / PEAK_HBM_GBS,
             "launch_ms_avg": head["call_ms_avg"],
-            "traffic": __import__("paper_2511_06345_amd.profile", fromlist=["x"]).stored_traffic(name, "pgk::reduce_max"),
+            "traffic": __import__("paper_2511_06345_amd.profile", fromlist=["x"]).stored_traffic(name, "reduce_max_"),
             "traffic_unit": "bytes per launch of the first (streaming) kernel (rocprofv3 FETCH_SIZE and WRITE_SIZE, scaled by "
                             "a plain 1 GiB copy); null: no summary taken with the kernel sources as they are now",
         },
@@ -577,6 +577,11 @@ def main():
     if args.gpus != 1:
         sys.exit("bench.py: this library is single-GPU; run with --gpus 1 (nothing here uses a second GPU)")
 
+    if not args.no_cpu_baseline:
+        # the oracle's C library is compiled (a child process) before this process touches the GPU:
+        # a process that has initialised the GPU starts no other program
+        import oracle
+        oracle.build()
     import torch
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible")
@@ -604,7 +609,8 @@ def main():
         return
     w = gen.WORKLOADS[name]
     if args.phases:
-        print(json.dumps({"phase_budget": phase_budget(name, pgk, gen, torch)}), flush=True)
+        print(json.dumps({"phase_budget": phase_budget(name, pgk, gen, torch, launches=args.steps, sets=args.buffer_sets,
+                                                       warmup=args.warmup)}), flush=True)
         return
     head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
     clocks = gpu_clocks()
