@@ -54,7 +54,7 @@ REDUCE_DESCR = {
 CONV_DESCR = {
     "v1": "v1: fp32 conv1d [16, 64, 65536] * [128, 64, 3], stride 1, pad 1, bias + ReLU (matrix-core path)",
     "v2": "v2: bf16 conv1d [8, 256, 16384] * [256, 256, 5], stride 1, pad 4, dilation 2, bias + SiLU (matrix-core path)",
-    "v3": "v3: fp32 conv1d [4, 48, 32768] * [64, 48, 5], stride 2, pad 2, bias (bounds-checked path)",
+    "v3": "v3: fp32 conv1d [4, 48, 32768] * [64, 48, 5], stride 2, pad 2, bias (matrix-core path on per-phase copies of the input)",
 }
 
 

@@ -1017,10 +1017,9 @@ int pgk_conv1d(const void* x, const void* w, const float* bias, void* y, int64_t
         int64_t ldb = L, cin_k = Cin;
         if (pl.table) {
             cin_k = pl.cin_pad;
-            if (pgk::launch_conv_repack_weights(w, wr, (int)Cout, (int)Cin, (int)pl.cin_pad, (int)Kw, dtype, st) != hipSuccess)
-                return PGK_ERR_HIP;
+            // the copies of the input and the regrouped, channel-padded weights in one launch
             if (pgk::launch_conv_phase_copies(x, xp, B, (int)Cin, (int)pl.cin_pad, (int)L, (int)pl.Lq, (int)pad, (int)stride,
-                                              pl.shifts, dtype, st) != hipSuccess) return PGK_ERR_HIP;
+                                              pl.shifts, w, wr, (int)Cout, (int)Kw, dtype, st) != hipSuccess) return PGK_ERR_HIP;
             bsrc = xp;
             ldb = pl.Lq;
             a.K = (int)(pl.cin_pad * Kw);

@@ -57,17 +57,42 @@ __global__ __launch_bounds__(256) void conv_repack_weights_kernel(const T* __res
     wr[t] = ci < Cin ? w[(co * Cin + ci) * Kw + k] : T(0);
 }
 
+// One 16-byte chunk of the regrouped weights: wr[co][k][ci0 .. ci0 + EPC) = w[co][ci][k] for ci < Cin,
+// 0 for the padding channels up to Cin_pad (a multiple of the chunk).  c: chunk index (co, k, ci / EPC).
+template <typename T>
+__device__ __forceinline__ void repack_weight_chunk(long long c, const T* __restrict__ w, T* __restrict__ wr,
+                                                    int Cout, int Cin, int Cin_pad, int Kw)
+{
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const int cpr = Cin_pad / EPC;
+    if (c >= (long long)Cout * Kw * cpr) return;
+    const int ci0 = (int)(c % cpr) * EPC;
+    const long long q = c / cpr;
+    const int k = (int)(q % Kw);
+    const long long co = q / Kw;
+    T v[EPC];
+#pragma unroll
+    for (int u = 0; u < EPC; ++u) v[u] = ci0 + u < Cin ? w[(co * Cin + ci0 + u) * Kw + k] : T(0);
+    u32x4 out;
+    __builtin_memcpy(&out, v, 16);
+    *(u32x4*)(wr + (size_t)c * EPC) = out;
+}
+
 // xc[c][b][ci][j] = x[b][ci][(j + h) * stride + phase - pad] (inside [0, L), ci < Cin; else 0) with
 // c = phase * shifts + h.  One thread per 16-byte chunk of the copies (rows of Lq elements, a
-// multiple of the chunk): element loads, one 16-byte store.
+// multiple of the chunk): element loads, one 16-byte store.  Also regroups the weights (padded to
+// Cin_pad channels) into wr.
 template <typename T>
 __global__ __launch_bounds__(256) void conv_phase_copies_kernel(const T* __restrict__ x, T* __restrict__ xc, long long B,
                                                                 int Cin, int Cin_pad, int L, int Lq, int pad, int stride,
-                                                                int shifts, long long total_chunks)
+                                                                int shifts, long long total_chunks,
+                                                                const T* __restrict__ w, T* __restrict__ wr, int Cout, int Kw)
 {
     constexpr int EPC = 16 / (int)sizeof(T);
     const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
-    if (t >= total_chunks) return;
+    // the threads after the copies regroup the weights (same launch: a second one costs as much
+    // as either piece of work)
+    if (t >= total_chunks) { repack_weight_chunk<T>(t - total_chunks, w, wr, Cout, Cin, Cin_pad, Kw); return; }
     const int cpr = Lq / EPC;                                // chunks per row
     const long long row = t / cpr;                           // (c * B + b) * Cin_pad + ci
     const int j0 = (int)(t - row * cpr) * EPC;
@@ -89,34 +114,41 @@ __global__ __launch_bounds__(256) void conv_phase_copies_kernel(const T* __restr
 }
 
 // Both preparations of the in-place path in one launch (each is a few microseconds of work;
-// a second launch costs as much again).  Workgroups [0, strip_blocks) fill the strips,
-// strips[e][row][j] = x[row][first[e] + j] inside [0, L), else 0, numbered as (slab of 256
-// columns, row, edge) with the slab fastest; the rest regroup the weights.
+// a second launch costs as much again).  One thread per 16-byte chunk of output: threads
+// [0, strip_chunks) fill the strips, strips[e][row][j] = x[row][first[e] + j] inside [0, L), else
+// 0 (W, the strip's row length, is a multiple of the chunk), numbered (chunk of the row, row,
+// edge) with the chunk fastest; the rest regroup the weights, wr[co][k][ci] = w[co][ci][k], eight
+// (bf16) or four (fp32) consecutive ci per thread (Cin is a multiple of the chunk on this path).
 template <typename T>
 __global__ __launch_bounds__(256) void conv_prepare_kernel(const T* __restrict__ x, T* __restrict__ strips, long long rows,
-                                                           int L, int W, int slabs, EdgeCols cols, unsigned int strip_blocks,
+                                                           int L, int W, EdgeCols cols, long long strip_chunks,
                                                            const T* __restrict__ w, T* __restrict__ wr, int Cout, int Cin, int Kw)
 {
-    if (blockIdx.x < strip_blocks) {
-        const unsigned int slab = blockIdx.x % (unsigned int)slabs;
-        const unsigned int r = blockIdx.x / (unsigned int)slabs;
-        const long long row = (long long)(r % (unsigned long long)rows);
-        const int e = (int)(r / (unsigned long long)rows);
-        const int j = (int)slab * 256 + (int)threadIdx.x;
-        if (j >= W) return;
-        const long long s = (long long)cols.first[e] + j;
-        strips[((size_t)e * (size_t)rows + (size_t)row) * (size_t)W + j] =
-            (s >= 0 && s < L) ? x[(size_t)row * (size_t)L + (size_t)s] : T(0);
+    constexpr int EPC = 16 / (int)sizeof(T);
+    const long long t = (long long)blockIdx.x * 256 + threadIdx.x;
+    T v[EPC];
+    T* dst;
+    if (t < strip_chunks) {
+        const int cpr = W / EPC;                              // chunks per strip row
+        const long long r = t / cpr;
+        const int j0 = (int)(t - r * cpr) * EPC;
+        const long long row = r % rows;
+        const int e = (int)(r / rows);
+        const T* src = x + (size_t)row * (size_t)L;
+        const long long s0 = (long long)cols.first[e] + j0;
+#pragma unroll
+        for (int u = 0; u < EPC; ++u) {
+            const long long sidx = s0 + u;
+            v[u] = (sidx >= 0 && sidx < L) ? src[sidx] : T(0);
+        }
+        dst = strips + ((size_t)e * (size_t)rows + (size_t)row) * (size_t)W + j0;
+    } else {
+        repack_weight_chunk<T>(t - strip_chunks, w, wr, Cout, Cin, Cin, Kw);
         return;
     }
-    const long long total = (long long)Cout * Cin * Kw;
-    const long long t = (long long)(blockIdx.x - strip_blocks) * 256 + threadIdx.x;     // index into wr: (co, k, ci)
-    if (t >= total) return;
-    const int ci = (int)(t % Cin);
-    const long long q = t / Cin;
-    const int k = (int)(q % Kw);
-    const long long co = q / Kw;
-    wr[t] = w[(co * Cin + ci) * Kw + k];
+    u32x4 out;
+    __builtin_memcpy(&out, v, 16);
+    *(u32x4*)dst = out;
 }
 
 }  // namespace
@@ -124,39 +156,44 @@ __global__ __launch_bounds__(256) void conv_prepare_kernel(const T* __restrict__
 hipError_t launch_conv_prepare(const void* x, void* strips, long long rows, int L, int W, int n_edges, const int* first_col,
                                const void* w, void* wr, int Cout, int Cin, int Kw, int dtype, hipStream_t s)
 {
+    const int epc = dtype == DT_BF16 ? 8 : 4;
     if (rows <= 0 || n_edges < 0 || n_edges > 3) return hipErrorInvalidValue;
+    // whole 16-byte chunks on both sides (the callers' plan guarantees it), 16-byte aligned buffers
+    if (Cin % epc != 0 || (n_edges > 0 && W % epc != 0)) return hipErrorInvalidValue;
+    if (((uintptr_t)strips | (uintptr_t)wr) % 16 != 0) return hipErrorInvalidValue;
     EdgeCols cols{};
     for (int e = 0; e < n_edges; ++e) cols.first[e] = first_col[e];
-    const int slabs = (W + 255) / 256;
-    const long long strip_blocks = n_edges > 0 ? (long long)slabs * rows * n_edges : 0;
-    const long long repack_blocks = ((long long)Cout * Cin * Kw + 255) / 256;
-    const long long blocks = strip_blocks + repack_blocks;
+    const long long strip_chunks = n_edges > 0 ? (long long)(W / epc) * rows * n_edges : 0;
+    const long long repack_chunks = (long long)Cout * Kw * (Cin / epc);
+    const long long blocks = (strip_chunks + repack_chunks + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(conv_prepare_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)x, (unsigned short*)strips, rows, L, W, slabs > 0 ? slabs : 1, cols,
-                           (unsigned int)strip_blocks, (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw);
+                           (const unsigned short*)x, (unsigned short*)strips, rows, L, W, cols, strip_chunks,
+                           (const unsigned short*)w, (unsigned short*)wr, Cout, Cin, Kw);
     else
         hipLaunchKernelGGL(conv_prepare_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)x,
-                           (float*)strips, rows, L, W, slabs > 0 ? slabs : 1, cols, (unsigned int)strip_blocks,
-                           (const float*)w, (float*)wr, Cout, Cin, Kw);
+                           (float*)strips, rows, L, W, cols, strip_chunks, (const float*)w, (float*)wr, Cout, Cin, Kw);
     return hipGetLastError();
 }
 
 hipError_t launch_conv_phase_copies(const void* x, void* xc, long long B, int Cin, int Cin_pad, int L, int Lq, int pad,
-                                    int stride, int shifts, int dtype, hipStream_t s)
+                                    int stride, int shifts, const void* w, void* wr, int Cout, int Kw, int dtype, hipStream_t s)
 {
     const int epc = dtype == DT_BF16 ? 8 : 4;
-    if (Lq % epc != 0 || B <= 0) return hipErrorInvalidValue;
+    if (Lq % epc != 0 || Cin_pad % epc != 0 || B <= 0) return hipErrorInvalidValue;
+    if (((uintptr_t)xc | (uintptr_t)wr) % 16 != 0) return hipErrorInvalidValue;
     const long long chunks = (long long)stride * shifts * B * Cin_pad * (Lq / epc);
-    const long long blocks = (chunks + 255) / 256;
+    const long long repack_chunks = (long long)Cout * Kw * (Cin_pad / epc);
+    const long long blocks = (chunks + repack_chunks + 255) / 256;
     if (blocks <= 0 || blocks > 0x7fffffffLL) return hipErrorInvalidValue;
     if (dtype == DT_BF16)
         hipLaunchKernelGGL(conv_phase_copies_kernel<unsigned short>, dim3((unsigned int)blocks), dim3(256), 0, s,
-                           (const unsigned short*)x, (unsigned short*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks);
+                           (const unsigned short*)x, (unsigned short*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks,
+                           (const unsigned short*)w, (unsigned short*)wr, Cout, Kw);
     else
         hipLaunchKernelGGL(conv_phase_copies_kernel<float>, dim3((unsigned int)blocks), dim3(256), 0, s, (const float*)x,
-                           (float*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks);
+                           (float*)xc, B, Cin, Cin_pad, L, Lq, pad, stride, shifts, chunks, (const float*)w, (float*)wr, Cout, Kw);
     return hipGetLastError();
 }
 

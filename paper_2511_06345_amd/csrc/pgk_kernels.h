@@ -158,8 +158,9 @@ hipError_t launch_conv_pad_input(const void* x, void* xp, long long rows, int L,
 // Copies of the input for the table-driven path: copy c = phase * shifts + h (phase < stride,
 // h < shifts) is xc[c][b][ci][j] = x[b][ci][(j + h) * stride + phase - pad] inside [0, L) and for
 // ci < Cin, else 0; ci runs to Cin_pad, j to Lq.
+// (the same launch regroups the weights: wr[co][k][ci] = w[co][ci][k], zero up to Cin_pad)
 hipError_t launch_conv_phase_copies(const void* x, void* xc, long long B, int Cin, int Cin_pad, int L, int Lq, int pad,
-                                    int stride, int shifts, int dtype, hipStream_t s);
+                                    int stride, int shifts, const void* w, void* wr, int Cout, int Kw, int dtype, hipStream_t s);
 // wr[co][k][ci] = w[co][ci][k] for ci < Cin, 0 for Cin <= ci < Cin_pad
 hipError_t launch_conv_repack_weights(const void* w, void* wr, int Cout, int Cin, int Cin_pad, int Kw, int dtype, hipStream_t s);
 // the regrouped weights and, in the same launch, strip e (e < n_edges, may be 0) of
