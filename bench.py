@@ -160,6 +160,8 @@ def gemm_kernel_name(w, pgk, gen):
     if not plan["matrix_core"]:
         return "pgk::gemm_guarded_kernel", plan
     bf = w.dtype == gen.BF16
+    if (bm, bn) == (32, 32):
+        return "pgk::gemm_tiny_f32_kernel", plan
     layout = {(256, 256): "4, 2, 3, 2", (128, 128): "2, 2, 3, 2" if bf else "2, 2, 2, 1", (64, 64): "2, 2, 2, 2",
               (256, 128): "4, 2, 3, 2", (128, 256): "2, 4, 3, 2", (32, 128): "1, 4, 2, 2", (128, 32): "4, 1, 2, 2"}[(bm, bn)]
     return f"MfmaCfg<{'true' if bf else 'false'}, {bm}, {bn}, {bk}, {layout}>, 0, false>", plan

@@ -30,7 +30,7 @@ def source_hash() -> str:
             h.update(f.read())
     return h.hexdigest()[:16]
 
-SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_mfma_conv.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
+SOURCES = ["pgk_api.hip", "pgk_gemm_mfma.hip", "pgk_gemm_mfma_conv.hip", "pgk_gemm_tiny.hip", "pgk_gemm_guarded.hip", "pgk_reduce.hip", "pgk_reduce_max.hip",
            "pgk_probe.hip", "pgk_conv.hip", "pgk_pack.hip"]
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

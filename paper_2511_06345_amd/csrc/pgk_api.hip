@@ -295,10 +295,24 @@ int half_tile_kind(int64_t M, int64_t N, int dtype, int64_t units, bool b_trans)
 // leave a quarter of the CUs idle or K is at most two bf16 K tiles, else the large tile -- unless its grid ends in a poorly
 // filled round and the round model above gives another shape at least 6 % less time (K below
 // 1024: the model is not consulted).
-int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans)
+// Latency-bound fp32 problems: so few 64 x 64 tiles that most of the chip would idle behind one
+// chain of K/2 dependent matrix instructions per wave, and a K too short for a two-pass split.
+// They run on 32 x 32 tiles whose four waves split the K range (256 x 256 x 256: 16 workgroups
+// with chains of 128 instructions become 64 workgroups with chains of 32).
+bool tiny_problem(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans, int64_t ldb)
+{
+    if (dtype != PGK_DTYPE_F32 || b_trans || K < 64 || K % 4 || N % 4 || (ldb ? ldb : N) % 4) return false;
+    if (M <= 32 || N <= 32) return false;                       // (the skinny tiles' business)
+    const long double tiles64 = (long double)((M + 63) / 64) * ((N + 63) / 64) * units;
+    const int64_t ksteps = (K + 31) / 32;
+    return tiles64 <= 64.0L && ksteps < 2 * 16;                 // (from 2 x 16 K tiles on, the K range is split in two passes)
+}
+
+int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bool b_trans, int64_t ldb = 0)
 {
     // (K = 0: a convolution, which keeps to the shapes its operand views were written for)
     if (const int skinny = skinny_tile_kind(M, N); K > 0 && skinny >= 0 && pgk::mfma_has_tile(dtype, skinny, b_trans)) return skinny;
+    if (K > 0 && tiny_problem(M, N, K, dtype, units, b_trans, ldb)) return pgk::TILE_TINY;
     if (large_tile_mostly_empty(M, N, dtype)) return pgk::TILE_SMALL;
     if (const int half = half_tile_kind(M, N, dtype, units, b_trans); half >= 0) return half;
     // One or two bf16 K tiles: there is no main loop for the large tile to be good at, and two small
@@ -330,7 +344,7 @@ Path choose_path(bool aligned, int64_t M, int64_t N, int64_t K, int dtype, int64
 {
     const bool ok = aligned && mfma_shape_ok(M, N, K, dtype, b_trans, ldb);
     if (!ok) return Path{false, false, pgk::guarded_tile_shape()};
-    int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans);
+    int kind = kind_forced >= 0 ? kind_forced : auto_tile_kind(M, N, K, dtype, units, b_trans, ldb);
     if (!pgk::mfma_has_tile(dtype, kind, b_trans)) kind = pgk::TILE_SMALL;      // (the narrow tile with a plain B)
     return Path{true, kind, pgk::mfma_tile_shape(dtype, kind)};
 }
@@ -377,7 +391,10 @@ int run_split_passes(const void* A, const void* B, const float* bias, void* C, f
                      int64_t K, int64_t batch, int act, int dtype, const SplitPlan& plan, int small_tile,
                      float* workspace, float* part, hipStream_t st, bool aligned, bool b_trans, int64_t ldb = 0)
 {
-    const Path path = choose_path(aligned, M, N, K, dtype, batch * plan.splits, small_tile, b_trans, ldb);
+    Path path = choose_path(aligned, M, N, K, dtype, batch * plan.splits, small_tile, b_trans, ldb);
+    // (the K-splitting tile of latency-bound problems has no first-pass form: its slices are its waves)
+    if (path.mfma && path.kind == pgk::TILE_TINY)
+        path = choose_path(aligned, M, N, K, dtype, batch * plan.splits, pgk::TILE_SMALL, b_trans, ldb);
     const int64_t tiles_m = (M + path.tile.bm - 1) / path.tile.bm;
     const int64_t tiles_n = (N + path.tile.bn - 1) / path.tile.bn;
     if ((long double)tiles_m * tiles_n * batch * plan.splits > 2.0e9L) return PGK_ERR_UNSUPPORTED;

@@ -8,11 +8,13 @@ bool mfma_has_tile(int dtype, int kind, bool b_trans)
 {
     if (kind == TILE_LARGE || kind == TILE_SMALL || kind == TILE_FLAT) return true;
     if (kind == TILE_NARROW) return b_trans;
+    if (kind == TILE_TINY) return dtype == DT_F32 && !b_trans;
     return (kind == TILE_TALL || kind == TILE_WIDE) && dtype == DT_BF16;   // (either layout of B)
 }
 
 TileShape mfma_tile_shape(int dtype, int kind)
 {
+    if (kind == TILE_TINY && dtype == DT_F32) return tiny_tile_shape();
     if (kind == TILE_NARROW)
         return dtype == DT_BF16 ? TileShape{CfgBF16NarrowT::BM, CfgBF16NarrowT::BN, CfgBF16NarrowT::BK}
                                 : TileShape{CfgF32NarrowT::BM, CfgF32NarrowT::BN, CfgF32NarrowT::BK};
@@ -35,6 +37,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
     // a convolution's operand views (one bias per row marks them) have instances of their own
     if (a.bias_per_row) return launch_gemm_mfma_conv(a, dtype, kind, out_mode, s);
     if (a.b_tiles_per_tap != 0x7fffffff || a.b_col_shift != 0 || a.edge_B[0] || a.b_use_tap_table) return hipErrorInvalidValue;
+    if (kind == TILE_TINY) return out_mode == 0 ? launch_gemm_tiny(a, s) : hipErrorInvalidValue;
     const bool small = kind == TILE_SMALL;
     if (kind == TILE_NARROW) return dtype == DT_BF16 ? launch_cfg<CfgBF16NarrowT, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32NarrowT, VIEW_GEMM>(a, out_mode, s);
     if (kind == TILE_FLAT) {

@@ -103,7 +103,9 @@ inline void set_b_transposed(GemmArgs& a)
 // column / row would be at most half full; and two skinny tiles per type, narrow (32 columns; B
 // transposed only) and flat (32 rows).  A kind the type does not have gives the large tile.
 struct TileShape { int bm, bn, bk; };
-enum { TILE_LARGE = 0, TILE_SMALL = 1, TILE_TALL = 2, TILE_WIDE = 3, TILE_NARROW = 4, TILE_FLAT = 5 };
+// TILE_TINY (fp32, B as [K][N] only): 32 x 32 tiles whose four waves split the K range -- the
+// latency-bound problems of a few tiles (pgk_gemm_tiny.hip).
+enum { TILE_LARGE = 0, TILE_SMALL = 1, TILE_TALL = 2, TILE_WIDE = 3, TILE_NARROW = 4, TILE_FLAT = 5, TILE_TINY = 6 };
 TileShape mfma_tile_shape(int dtype, int kind);
 bool mfma_has_tile(int dtype, int kind, bool b_trans);
 TileShape guarded_tile_shape();
@@ -117,6 +119,11 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
 // entries, B tiles walking tap after tap, edge strips; B as [K][N], out_mode 0); reached through
 // launch_gemm_mfma.
 hipError_t launch_gemm_mfma_conv(const GemmArgs& a, int dtype, int kind, int out_mode, hipStream_t s);
+
+// fp32, 32 x 32 tiles, K split over the four waves of a workgroup (out_mode 0; K, N, ldb multiples
+// of 4, A and B on 16-byte boundaries); reached through launch_gemm_mfma with TILE_TINY.
+TileShape tiny_tile_shape();
+hipError_t launch_gemm_tiny(const GemmArgs& a, hipStream_t s);
 
 // The large bf16 tile, plain operand views, out_mode 0, with phase stamps (a.stamps set).
 hipError_t launch_gemm_mfma_timed(const GemmArgs& a, hipStream_t s);

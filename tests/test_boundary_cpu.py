@@ -81,8 +81,8 @@ def test_fused_workspace_is_the_callers(lib):
     # row sums over four tile columns of 256: one fp32 partial per row and tile column
     assert q(16384, 1024, 4096, 1, BF16, RS) == 4 * 16384 * 4
     assert q(16384, 1024, 4096, 1, BF16) == 0
-    # the small fp32 workload: four tile columns of 64
-    assert q(256, 256, 256, 1, F32, RS) == 4 * 256 * 4
+    # the small fp32 workload: eight tile columns of 32 (the K-splitting tile of latency-bound problems)
+    assert q(256, 256, 256, 1, F32, RS) == 8 * 256 * 4
     # one tile column: the kernel's row sums are final
     assert q(65536, 128, 1024, 1, BF16, RS) == 0
     # few tiles and a long K: the partial products of the automatic split (8 slices here)
@@ -177,12 +177,23 @@ def test_tile_table_and_split_rule(lib):
         assert got == {"matrix_core": matrix_core, "tile": tile, "slices": slices, "workgroups": wgs}, (shape, dtype, got)
 
     # the five workloads (c5 through the fused call: same plan as the split call's automatic one)
-    expect((256, 256, 256, 1), F32, (64, 64, 32), 1, 16)
+    expect((256, 256, 256, 1), F32, (32, 32, 32), 1, 64)
     expect((4096, 4096, 4096, 1), F32, (128, 128, 32), 1, 1024)
     expect((8192, 8192, 8192, 1), BF16, (256, 256, 64), 1, 1024)
     expect((16384, 1024, 4096, 1), BF16, (256, 256, 64), 1, 256)
     expect((256, 256, 65536, 16), F32, (128, 128, 32), 8, 512)
     assert lib.pgk_splitk_auto_splits(256, 256, 65536, 16, F32, 0) == 8
+    # latency-bound fp32 problems (at most 64 tiles of 64 x 64, K below 32 K tiles, plain B, K and N
+    # multiples of 4): 32 x 32 tiles whose waves split K; otherwise the small tile as before
+    expect((128, 128, 64, 1), F32, (32, 32, 32), 1, 16)
+    expect((100, 36, 64, 2), F32, (32, 32, 32), 1, 16)
+    expect((512, 512, 992, 1), F32, (32, 32, 32), 1, 256)
+    expect((512, 512, 1024, 1), F32, (64, 64, 32), 2, 128)              # 32 K tiles: two passes
+    expect((256, 256, 256, 1), F32, (64, 64, 32), 1, 16, bt=True)
+    expect((256, 256, 32, 1), F32, (64, 64, 32), 1, 16)                 # a single K step: nothing to split
+    expect((256, 258, 256, 1), F32, (64, 64, 32), 1, 20)                # N off the 16-byte grid
+    expect((576, 512, 256, 1), F32, (64, 64, 32), 1, 72)                # more than 64 tiles of 64 x 64
+    expect((256, 256, 256, 1), BF16, (128, 128, 64), 1, 4)
     # last tile column / row at most half full: half tiles (bf16, either layout of B)
     expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256)
     expect((128, 65536, 1024, 1), BF16, (128, 256, 64), 1, 256)
@@ -379,7 +390,7 @@ def test_plan_is_consistent_on_random_shapes(lib):
     least 16 K tiles each, and only small problems are left to the bounds-checked kernel."""
     rng = np.random.default_rng(7)
     tiles = {gen.BF16: {(256, 256, 64), (128, 128, 64), (256, 128, 64), (128, 256, 64), (128, 32, 64), (32, 128, 64)},
-             gen.F32: {(128, 128, 32), (64, 64, 32), (128, 32, 32), (32, 128, 32)}}
+             gen.F32: {(128, 128, 32), (64, 64, 32), (128, 32, 32), (32, 128, 32), (32, 32, 32)}}
     for n in range(3000):
         dtype = gen.BF16 if rng.integers(2) else gen.F32
         hi = [40, 300, 3000, 40000][n % 4]
@@ -397,9 +408,12 @@ def test_plan_is_consistent_on_random_shapes(lib):
             assert p["tile"] in tiles[dtype], what
             if p["slices"] > 1:
                 assert -(-K // bk) // p["slices"] >= 16, what
-            if bm == 32:
+            if (bm, bn) == (32, 32):
+                assert dtype == gen.F32 and not bt and M > 32 and N > 32 and K % 4 == 0 and N % 4 == 0 and 64 <= K < 1024, what
+                assert -(-M // 64) * -(-N // 64) * batch <= 64 and p["slices"] == 1, what
+            elif bm == 32:
                 assert M <= 32, what
-            if bn == 32:
+            elif bn == 32:
                 assert N <= 32 and M > 32, what
         else:
             assert p["tile"] == (64, 64, 16) and p["slices"] == 1, what
