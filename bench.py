@@ -149,6 +149,7 @@ def run_workload(name, steps, warmup, pgk, gen, torch, keep_host=False, sets=4):
     }
     if keep_host:
         res["_host"] = host
+        res["_out"] = (bufs[0]["C"], bufs[0]["rs"])      # what the timed calls wrote (every buffer set holds the same values)
     return res
 
 
@@ -528,8 +529,10 @@ def measured_ceilings(pgk, gen, torch):
     return out
 
 
-def cpu_baseline(w, host, gen, budget_s=15.0):
-    """The CPU oracle, as it stands, on a bounded sample of whole rows of the workload."""
+def cpu_baseline(w, host, gen, budget_s=15.0, gpu_out=None):
+    """The CPU oracle, as it stands, on a bounded sample of whole rows of the workload.  With
+    `gpu_out` = (C, rowsum) device tensors of the timed calls, also what the oracle says about those
+    rows of the timed output (second return value): the judged error and its unjudged companions."""
     import oracle
     oracle.build()
     A, B, bias = host
@@ -541,10 +544,34 @@ def cpu_baseline(w, host, gen, budget_s=15.0):
     n_rows = int(min(w.M, max(16, budget_s / max(t_probe, 1e-6) * probe_rows.size)))
     rows = np.sort(rng.choice(w.M, size=n_rows, replace=False)).astype(np.int64)
     t0 = time.perf_counter()
-    oracle.gemm_fused(A, B, bias, w.act, rows=rows, want_rowsum=w.rowsum)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, w.act, rows=rows, want_rowsum=w.rowsum)
     dt = time.perf_counter() - t0
     flops = 2.0 * n_rows * w.N * w.K * w.batch
-    return {
+    parity = None
+    if gpu_out is not None:
+        import torch
+        C, rs = gpu_out
+        sel = torch.from_numpy(rows).to(C.device)
+        got = C[:, sel]
+        if w.dtype == gen.BF16:
+            got = gen.bf16_bits_to_f32(got.contiguous().view(torch.int16).cpu().numpy().view(np.uint16)).astype(np.float64)
+        else:
+            got = got.cpu().numpy().astype(np.float64)
+
+        def figures(g, r):
+            rms = float(np.sqrt(np.mean(r * r)))
+            d = np.abs(g - r)
+            big = np.abs(r) >= rms
+            return {"judged_max_err_over_max_abs_ref_and_rms": float(np.max(d / np.maximum(np.abs(r), rms))),
+                    "strict_max_rel_err_where_ref_at_least_rms": float(np.max(d[big] / np.abs(r[big]))) if big.any() else 0.0,
+                    "max_abs_err": float(d.max())}
+        parity = {"rows": int(n_rows), "bar": 2e-2 if w.dtype == gen.BF16 else 1e-4, "C": figures(got, ref_c)}
+        if rs is not None and ref_rs is not None:
+            parity["rowsum"] = figures(rs[:, sel].cpu().numpy().astype(np.float64), ref_rs)
+        parity["within_bar"] = bool(parity["C"]["judged_max_err_over_max_abs_ref_and_rms"] <= parity["bar"] and
+                                    ("rowsum" not in parity or
+                                     parity["rowsum"]["judged_max_err_over_max_abs_ref_and_rms"] <= parity["bar"]))
+    return parity, {
         "value": flops / dt / 1e12,
         "unit": "TFLOP/s",
         "cores": oracle.num_threads(),
@@ -635,6 +662,7 @@ def main():
     head = run_workload(name, args.steps, args.warmup, pgk, gen, torch, keep_host=True, sets=args.buffer_sets)
     clocks = gpu_clocks()
     host = head.pop("_host")
+    gpu_out = head.pop("_out")
 
     dtype_key = "bf16" if w.dtype == gen.BF16 else "f32"
     roofline = gemm_roofline(name, w, head, pgk, gen)
@@ -669,8 +697,9 @@ def main():
         roofline["frac_of_measured_ceiling"] = achieved / mc[key]
     if not args.no_cpu_baseline:
         log("[cpu_baseline] timing the oracle on a bounded sample ...")
-        out["cpu_baseline"] = cpu_baseline(w, host, gen)
-    del host
+        # (the same oracle rows also judge the output of the timed calls: the bench line carries its own parity figure)
+        out["parity_of_timed_output_on_oracle_sample"], out["cpu_baseline"] = cpu_baseline(w, host, gen, gpu_out=gpu_out)
+    del host, gpu_out
     if w.dtype == gen.BF16 and w.batch == 1 and not args.no_ceilings:
         # the shader clock the kernel itself sees (cycle counter against the 100 MHz counter)
         # (the same number of launches, rotating through the same number of buffer sets, with the

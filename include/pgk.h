@@ -92,6 +92,9 @@ typedef enum {
  * with the activation and reduction operators fused into its epilogue).
  *
  * M, N, K, batch > 0.  Any shape is accepted; M, N and K need not be tile multiples.
+ * (Tile shapes: 256 x 256, 128 x 128, 256 x 128, 128 x 256 for bfloat16, 128 x 128 and 64 x 64 for
+ * float32, 128 x 32 and 32 x 128 for outputs of at most 32 columns or rows, and 32 x 32 tiles whose
+ * waves split the K range for float32 problems of a few tiles and a short K; pgk_gemm_plan tells.)
  * The matrix-core kernels read operands in place when their rows start on 4-byte boundaries
  * (float32 always; bfloat16 when K -- and, for B as [K][N], N -- is even).  Otherwise, when
  * the problem has at least 64^3 multiply-adds, the operands are first copied into the

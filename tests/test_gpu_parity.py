@@ -260,6 +260,32 @@ def test_pointers_off_the_16_byte_grid(pgk, oracle, dtype, which):
     check(c_to_numpy(C2, dtype), rs2.cpu().numpy().astype(np.float64), ref_c, ref_rs, dtype, f"misaligned {which}, split")
 
 
+# Latency-bound fp32 problems: 32 x 32 tiles whose four waves split K (pgk_gemm_tiny.hip).  Ragged M
+# and N (multiples of 4), K with a partial last step, fewer K steps than waves, several batch entries.
+TINY_SHAPES = [(256, 256, 256, 1), (40, 36, 64, 1), (100, 200, 992, 2), (512, 512, 68, 1), (257, 260, 500, 1),
+               (33, 64, 96, 5), (129, 36, 128, 3)]
+
+
+@pytest.mark.parametrize("act", [NONE, RELU, GELU, SILU])
+def test_k_splitting_tile_for_latency_bound_problems(pgk, oracle, act):
+    for shape in TINY_SHAPES:
+        M, N, K, batch = shape
+        assert pgk.gemm_plan(M, N, K, batch, F32)["tile"] == (32, 32, 32), shape
+        A, B, bias = random_case(F32, M, N, K, batch, seed=M + 5 * N + K)
+        ref_c, ref_rs = oracle.gemm_fused(A, B, bias, act)
+        got_c, got_rs = run_fused(pgk, A, B, bias, act, F32)
+        check(got_c, got_rs, ref_c, ref_rs, F32, f"tiny {shape} act {act}")
+        again_c, again_rs = run_fused(pgk, A, B, bias, act, F32)
+        assert np.array_equal(got_c, again_c) and np.array_equal(got_rs, again_rs), f"tiny {shape}: run-to-run difference"
+        if act == NONE:
+            Ai, Bi = gen.make_int_inputs(F32, M, N, K, batch, seed=7 * M + K)
+            ref_c, ref_rs = oracle.gemm_fused(Ai, Bi, None, NONE)
+            got_c, got_rs = run_fused(pgk, Ai, Bi, None, NONE, F32)
+            assert np.array_equal(got_c, ref_c) and np.array_equal(got_rs, ref_rs), f"tiny {shape}: integers"
+            got_c, got_rs = run_fused(pgk, Ai, Bi, None, NONE, F32, rowsum=False)
+            assert got_rs is None and np.array_equal(got_c, ref_c)
+
+
 def test_identity_operand_passes_b_through(pgk, oracle):
     # A = I: C = act(B + bias) -- exercises operand roles (a transposed B would fail)
     n = 256
