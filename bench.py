@@ -214,20 +214,25 @@ def gemm_roofline(name, w, res, pgk, gen):
 
 
 def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
-    """Where the time of the large bf16 kernel goes on workload `name` (c3 or c4), and at which
-    shader clock: `launches` timed launches of the measurement instance of the kernel
+    """Where the time of the large-tile kernel goes on workload `name` (c3, c4: bf16; c2: fp32), and at
+    which shader clock: `launches` timed launches of the measurement instance of the kernel
     (pgk_probe_gemm_phases: the shipping kernel plus cycle-counter / 100 MHz-counter stamps),
     rotating through `sets` copies of the buffers like the timed region of the bench.  Per launch:
     event time, clock (cycles per tick summed over the workgroups), main-loop cycles per K tile;
     the stamps of the last launch are reduced to medians over the workgroups of each round."""
     w = gen.WORKLOADS[name]
-    if w.dtype != gen.BF16 or w.batch != 1:
-        raise SystemExit("--phases: the timed instance is the large bf16 kernel (workloads c3, c4)")
+    if w.batch != 1 or w.call != "fused" or w.flops < 1e11:
+        raise SystemExit("--phases: the timed instances are the large-tile kernels (workloads c2, c3, c4)")
+    # tile, workgroups resident on one CU (registers and LDS of the instance), matrix-core flops per
+    # cycle of one CU (published peak / 256 CUs / 2.4 GHz)
+    bf16 = w.dtype == gen.BF16
+    bm, bn, bk, per_cu, cu_flops_per_cycle = (256, 256, 64, 1, 4096) if bf16 else (128, 128, 32, 2, 256)
+    issue_cycles = bm * bn * bk * 2 // cu_flops_per_cycle * per_cu   # per K tile, as one workgroup sees them
     _, (dA, dB, dbias) = device_inputs(w, gen, torch)
-    tiles_n = -(-w.N // 256)
-    wgs = -(-w.M // 256) * tiles_n
+    tiles_n = -(-w.N // bn)
+    wgs = -(-w.M // bm) * tiles_n
     bufs = [dict(A=dA if i == 0 else dA.clone(), B=dB if i == 0 else dB.clone(),
-                 C=torch.empty((1, w.M, w.N), dtype=torch.bfloat16, device="cuda"),
+                 C=torch.empty((1, w.M, w.N), dtype=torch.bfloat16 if bf16 else torch.float32, device="cuda"),
                  part=torch.empty((tiles_n, w.M), dtype=torch.float32, device="cuda") if w.rowsum else None)
             for i in range(max(1, sets))]
     stamps = torch.zeros((launches, wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
@@ -249,19 +254,21 @@ def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
     torch.cuda.synchronize()
     per_ms = np.array([ev[i].elapsed_time(ev[i + 1]) for i in range(launches)])
     st_all = stamps.cpu().numpy().astype(np.float64)
-    kt = -(-w.K // 64)
+    kt = -(-w.K // bk)
     clocks, loop_cycles = [], []
     for st in st_all:
         cyc, tick = st[:, 0:12:2], st[:, 1:12:2]
         clocks.append((cyc[:, 5] - cyc[:, 0]).sum() / (tick[:, 5] - tick[:, 0]).sum() * 0.1)
-        loop_cycles.append(float(np.median(cyc[:, 2] - cyc[:, 1])) / max(1, kt - 1))
+        # (workgroups of the first round: every CU holds its full set of them for the whole loop)
+        first = np.argsort(tick[:, 0], kind="stable")[:256 * per_cu]
+        loop_cycles.append(float(np.median(cyc[first, 2] - cyc[first, 1])) / max(1, kt - 1))
     st = st_all[-1]
     cyc, tick = st[:, 0:12:2], st[:, 1:12:2]                      # [workgroup][stamp]
     t0 = tick[:, 0].min()
     us = (tick - t0) / 100.0                                      # 100 MHz ticks -> microseconds since the first entry
-    cus = 256
+    cus = 256 * per_cu                                            # workgroups resident at once
     rounds = max(1, -(-wgs // cus))
-    order = np.argsort(us[:, 0], kind="stable")                   # by entry time: round r = r-th group of 256
+    order = np.argsort(us[:, 0], kind="stable")                   # by entry time: round r = r-th group of that many
     names = ["entry -> first K tile landed", "main loop", "bias/activation(/row sums) -> tile staged in LDS",
              "stores issued", "stores acknowledged"]
     per_round = []
@@ -280,7 +287,7 @@ def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
     clk = float(np.median(clocks))
     ms = float(np.median(per_ms))
     achieved = w.flops / (ms * 1e-3) / 1e12
-    peak_at_clock = PEAK_TFLOPS["bf16"] * clk / 2.4
+    peak_at_clock = PEAK_TFLOPS["bf16" if bf16 else "f32"] * clk / 2.4
     return {
         "workload": DESCR[name], "workgroups": int(wgs), "rounds": rounds, "k_tiles": kt,
         "launches": launches, "buffer_sets": len(bufs),
@@ -289,8 +296,9 @@ def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
         "shader_clock_ghz_under_kernel": clk,
         "shader_clock_ghz_min_max": [float(min(clocks)), float(max(clocks))],
         "main_loop_cycles_per_k_tile": float(np.median(loop_cycles)),
-        "mfma_issue_cycles_per_k_tile": 2048,
-        "main_loop_issue_efficiency": 2048.0 / float(np.median(loop_cycles)),
+        "workgroups_per_cu": per_cu,
+        "mfma_issue_cycles_per_k_tile": issue_cycles,
+        "main_loop_issue_efficiency": issue_cycles / float(np.median(loop_cycles)),
         "achieved_tflops": achieved,
         "peak_tflops_at_this_clock": peak_at_clock,      # the published peak is quoted at 2.4 GHz
         "frac_of_peak_at_this_clock": achieved / peak_at_clock,
@@ -718,7 +726,7 @@ def main():
         # (the same oracle rows also judge the output of the timed calls: the bench line carries its own parity figure)
         out["parity_of_timed_output_on_oracle_sample"], out["cpu_baseline"] = cpu_baseline(w, host, gen, gpu_out=gpu_out)
     del host, gpu_out
-    if w.dtype == gen.BF16 and w.batch == 1 and not args.no_ceilings:
+    if w.call == "fused" and w.batch == 1 and w.flops >= 1e11 and not args.no_ceilings:
         # the shader clock the kernel itself sees (cycle counter against the 100 MHz counter)
         # (the same number of launches, rotating through the same number of buffer sets, with the
         # measurement instance of the kernel: what the chip's power management grants this kernel)

@@ -332,27 +332,28 @@ int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, i
 int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream);
 
 /*
- * pgk_probe_gemm_phases -- where the time of the large bfloat16 kernel goes (the per-phase
+ * pgk_probe_gemm_phases -- where the time of the large-tile matrix-core kernel goes (the per-phase
  * evidence a performance engineer asks a profiler for, Section 3.2, which the counters do not
- * give): one launch of a measurement instance of the 256 x 256 x 64 matrix-core kernel on
- * C = act(A*B + bias), batch 1, B as [K][N], in which thread 0 of every workgroup stamps the
- * shader-clock cycle counter and the constant 100 MHz counter at six points -- kernel entry,
- * first K tile landed, end of the main loop, output tile staged (bias, activation, row sums
- * done), stores issued, stores acknowledged.  The instance is the shipping kernel plus those
- * stamps and one wait for the stores at the very end; results in C are the same.
+ * give): one launch of a measurement instance of the 256 x 256 x 64 bfloat16 kernel or of the
+ * 128 x 128 x 32 float32 kernel (`dtype`) on C = act(A*B + bias), batch 1, B as [K][N], in which
+ * wave 0 of every workgroup stamps the shader-clock cycle counter and the constant 100 MHz counter
+ * at six points -- kernel entry, first K tile landed, end of the main loop, output tile staged
+ * (bias, activation, row sums done), stores issued, stores acknowledged.  The instance is the
+ * shipping kernel plus those stamps and one wait for the stores at the very end; results in C
+ * are the same.
  *
  *     stamps  device memory, 8-byte aligned, 16 uint64 per workgroup (= per output tile, in
  *             launch order): words 2k, 2k+1 = cycles, ticks of stamp k (k = 0..5); word 12 the
  *             hardware id register of the wave, word 13 the XCD number; 14, 15 unused
- *     rowsum_partials  NULL, or device memory for ceil(N/256) * M floats: the per-tile-column
+ *     rowsum_partials  NULL, or device memory for (tile columns) * M floats: the per-tile-column
  *             partial row sums (the row-sum epilogue is then the one timed)
  *     *workgroups_out (host pointer, may be NULL) receives the number of workgroups
  *
- * A and B 16-byte aligned, K and N even (operands read in place); else PGK_ERR_UNSUPPORTED.
- * stamps_bytes too small: PGK_ERR_WORKSPACE.
+ * A and B 16-byte aligned, operand rows on 4-byte boundaries (bfloat16: K and N even); else
+ * PGK_ERR_UNSUPPORTED.  stamps_bytes too small: PGK_ERR_WORKSPACE.
  */
 int pgk_probe_gemm_phases(const void* A, const void* B, const float* bias, void* C, float* rowsum_partials,
-                          int64_t M, int64_t N, int64_t K, int act,
+                          int64_t M, int64_t N, int64_t K, int act, int dtype,
                           uint64_t* stamps, size_t stamps_bytes, int32_t* workgroups_out, void* stream);
 int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream);
 

@@ -85,7 +85,7 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_probe_mfma.restype = ci
     lib.pgk_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
     lib.pgk_probe_gemm_phases.restype = ci
-    lib.pgk_probe_gemm_phases.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, vp, ctypes.c_size_t,
+    lib.pgk_probe_gemm_phases.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, ctypes.c_size_t,
                                           ctypes.POINTER(ctypes.c_int32), vp]
     lib.pgk_probe_stream_read.restype = ci
     lib.pgk_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
@@ -383,11 +383,12 @@ STAMP_WORDS = 16      # uint64 per workgroup written by pgk_probe_gemm_phases
 
 def probe_gemm_phases(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Tensor], act: int, out: torch.Tensor,
                       stamps: torch.Tensor, rowsum_partials: Optional[torch.Tensor] = None, stream=None) -> int:
-    """One launch of the timed instance of the large bf16 kernel (pgk_probe_gemm_phases); `stamps` is
-    an int64 device tensor of at least 16 words per workgroup.  Returns the number of workgroups."""
+    """One launch of the timed instance of the large-tile kernel of the operands' type
+    (pgk_probe_gemm_phases); `stamps` is an int64 device tensor of at least 16 words per workgroup.
+    Returns the number of workgroups."""
     batch, M, N, K, dtype = _shape(A, B)
-    if batch != 1 or dtype != BF16:
-        raise ValueError("the phase probe takes one bf16 problem")
+    if batch != 1:
+        raise ValueError("the phase probe takes one problem (batch 1)")
     dev = A.device
     C = _check_out(out, "out", (1, M, N), A.dtype, dev)
     if not (stamps.is_cuda and stamps.dtype == torch.int64 and stamps.is_contiguous() and stamps.device == dev):
@@ -395,7 +396,7 @@ def probe_gemm_phases(A: torch.Tensor, B: torch.Tensor, bias: Optional[torch.Ten
     wgs = ctypes.c_int32(0)
     rc = load_library().pgk_probe_gemm_phases(
         A.data_ptr(), B.data_ptr(), _check_bias(bias, N, dev) or None, C.data_ptr(),
-        rowsum_partials.data_ptr() if rowsum_partials is not None else None, M, N, K, int(act),
+        rowsum_partials.data_ptr() if rowsum_partials is not None else None, M, N, K, int(act), dtype,
         stamps.data_ptr(), stamps.numel() * 8, ctypes.byref(wgs), _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_probe_gemm_phases")

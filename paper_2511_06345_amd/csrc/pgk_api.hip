@@ -1113,14 +1113,14 @@ int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, doubl
 }
 
 int pgk_probe_gemm_phases(const void* A, const void* B, const float* bias, void* C, float* rowsum_partials,
-                          int64_t M, int64_t N, int64_t K, int act, uint64_t* stamps, size_t stamps_bytes,
+                          int64_t M, int64_t N, int64_t K, int act, int dtype, uint64_t* stamps, size_t stamps_bytes,
                           int32_t* workgroups_out, void* stream)
 {
-    int rc = validate_common(A, B, C, M, N, K, 1, act, PGK_DTYPE_BF16);
+    int rc = validate_common(A, B, C, M, N, K, 1, act, dtype);
     if (rc != PGK_OK) return rc;
     if (!stamps || (reinterpret_cast<uintptr_t>(stamps) & 7u)) return PGK_ERR_INVALID_ARG;
-    const pgk::TileShape t = pgk::mfma_tile_shape(PGK_DTYPE_BF16, pgk::TILE_LARGE);
-    if (!aligned16(A) || !aligned16(B) || !mfma_shape_ok(M, N, K, PGK_DTYPE_BF16) || needs_packing(N, K, PGK_DTYPE_BF16, false))
+    const pgk::TileShape t = pgk::mfma_tile_shape(dtype, pgk::TILE_LARGE);
+    if (!aligned16(A) || !aligned16(B) || !mfma_shape_ok(M, N, K, dtype) || needs_packing(N, K, dtype, false))
         return PGK_ERR_UNSUPPORTED;
     const int64_t tiles_m = (M + t.bm - 1) / t.bm, tiles_n = (N + t.bn - 1) / t.bn;
     if ((long double)tiles_m * tiles_n > 1.0e6L) return PGK_ERR_UNSUPPORTED;
@@ -1130,13 +1130,13 @@ int pgk_probe_gemm_phases(const void* A, const void* B, const float* bias, void*
     a.A = A; a.B = B; a.bias = bias; a.C = C; a.rs_part = rowsum_partials;
     a.M = (int)M; a.N = (int)N; a.K = (int)K; a.batch = 1;
     pgk::fill_plain_views(a);
-    mark_ragged_rows(a, PGK_DTYPE_BF16);
+    mark_ragged_rows(a, dtype);
     a.act = act; a.splits = 1;
     a.k_slice = (int)(((K + t.bk - 1) / t.bk) * t.bk);
     a.tiles_m = (int)tiles_m; a.tiles_n = (int)tiles_n;
     a.group_m = group_m_for(a.tiles_m, a.tiles_n);
     a.stamps = reinterpret_cast<unsigned long long*>(stamps);
-    return pgk::launch_gemm_mfma_timed(a, static_cast<hipStream_t>(stream)) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+    return pgk::launch_gemm_mfma_timed(a, dtype, static_cast<hipStream_t>(stream)) == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
 int pgk_probe_stream_read(const void* src, size_t bytes, float* sink, void* stream)

@@ -54,10 +54,10 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, int dtype, int kind, int out_mode
     return small ? launch_cfg<CfgF32Small, VIEW_GEMM>(a, out_mode, s) : launch_cfg<CfgF32, VIEW_GEMM>(a, out_mode, s);
 }
 
-hipError_t launch_gemm_mfma_timed(const GemmArgs& a, hipStream_t s)
+hipError_t launch_gemm_mfma_timed(const GemmArgs& a, int dtype, hipStream_t s)
 {
     if (a.b_trans || a.bias_per_row || a.splits != 1 || !a.stamps) return hipErrorInvalidValue;
-    return launch_cfg<CfgBF16, VIEW_GEMM, true>(a, 0, s);
+    return dtype == DT_BF16 ? launch_cfg<CfgBF16, VIEW_GEMM, true>(a, 0, s) : launch_cfg<CfgF32, VIEW_GEMM, true>(a, 0, s);
 }
 
 }  // namespace pgk

@@ -125,8 +125,8 @@ hipError_t launch_gemm_mfma_conv(const GemmArgs& a, int dtype, int kind, int out
 TileShape tiny_tile_shape();
 hipError_t launch_gemm_tiny(const GemmArgs& a, hipStream_t s);
 
-// The large bf16 tile, plain operand views, out_mode 0, with phase stamps (a.stamps set).
-hipError_t launch_gemm_mfma_timed(const GemmArgs& a, hipStream_t s);
+// The large tile of either type, plain operand views, out_mode 0, with phase stamps (a.stamps set).
+hipError_t launch_gemm_mfma_timed(const GemmArgs& a, int dtype, hipStream_t s);
 
 // Bounds-checked kernel for every other shape.
 hipError_t launch_gemm_guarded(const GemmArgs& a, int dtype, int out_mode, hipStream_t s);

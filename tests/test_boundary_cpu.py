@@ -321,6 +321,19 @@ def test_probes_reject_bad_arguments_on_the_host(lib):
     assert lib.pgk_probe_stream_read(0x2000, 1000, 0x1000, None) == INVALID     # not a multiple of 16
     assert lib.pgk_probe_stream_read(0x2004, 1024, 0x1000, None) == INVALID     # misaligned
 
+    # the phase probe: both large-tile instances, 16 words of stamps per output tile
+    F32, BF16 = gen.F32, gen.BF16
+    wgs = ctypes.c_int32(-1)
+
+    def phases(A=0x1000, B=0x2000, C=0x3000, M=512, N=512, K=256, act=0, dtype=BF16, stamps=0x4000, nbytes=1 << 20):
+        return lib.pgk_probe_gemm_phases(A, B, None, C, None, M, N, K, act, dtype, stamps, nbytes, ctypes.byref(wgs), None)
+    assert phases(A=None) == INVALID and phases(stamps=None) == INVALID and phases(stamps=0x4004) == INVALID
+    assert phases(dtype=7) == INVALID and phases(act=9) == INVALID
+    assert phases(A=0x1008) == UNSUPPORTED                       # operands must sit on 16-byte boundaries
+    assert phases(N=511) == UNSUPPORTED                          # bf16 rows on 4-byte boundaries
+    assert phases(nbytes=4 * 16 * 8 - 1) == WORKSPACE and wgs.value == 4       # 2 x 2 tiles of 256 x 256
+    assert phases(dtype=F32, nbytes=16 * 16 * 8 - 1) == WORKSPACE and wgs.value == 16   # 4 x 4 tiles of 128 x 128
+
 
 def test_python_binding_validates_before_calling(lib):
     import torch

@@ -286,6 +286,35 @@ def test_k_splitting_tile_for_latency_bound_problems(pgk, oracle, act):
             assert got_rs is None and np.array_equal(got_c, ref_c)
 
 
+@pytest.mark.parametrize("dtype,shape", [(BF16, (520, 776, 200)), (BF16, (256, 256, 64)), (F32, (260, 392, 100)),
+                                         (F32, (128, 128, 32))])
+@pytest.mark.parametrize("act", [NONE, GELU])
+def test_measurement_instance_computes_what_the_kernel_computes(pgk, oracle, dtype, shape, act):
+    """pgk_probe_gemm_phases: the large-tile kernel of either type with phase stamps.  Its C and its
+    per-tile-column partial row sums meet the oracle to the same bar as the fused call, and every
+    workgroup leaves six stamps in time order."""
+    import torch
+    M, N, K = shape
+    bm, bn = (256, 256) if dtype == BF16 else (128, 128)
+    A, B, bias = random_case(dtype, M, N, K, 1, seed=M + N + K)
+    ref_c, ref_rs = oracle.gemm_fused(A, B, bias, act)
+    dA, dB = to_device(A, dtype), to_device(B, dtype)
+    tiles_n, wgs = -(-N // bn), -(-M // bm) * -(-N // bn)
+    C = torch.empty((1, M, N), dtype=dA.dtype, device="cuda")
+    part = torch.full((tiles_n, M), float("nan"), dtype=torch.float32, device="cuda")
+    stamps = torch.zeros((wgs, pgk.STAMP_WORDS), dtype=torch.int64, device="cuda")
+    assert pgk.probe_gemm_phases(dA, dB, torch.from_numpy(bias).cuda(), act, C, stamps, rowsum_partials=part) == wgs
+    torch.cuda.synchronize()
+    got_rs = part.cpu().numpy().astype(np.float64).sum(axis=0)[None, :]
+    check(c_to_numpy(C, dtype), got_rs, ref_c, ref_rs, dtype, f"timed instance {shape} act {act}")
+    st = stamps.cpu().numpy()
+    cycles, ticks = st[:, 0:12:2], st[:, 1:12:2]
+    assert np.all(np.diff(cycles, axis=1) > 0) and np.all(np.diff(ticks, axis=1) >= 0)
+    # too little room for the stamps: refused before any launch
+    with pytest.raises(pgk.PgkError):
+        pgk.probe_gemm_phases(dA, dB, None, act, C, stamps.reshape(-1)[:wgs * pgk.STAMP_WORDS - 1].clone())
+
+
 def test_identity_operand_passes_b_through(pgk, oracle):
     # A = I: C = act(B + bias) -- exercises operand roles (a transposed B would fail)
     n = 256
