@@ -552,6 +552,26 @@ def measured_ceilings(pgk, gen, torch):
     t = timed(lambda: pgk.probe_stream_read(buf, sink))
     out["hbm_stream_read_gbs"] = buf.numel() * 4 / t / 1e9
     del buf
+    # the bf16 matrix instruction fed the way the 256x256x64 kernel feeds it (pgk_probe_mfma_fed):
+    # operands re-read from LDS; plus the 64 KiB copies per K tile out of L2; plus every fifth of
+    # those pieces streamed from memory (the kernel's L2 hit rate on c3 is 80 %)
+    clock = torch.zeros(4, dtype=torch.int64, device="cuda")
+    resident = 2 << 20
+    src = (torch.randn(((1 << 30) + resident) // 2, dtype=torch.float32, device="cuda") * 0.01).to(torch.bfloat16)
+    fed = {}
+    for key, kw in (("lds_operand_reads", {}),
+                    ("lds_operand_reads_and_copies_from_l2", {"src": src, "resident_bytes": resident}),
+                    ("lds_operand_reads_and_copies_one_in_five_from_memory",
+                     {"src": src, "resident_bytes": resident, "stream_every": 5})):
+        flops = [0.0]
+
+        def launch():
+            flops[0] = pgk.probe_mfma_fed(1000, clock, **kw)
+        t = timed(launch)
+        cyc, tick = (int(v) for v in clock[:2].cpu())
+        fed[key] = {"tflops": flops[0] / t / 1e12, "shader_clock_ghz": cyc / max(1, tick) * 0.1}
+    out["mfma_bf16_fed_like_the_large_kernel"] = fed
+    del src
     return out
 
 

@@ -316,7 +316,7 @@ size_t pgk_conv1d_workspace_bytes(int64_t B, int64_t Cin, int64_t L, int64_t Cou
 int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, int64_t dilation);
 
 /*
- * pgk_probe_mfma / pgk_probe_stream_read / pgk_probe_gemm_phases -- measurement aids, not operators: what the chip
+ * pgk_probe_mfma / pgk_probe_mfma_fed / pgk_probe_stream_read / pgk_probe_gemm_phases -- measurement aids, not operators: what the chip
  * sustains under its power limit, to read a kernel's numbers against (the paper's Section 3.2
  * lists matrix-unit activity and memory throughput among a performance engineer's evidence).
  *
@@ -330,6 +330,31 @@ int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, i
  * written in practice.  Time the calls with events on `stream`.  iters in [1, 2^20].
  */
 int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, double* flops_out, void* stream);
+
+/*
+ * pgk_probe_mfma_fed -- the bfloat16 matrix instruction fed the way the 256 x 256 x 64 GEMM kernel
+ * feeds it, and nothing else of that kernel: 256 workgroups of eight waves; per iteration (one
+ * "K tile") a wave issues 32 instructions whose operands it re-reads from LDS at the kernel's
+ * addresses (192 KiB per CU and iteration), all waves meet at one barrier, and with copies != 0
+ * the workgroup also copies one 64 KiB piece of `src` straight into LDS (eight 1 KiB
+ * instructions per wave), awaited before the barrier.  Read against pgk_probe_mfma with random
+ * operands (registers only) it shows what the LDS reads and the copies cost in sustained rate and
+ * shader clock under the power limit.
+ *
+ *     iters           even, in [2, 2^20]
+ *     src             device memory, 16-byte aligned, src_bytes a multiple of 64 KiB, holding finite
+ *                     bfloat16 values (they become operands); ignored when copies == 0
+ *     resident_bytes  multiple of 64 KiB, <= src_bytes: the leading pieces every workgroup cycles
+ *                     through (they stay in L2)
+ *     stream_every    0, or n > 0: every n-th iteration's piece comes from the rest of src
+ *                     instead, each piece read once per launch as long as the rest is large
+ *                     enough (a stream from memory, as for operand panels that have left L2)
+ *     clock_out       device memory, 8-byte aligned, 3 uint64: [0] shader-clock cycles and [1]
+ *                     100 MHz ticks that workgroup 0 spent in its loop; [2] not written in practice
+ *     *flops_out      (host pointer, may be NULL) floating-point operations of one launch
+ */
+int pgk_probe_mfma_fed(int copies, int iters, const void* src, size_t src_bytes, size_t resident_bytes,
+                       int stream_every, uint64_t* clock_out, double* flops_out, void* stream);
 
 /*
  * pgk_probe_gemm_phases -- where the time of the large-tile matrix-core kernel goes (the per-phase

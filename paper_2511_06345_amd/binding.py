@@ -23,7 +23,7 @@ EXPORTS = ("pgk_gemm_fused", "pgk_gemm_splitk", "pgk_gemm_fused_bt", "pgk_gemm_s
            "pgk_gemm_fused_static", "pgk_gemm_fused_static_max_bytes",
            "pgk_splitk_auto_splits", "pgk_reduce_max", "pgk_reduce_max_workspace_bytes", "pgk_conv1d",
            "pgk_conv1d_workspace_bytes", "pgk_conv1d_out_len", "pgk_probe_mfma", "pgk_probe_stream_read",
-           "pgk_probe_gemm_phases",
+           "pgk_probe_gemm_phases", "pgk_probe_mfma_fed",
            "pgk_status_string", "pgk_version")
 
 # pgk_ws_flags_t
@@ -84,6 +84,9 @@ def load_library() -> ctypes.CDLL:
     lib.pgk_conv1d_out_len.argtypes = [i64] * 5
     lib.pgk_probe_mfma.restype = ci
     lib.pgk_probe_mfma.argtypes = [ci, ci, ci, vp, ctypes.POINTER(ctypes.c_double), vp]
+    lib.pgk_probe_mfma_fed.restype = ci
+    lib.pgk_probe_mfma_fed.argtypes = [ci, ci, vp, ctypes.c_size_t, ctypes.c_size_t, ci, vp,
+                                       ctypes.POINTER(ctypes.c_double), vp]
     lib.pgk_probe_gemm_phases.restype = ci
     lib.pgk_probe_gemm_phases.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, ci, ci, vp, ctypes.c_size_t,
                                           ctypes.POINTER(ctypes.c_int32), vp]
@@ -375,6 +378,27 @@ def probe_mfma(dtype: int, random_operands: bool, iters: int, sink: torch.Tensor
                                        ctypes.byref(flops), _stream_ptr(stream) or None)
     if rc != 0:
         raise PgkError(rc, "pgk_probe_mfma")
+    return float(flops.value)
+
+
+def probe_mfma_fed(iters: int, clock_out: torch.Tensor, src: Optional[torch.Tensor] = None, resident_bytes: int = 0,
+                   stream_every: int = 0, stream=None) -> float:
+    """Enqueues the matrix-instruction loop fed from LDS (pgk_probe_mfma_fed), with the 64 KiB copies
+    per iteration when `src` (contiguous bf16 device tensor, a multiple of 64 KiB) is given;
+    `clock_out`: int64 device tensor of at least 3 words.  Returns the flop count of the launch."""
+    if not (clock_out.is_cuda and clock_out.dtype == torch.int64 and clock_out.is_contiguous() and clock_out.numel() >= 3):
+        raise ValueError("clock_out must be a contiguous int64 device tensor of at least 3 words")
+    src_ptr, src_bytes = None, 0
+    if src is not None:
+        if not (src.is_cuda and src.dtype == torch.bfloat16 and src.is_contiguous() and src.device == clock_out.device):
+            raise ValueError("src must be a contiguous bfloat16 tensor on the device of clock_out")
+        src_ptr, src_bytes = src.data_ptr(), src.numel() * 2
+    flops = ctypes.c_double(0.0)
+    rc = load_library().pgk_probe_mfma_fed(int(src is not None), int(iters), src_ptr, src_bytes, int(resident_bytes),
+                                           int(stream_every), clock_out.data_ptr(), ctypes.byref(flops),
+                                           _stream_ptr(stream) or None)
+    if rc != 0:
+        raise PgkError(rc, "pgk_probe_mfma_fed")
     return float(flops.value)
 
 

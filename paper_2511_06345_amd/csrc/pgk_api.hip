@@ -1112,6 +1112,27 @@ int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, doubl
     return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
 }
 
+int pgk_probe_mfma_fed(int copies, int iters, const void* src, size_t src_bytes, size_t resident_bytes,
+                       int stream_every, uint64_t* clock_out, double* flops_out, void* stream)
+{
+    if (!clock_out || (reinterpret_cast<uintptr_t>(clock_out) & 7u)) return PGK_ERR_INVALID_ARG;
+    if (iters < 2 || iters > (1 << 20) || (iters & 1) || stream_every < 0) return PGK_ERR_INVALID_ARG;
+    const size_t piece = 65536;
+    unsigned int resident = 1, streamed = 0;
+    if (copies) {
+        if (!src || !aligned16(src) || src_bytes < piece || src_bytes % piece != 0) return PGK_ERR_INVALID_ARG;
+        if (resident_bytes < piece || resident_bytes % piece != 0 || resident_bytes > src_bytes) return PGK_ERR_INVALID_ARG;
+        if (src_bytes / piece > 0x7fffffffu) return PGK_ERR_UNSUPPORTED;
+        resident = (unsigned int)(resident_bytes / piece);
+        streamed = (unsigned int)((src_bytes - resident_bytes) / piece);
+    }
+    if (flops_out) *flops_out = 2.0 * 32 * 32 * 16 * 32.0 * iters * 8.0 * kNumCUs;
+    const hipError_t e = pgk::launch_probe_mfma_fed(copies != 0, iters, src, resident, streamed, stream_every,
+                                                    reinterpret_cast<unsigned long long*>(clock_out),
+                                                    static_cast<hipStream_t>(stream));
+    return e == hipSuccess ? PGK_OK : PGK_ERR_HIP;
+}
+
 int pgk_probe_gemm_phases(const void* A, const void* B, const float* bias, void* C, float* rowsum_partials,
                           int64_t M, int64_t N, int64_t K, int act, int dtype, uint64_t* stamps, size_t stamps_bytes,
                           int32_t* workgroups_out, void* stream)

@@ -187,6 +187,11 @@ hipError_t launch_transpose_pad(const void* src, void* dst, long long batch, int
 // threads, `iters` x 32 instructions per wave, zero or random operands) and a streaming
 // read of `bytes` (16-byte aligned).  `sink`: one float the kernels never really write.
 hipError_t launch_probe_mfma(int dtype, int random_operands, int iters, int workgroups, float* sink, hipStream_t s);
+// bf16 matrix instructions with operands re-read from LDS (and, with `copies`, 64 KiB direct-to-LDS
+// copies per 32 instructions of a wave): 256 workgroups of 512 threads.  iters even, >= 2;
+// src = (resident + streamed) pieces of 64 KiB; clock_out = 3 words of device memory.
+hipError_t launch_probe_mfma_fed(bool copies, int iters, const void* src, unsigned int resident, unsigned int streamed,
+                                 int stream_every, unsigned long long* clock_out, hipStream_t s);
 hipError_t launch_probe_stream_read(const void* src, size_t bytes, float* sink, hipStream_t s);
 
 }  // namespace pgk

@@ -6,6 +6,9 @@
 //     eight independent accumulators, two waves per SIMD -- nothing but the matrix pipe works.
 //     With all-zero operands nothing toggles and the clock stays at its maximum; with random
 //     operands the power limit lowers the clock, which is what a real GEMM sees.
+//   * probe_mfma_fed: the same instruction with its operands re-read from LDS at the rate and
+//     addresses of the large bf16 GEMM kernel, and optionally that kernel's global -> LDS copies:
+//     what each kind of data movement costs in clock, with none of the GEMM's other work.
 //   * probe_stream_read: every lane reads 16 bytes at a time, grid-stride, and adds them up.
 #include <hip/hip_runtime.h>
 
@@ -79,7 +82,167 @@ __global__ __launch_bounds__(256) void probe_stream_read_kernel(const u32x4* __r
     if (s == 0x12345679u) sink[0] = 1.0f;
 }
 
+// The matrix instruction fed the way the large bf16 GEMM kernel feeds it, with nothing else of
+// that kernel: 256 workgroups of eight waves (two per SIMD), each wave the 64 x 128 part of a
+// 256 x 256 x 64 tile -- per "K tile" 32 instructions whose operands it re-reads from LDS (two
+// 128-bit reads and eight transposing 64-bit reads per step of 16, at the kernel's swizzled
+// addresses and in its pinned order: 192 KiB per CU and tile), one barrier per tile, and with
+// COPIES also the eight 1 KiB direct-to-LDS copies per wave and tile (64 KiB per CU) from `src`,
+// issued in the tile's first step and awaited before the barrier (two LDS stages: a copy has
+// three quarters of a tile to land, less than in the kernel's deeper rings).
+// The LDS holds small random bf16 values (then whatever the copies bring).  Tile t of workgroup w
+// comes from the first `resident` 64 KiB pieces of src (w + t modulo resident: every piece is read
+// by all workgroups, so it stays in L2) except every `stream_every`-th, which walks through the
+// rest of src (a stream from memory).  Workgroup 0 reports the cycles and 100 MHz ticks of its loop.
+template <bool COPIES>
+__global__ __launch_bounds__(512) void probe_mfma_fed_kernel(int iters, const unsigned char* __restrict__ src,
+                                                             unsigned int resident, unsigned int streamed,
+                                                             int stream_every, unsigned long long* clock_out)
+{
+    constexpr int RA = 128, RB = 512, STAGE = 32768;
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_a1[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_b0[STAGE];
+    __shared__ __attribute__((aligned(1024))) unsigned char lds_b1[STAGE];
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave >> 1, wn = wave & 1;
+    {
+        unsigned char* const all[4] = {lds_a0, lds_a1, lds_b0, lds_b1};
+#pragma unroll
+        for (int a = 0; a < 4; ++a)
+            for (int c = tid; c < STAGE / 16; c += 512) {
+                u32x4 v;
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    v[e] = (mix32((unsigned int)c * 747796405u + (a * 4 + e) * 2891336453u + blockIdx.x * 277803737u) & 0x807f807fu) | 0x3c003c00u;
+                *(u32x4*)(all[a] + c * 16) = v;
+            }
+    }
+    __syncthreads();
+
+    const int half = lane >> 5, l32 = lane & 31;
+    int a_koff[4], b_off[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) a_koff[s] = (wm * 64 + l32) * RA + (((2 * s + half) ^ ((l32 / 2) % 8)) * 16);
+    {
+        const int grp = lane >> 4, pl = lane & 15;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int n = wn * 128 + 32 * j + 16 * (grp & 1) + 4 * (pl & 3);
+            const int krow = 8 * (grp >> 1) + (pl >> 2);
+            const int c = (n >> 3) ^ (4 * (krow & 3));
+            b_off[j] = krow * RB + c * 16 + (n & 7) * 2;
+        }
+    }
+
+    struct Frag { bf16x8 a[2]; s16x4 blo[4], bhi[4]; };
+    // LDS fetch number q of a step, in the order the instructions need them: A fragment 0, the
+    // eight halves of the B fragments, A fragment 1
+    auto fetch_op = [&](const unsigned char* as, const unsigned char* bs, int s, Frag& f, int q) __attribute__((always_inline)) {
+        if (q == 0 || q == 9) {
+            const int i = q == 0 ? 0 : 1;
+            f.a[i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
+        } else {
+            const int j = (q - 1) / 2, h = (q - 1) % 2;
+            const s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4*)PGK_LDS(bs + b_off[j] + (16 * s + 4 * h) * RB));
+            if (h == 0) f.blo[j] = v; else f.bhi[j] = v;
+        }
+    };
+    f32x16 acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    auto mfma_op = [&](const Frag& f, int m) __attribute__((always_inline)) {
+        const int i = m / 4, j = m % 4;
+        const s16x8 both = __builtin_shufflevector(f.blo[j], f.bhi[j], 0, 1, 2, 3, 4, 5, 6, 7);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), f.a[i], acc[i][j], 0, 0, 0);
+    };
+    // instruction m of this wave's share of the copy of one 64 KiB piece: 4 KiB of the A stage
+    // (m < 4), 4 KiB of the B stage; every address stays inside the piece (the resource ends there)
+    const unsigned int voff = (unsigned int)wave * 8192u + (unsigned int)lane * 16u;
+    auto copy_op = [&](const unsigned char* piece, unsigned char* aw, unsigned char* bw, int m) __attribute__((always_inline)) {
+        const auto rsrc = __builtin_amdgcn_make_buffer_rsrc((void*)piece, 0, 65536, 0x00020000);
+        unsigned char* dst = (m < 4 ? aw : bw) + wave * 4096 + (m % 4) * 1024;
+        __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, PGK_LDS(dst), 16, voff + (unsigned int)m * 1024u, 0, 0, 0);
+    };
+    auto piece_of = [&](int t) __attribute__((always_inline)) -> const unsigned char* {
+        unsigned int idx = ((unsigned int)blockIdx.x + (unsigned int)t) % resident;
+        if (stream_every > 0 && streamed > 0 && t % stream_every == 0)
+            idx = resident + ((unsigned int)blockIdx.x + 256u * (unsigned int)(t / stream_every)) % streamed;
+        return src + (size_t)idx * 65536;
+    };
+    // One tile, in the GEMM kernel's order: operands from (ar, br); instruction m of a step, then
+    // the fetches of the next step's operands that belong to slot m (spread over the first six
+    // slots) and, in the first step, copy instruction m of `piece` into (aw, bw) -- the stages
+    // the previous tile was read from.  Before the last step's instructions: wait for the copies
+    // and this wave's LDS reads, meet the other waves, and fetch the next tile's first operands
+    // from (aw, bw).  The order is pinned by scheduling barriers, as in the kernel.
+    auto ds_first = [](int m) { return m >= 6 ? 10 : (m * 10) / 6; };
+    auto tile = [&](const unsigned char* ar, const unsigned char* br, unsigned char* aw, unsigned char* bw,
+                    const unsigned char* piece, Frag (&frag)[2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+            const bool last = s == 3;
+            if (last) {
+                __builtin_amdgcn_sched_barrier(0);
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)\n\ts_barrier" ::: "memory");
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int m = 0; m < 8; ++m) {
+                mfma_op(frag[s & 1], m);
+                __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                for (int q = ds_first(m); q < ds_first(m + 1); ++q)
+                    fetch_op(last ? aw : ar, last ? bw : br, last ? 0 : s + 1, frag[(s + 1) & 1], q);
+                if constexpr (COPIES) {
+                    if (s == 0) copy_op(piece, aw, bw, m);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+
+    Frag frag[2];
+#pragma unroll
+    for (int q = 0; q < 10; ++q) fetch_op(lds_a0, lds_b0, 0, frag[0], q);
+    const unsigned long long cyc0 = __builtin_readcyclecounter();
+    const unsigned long long tick0 = __builtin_amdgcn_s_memrealtime();
+    for (int t = 0; t < iters; t += 2) {          // iters is even (the launcher sees to it)
+        tile(lds_a0, lds_b0, lds_a1, lds_b1, COPIES ? piece_of(t) : src, frag);
+        tile(lds_a1, lds_b1, lds_a0, lds_b0, COPIES ? piece_of(t + 1) : src, frag);
+    }
+    float sum = 0.0f;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) sum += acc[i][j][0] + acc[i][j][9];
+    const unsigned long long cyc1 = __builtin_readcyclecounter();
+    const unsigned long long tick1 = __builtin_amdgcn_s_memrealtime();
+    if (blockIdx.x == 0 && wave == 0) {
+        clock_out[0] = cyc1 - cyc0;
+        clock_out[1] = tick1 - tick0;
+    }
+    if (sum == 12345.678f) clock_out[2] = 1;      // keeps the work alive; never true in practice
+}
+
 }  // namespace
+
+hipError_t launch_probe_mfma_fed(bool copies, int iters, const void* src, unsigned int resident, unsigned int streamed,
+                                 int stream_every, unsigned long long* clock_out, hipStream_t s)
+{
+    if (iters < 2 || (iters & 1) || !clock_out) return hipErrorInvalidValue;
+    if (copies && (!src || resident == 0)) return hipErrorInvalidValue;
+    if (copies) hipLaunchKernelGGL(probe_mfma_fed_kernel<true>, dim3(256), dim3(512), 0, s, iters, (const unsigned char*)src, resident, streamed, stream_every, clock_out);
+    else hipLaunchKernelGGL(probe_mfma_fed_kernel<false>, dim3(256), dim3(512), 0, s, iters, (const unsigned char*)src, 1u, 0u, 0, clock_out);
+    return hipGetLastError();
+}
 
 hipError_t launch_probe_mfma(int dtype, int random_operands, int iters, int workgroups, float* sink, hipStream_t s)
 {

@@ -321,6 +321,16 @@ def test_probes_reject_bad_arguments_on_the_host(lib):
     assert lib.pgk_probe_stream_read(0x2000, 1000, 0x1000, None) == INVALID     # not a multiple of 16
     assert lib.pgk_probe_stream_read(0x2004, 1024, 0x1000, None) == INVALID     # misaligned
 
+    # the fed matrix-instruction probe: even iteration count, whole 64 KiB pieces
+    def fed(copies=1, iters=10, src=0x10000, nbytes=1 << 20, resident=1 << 16, every=0, clock=0x4000):
+        return lib.pgk_probe_mfma_fed(copies, iters, src, nbytes, resident, every, clock, None, None)
+    assert fed(clock=None) == INVALID and fed(clock=0x4004) == INVALID
+    assert fed(iters=0) == INVALID and fed(iters=3) == INVALID and fed(iters=(1 << 20) + 2) == INVALID
+    assert fed(src=None) == INVALID and fed(src=0x10008) == INVALID
+    assert fed(nbytes=1000) == INVALID and fed(nbytes=(1 << 16) + 16) == INVALID
+    assert fed(resident=0) == INVALID and fed(resident=1 << 21) == INVALID and fed(resident=100) == INVALID
+    assert fed(every=-1) == INVALID
+
     # the phase probe: both large-tile instances, 16 words of stamps per output tile
     F32, BF16 = gen.F32, gen.BF16
     wgs = ctypes.c_int32(-1)

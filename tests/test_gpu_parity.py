@@ -315,6 +315,25 @@ def test_measurement_instance_computes_what_the_kernel_computes(pgk, oracle, dty
         pgk.probe_gemm_phases(dA, dB, None, act, C, stamps.reshape(-1)[:wgs * pgk.STAMP_WORDS - 1].clone())
 
 
+def test_fed_matrix_instruction_probe_runs_and_reports_its_clock(pgk):
+    """pgk_probe_mfma_fed (a measurement aid): every form finishes, reports cycles and ticks of a
+    plausible shader clock, and leaves its source untouched."""
+    import torch
+    clock = torch.zeros(4, dtype=torch.int64, device="cuda")
+    src = (torch.randn((8 << 20) // 2, device="cuda") * 0.01).to(torch.bfloat16)       # 8 MiB: 128 pieces
+    before = src.clone()
+    for kw in ({}, {"src": src, "resident_bytes": 1 << 20}, {"src": src, "resident_bytes": 1 << 20, "stream_every": 3}):
+        clock.zero_()
+        flops = pgk.probe_mfma_fed(64, clock, **kw)
+        torch.cuda.synchronize()
+        assert flops == 2.0 * 32 * 32 * 16 * 32 * 64 * 8 * 256
+        cycles, ticks, alive = (int(v) for v in clock[:3].cpu())
+        assert alive == 0 and ticks > 0 and 0.4 <= cycles / ticks * 0.1 <= 2.6, (cycles, ticks)
+    assert torch.equal(src, before)
+    with pytest.raises(pgk.PgkError):
+        pgk.probe_mfma_fed(63, clock)
+
+
 def test_identity_operand_passes_b_through(pgk, oracle):
     # A = I: C = act(B + bias) -- exercises operand roles (a transposed B would fail)
     n = 256
