@@ -29,6 +29,7 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstddef>
 #include <type_traits>
 
 #include "pgk_device.h"
@@ -54,7 +55,12 @@ struct MfmaCfgBase {
     static constexpr int NT = NW * 64;             // threads per workgroup
     static constexpr int WM = BM / WGM;            // rows per wave
     static constexpr int WN = BN / WGN;            // cols per wave
-    static constexpr int TM = WM / 32, TN = WN / 32;
+    static constexpr int TM = WM / 32, TN = WN / 32;   // 32 x 32 accumulator blocks per wave (fp32 instruction)
+    // bf16 uses the 16 x 16 x 32 instruction: 16 x 16 blocks; the B fragments of a step of 32 along
+    // K are fetched and used in groups of at most four blocks (JG), which bounds the registers
+    // the operand double buffers take
+    static constexpr int TM16 = WM / 16, TN16 = WN / 16;
+    static constexpr int JG = TN16 > 4 ? 4 : TN16, NJH = TN16 / JG;
     static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
     static constexpr int RB = BT ? BK * ES : BN * ES;   // LDS row bytes of the B tile
     static constexpr int A_BYTES = BM * RA, B_BYTES = BN * BK * ES;
@@ -88,9 +94,9 @@ __device__ __forceinline__ int swz_a(int row) { return (row / (16 / CPR)) % CPR;
 template <bool BF16>
 __device__ __forceinline__ int swz_b(int krow)
 {
-    // bf16: the transposing read of a 16-lane group touches 4 consecutive k rows;
-    // fp32: the two half-waves read rows 4 apart.
-    return BF16 ? 4 * (krow & 3) : 8 * ((krow >> 2) & 1);
+    // bf16: the transposing read of a 16-lane group touches 4 consecutive k rows, and the two
+    // groups that are served together sit 8 rows apart; fp32: the two half-waves read rows 4 apart.
+    return BF16 ? (4 * (krow & 3)) ^ (2 * ((krow >> 3) & 1)) : 8 * ((krow >> 2) & 1);
 }
 
 // Epilogue, part 1: bias + activation on the accumulators, row-sum contribution, and
@@ -185,6 +191,69 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
     }
 }
 
+// The same for the bf16 kernels, whose accumulators are 16 x 16 blocks (v_mfma_f32_16x16x32_bf16
+// with the operand roles swapped): lane (l16 = lane % 16, grp = lane / 16) holds, of block (i, j)
+// of its wave's part, row 16 i + l16 and the four columns 16 j + 4 grp ..: one unit per block.
+// Output is bf16.  The staging layout is the one above; the sixteen rows and four units a wave
+// writes at once fall in different banks under the same XOR.
+template <int ACT, int KIND, typename Cfg, bool HAS_BIAS = true>
+__device__ __forceinline__ void epilogue_to_lds16(f32x4 (&acc)[Cfg::TM16][Cfg::TN16], const float* bias,
+                                                  const float* bias_row,
+                                                  int n_rem, int wm, int wn, int lane,
+                                                  unsigned char* const (&obj)[4], float* rs_lds)
+{
+    constexpr int TM16 = Cfg::TM16, TN16 = Cfg::TN16;
+    constexpr int UB = 8;                                 // bytes per unit
+    constexpr int ROW_BYTES = Cfg::BN * 2;
+    constexpr int UNITS = ROW_BYTES / UB;                 // units per row
+    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
+    constexpr bool ROWSUM = KIND == EPI_ROWSUM || KIND == EPI_ROWSUM_MASKED;
+    const int grp = lane >> 4;
+    const int row_in = lane & 15;
+#pragma unroll
+    for (int i = 0; i < TM16; ++i) {
+        float rs = 0.0f;
+        const int row = wm * Cfg::WM + 16 * i + row_in;   // row inside the tile
+        const int o = (wm * Cfg::WM + 16 * i) / ROWS_PER_OBJ;
+        unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
+                              (row % ROWS_PER_OBJ) * ROW_BYTES;
+        const int key = (2 * row) % UNITS;
+        float br = 0.0f;
+        if constexpr (KIND == EPI_ROWBIAS) br = bias_row[row];
+#pragma unroll
+        for (int j = 0; j < TN16; ++j) {
+            const int col = wn * Cfg::WN + 16 * j + 4 * grp;   // column inside the tile
+            f32x4 bv;
+            if constexpr (HAS_BIAS && KIND != EPI_ROWBIAS) bv = *(const f32x4*)(bias + col);
+            else bv = f32x4{br, br, br, br};
+            float y[4];
+            // columns past the end of a ragged N add nothing to the row sum: `left` of this
+            // unit's four exist.  (Kept opaque, so that each comparison is made where it is
+            // used: hoisted out of the loops, the lane masks of a wave's outputs would live in
+            // scalar registers and spill.)
+            int left = n_rem - col;
+            if constexpr (KIND == EPI_ROWSUM_MASKED) asm volatile("" : "+v"(left));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                y[e] = activate<ACT>(acc[i][j][e] + bv[e]);
+                if constexpr (KIND == EPI_ROWSUM) rs += y[e];
+                else if constexpr (KIND == EPI_ROWSUM_MASKED) rs += e < left ? y[e] : 0.0f;
+            }
+            unsigned char* dst = base + (((col >> 2) ^ key) * UB);
+            u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+            *(u32x2*)dst = pk;
+            // keeps the bias fetches of later blocks below this block's work
+            if (j % 4 == 3) asm volatile("" ::: "memory");
+        }
+        if constexpr (ROWSUM) {
+            // the four lanes that share a row, in a fixed order
+            rs += __shfl_xor(rs, 16);
+            rs += __shfl_xor(rs, 32);
+            if (grp == 0) rs_lds[wn * Cfg::BM + row] = rs;
+        }
+    }
+}
+
 // Epilogue, part 2: the staged tile goes to global memory as whole rows: a wave
 // instruction stores 64 x 16 bytes = complete 128-byte lines of consecutive rows.
 // STREAM: the output is not read again soon (C, as opposed to split-K partial products):
@@ -264,7 +333,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     constexpr bool BF16 = Cfg::BF16;
     constexpr int BM = Cfg::BM, BN = Cfg::BN, BK = Cfg::BK, ES = Cfg::ES;
     constexpr int TM = Cfg::TM, TN = Cfg::TN, RA = Cfg::RA, RB = Cfg::RB;
-    constexpr int NS = BF16 ? BK / 16 : BK / 8;   // operand-fetch steps per K tile
+    // operand-fetch steps per K tile: fp32 steps of 8 along K; bf16 steps of 32, each cut into
+    // NJH sub-steps over groups of JG B fragments
+    constexpr int JG = Cfg::JG, NJH = Cfg::NJH;
+    constexpr int NS = BF16 ? (BK / 32) * NJH : BK / 8;
     static_assert(NS % 2 == 0, "fragment double buffer assumes an even step count");
 
     // Separate LDS objects per stage and operand (not one array indexed by stage): the
@@ -458,6 +530,22 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // B tiles likewise: b_step further down -- in a convolution's view, after every
     // b_tiles_per_tap tiles the rows start over and the columns move on by b_tap_step elements
     // (a convolution read as a sum of shifted GEMMs, tap after tap).
+    // The tap table is handed out from a vector register pair -- lane t holds the entry of tap t --
+    // with v_readlane: an index known only at run time into the by-value argument would cost a
+    // memory access per tap inside the pinned instruction sequence of the main loop (and its wait
+    // would also wait for every LDS fetch in flight).
+    long long tap_of_lane = 0;
+    if constexpr (VIEW == VIEW_CONV) {
+        const __attribute__((address_space(4))) long long* const tap_table =
+            (const __attribute__((address_space(4))) long long*)((const __attribute__((address_space(4))) char*)
+                __builtin_amdgcn_kernarg_segment_ptr() + offsetof(GemmArgs, b_tap_off));
+        tap_of_lane = tap_table[lane & 31];
+    }
+    auto tap_entry = [&](int t) __attribute__((always_inline)) -> long long {
+        const unsigned int lo = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)(unsigned long long)tap_of_lane, t);
+        const unsigned int hi = (unsigned int)__builtin_amdgcn_readlane((int)(unsigned int)((unsigned long long)tap_of_lane >> 32), t);
+        return (long long)(((unsigned long long)hi << 32) | lo);
+    };
     size_t b_next_off = VIEW == VIEW_CONV ? (p.b_use_tap_table ? (size_t)p.b_tap_off[0] : 0) : (size_t)k_rot * b_step;
     int b_next_row_tile = 0, b_taps_done = 0, b_next_tile = k_rot;
     const long long b_tap_jump = VIEW == VIEW_CONV ? (long long)p.b_tap_step * ES - (long long)p.b_tiles_per_tap * (long long)b_step : 0;
@@ -473,13 +561,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             if constexpr (VIEW == VIEW_GEMM) {
                 if (++b_next_tile == KT) { b_next_tile = 0; b_next_off = 0; }
             } else {
-                if (++b_next_row_tile == p.b_tiles_per_tap) {
-                    b_next_row_tile = 0;
-                    ++b_taps_done;
-                    // (the last advance comes after the final tile: the index is kept inside the table)
-                    if (p.b_use_tap_table) b_next_off = (size_t)p.b_tap_off[b_taps_done < 32 ? b_taps_done : 31];
-                    else b_next_off = (size_t)((long long)b_next_off + b_tap_jump);
-                }
+                // (written without branches: a branch here would cut the pinned instruction
+                // sequence of the tile into basic blocks)
+                const bool new_tap = ++b_next_row_tile == p.b_tiles_per_tap;
+                b_next_row_tile = new_tap ? 0 : b_next_row_tile;
+                b_taps_done += new_tap ? 1 : 0;
+                // (the last advance comes after the final tile: the index is kept inside the table)
+                const long long from_table = tap_entry(b_taps_done < 32 ? b_taps_done : 31);
+                const long long stepped = (long long)b_next_off + b_tap_jump;
+                b_next_off = new_tap ? (size_t)(p.b_use_tap_table ? from_table : stepped) : b_next_off;
             }
         }
     };
@@ -529,32 +619,47 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     };
 
     // ---- per-lane LDS read offsets
-    const int half = lane >> 5;     // which K half of the MFMA operand this lane feeds
+    // fp32 (32 x 32 x 2 instruction): lane = (l32, half); bf16 (16 x 16 x 32): lane = (l16, grp),
+    // group grp of sixteen lanes feeds k values 8 grp .. 8 grp + 7 of a step of 32
+    const int half = lane >> 5;     // fp32: which K half of the MFMA operand this lane feeds
     const int l32 = lane & 31;
-    // A rows (MFMA "B" operand): row = wave row base + 32 i + l32, logical chunk 2 s + half
-    const int a_row_off = (wm * Cfg::WM + l32) * RA;
-    int a_koff[NS];                 // per step: row offset + swizzled chunk offset (bytes)
+    const int grp = lane >> 4;
+    const int l16 = lane & 15;
+    constexpr int NKS = BF16 ? BK / 32 : NS;    // steps along K per tile (bf16: of 32; fp32: of 8)
+    // A rows (MFMA "B" operand).  fp32: row = wave row base + 32 i + l32, logical chunk 2 s + half;
+    // bf16: row = wave row base + 16 i + l16, logical chunk 4 s + grp.  (The swizzle term only
+    // depends on the row's low bits, which the block offset leaves alone.)
+    int a_koff[NKS];                // per step: row offset + swizzled chunk offset (bytes)
 #pragma unroll
-    for (int s = 0; s < NS; ++s) a_koff[s] = a_row_off + (((2 * s + half) ^ swz_a<Cfg::A_CPR>(l32)) * 16);
+    for (int s = 0; s < NKS; ++s) {
+        if constexpr (BF16) a_koff[s] = (wm * Cfg::WM + l16) * RA + (((4 * s + grp) ^ swz_a<Cfg::A_CPR>(l16)) * 16);
+        else a_koff[s] = (wm * Cfg::WM + l32) * RA + (((2 * s + half) ^ swz_a<Cfg::A_CPR>(l32)) * 16);
+    }
     // B columns (MFMA "A" operand)
-    int b_off[Cfg::BT ? NS : TN];
+    constexpr int TNB = BF16 ? Cfg::TN16 : TN;
+    int b_off[Cfg::BT ? NKS : TNB];
     if constexpr (Cfg::BT) {
         // transposed B: column n of B is row n of the LDS tile; per step like a_koff
 #pragma unroll
-        for (int s = 0; s < NS; ++s)
-            b_off[s] = (wn * Cfg::WN + l32) * RB + (((2 * s + half) ^ swz_a<Cfg::B_CPR>(l32)) * 16);
+        for (int s = 0; s < NKS; ++s) {
+            if constexpr (BF16) b_off[s] = (wn * Cfg::WN + l16) * RB + (((4 * s + grp) ^ swz_a<Cfg::B_CPR>(l16)) * 16);
+            else b_off[s] = (wn * Cfg::WN + l32) * RB + (((2 * s + half) ^ swz_a<Cfg::B_CPR>(l32)) * 16);
+        }
     } else if constexpr (BF16) {
-        const int grp = lane >> 4, pl = lane & 15;
+        // a transposing read hands lane i of a sixteen-lane group the four k values of column i:
+        // lane pl of the group points at k row pl / 4, columns 4 (pl % 4) ..; group grp reads the
+        // rows 8 grp .. of its step (the second half of the eight four rows further down)
+        const int pl = lane & 15;
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            const int n = wn * Cfg::WN + 32 * j + 16 * (grp & 1) + 4 * (pl & 3);
-            const int krow = 8 * (grp >> 1) + (pl >> 2);
+        for (int j = 0; j < TNB; ++j) {
+            const int n = wn * Cfg::WN + 16 * j + 4 * (pl & 3);
+            const int krow = 8 * grp + (pl >> 2);
             const int c = (n >> 3) ^ swz_b<true>(krow);
             b_off[j] = krow * RB + c * 16 + (n & 7) * 2;
         }
     } else {
 #pragma unroll
-        for (int j = 0; j < TN; ++j) {
+        for (int j = 0; j < TNB; ++j) {
             const int n = wn * Cfg::WN + 32 * j + l32;
             const int krow = 4 * half;
             const int c = (n >> 2) ^ swz_b<false>(krow);
@@ -562,73 +667,105 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         }
     }
 
-    // Operand fragments for one step.  bf16: one step = one MFMA K (16); the B
-    // operand arrives as two transposing 64-bit reads.  fp32: one step = 8 K values =
-    // four MFMAs per tile pair.
-    // Transposed B: its fragments look like A's (one 128-bit read per 32 columns and step).
-    struct FragBF16 { bf16x8 a[TM]; s16x4 blo[TN], bhi[TN]; };
+    // Operand fragments.
+    // fp32: one step = 8 K values = four MFMAs per pair of 32 x 32 blocks; fragments of a step in
+    // frag[step parity].
+    // bf16: one step = one MFMA K (32) for every pair of 16 x 16 blocks, cut into NJH sub-steps over
+    // groups of JG B fragments; the A fragments of a step live in fa[step parity], the B fragments
+    // of a sub-step in fb[sub-step parity].  A plain B operand arrives as two transposing 64-bit
+    // reads per fragment, a transposed one (and A) as one 128-bit read.
+    // Below, "step" ss counts sub-steps for bf16: ss = NJH * (step along K) + (fragment group).
     struct FragF32 { f32x4 a[TM]; float b[4][TN]; };
-    struct FragBF16T { bf16x8 a[TM]; bf16x8 bt[TN]; };
     struct FragF32T { f32x4 a[TM]; f32x4 bt[TN]; };
-    using Frag = typename std::conditional<Cfg::BT, typename std::conditional<BF16, FragBF16T, FragF32T>::type,
-                                           typename std::conditional<BF16, FragBF16, FragF32>::type>::type;
+    struct FragB16 { s16x4 blo[JG], bhi[JG]; };
+    struct FragB16T { bf16x8 bt[JG]; };
+    using Frag = typename std::conditional<Cfg::BT, typename std::conditional<BF16, FragB16T, FragF32T>::type,
+                                           typename std::conditional<BF16, FragB16, FragF32>::type>::type;
+    Frag frag[2];
+    bf16x8 fa[2][BF16 ? Cfg::TM16 : 1];
 
-    // LDS fetches of one step, numbered in the order the MFMAs need them (the MFMAs
-    // run over the A fragments in the outer loop): A fragment 0, every B fragment,
-    // then the remaining A fragments.
-    constexpr int N_DS = Cfg::BT ? TM + TN : BF16 ? TM + 2 * TN : TM + 4 * TN;
-    auto fetch_op = [&](auto sta, auto stb, int s, Frag& f, int q) __attribute__((always_inline)) {
+    // LDS fetches that step ss needs, numbered in the order its MFMAs need them (the MFMAs run
+    // over the A fragments in the outer loop): A fragment 0, every B fragment, then the remaining
+    // A fragments.  bf16: the A fragments belong to the first sub-step of a step along K only.
+    constexpr int NB_DS = Cfg::BT ? (BF16 ? JG : TN) : BF16 ? 2 * JG : 4 * TN;   // B fetches of a step
+    auto n_ds = [](int ss) { return BF16 ? (ss % NJH == 0 ? Cfg::TM16 + NB_DS : NB_DS) : TM + NB_DS; };
+    auto fetch_op = [&](auto sta, auto stb, int ss, int q) __attribute__((always_inline)) {
         const unsigned char* as = lds_a(sta);
         const unsigned char* bs = lds_b(stb);
-        constexpr int NB = Cfg::BT ? TN : BF16 ? 2 * TN : 4 * TN;
-        if (q == 0 || q > NB) {
-            const int i = q == 0 ? 0 : q - NB;
-            if constexpr (BF16)
-                f.a[i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
-            else
-                f.a[i] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
-        } else if constexpr (Cfg::BT) {
-            const int j = q - 1;
-            if constexpr (BF16)
-                f.bt[j] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
-            else
-                f.bt[j] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
-        } else if constexpr (BF16) {
-            const int j = (q - 1) / 2, h = (q - 1) % 2;
-            const unsigned char* src = bs + b_off[j] + (16 * s + 4 * h) * RB;
-            s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)PGK_LDS(src));
-            if (h == 0) f.blo[j] = v; else f.bhi[j] = v;
+        Frag& f = frag[ss & 1];
+        if constexpr (BF16) {
+            const int s = ss / NJH, jh = ss % NJH;
+            const bool with_a = jh == 0;
+            if (with_a && (q == 0 || q > NB_DS)) {
+                const int i = q == 0 ? 0 : q - NB_DS;
+                fa[s & 1][i] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(as + i * 16 * RA + a_koff[s]);
+            } else {
+                const int qb = with_a ? q - 1 : q;
+                if constexpr (Cfg::BT) {
+                    const int j = JG * jh + qb;
+                    f.bt[qb] = *(const __attribute__((address_space(3))) bf16x8*)PGK_LDS(bs + j * 16 * RB + b_off[s]);
+                } else {
+                    const int jj = qb / 2, h = qb % 2;
+                    const unsigned char* src = bs + b_off[JG * jh + jj] + (32 * s + 4 * h) * RB;
+                    s16x4 v = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)PGK_LDS(src));
+                    if (h == 0) f.blo[jj] = v; else f.bhi[jj] = v;
+                }
+            }
         } else {
-            const int t = (q - 1) / TN, j = (q - 1) % TN;
-            f.b[t][j] = *(const __attribute__((address_space(3))) float*)PGK_LDS(bs + b_off[j] + (8 * s + t) * RB);
+            const int s = ss;
+            if (q == 0 || q > NB_DS) {
+                const int i = q == 0 ? 0 : q - NB_DS;
+                f.a[i] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(as + i * 32 * RA + a_koff[s]);
+            } else if constexpr (Cfg::BT) {
+                const int j = q - 1;
+                f.bt[j] = *(const __attribute__((address_space(3))) f32x4*)PGK_LDS(bs + j * 32 * RB + b_off[s]);
+            } else {
+                const int t = (q - 1) / TN, j = (q - 1) % TN;
+                f.b[t][j] = *(const __attribute__((address_space(3))) float*)PGK_LDS(bs + b_off[j] + (8 * s + t) * RB);
+            }
         }
     };
-    auto read_frags = [&](auto sta, auto stb, int s, Frag& f) __attribute__((always_inline)) {
+    auto read_frags = [&](auto sta, auto stb, int ss) __attribute__((always_inline)) {
 #pragma unroll
-        for (int q = 0; q < N_DS; ++q) fetch_op(sta, stb, s, f, q);
+        for (int q = 0; q < n_ds(ss); ++q) fetch_op(sta, stb, ss, q);
     };
 
-    f32x16 acc[TM][TN];
+    // accumulators: fp32 kernels 32 x 32 blocks (acc), bf16 kernels 16 x 16 blocks (acc16)
+    f32x16 acc[BF16 ? 1 : TM][BF16 ? 1 : TN];
+    f32x4 acc16[BF16 ? Cfg::TM16 : 1][BF16 ? Cfg::TN16 : 1];
+    if constexpr (BF16) {
 #pragma unroll
-    for (int i = 0; i < TM; ++i)
+        for (int i = 0; i < Cfg::TM16; ++i)
 #pragma unroll
-        for (int j = 0; j < TN; ++j)
+            for (int j = 0; j < Cfg::TN16; ++j)
 #pragma unroll
-            for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+                for (int v = 0; v < 4; ++v) acc16[i][j][v] = 0.0f;
+    } else {
+#pragma unroll
+        for (int i = 0; i < TM; ++i)
+#pragma unroll
+            for (int j = 0; j < TN; ++j)
+#pragma unroll
+                for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.0f;
+    }
 
-    // MFMA number m of a step (A fragments in the outer loop)
-    constexpr int N_MFMA = BF16 ? TM * TN : 4 * TM * TN;
-    auto mfma_op = [&](const Frag& f, int m) __attribute__((always_inline)) {
-        if constexpr (Cfg::BT && BF16) {
-            const int i = m / TN, j = m % TN;
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(f.bt[j], f.a[i], acc[i][j], 0, 0, 0);
+    // MFMA number m of step ss (A fragments in the outer loop)
+    constexpr int N_MFMA = BF16 ? Cfg::TM16 * JG : 4 * TM * TN;
+    auto mfma_op = [&](int ss, int m) __attribute__((always_inline)) {
+        const Frag& f = frag[ss & 1];
+        if constexpr (BF16) {
+            const int s = ss / NJH, jh = ss % NJH;
+            const int i = m / JG, jj = m % JG;
+            const int j = JG * jh + jj;
+            if constexpr (Cfg::BT) {
+                acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(f.bt[jj], fa[s & 1][i], acc16[i][j], 0, 0, 0);
+            } else {
+                const s16x8 both = __builtin_shufflevector(f.blo[jj], f.bhi[jj], 0, 1, 2, 3, 4, 5, 6, 7);
+                acc16[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, both), fa[s & 1][i], acc16[i][j], 0, 0, 0);
+            }
         } else if constexpr (Cfg::BT) {
             const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.bt[j][t], f.a[i][t], acc[i][j], 0, 0, 0);
-        } else if constexpr (BF16) {
-            const int i = m / TN, j = m % TN;
-            const s16x8 both = __builtin_shufflevector(f.blo[j], f.bhi[j], 0, 1, 2, 3, 4, 5, 6, 7);
-            acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), f.a[i], acc[i][j], 0, 0, 0);
         } else {
             const int t = m / (TM * TN), i = (m / TN) % TM, j = m % TN;
             acc[i][j] = __builtin_amdgcn_mfma_f32_32x32x2f32(f.b[t][j], f.a[i][t], acc[i][j], 0, 0, 0);
@@ -659,8 +796,6 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // tile after next and may still be in flight when the next tile is awaited.
     constexpr int STEADY_IN_FLIGHT = (SA - 2) * Cfg::A_CPW;
 
-    Frag frag[2];
-
     // One K tile: A operands from A stage kt % SA, B operands from B stage kt % 2.
     //   * Operands of step s+1 are fetched while the MFMAs of step s issue.
     //   * Before the MFMAs of the last step, when a next tile exists: wait for its
@@ -685,7 +820,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // them has the remaining MFMAs to come back before the next step needs it.
     // has_a / has_b: tile kt+2 exists (its A / B copy is issued here).
     constexpr int DS_SLOTS = N_MFMA - N_MFMA / 4;
-    auto ds_first = [](int m) { return m >= DS_SLOTS ? N_DS : (m * N_DS) / DS_SLOTS; };
+    auto ds_first = [](int m, int nds) { return m >= DS_SLOTS ? nds : (m * nds) / DS_SLOTS; };
     auto tile_body = [&](int kt, auto sta, auto stb, auto steady_tag, bool has_next, bool has_a, bool has_b) __attribute__((always_inline)) {
         constexpr int STA = decltype(sta)::value, STB = decltype(stb)::value;
         constexpr bool STEADY = decltype(steady_tag)::value != 0;
@@ -708,14 +843,15 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
                     else wait_copies_and_sync(IC<0>{});
                 }
             }
+            const int nds = n_ds(last ? 0 : s + 1);       // fetches of the step that comes next
 #pragma unroll
             for (int m = 0; m < N_MFMA; ++m) {
-                mfma_op(frag[s & 1], m);
+                mfma_op(s, m);
                 if (fetch) {
 #pragma unroll
-                    for (int q = ds_first(m); q < ds_first(m + 1); ++q) {
-                        if (!last) fetch_op(sta, stb, s + 1, frag[(s + 1) & 1], q);
-                        else fetch_op(NextA{}, NextB{}, 0, frag[0], q);
+                    for (int q = ds_first(m, nds); q < ds_first(m + 1, nds); ++q) {
+                        if (!last) fetch_op(sta, stb, s + 1, q);
+                        else fetch_op(NextA{}, NextB{}, 0, q);
                     }
                 }
 #pragma unroll
@@ -754,7 +890,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         else wait_copies_and_sync(IC<0>{});
         if (KT > 1) copy_a(1, IC<1>{});
     }
-    read_frags(IC<0>{}, IC<0>{}, 0, frag[0]);
+    read_frags(IC<0>{}, IC<0>{}, 0);
     stamp(1);      // the first K tile has landed
 
     int kt = 0;
@@ -820,25 +956,24 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             epilogue_store<false, Cfg, false>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
         } else {
 #pragma unroll
-            for (int i = 0; i < TM; ++i) {
-                const size_t row_off = (size_t)(wm * Cfg::WM + 32 * i + l32) * (size_t)p.N;
+            for (int i = 0; i < Cfg::TM16; ++i) {
+                const int row = wm * Cfg::WM + 16 * i + l16;
+                const size_t row_off = (size_t)row * (size_t)p.N;
 #pragma unroll
-                for (int j = 0; j < TN; ++j)
+                for (int j = 0; j < Cfg::TN16; ++j) {
+                    const int n = wn * Cfg::WN + 16 * j + 4 * grp;
+                    const f32x4 o = acc16[i][j];
+                    if (row < m_rem) {
+                        if (n + 4 <= n_rem) {
+                            typedef f32x4 f32x4_at_element __attribute__((aligned(4)));   // rows of any N
+                            *(f32x4_at_element*)((float*)w + row_off + n) = o;
+                        } else {
 #pragma unroll
-                    for (int g = 0; g < 4; ++g) {
-                        const int n = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;
-                        f32x4 o = {acc[i][j][4 * g], acc[i][j][4 * g + 1], acc[i][j][4 * g + 2], acc[i][j][4 * g + 3]};
-                        if (wm * Cfg::WM + 32 * i + l32 < m_rem) {
-                            if (n + 4 <= n_rem) {
-                                typedef f32x4 f32x4_at_element __attribute__((aligned(4)));   // rows of any N
-                                *(f32x4_at_element*)((float*)w + row_off + n) = o;
-                            } else {
-#pragma unroll
-                                for (int e = 0; e < 3; ++e)
-                                    if (n + e < n_rem) ((float*)w)[row_off + n + e] = o[e];
-                            }
+                            for (int e = 0; e < 3; ++e)
+                                if (n + e < n_rem) ((float*)w)[row_off + n + e] = o[e];
                         }
                     }
+                }
             }
         }
         return;
@@ -863,11 +998,20 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     auto run_epilogue = [&](auto kind) __attribute__((always_inline)) {
         constexpr int KIND = decltype(kind)::value;
         const float* br = KIND == EPI_ROWBIAS ? bias_lds_row : nullptr;
-        switch (p.act) {
-        case ACT_RELU: epilogue_to_lds<ACT_RELU, BF16, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-        case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, BF16, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-        case ACT_SILU: epilogue_to_lds<ACT_SILU, BF16, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-        default: epilogue_to_lds<ACT_NONE, BF16, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+        if constexpr (BF16) {
+            switch (p.act) {
+            case ACT_RELU: epilogue_to_lds16<ACT_RELU, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_GELU_TANH: epilogue_to_lds16<ACT_GELU_TANH, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_SILU: epilogue_to_lds16<ACT_SILU, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            default: epilogue_to_lds16<ACT_NONE, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            }
+        } else {
+            switch (p.act) {
+            case ACT_RELU: epilogue_to_lds<ACT_RELU, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_SILU: epilogue_to_lds<ACT_SILU, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            default: epilogue_to_lds<ACT_NONE, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            }
         }
     };
     if constexpr (VIEW == VIEW_CONV) {
