@@ -321,7 +321,8 @@ int64_t pgk_conv1d_out_len(int64_t L, int64_t Kw, int64_t stride, int64_t pad, i
  * lists matrix-unit activity and memory throughput among a performance engineer's evidence).
  *
  * pgk_probe_mfma launches 512 workgroups (two per CU, two waves per SIMD) in which every wave
- * issues iters * 32 matrix instructions of `dtype` on register operands -- all zero
+ * issues, per iteration, the matrix instructions of `dtype` that the kernels use (bfloat16: 64 of
+ * 16 x 16 x 32; float32: 32 of 32 x 32 x 2) on register operands -- all zero
  * (random_operands = 0: nothing toggles, the clock stays high) or random finite values
  * (random_operands = 1: what a real GEMM's operands do to the clock).  *flops_out (host
  * pointer, may be NULL) receives the floating-point operations of one launch.
@@ -334,8 +335,8 @@ int pgk_probe_mfma(int dtype, int random_operands, int iters, float* sink, doubl
 /*
  * pgk_probe_mfma_fed -- the bfloat16 matrix instruction fed the way the 256 x 256 x 64 GEMM kernel
  * feeds it, and nothing else of that kernel: 256 workgroups of eight waves; per iteration (one
- * "K tile") a wave issues 32 instructions whose operands it re-reads from LDS at the kernel's
- * addresses (192 KiB per CU and iteration), all waves meet at one barrier, and with copies != 0
+ * "K tile") a wave issues 64 instructions (16 x 16 x 32) whose operands it re-reads from LDS at the
+ * kernel's addresses (192 KiB per CU and iteration), all waves meet at one barrier, and with copies != 0
  * the workgroup also copies one 64 KiB piece of `src` straight into LDS (eight 1 KiB
  * instructions per wave), awaited before the barrier.  Read against pgk_probe_mfma with random
  * operands (registers only) it shows what the LDS reads and the copies cost in sustained rate and

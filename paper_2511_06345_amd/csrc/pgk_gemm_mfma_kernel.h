@@ -18,10 +18,16 @@
 //    and the A-matrix rows the "B" operand), so the accumulator tile a lane holds
 //    is one row of C with runs of 4 consecutive columns.  Row sums are then
 //    mostly in-lane adds, bias loads and C stores are 4 elements wide.
-//  * bf16: v_mfma_f32_32x32x16_bf16.  A rows are K-contiguous in LDS
+//  * bf16: v_mfma_f32_16x16x32_bf16.  A rows are K-contiguous in LDS
 //    (ds_read_b128); B is N-contiguous, so its operand is gathered with the
-//    transposing ds_read_b64_tr_b16.
-//  * fp32: v_mfma_f32_32x32x2_f32.
+//    transposing ds_read_b64_tr_b16.  Of the two bf16 shapes this one reads and
+//    writes half as many accumulator registers per multiply-add (a 16 x 16 block
+//    per 32 k values instead of a 32 x 32 block per 16), and under the board's power
+//    limit that shows as clock: matrix instructions alone on random register
+//    operands sustain 2230 TFLOP/s with it against 1940 with 32 x 32 x 16, the
+//    8192^3 GEMM 764 against 837 us on the same machine.
+//  * fp32: v_mfma_f32_32x32x2_f32 (at a sixteenth of the bf16 rate the matrix
+//    pipes are not what the power limit sees).
 //  * Workgroup ids are remapped so that each XCD (own L2) works on a compact
 //    group of tiles.
 #ifndef PGK_GEMM_MFMA_KERNEL_H
@@ -99,10 +105,10 @@ __device__ __forceinline__ int swz_b(int krow)
     return BF16 ? (4 * (krow & 3)) ^ (2 * ((krow >> 3) & 1)) : 8 * ((krow >> 2) & 1);
 }
 
-// Epilogue, part 1: bias + activation on the accumulators, row-sum contribution, and
-// the output tile written to LDS in the output element type.  A lane's accumulators
-// are rows of C in runs of 4 consecutive columns (8 bytes as bf16, 16 bytes as fp32);
-// such a run is one "unit".  The tile is spread over (up to) four operand buffers of
+// Epilogue, part 1 (fp32 kernels; the bf16 kernels have the variant below): bias + activation
+// on the accumulators, row-sum contribution, and the output tile written to LDS.  A lane's
+// accumulators are rows of C in runs of 4 consecutive columns (16 bytes); such a run is one
+// "unit".  The tile is spread over (up to) four operand buffers of
 // the main loop, whole rows of BN elements each; inside a row the unit index is
 // XORed with twice the row index, so that the 32 rows a wave writes at once fall in
 // different banks, and so that the pair of units forming a 16-byte chunk stays
@@ -116,15 +122,15 @@ __device__ __forceinline__ int swz_b(int krow)
 // HAS_BIAS false: `bias` is not read (the split-K partial products).
 enum { EPI_PLAIN = 0, EPI_ROWSUM = 1, EPI_ROWSUM_MASKED = 2, EPI_ROWBIAS = 3 };
 
-template <int ACT, bool OUT_BF16, int KIND, typename Cfg, bool HAS_BIAS = true>
+template <int ACT, int KIND, typename Cfg, bool HAS_BIAS = true>
 __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
                                                 const float* bias_row,
                                                 int n_rem, int wm, int wn, int lane,
                                                 unsigned char* const (&obj)[4], float* rs_lds)
 {
     constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int UB = OUT_BF16 ? 8 : 16;                 // bytes per unit
-    constexpr int ROW_BYTES = Cfg::BN * (OUT_BF16 ? 2 : 4);
+    constexpr int UB = 16;                                // bytes per unit
+    constexpr int ROW_BYTES = Cfg::BN * 4;
     constexpr int UNITS = ROW_BYTES / UB;                 // units per row
     constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
     constexpr bool ROWSUM = KIND == EPI_ROWSUM || KIND == EPI_ROWSUM_MASKED;
@@ -172,13 +178,8 @@ __device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN],
                     else if constexpr (KIND == EPI_ROWSUM_MASKED) rs += e < left ? y[e] : 0.0f;
                 }
                 unsigned char* dst = base + (((col >> 2) ^ key) * UB);
-                if constexpr (OUT_BF16) {
-                    u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
-                    *(u32x2*)dst = pk;
-                } else {
-                    f32x4 v = {y[0], y[1], y[2], y[3]};
-                    *(f32x4*)dst = v;
-                }
+                f32x4 v = {y[0], y[1], y[2], y[3]};
+                *(f32x4*)dst = v;
             }
             // keeps the next block's bias fetches below this block's work: hoisting all of
             // them to the top would cost 64 registers
@@ -951,7 +952,7 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
                                             (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
         if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, false, EPI_PLAIN, Cfg, false>(acc, nullptr, nullptr, n_rem, wm, wn, lane, obj, nullptr);
+            epilogue_to_lds<ACT_NONE, EPI_PLAIN, Cfg, false>(acc, nullptr, nullptr, n_rem, wm, wn, lane, obj, nullptr);
             __syncthreads();
             epilogue_store<false, Cfg, false>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
         } else {
@@ -1007,10 +1008,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             }
         } else {
             switch (p.act) {
-            case ACT_RELU: epilogue_to_lds<ACT_RELU, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            case ACT_SILU: epilogue_to_lds<ACT_SILU, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            default: epilogue_to_lds<ACT_NONE, false, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_RELU: epilogue_to_lds<ACT_RELU, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_SILU: epilogue_to_lds<ACT_SILU, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            default: epilogue_to_lds<ACT_NONE, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
             }
         }
     };
