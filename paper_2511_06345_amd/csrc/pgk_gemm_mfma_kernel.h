@@ -63,10 +63,12 @@ struct MfmaCfgBase {
     static constexpr int WN = BN / WGN;            // cols per wave
     static constexpr int TM = WM / 32, TN = WN / 32;   // 32 x 32 accumulator blocks per wave (fp32 instruction)
     // bf16 uses the 16 x 16 x 32 instruction: 16 x 16 blocks; the B fragments of a step of 32 along
-    // K are fetched and used in groups of at most four blocks (JG), which bounds the registers
-    // the operand double buffers take
+    // K are fetched and used in groups of JG blocks -- half of the wave's columns, at least two
+    // blocks -- which bounds the registers the operand double buffers take and gives a K tile
+    // four sub-steps, so that the wait for the next tile's copies (before the last one) comes
+    // three quarters of the way through the tile
     static constexpr int TM16 = WM / 16, TN16 = WN / 16;
-    static constexpr int JG = TN16 > 4 ? 4 : TN16, NJH = TN16 / JG;
+    static constexpr int JG = TN16 > 2 ? TN16 / 2 : TN16, NJH = TN16 / JG;
     static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
     static constexpr int RB = BT ? BK * ES : BN * ES;   // LDS row bytes of the B tile
     static constexpr int A_BYTES = BM * RA, B_BYTES = BN * BK * ES;
