@@ -8,8 +8,9 @@
 // library's own design for CDNA4:
 //
 //  * One workgroup owns a BM x BN tile of C.  A and B tiles of BK along K are
-//    copied global -> LDS with 128-bit direct-to-LDS loads into a two-stage
-//    ring, so the copy of tile kt+1 overlaps the matrix-core work on tile kt.
+//    copied global -> LDS with 128-bit direct-to-LDS loads into rings of two
+//    (or, for the A tiles of the bf16 kernels, three) stages, so the copies of the
+//    next tiles overlap the matrix-core work on tile kt.
 //  * LDS rows are stored in 16-byte chunks whose position is XOR-swizzled with
 //    the row index; the direct-to-LDS write is always one contiguous 1 KiB per
 //    wave instruction, so the swizzle is applied by choosing which global chunk
@@ -65,8 +66,8 @@ struct MfmaCfgBase {
     // bf16 uses the 16 x 16 x 32 instruction: 16 x 16 blocks; the B fragments of a step of 32 along
     // K are fetched and used in groups of JG blocks -- half of the wave's columns, at least two
     // blocks -- which bounds the registers the operand double buffers take and gives a K tile
-    // four sub-steps, so that the wait for the next tile's copies (before the last one) comes
-    // three quarters of the way through the tile
+    // four sub-steps (two on the skinny tiles), so that the wait for the next tile's copies
+    // (before the last one) comes three quarters of the way through the tile
     static constexpr int TM16 = WM / 16, TN16 = WN / 16;
     static constexpr int JG = TN16 > 2 ? TN16 / 2 : TN16, NJH = TN16 / JG;
     static constexpr int RA = BK * ES;             // LDS row bytes of the A tile
@@ -799,7 +800,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // tile after next and may still be in flight when the next tile is awaited.
     constexpr int STEADY_IN_FLIGHT = (SA - 2) * Cfg::A_CPW;
 
-    // One K tile: A operands from A stage kt % SA, B operands from B stage kt % 2.
+    // One K tile: A operands from A stage kt % SA, B operands from B stage kt % 2.  ("Step": a
+    // sub-step for bf16.)
     //   * Operands of step s+1 are fetched while the MFMAs of step s issue.
     //   * Before the MFMAs of the last step, when a next tile exists: wait for its
     //     copies, meet the other waves, fetch its first operands, and issue the first
@@ -812,7 +814,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     //     the barrier; the A copy then has a whole extra tile to land.
     //   * Copy instructions are spaced evenly between the MFMAs of their step: a burst
     //     would fill the texture-address path (about 16 cycles per 1 KiB instruction
-    //     for the whole CU) and stall the in-order waves.
+    //     for the whole CU) and stall the in-order waves (all copies back to back around the
+    //     barrier: 9 % more cycles per K tile), while copies in the middle steps of a tile
+    //     cost more than in the first and the last one (the A copy spread over three
+    //     sub-steps: 3 % more).
     // `steady`: every tile up to kt+SA-1 and kt+2 exists, so the in-flight count at the
     // wait is the steady-state one; otherwise the wait is for all copies.
     // The instruction order of a step is written out and pinned (a scheduling barrier
