@@ -269,8 +269,8 @@ def phase_budget(name, pgk, gen, torch, launches=6, sets=1, warmup=2):
     cus = 256 * per_cu                                            # workgroups resident at once
     rounds = max(1, -(-wgs // cus))
     order = np.argsort(us[:, 0], kind="stable")                   # by entry time: round r = r-th group of that many
-    names = ["entry -> first K tile landed", "main loop", "bias/activation(/row sums) -> tile staged in LDS",
-             "stores issued", "stores acknowledged"]
+    names = ["entry -> first K tile landed", "main loop", "tile's biases handed out through LDS",
+             "bias + activation (+ row sums), staging through LDS, stores issued", "stores acknowledged"]
     per_round = []
     for r in range(rounds):
         sel = order[r * cus:(r + 1) * cus]

@@ -363,8 +363,9 @@ int pgk_probe_mfma_fed(int copies, int iters, const void* src, size_t src_bytes,
  * give): one launch of a measurement instance of the 256 x 256 x 64 bfloat16 kernel or of the
  * 128 x 128 x 32 float32 kernel (`dtype`) on C = act(A*B + bias), batch 1, B as [K][N], in which
  * wave 0 of every workgroup stamps the shader-clock cycle counter and the constant 100 MHz counter
- * at six points -- kernel entry, first K tile landed, end of the main loop, output tile staged
- * (bias, activation, row sums done), stores issued, stores acknowledged.  The instance is the
+ * at six points -- kernel entry, first K tile landed, end of the main loop, the tile's biases
+ * handed out through LDS, output done (bias, activation, row sums, staging through LDS and the
+ * stores issued), stores acknowledged.  The instance is the
  * shipping kernel plus those stamps and one wait for the stores at the very end; results in C
  * are the same.
  *

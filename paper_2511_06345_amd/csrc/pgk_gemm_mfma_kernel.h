@@ -258,6 +258,106 @@ __device__ __forceinline__ void epilogue_to_lds16(f32x4 (&acc)[Cfg::TM16][Cfg::T
     }
 }
 
+// The bf16 epilogue of the tiles whose waves own at least 64 columns (row pieces of 128 bytes
+// and more): every wave stages and stores its own part of the tile, sixteen rows at a time, with
+// no workgroup barrier -- bias + activation + rounding of a 16-row block into a piece of LDS that
+// only this wave touches (the LDS operations of one wave are carried out in order), read back as
+// 16-byte chunks of whole row pieces, stored, and on to the next block while those stores drain.
+// A wave instruction stores 64 x 16 bytes = complete 128-byte lines of 4 (or 8) consecutive rows.
+// The activation arithmetic of a block so overlaps the stores of the one before, where the
+// workgroup-wide form (stage everything, barrier, store everything) adds the two up.
+// Staging layout of a block: [16 rows][WN columns] bf16, the 8-byte unit index XORed with a key of
+// the row (rows that share a 256-byte bank period share the key), so that the sixteen rows and
+// four units a wave writes at once, and the row pieces it reads back, fall in different banks.
+// Row sums as in the workgroup-wide form: per-wave partials to rs_lds, combined by the caller
+// after a barrier.
+template <int ACT, int KIND, typename Cfg, bool HAS_BIAS = true>
+__device__ __forceinline__ void epilogue_wave16(f32x4 (&acc)[Cfg::TM16][Cfg::TN16], const float* bias,
+                                                const float* bias_row, unsigned char* out_tile, size_t ld_bytes,
+                                                int m_rem, int n_rem, int wm, int wn, int wave, int lane,
+                                                unsigned char* const (&obj)[4], float* rs_lds)
+{
+    constexpr int TM16 = Cfg::TM16, TN16 = Cfg::TN16;
+    constexpr int ROWB = Cfg::WN * 2;                     // bytes of a row piece
+    constexpr int UNITS = ROWB / 8;                       // 8-byte units per row piece
+    constexpr int RPP = ROWB >= 256 ? 1 : 256 / ROWB;     // rows per 256-byte bank period
+    constexpr int BLK = 16 * ROWB;                        // bytes of a staged block
+    constexpr int WAVE_BYTES = TM16 * BLK;                // all blocks of a wave
+    constexpr int WPP = Cfg::PIECE_BYTES / WAVE_BYTES;    // waves per operand buffer
+    constexpr int CPR = ROWB / 16;                        // 16-byte chunks per row piece
+    constexpr int CH = 16 * CPR / 64;                     // chunks per lane and block
+    static_assert(ROWB >= 128 && Cfg::PIECE_BYTES % WAVE_BYTES == 0 && Cfg::NW <= 4 * WPP && 16 * CPR % 64 == 0,
+                  "row pieces of whole lines; the operand buffers hold every wave's blocks");
+    constexpr bool ROWSUM = KIND == EPI_ROWSUM || KIND == EPI_ROWSUM_MASKED;
+    const int grp = lane >> 4;
+    const int row_in = lane & 15;
+    const int o = wave / WPP;
+    unsigned char* const mine = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) + (wave % WPP) * WAVE_BYTES;
+    const int wkey = (2 * (row_in / RPP)) % UNITS;        // key of the row this lane writes
+    using chunk_at_element = u32x4_align2;
+#pragma unroll
+    for (int i = 0; i < TM16; ++i) {
+        unsigned char* const blk = mine + i * BLK;
+        const int row = wm * Cfg::WM + 16 * i + row_in;   // row inside the tile
+        float rs = 0.0f;
+        float br = 0.0f;
+        if constexpr (KIND == EPI_ROWBIAS) br = bias_row[row];
+#pragma unroll
+        for (int j = 0; j < TN16; ++j) {
+            const int colw = 16 * j + 4 * grp;            // column inside the wave's part
+            const int col = wn * Cfg::WN + colw;          // ... inside the tile
+            f32x4 bv;
+            if constexpr (HAS_BIAS && KIND != EPI_ROWBIAS) bv = *(const f32x4*)(bias + col);
+            else bv = f32x4{br, br, br, br};
+            float y[4];
+            int left = n_rem - col;
+            if constexpr (KIND == EPI_ROWSUM_MASKED) asm volatile("" : "+v"(left));
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                y[e] = activate<ACT>(acc[i][j][e] + bv[e]);
+                if constexpr (KIND == EPI_ROWSUM) rs += y[e];
+                else if constexpr (KIND == EPI_ROWSUM_MASKED) rs += e < left ? y[e] : 0.0f;
+            }
+            u32x2 pk = {pack_bf16x2(y[0], y[1]), pack_bf16x2(y[2], y[3])};
+            *(u32x2*)(blk + row_in * ROWB + (((colw >> 2) ^ wkey) * 8)) = pk;
+            if (j % 4 == 3) asm volatile("" ::: "memory");
+        }
+        if constexpr (ROWSUM) {
+            rs += __shfl_xor(rs, 16);
+            rs += __shfl_xor(rs, 32);
+            if (grp == 0) rs_lds[wn * Cfg::BM + row] = rs;
+        }
+        // the block's row pieces, 16 bytes per lane and instruction, back from LDS and out
+        u32x4 v[CH];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const int c = lane + 64 * t;
+            const int r = c / CPR, cc = c % CPR;
+            const int key = (2 * (r / RPP)) % UNITS;
+            v[t] = *(const u32x4*)(blk + r * ROWB + (((2 * cc) ^ key) * 8));
+        }
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const int c = lane + 64 * t;
+            const int r = c / CPR, cc = c % CPR;
+            const int trow = wm * Cfg::WM + 16 * i + r;
+            const int left = n_rem - (wn * Cfg::WN + cc * 8);     // elements of this chunk that exist
+            if (trow >= m_rem || left <= 0) continue;
+            unsigned char* at = out_tile + (size_t)trow * ld_bytes + (size_t)(wn * Cfg::WN) * 2 + (size_t)cc * 16;
+            if (left >= 8) {
+                __builtin_nontemporal_store(v[t], (chunk_at_element*)at);
+            } else {
+#pragma unroll
+                for (int e = 0; e < 7; ++e) {
+                    if (e >= left) break;
+                    const unsigned int word = v[t][e / 2];
+                    ((unsigned short*)at)[e] = (unsigned short)(e % 2 ? word >> 16 : word & 0xffffu);
+                }
+            }
+        }
+    }
+}
+
 // Epilogue, part 2: the staged tile goes to global memory as whole rows: a wave
 // instruction stores 64 x 16 bytes = complete 128-byte lines of consecutive rows.
 // STREAM: the output is not read again soon (C, as opposed to split-K partial products):
@@ -1003,10 +1103,22 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     // Epilogue kinds: plain (column bias only: one add per output), with row sums over a full tile
     // (no masking), with row sums over a ragged last tile column (columns past N masked out), and
     // the convolution's (one bias per row, no row sums).
+    unsigned char* c_tile = (unsigned char*)p.C +
+        ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
+    // bf16 tiles whose waves own row pieces of at least one 128-byte line stage and store per wave
+    constexpr bool WAVE_EPILOGUE = BF16 && Cfg::WN * 2 >= 128;
+    stamp(3);          // biases staged (per-wave epilogue: what follows is activation, staging and stores interleaved)
     auto run_epilogue = [&](auto kind) __attribute__((always_inline)) {
         constexpr int KIND = decltype(kind)::value;
         const float* br = KIND == EPI_ROWBIAS ? bias_lds_row : nullptr;
-        if constexpr (BF16) {
+        if constexpr (BF16 && WAVE_EPILOGUE) {
+            switch (p.act) {
+            case ACT_RELU: epilogue_wave16<ACT_RELU, KIND, Cfg>(acc16, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            case ACT_GELU_TANH: epilogue_wave16<ACT_GELU_TANH, KIND, Cfg>(acc16, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            case ACT_SILU: epilogue_wave16<ACT_SILU, KIND, Cfg>(acc16, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            default: epilogue_wave16<ACT_NONE, KIND, Cfg>(acc16, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            }
+        } else if constexpr (BF16) {
             switch (p.act) {
             case ACT_RELU: epilogue_to_lds16<ACT_RELU, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
             case ACT_GELU_TANH: epilogue_to_lds16<ACT_GELU_TANH, KIND, Cfg>(acc16, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
@@ -1030,11 +1142,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         else if (n_rem == BN) run_epilogue(IC<EPI_ROWSUM>{});
         else run_epilogue(IC<EPI_ROWSUM_MASKED>{});
     }
-    __syncthreads();
-    stamp(3);          // bias, activation and row sums done, output tile staged
-    unsigned char* c_tile = (unsigned char*)p.C +
-        ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
-    epilogue_store<BF16, Cfg, true>(c_tile, (size_t)p.N * ES, tid, m_rem, n_rem, obj);
+    // (the per-wave epilogue has stored its output already; its waves only meet again when
+    // they have row sums to add up)
+    if (!WAVE_EPILOGUE || p.rs_part) __syncthreads();
+    if constexpr (!WAVE_EPILOGUE) epilogue_store<BF16, Cfg, true>(c_tile, (size_t)p.N * ES, tid, m_rem, n_rem, obj);
     if (p.rs_part && tid < m_rem) {
         // partial row sums of the waves that share a row, added in wave-column order
         float s = rs_buf[tid];

@@ -66,7 +66,7 @@ struct GemmArgs {
 };
 
 // Words per workgroup the timed instance writes: six (cycle counter, 100 MHz counter) pairs --
-// kernel entry, first K tile landed, end of the main loop, output tile staged, stores issued,
+// kernel entry, first K tile landed, end of the main loop, biases staged, stores issued,
 // stores acknowledged -- then the hardware id register and the XCD number, two words unused.
 constexpr int kStampWords = 16;
 
