@@ -108,14 +108,14 @@ __device__ __forceinline__ int swz_b(int krow)
     return BF16 ? (4 * (krow & 3)) ^ (2 * ((krow >> 3) & 1)) : 8 * ((krow >> 2) & 1);
 }
 
-// Epilogue, part 1 (fp32 kernels; the bf16 kernels have the variant below): bias + activation
-// on the accumulators, row-sum contribution, and the output tile written to LDS.  A lane's
-// accumulators are rows of C in runs of 4 consecutive columns (16 bytes); such a run is one
-// "unit".  The tile is spread over (up to) four operand buffers of
-// the main loop, whole rows of BN elements each; inside a row the unit index is
-// XORed with twice the row index, so that the 32 rows a wave writes at once fall in
-// different banks, and so that the pair of units forming a 16-byte chunk stays
-// adjacent for part 2.
+// Epilogues.  A lane's accumulators are rows of C in runs of 4 consecutive columns; such a run is
+// one "unit" (16 bytes as fp32, 8 as bf16).  Bias, activation, rounding and the row-sum
+// contribution are applied to the accumulators, the output goes through LDS (the operand buffers
+// of the main loop, free by then) to turn units into whole row pieces, and is stored as 16-byte
+// chunks.  Two forms: per wave (epilogue_wave32, epilogue_wave16 below: every wave on its own
+// part of the tile, no workgroup barrier) wherever a wave's row pieces are whole 128-byte lines,
+// and workgroup-wide (epilogue_to_lds16 + epilogue_store: stage the whole tile, barrier, store
+// whole tile rows) for the bf16 tiles whose waves own 32 columns.
 // `bias` / `bias_row`: this tile's column or row biases, already in LDS (see the kernel).
 // KIND: EPI_PLAIN -- column bias only, no row sum: the per-element work is one add, the
 // activation and the rounding (the large GEMMs' case); EPI_ROWSUM -- plus the row sums of a
@@ -125,81 +125,13 @@ __device__ __forceinline__ int swz_b(int krow)
 // HAS_BIAS false: `bias` is not read (the split-K partial products).
 enum { EPI_PLAIN = 0, EPI_ROWSUM = 1, EPI_ROWSUM_MASKED = 2, EPI_ROWBIAS = 3 };
 
-template <int ACT, int KIND, typename Cfg, bool HAS_BIAS = true>
-__device__ __forceinline__ void epilogue_to_lds(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
-                                                const float* bias_row,
-                                                int n_rem, int wm, int wn, int lane,
-                                                unsigned char* const (&obj)[4], float* rs_lds)
-{
-    constexpr int TM = Cfg::TM, TN = Cfg::TN;
-    constexpr int UB = 16;                                // bytes per unit
-    constexpr int ROW_BYTES = Cfg::BN * 4;
-    constexpr int UNITS = ROW_BYTES / UB;                 // units per row
-    constexpr int ROWS_PER_OBJ = Cfg::PIECE_BYTES / ROW_BYTES;   // output rows one operand buffer holds
-    constexpr bool ROWSUM = KIND == EPI_ROWSUM || KIND == EPI_ROWSUM_MASKED;
-    const int half = lane >> 5;
-    const int row_in = lane & 31;
-    // per accumulator block row: where its output row is staged, its row bias, its row sum
-    // Block by block (32 rows x 32 columns of the wave's part): the lane's sixteen column
-    // biases of the block are fetched together, one LDS round trip per block instead of one
-    // per group of four outputs.  `bias` always points at staged values, zero when the call has
-    // no column bias.
-#pragma unroll
-    for (int i = 0; i < TM; ++i) {
-        float rs = 0.0f;
-        const int row = wm * Cfg::WM + 32 * i + row_in;   // row inside the tile
-        const int o = (wm * Cfg::WM + 32 * i) / ROWS_PER_OBJ;
-        unsigned char* base = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) +
-                              (row % ROWS_PER_OBJ) * ROW_BYTES;
-        const int key = (2 * row) % UNITS;
-        // bias added to rows instead of columns: staged in LDS, zero past the edge
-        float br = 0.0f;
-        if constexpr (KIND == EPI_ROWBIAS) br = bias_row[row];
-#pragma unroll
-        for (int j = 0; j < TN; ++j) {
-            f32x4 bvs[4];
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                if constexpr (HAS_BIAS && KIND != EPI_ROWBIAS) bvs[g] = *(const f32x4*)(bias + wn * Cfg::WN + 32 * j + 8 * g + 4 * half);
-                else bvs[g] = f32x4{br, br, br, br};
-            }
-#pragma unroll
-            for (int g = 0; g < 4; ++g) {
-                const int col = wn * Cfg::WN + 32 * j + 8 * g + 4 * half;   // column inside the tile
-                const f32x4 bv = bvs[g];
-                float y[4];
-                // columns past the end of a ragged N add nothing to the row sum: `left` of this
-                // unit's four exist.  (Kept opaque, so that each comparison is made where it is
-                // used: hoisted out of the loops, the 128 lane masks of a wave's outputs would
-                // live in scalar registers and spill.)
-                int left = n_rem - col;
-                if constexpr (KIND == EPI_ROWSUM_MASKED) asm volatile("" : "+v"(left));
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    y[e] = activate<ACT>(acc[i][j][4 * g + e] + bv[e]);
-                    if constexpr (KIND == EPI_ROWSUM) rs += y[e];
-                    else if constexpr (KIND == EPI_ROWSUM_MASKED) rs += e < left ? y[e] : 0.0f;
-                }
-                unsigned char* dst = base + (((col >> 2) ^ key) * UB);
-                f32x4 v = {y[0], y[1], y[2], y[3]};
-                *(f32x4*)dst = v;
-            }
-            // keeps the next block's bias fetches below this block's work: hoisting all of
-            // them to the top would cost 64 registers
-            asm volatile("" ::: "memory");
-        }
-        if constexpr (ROWSUM) {
-            rs += __shfl_xor(rs, 32);
-            if (half == 0) rs_lds[wn * Cfg::BM + row] = rs;
-        }
-    }
-}
-
-// The same for the bf16 kernels, whose accumulators are 16 x 16 blocks (v_mfma_f32_16x16x32_bf16
+// Workgroup-wide staging of a bf16 tile whose accumulators are 16 x 16 blocks (v_mfma_f32_16x16x32_bf16
 // with the operand roles swapped): lane (l16 = lane % 16, grp = lane / 16) holds, of block (i, j)
 // of its wave's part, row 16 i + l16 and the four columns 16 j + 4 grp ..: one unit per block.
-// Output is bf16.  The staging layout is the one above; the sixteen rows and four units a wave
-// writes at once fall in different banks under the same XOR.
+// Output is bf16.  The tile is spread over (up to) four operand buffers, whole rows of BN
+// elements each; inside a row the unit index is XORed with twice the row index, so that the
+// sixteen rows and four units a wave writes at once fall in different banks, and so that the
+// pair of units forming a 16-byte chunk stays adjacent for epilogue_store.
 template <int ACT, int KIND, typename Cfg, bool HAS_BIAS = true>
 __device__ __forceinline__ void epilogue_to_lds16(f32x4 (&acc)[Cfg::TM16][Cfg::TN16], const float* bias,
                                                   const float* bias_row,
@@ -352,6 +284,98 @@ __device__ __forceinline__ void epilogue_wave16(f32x4 (&acc)[Cfg::TM16][Cfg::TN1
                     if (e >= left) break;
                     const unsigned int word = v[t][e / 2];
                     ((unsigned short*)at)[e] = (unsigned short)(e % 2 ? word >> 16 : word & 0xffffu);
+                }
+            }
+        }
+    }
+}
+
+// The per-wave epilogue of the fp32 kernels (32 x 32 accumulator blocks: lane (l32, half) holds,
+// of block (i, j), row 32 i + l32 and the columns 32 j + 8 g + 4 half .., g = 0..3; a unit is 16
+// bytes): a wave's row pieces are 128 or 256 bytes for every fp32 tile shape, so all of them
+// take this form.  STREAM: non-temporal stores (C); plain ones for split-K partial products,
+// which the second pass reads back soon.
+template <int ACT, int KIND, typename Cfg, bool HAS_BIAS, bool STREAM>
+__device__ __forceinline__ void epilogue_wave32(f32x16 (&acc)[Cfg::TM][Cfg::TN], const float* bias,
+                                                const float* bias_row, unsigned char* out_tile, size_t ld_bytes,
+                                                int m_rem, int n_rem, int wm, int wn, int wave, int lane,
+                                                unsigned char* const (&obj)[4], float* rs_lds)
+{
+    constexpr int TM = Cfg::TM, TN = Cfg::TN;
+    constexpr int ROWB = Cfg::WN * 4;                     // bytes of a row piece
+    constexpr int UNITS = ROWB / 16;                      // 16-byte units (= chunks) per row piece
+    constexpr int RPP = ROWB >= 256 ? 1 : 256 / ROWB;     // rows per 256-byte bank period
+    constexpr int BLK = 32 * ROWB;                        // bytes of a staged block
+    constexpr int WAVE_BYTES = TM * BLK;
+    constexpr int WPP = Cfg::PIECE_BYTES / WAVE_BYTES;    // waves per operand buffer
+    constexpr int CH = 32 * UNITS / 64;                   // chunks per lane and block
+    static_assert(ROWB >= 128 && Cfg::PIECE_BYTES % WAVE_BYTES == 0 && Cfg::NW <= 4 * WPP && (32 * UNITS) % 64 == 0,
+                  "row pieces of whole lines; the operand buffers hold every wave's blocks");
+    constexpr bool ROWSUM = KIND == EPI_ROWSUM || KIND == EPI_ROWSUM_MASKED;
+    const int half = lane >> 5;
+    const int row_in = lane & 31;
+    const int o = wave / WPP;
+    unsigned char* const mine = (o == 0 ? obj[0] : o == 1 ? obj[1] : o == 2 ? obj[2] : obj[3]) + (wave % WPP) * WAVE_BYTES;
+    const int wkey = (row_in / RPP) % UNITS;              // key of the row this lane writes
+    using chunk_at_element = u32x4_align4;
+#pragma unroll
+    for (int i = 0; i < TM; ++i) {
+        unsigned char* const blk = mine + i * BLK;
+        const int row = wm * Cfg::WM + 32 * i + row_in;   // row inside the tile
+        float rs = 0.0f;
+        float br = 0.0f;
+        if constexpr (KIND == EPI_ROWBIAS) br = bias_row[row];
+#pragma unroll
+        for (int j = 0; j < TN; ++j) {
+            f32x4 bvs[4];
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                if constexpr (HAS_BIAS && KIND != EPI_ROWBIAS) bvs[g] = *(const f32x4*)(bias + wn * Cfg::WN + 32 * j + 8 * g + 4 * half);
+                else bvs[g] = f32x4{br, br, br, br};
+            }
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                const int colw = 32 * j + 8 * g + 4 * half;   // column inside the wave's part
+                int left = n_rem - (wn * Cfg::WN + colw);
+                if constexpr (KIND == EPI_ROWSUM_MASKED) asm volatile("" : "+v"(left));
+                f32x4 y;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    y[e] = activate<ACT>(acc[i][j][4 * g + e] + bvs[g][e]);
+                    if constexpr (KIND == EPI_ROWSUM) rs += y[e];
+                    else if constexpr (KIND == EPI_ROWSUM_MASKED) rs += e < left ? y[e] : 0.0f;
+                }
+                *(f32x4*)(blk + row_in * ROWB + (((colw >> 2) ^ wkey) * 16)) = y;
+            }
+            asm volatile("" ::: "memory");
+        }
+        if constexpr (ROWSUM) {
+            rs += __shfl_xor(rs, 32);
+            if (half == 0) rs_lds[wn * Cfg::BM + row] = rs;
+        }
+        u32x4 v[CH];
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const int c = lane + 64 * t;
+            const int r = c / UNITS, cc = c % UNITS;
+            v[t] = *(const u32x4*)(blk + r * ROWB + ((cc ^ ((r / RPP) % UNITS)) * 16));
+        }
+#pragma unroll
+        for (int t = 0; t < CH; ++t) {
+            const int c = lane + 64 * t;
+            const int r = c / UNITS, cc = c % UNITS;
+            const int trow = wm * Cfg::WM + 32 * i + r;
+            const int left = n_rem - (wn * Cfg::WN + cc * 4);     // elements of this chunk that exist
+            if (trow >= m_rem || left <= 0) continue;
+            unsigned char* at = out_tile + (size_t)trow * ld_bytes + (size_t)(wn * Cfg::WN) * 4 + (size_t)cc * 16;
+            if (left >= 4) {
+                if constexpr (STREAM) __builtin_nontemporal_store(v[t], (chunk_at_element*)at);
+                else *(chunk_at_element*)at = v[t];
+            } else {
+#pragma unroll
+                for (int e = 0; e < 3; ++e) {
+                    if (e >= left) break;
+                    ((unsigned int*)at)[e] = v[t][e];
                 }
             }
         }
@@ -1059,9 +1083,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
         unsigned char* w = (unsigned char*)(p.ws + ((size_t)b * p.splits + sp) * (size_t)p.M * (size_t)p.N +
                                             (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN);
         if constexpr (!BF16) {
-            epilogue_to_lds<ACT_NONE, EPI_PLAIN, Cfg, false>(acc, nullptr, nullptr, n_rem, wm, wn, lane, obj, nullptr);
-            __syncthreads();
-            epilogue_store<false, Cfg, false>(w, (size_t)p.N * 4, tid, m_rem, n_rem, obj);
+            epilogue_wave32<ACT_NONE, EPI_PLAIN, Cfg, false, false>(acc, nullptr, nullptr, w, (size_t)p.N * 4, m_rem, n_rem,
+                                                                    wm, wn, wave, lane, obj, nullptr);
         } else {
 #pragma unroll
             for (int i = 0; i < Cfg::TM16; ++i) {
@@ -1106,7 +1129,8 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
     unsigned char* c_tile = (unsigned char*)p.C +
         ((size_t)b * p.M * p.N + (size_t)tm * BM * (size_t)p.N + (size_t)tn * BN) * ES;
     // bf16 tiles whose waves own row pieces of at least one 128-byte line stage and store per wave
-    constexpr bool WAVE_EPILOGUE = BF16 && Cfg::WN * 2 >= 128;
+    // (so do all fp32 tiles: their waves' row pieces are 128 or 256 bytes)
+    constexpr bool WAVE_EPILOGUE = !BF16 || Cfg::WN * 2 >= 128;
     stamp(3);          // biases staged (per-wave epilogue: what follows is activation, staging and stores interleaved)
     auto run_epilogue = [&](auto kind) __attribute__((always_inline)) {
         constexpr int KIND = decltype(kind)::value;
@@ -1127,10 +1151,10 @@ __global__ __launch_bounds__(Cfg::NT, Cfg::WAVES_PER_SIMD) void gemm_mfma_kernel
             }
         } else {
             switch (p.act) {
-            case ACT_RELU: epilogue_to_lds<ACT_RELU, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            case ACT_GELU_TANH: epilogue_to_lds<ACT_GELU_TANH, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            case ACT_SILU: epilogue_to_lds<ACT_SILU, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
-            default: epilogue_to_lds<ACT_NONE, KIND, Cfg>(acc, bias_col, br, n_rem, wm, wn, lane, obj, rs_lds); break;
+            case ACT_RELU: epilogue_wave32<ACT_RELU, KIND, Cfg, true, true>(acc, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            case ACT_GELU_TANH: epilogue_wave32<ACT_GELU_TANH, KIND, Cfg, true, true>(acc, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            case ACT_SILU: epilogue_wave32<ACT_SILU, KIND, Cfg, true, true>(acc, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
+            default: epilogue_wave32<ACT_NONE, KIND, Cfg, true, true>(acc, bias_col, br, c_tile, (size_t)p.N * ES, m_rem, n_rem, wm, wn, wave, lane, obj, rs_lds); break;
             }
         }
     };
