@@ -322,7 +322,19 @@ int auto_tile_kind(int64_t M, int64_t N, int64_t K, int dtype, int64_t units, bo
     if (dtype == PGK_DTYPE_BF16 && K > 0 && K <= 128 && N < 16384) return pgk::TILE_SMALL;
     const pgk::TileShape big = pgk::mfma_tile_shape(dtype, false);
     const long double wgs = (long double)((M + big.bm - 1) / big.bm) * ((N + big.bn - 1) / big.bn) * units;
-    if (wgs < 0.75L * kNumCUs) return pgk::TILE_SMALL;
+    if (dtype == PGK_DTYPE_BF16) {
+        // One large tile fits a CU, two small ones, one half tile.  Up to half the CUs' worth of
+        // large tiles the half and small tiles still run in a single round and win (2560 x 3072 x
+        // 4096, 120 large tiles: 75 us large, 62 small, 55 tall); one large tile more and they
+        // need a second round while the large tiles do not (2816 x 3072 x 4096, 132: 78 us large,
+        // 86 small, 100 tall; the same up to 196).  With at least 192 of them the tall tile is
+        // the better single round from 16 K tiles on (5-12 % ahead of the small one).
+        if (wgs <= 0.5L * kNumCUs)
+            return (K >= 1024 && 2 * wgs >= 0.75L * kNumCUs && pgk::mfma_has_tile(dtype, pgk::TILE_TALL, b_trans)) ? pgk::TILE_TALL
+                                                                                                                : pgk::TILE_SMALL;
+    } else if (wgs < 0.75L * kNumCUs) {
+        return pgk::TILE_SMALL;
+    }
     int best = pgk::TILE_LARGE;
     if (K >= 1024 && wgs > kNumCUs) {      // (the fit does not hold for short K, where the epilogues weigh more)
         double best_time = 0.94 * estimated_rounds_time(M, N, K, dtype, units, pgk::TILE_LARGE);
@@ -454,8 +466,12 @@ FusedPlan plan_fused(bool aligned, int64_t M, int64_t N, int64_t K, int64_t batc
     // (skinny tiles run at the speed of their operand stream, which takes two workgroups per CU
     // to keep busy: 16 x 32000 x 4096 fp32, 250 flat tiles, 122 us in one piece and 94 us in two slices)
     const bool skinny = fp.path.kind == pgk::TILE_NARROW || fp.path.kind == pgk::TILE_FLAT;
-    const bool few_tiles = (long double)tiles_m * tiles_n * batch < (skinny ? (3 * kNumCUs) / 2 : (3 * kNumCUs) / 4);
-    const bool long_k = big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
+    // (a bf16 large-tile grid is only chosen from half the CUs' worth of tiles on, and then runs
+    // in one piece: two slices of 160 tiles would be a round and a quarter plus the second pass)
+    const bool bf16_large = dtype == PGK_DTYPE_BF16 && fp.path.kind == pgk::TILE_LARGE;
+    const bool few_tiles = !bf16_large &&
+                           (long double)tiles_m * tiles_n * batch < (skinny ? (3 * kNumCUs) / 2 : (3 * kNumCUs) / 4);
+    const bool long_k = !bf16_large && big_tiles < (3 * kNumCUs) / 4 && (K + big.bk - 1) / big.bk >= kLongKSteps;
     // (The fp32 small tile fits a CU four times; a grid that fills less than three quarters of
     // those places leaves each CU with one wave per SIMD and nothing to hide its waits behind.
     // From 128 K tiles on the split pays: 16384 x 64 x 8192 275 -> 173 us, 1024 x 1024 x 4096 81 -> 72 us;

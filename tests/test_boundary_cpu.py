@@ -200,10 +200,19 @@ def test_tile_table_and_split_rule(lib):
     expect((65536, 128, 1024, 1), BF16, (256, 128, 64), 1, 256, bt=True)
     expect((65536, 384, 512, 1), BF16, (256, 256, 64), 1, 512)           # a quarter of padding: large tile stays
     expect((65536, 128, 1024, 1), F32, (128, 128, 32), 1, 512)
-    # three quarters of a large tile empty, or a grid below 192 workgroups: small tile
+    # three quarters of a large tile empty, or a grid of few large tiles: small tile
     expect((64, 65536, 1024, 1), BF16, (128, 128, 64), 1, 512)
     expect((1024, 1024, 1024, 1), BF16, (128, 128, 64), 1, 64)
     expect((2048, 2048, 2048, 1), BF16, (128, 128, 64), 1, 256)
+    # bf16 grids of at most half the CUs' worth of large tiles: one round of half (from 96 large
+    # tiles and 16 K tiles on) or small tiles; one large tile more: the large tile, in one piece
+    expect((2560, 3072, 4096, 1), BF16, (256, 128, 64), 1, 10 * 24)
+    expect((2048, 4096, 8192, 1), BF16, (256, 128, 64), 1, 8 * 32)
+    expect((2560, 3072, 512, 1), BF16, (128, 128, 64), 1, 20 * 24)
+    expect((2304, 2560, 4096, 1), BF16, (128, 128, 64), 1, 18 * 20)
+    expect((2816, 3072, 4096, 1), BF16, (256, 256, 64), 1, 11 * 12)
+    expect((3072, 3584, 16384, 1), BF16, (256, 256, 64), 1, 12 * 14)
+    expect((3584, 3584, 512, 1), BF16, (256, 256, 64), 1, 14 * 14)
     # a large-tile grid that ends in a poorly filled round, K from 1024 on: the shape the round model prefers
     expect((4097, 4096, 4096, 1), BF16, (128, 128, 64), 1, 33 * 32)
     expect((4608, 4608, 4096, 1), BF16, (256, 128, 64), 1, 18 * 36)
